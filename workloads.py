@@ -1,0 +1,196 @@
+"""Seeded synthetic inputs for the layer-quantization path.
+
+This module only *makes inputs*: weight matrices W (d_row x d_col, fp32),
+calibration inputs X (d_col x N, fp32) and the shape lists of the benchmark
+configurations.  It holds none of the method's arithmetic (no Hessian, no
+quantizer, no ordering) and is the one piece of code that both the CPU oracle's
+tests and the GPU path's tests/bench import, so that both sides see identical
+bits.
+
+The inputs stand in for the trained ResNet / YOLOv5 weights and the ImageNet /
+COCO calibration activations of the paper's experiments (Section 6.1), which are
+not available offline: shapes follow the public architectures, values are
+He-normal weights and ReLU(N(0,1)) activations.
+
+Random numbers come from a counter-based generator defined here (so that any
+element can be produced independently of the others and the result does not
+depend on chunking): element n of stream s under seed k is
+
+    h   = mix64(mix64(k * GOLDEN + s) + n * GOLDEN)        (64-bit, wrapping)
+    u1  = ((h >> 32) + 1) / 2^32        in (0, 1]
+    u2  = (h & 0xffffffff) / 2^32       in [0, 1)
+    z   = sqrt(-2 ln u1) * cos(2 pi u2)                     (fp64, Box-Muller)
+
+and the fp32 value is float32(std * z).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_CHUNK = 1 << 22
+
+STREAM_W = 1
+STREAM_ACT = 2
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    """SplitMix64 output function (Steele, Lea, Flood 2014), vectorised."""
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def _stream_key(seed: int, stream: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = np.uint64(seed & 0xFFFFFFFFFFFFFFFF) * _GOLDEN + np.uint64(stream)
+        return _mix64(np.asarray(k, dtype=np.uint64))[()]
+
+
+def normal_f64(count: int, seed: int, stream: int, offset: int = 0) -> np.ndarray:
+    """`count` standard normals (fp64) for counters offset..offset+count-1."""
+    out = np.empty(count, dtype=np.float64)
+    key = _stream_key(seed, stream)
+    two_pi = 2.0 * np.pi
+    inv32 = 1.0 / 4294967296.0
+    with np.errstate(over="ignore"):
+        for lo in range(0, count, _CHUNK):
+            hi = min(count, lo + _CHUNK)
+            n = np.arange(offset + lo, offset + hi, dtype=np.uint64)
+            h = _mix64(key + n * _GOLDEN)
+            u1 = ((h >> np.uint64(32)).astype(np.float64) + 1.0) * inv32
+            u2 = (h & np.uint64(0xFFFFFFFF)).astype(np.float64) * inv32
+            out[lo:hi] = np.sqrt(-2.0 * np.log(u1)) * np.cos(two_pi * u2)
+    return out
+
+
+def normal_f32(shape, std: float, seed: int, stream: int) -> np.ndarray:
+    count = int(np.prod(shape))
+    return (normal_f64(count, seed, stream) * std).astype(np.float32).reshape(shape)
+
+
+def relu_normal_f32(shape, seed: int, stream: int) -> np.ndarray:
+    """max(N(0,1), 0) in fp32."""
+    a = normal_f32(shape, 1.0, seed, stream)
+    np.maximum(a, 0.0, out=a)
+    return a
+
+
+def im2col(maps: np.ndarray, k: int, stride: int, pad: int) -> np.ndarray:
+    """Unfold feature maps into the (d_col x N) input matrix of a k x k conv.
+
+    maps: (images, H, W, C) fp32.  Returns X with
+      row index    = c * k*k + ky * k + kx
+      column index = image * Ho*Wo + y * Wo + x
+    and zeros where the window leaves the map (zero padding).
+    """
+    n, h, w, c = maps.shape
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    padded = np.zeros((n, h + 2 * pad, w + 2 * pad, c), dtype=maps.dtype)
+    padded[:, pad:pad + h, pad:pad + w, :] = maps
+    x = np.empty((c, k, k, n, ho, wo), dtype=maps.dtype)
+    for ky in range(k):
+        for kx in range(k):
+            win = padded[:, ky:ky + stride * ho:stride, kx:kx + stride * wo:stride, :]
+            x[:, ky, kx] = np.transpose(win, (3, 0, 1, 2))
+    return x.reshape(c * k * k, n * ho * wo)
+
+
+@dataclasses.dataclass(frozen=True)
+class LayerSpec:
+    """One layer-quantization problem: shapes, quantizer settings, input recipe."""
+    name: str
+    d_row: int
+    d_col: int
+    n: int                       # calibration columns N
+    bits: int = 4
+    group: int = 0               # 0 = one grid per row
+    damp: float = 0.01
+    w_std: Optional[float] = None  # None = He-normal sqrt(2 / d_col)
+    conv: Optional[Tuple[int, int, int, int, int]] = None  # (images, side, channels, k, pad) stride 1
+    seed: int = 0
+    layer_index: int = 0
+
+    @property
+    def weights(self) -> int:
+        return self.d_row * self.d_col
+
+    def make_w(self) -> np.ndarray:
+        std = self.w_std if self.w_std is not None else float(np.sqrt(2.0 / self.d_col))
+        return normal_f32((self.d_row, self.d_col), std, self.seed,
+                          STREAM_W + 16 * self.layer_index)
+
+    def make_x(self, n: Optional[int] = None) -> np.ndarray:
+        """X (d_col x n).  For conv recipes n must be the full N."""
+        stream = STREAM_ACT + 16 * self.layer_index
+        if self.conv is not None:
+            images, side, ch, k, pad = self.conv
+            maps = relu_normal_f32((images, side, side, ch), self.seed, stream)
+            x = im2col(maps, k, 1, pad)
+            assert x.shape == (self.d_col, self.n), (x.shape, self.d_col, self.n)
+            return x
+        n = self.n if n is None else n
+        return relu_normal_f32((self.d_col, n), self.seed, stream)
+
+
+def configs() -> Dict[str, LayerSpec]:
+    """The benchmark configurations (layer shapes of the evaluation models)."""
+    c: Dict[str, LayerSpec] = {}
+    c["c1_tiny"] = LayerSpec("c1_tiny", 64, 128, 512, bits=4, w_std=0.05)
+    # 3x3 conv 256->256 on 14x14 maps, 128 images -> X = 2304 x 25088
+    c["c2_resnet50_3x3"] = LayerSpec("c2_resnet50_3x3", 256, 2304, 25088, bits=4,
+                                     conv=(128, 14, 256, 3, 1))
+    c["c3a_expand_w8"] = LayerSpec("c3a_expand_w8", 2048, 512, 25088, bits=8, layer_index=1)
+    c["c3a_expand_w4"] = LayerSpec("c3a_expand_w4", 2048, 512, 25088, bits=4, layer_index=1)
+    c["c3b_fc_w8"] = LayerSpec("c3b_fc_w8", 1000, 2048, 1024, bits=8, layer_index=2)
+    c["c3b_fc_w4"] = LayerSpec("c3b_fc_w4", 1000, 2048, 1024, bits=4, layer_index=2)
+    c["c5_large_d"] = LayerSpec("c5_large_d", 2048, 4608, 49152, bits=3, group=128, layer_index=3)
+    return c
+
+
+# Shape classes of the whole-model sweep: (count, d_row, d_col, N) with 128 images.
+RESNET50_CLASSES: List[Tuple[int, int, int, int]] = [
+    (1, 64, 147, 1605632),
+    (1, 64, 64, 401408), (3, 64, 576, 401408), (4, 256, 64, 401408),
+    (2, 64, 256, 401408), (1, 128, 256, 401408),
+    (4, 128, 1152, 100352), (4, 512, 128, 100352), (1, 512, 256, 100352),
+    (3, 128, 512, 100352), (1, 256, 512, 100352),
+    (6, 256, 2304, 25088), (6, 1024, 256, 25088), (1, 1024, 512, 25088),
+    (5, 256, 1024, 25088), (1, 512, 1024, 25088),
+    (3, 512, 4608, 6272), (3, 2048, 512, 6272), (1, 2048, 1024, 6272),
+    (2, 512, 2048, 6272),
+    (1, 1000, 2048, 128),
+]
+
+YOLOV5S_CLASSES: List[Tuple[int, int, int, int]] = [
+    (1, 32, 108, 13107200),
+    (1, 64, 288, 3276800), (2, 32, 64, 3276800), (1, 64, 64, 3276800),
+    (1, 32, 32, 3276800), (1, 32, 288, 3276800),
+    (1, 128, 576, 819200), (2, 64, 128, 819200), (2, 128, 128, 819200),
+    (3, 64, 64, 819200), (3, 64, 576, 819200), (2, 64, 256, 819200),
+    (1, 255, 128, 819200),
+    (1, 256, 1152, 204800), (5, 128, 256, 204800), (3, 256, 256, 204800),
+    (5, 128, 128, 204800), (6, 128, 1152, 204800), (2, 128, 512, 204800),
+    (1, 255, 256, 204800),
+    (1, 512, 2304, 51200), (6, 256, 512, 51200), (2, 512, 512, 51200),
+    (2, 256, 256, 51200), (3, 256, 2304, 51200), (1, 512, 1024, 51200),
+    (1, 255, 512, 51200),
+]
+
+
+def sweep_layers(model: str) -> List[LayerSpec]:
+    """Expanded per-layer list of the whole-model sweep (4-bit, per-row grids)."""
+    classes = {"resnet50": RESNET50_CLASSES, "yolov5s": YOLOV5S_CLASSES}[model]
+    out: List[LayerSpec] = []
+    idx = 100 if model == "resnet50" else 300
+    for count, r, d, n in classes:
+        for rep in range(count):
+            out.append(LayerSpec(f"{model}_{r}x{d}_n{n}_{rep}", r, d, n, bits=4, layer_index=idx))
+            idx += 1
+    return out
