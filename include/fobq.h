@@ -1,0 +1,163 @@
+/*
+ * libfobq -- sensitivity-guided, row-parallel, Hessian-compensated layer
+ * quantization on one AMD MI355X (gfx950).  C ABI; every pointer named
+ * "device" is HIP device memory on the context's GPU, everything else is host
+ * memory.  No function throws; every function returns a fobq_status (or a
+ * pointer, for fobq_last_error).
+ *
+ * The method (Zheng et al., "Sensitivity-Aware Post-Training Quantization for
+ * Deep Neural Networks"), in the paper's notation: a layer has weights W
+ * (d_row x d_col) and calibration inputs X (d_col x N); the layer objective is
+ * |WX - W^X|^2 (Section 3, Eq. 2), whose Hessian with respect to one row of W
+ * is 2 X X^T.  All rows share the one inverse Hessian Hinv (Section 4.2).
+ *
+ * Arithmetic: the whole path computes in fp64 (inputs W and X are fp32 and are
+ * widened exactly).  The rounding decision code = rint(w / scale) + zero is
+ * taken in fp64.
+ *
+ * Layouts: all matrices are dense row-major.  W is d_row x d_col, X is
+ * d_col x n with row stride ld (elements), H is d_col x d_col.
+ *
+ * Ownership: inputs are never modified; outputs are caller-allocated and
+ * caller-owned; scratch memory is owned by the context, grows on demand
+ * (hipMalloc, which synchronises the device) and is released by fobq_destroy.
+ * A context is bound to one device and one HIP stream and must not be used
+ * from two threads at once.
+ */
+#ifndef FOBQ_H
+#define FOBQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fobq_ctx fobq_ctx;
+
+typedef enum {
+    FOBQ_OK = 0,
+    FOBQ_EINVAL = -1, /* bad argument (shape, bits, group, NULL pointer, bad permutation)  */
+    FOBQ_ENOMEM = -2, /* device or host allocation failed                                   */
+    FOBQ_EHIP = -3,   /* a HIP call failed; fobq_last_error has the HIP error string        */
+    FOBQ_ENOTPD = -4, /* a Cholesky / elimination pivot was <= 0 or not finite              */
+    FOBQ_ESTATE = -5  /* call sequence error (e.g. accumulate before begin)                 */
+} fobq_status;
+
+/* Column processing order (Section 4.2, step 3; Table 3 "No Sorting"). */
+typedef enum {
+    FOBQ_ORDER_NATURAL = 0,    /* columns 0, 1, 2, ...                                       */
+    FOBQ_ORDER_SENSI_DESC = 1, /* by S_j = sum_i L_q(w_ij), descending; ties keep index order */
+    FOBQ_ORDER_CUSTOM = 2      /* caller-supplied permutation perm_in                         */
+} fobq_order;
+
+typedef struct {
+    int32_t bits;       /* 2..8: grid has 2^bits levels, codes 0..2^bits-1                   */
+    int32_t group;      /* 0: one grid per row; g > 0: one grid per row and per g consecutive */
+                        /* original columns (g must divide d_col)                            */
+    double  damp;       /* relative damping: lambda = damp * mean(diag H) + damp_abs          */
+    double  damp_abs;   /* absolute addend to diag H (Section 6.1 "damping value")           */
+    int32_t order;      /* fobq_order                                                        */
+    int32_t block;      /* 1: unblocked rank-1 updates, one launch per column (Eq. 11, 12    */
+                        /* literally); 0: default blocked form (64); 2..64: block width B of */
+                        /* the deferred rank-B updates                                       */
+    int32_t stop_after; /* -1: all columns; t >= 0: stop after t columns (test hook)         */
+    int32_t reserved;   /* must be 0                                                         */
+    const int32_t* perm_in; /* device, d_col entries; used iff order == FOBQ_ORDER_CUSTOM    */
+} fobq_opts;
+
+/* All device pointers, caller-allocated; NULL = output not wanted. */
+typedef struct {
+    uint8_t* codes;     /* d_row x d_col, original column order                               */
+    float*   scales;    /* d_row x G, G = d_col / group (1 if group == 0)                     */
+    float*   zeros;     /* d_row x G, integer-valued zero points                              */
+    float*   Q;         /* d_row x d_col dequantized weights scale * (code - zero)            */
+    int32_t* perm;      /* d_col: perm[t] = original index of the column processed at step t  */
+    double*  W_work;    /* d_row x d_col running weights, PROCESSING order (column t = step t):*/
+                        /* processed columns hold their value when quantized                  */
+    double*  Hinv_work; /* d_col x d_col running shared inverse, PROCESSING order; rows and   */
+                        /* columns of processed steps are 0                                   */
+    double*  loss;      /* 1 value: sum over steps and rows of (w - q)^2 / (2 [Hinv]_tt)      */
+} fobq_out;
+
+/* Create a context on `device` whose work is enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream).  Host call. */
+int fobq_create(fobq_ctx** ctx, int device, void* hip_stream);
+/* Synchronises the stream, frees all scratch memory.  NULL is accepted. */
+int fobq_destroy(fobq_ctx* ctx);
+/* Text of the last error on this context ("" if none).  Valid until the next call. */
+const char* fobq_last_error(const fobq_ctx* ctx);
+
+/*
+ * Hessian of the layer objective (Section 3, Eq. 2): H = (2 / N) X X^T, N the
+ * total number of calibration columns, accumulated over chunks of columns.
+ *   begin       resets the accumulator for a d_col x d_col Hessian.
+ *   accumulate  adds X_c X_c^T for a chunk X_c (device, fp32, d_col x n, row
+ *               stride ld >= n).  Enqueues work and returns; X must stay valid
+ *               until the stream reaches that work.
+ *   finalize    applies 2 / N, mirrors to a full symmetric matrix kept in the
+ *               context, and, if H_out != NULL (device, d_col x d_col fp64),
+ *               copies it there.  Enqueues and returns.
+ * Errors: EINVAL on bad sizes/NULL, ESTATE on wrong call order, ENOMEM, EHIP.
+ */
+int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col);
+int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld);
+int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
+
+/*
+ * Quantize one layer (Section 4.2, steps 1-5):
+ *   damp H and invert it through its Cholesky factor (Section 5 item 1,
+ *   Section 6.1); freeze the min-max grid of every row / group from W;
+ *   column scores S_j (Eq. 10 summed over rows) and the processing order;
+ *   then for each column in that order quantize all rows at once, push
+ *   e = (w - q) / [Hinv]_tt into the columns not yet quantized (Eq. 9 / 11) and
+ *   eliminate the column from the one shared Hinv (Eq. 12).
+ * W: device fp32 d_row x d_col.  H: device fp64 d_col x d_col full symmetric
+ * undamped Hessian, or NULL to use the one accumulated in the context
+ * (fobq_hessian_finalize must have been called with the same d_col).
+ * The call enqueues all work on the context's stream, then SYNCHRONISES the
+ * stream and reports device-detected failures (ENOTPD, bad custom permutation).
+ * On error the contents of the outputs are unspecified.
+ */
+int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
+                        const double* H, const fobq_opts* opts, const fobq_out* out);
+
+/* ---- stage-level entry points (test and benchmark hooks) ------------------ */
+
+/* Hinv = H^-1 for symmetric positive definite H via H = L L^T, L^-1, L^-T L^-1
+ * (Section 5 item 1).  H, Hinv: device fp64 d x d (Hinv full symmetric).
+ * Synchronises; ENOTPD if a pivot is <= 0. */
+int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d, double* Hinv);
+
+/* Column scores and order (Section 4.2 steps 1-3) from W and the diagonal of
+ * Hinv (device fp64 d x d): S (device fp64 d_col, may be NULL) and perm (device
+ * int32 d_col, may be NULL) for opts->order.  Uses opts->bits, group, order,
+ * perm_in.  Synchronises. */
+int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
+                     const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);
+
+/* ---- stage timing ---------------------------------------------------------- */
+typedef enum {
+    FOBQ_STAGE_XXT = 0,      /* the X X^T kernel launches only                              */
+    FOBQ_STAGE_FINALIZE = 1, /* split reduction, 2/N, mirror                                */
+    FOBQ_STAGE_CHOLESKY = 2, /* damping + H = L L^T                                         */
+    FOBQ_STAGE_INVERSE = 3,  /* L^-1 and L^-T L^-1                                          */
+    FOBQ_STAGE_ORDER = 4,    /* grid, sensitivity, sort                                     */
+    FOBQ_STAGE_PERMUTE = 5,  /* gather W and Hinv into processing order                     */
+    FOBQ_STAGE_ELIMINATE = 6,/* shared-Hinv elimination (blocked form only)                 */
+    FOBQ_STAGE_COLUMNS = 7,  /* column loop: quantize + compensate (+ Eq. 12 when unblocked)*/
+    FOBQ_STAGE_EMIT = 8,     /* scatter to original order, loss                             */
+    FOBQ_STAGE_COUNT = 9
+} fobq_stage;
+
+/* Turn hipEvent timing of the stages on or off (off by default). */
+int fobq_profile_enable(fobq_ctx* ctx, int on);
+/* Synchronises, folds pending events, returns accumulated milliseconds and the
+ * number of timed intervals of `stage` since the last reset. */
+int fobq_profile_get(fobq_ctx* ctx, int stage, double* ms, int64_t* intervals);
+int fobq_profile_reset(fobq_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOBQ_H */

@@ -1,0 +1,13 @@
+"""MI355X-native layer quantization (sensitivity-guided, row-parallel,
+Hessian-compensated).  Thin ctypes binding over libfobq.so; every step of the
+method runs in the HIP kernels of the library."""
+from .binding import (  # noqa: F401
+    FobqError, Ctx, LayerOutput,
+    OK, EINVAL, ENOMEM, EHIP, ENOTPD, ESTATE,
+    ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM,
+    STAGES, lib_path, load_library,
+    fobq_create, fobq_destroy, fobq_last_error,
+    fobq_hessian_begin, fobq_hessian_accumulate, fobq_hessian_finalize,
+    fobq_quantize_layer, fobq_spd_inverse, fobq_sensitivity,
+    fobq_profile_enable, fobq_profile_get, fobq_profile_reset,
+)

@@ -1,0 +1,251 @@
+"""ctypes binding of include/fobq.h.  Argument marshalling only: torch supplies
+device memory and the HIP stream; no arithmetic of the method happens here.
+There is no CPU fallback: if libfobq.so is missing the import of the library
+fails loudly."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+OK, EINVAL, ENOMEM, EHIP, ENOTPD, ESTATE = 0, -1, -2, -3, -4, -5
+ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM = 0, 1, 2
+STAGES = ("xxt", "finalize", "cholesky", "inverse", "order", "permute", "eliminate", "columns", "emit")
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libfobq.so")
+
+
+class FobqOpts(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32),
+                ("damp", ctypes.c_double), ("damp_abs", ctypes.c_double),
+                ("order", ctypes.c_int32), ("block", ctypes.c_int32),
+                ("stop_after", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("perm_in", ctypes.c_void_p)]
+
+
+class FobqOut(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
+                ("Q", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("W_work", ctypes.c_void_p),
+                ("Hinv_work", ctypes.c_void_p), ("loss", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libfobq.so (built by paper_2509_05576_amd/build.py).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: build it with `python -m paper_2509_05576_amd.build` "
+                                "(there is no fallback implementation)")
+    lib = ctypes.CDLL(path)
+    vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
+    lib.fobq_create.argtypes = [ctypes.POINTER(vp), i32, vp]
+    lib.fobq_destroy.argtypes = [vp]
+    lib.fobq_last_error.argtypes = [vp]
+    lib.fobq_last_error.restype = ctypes.c_char_p
+    lib.fobq_hessian_begin.argtypes = [vp, i64]
+    lib.fobq_hessian_accumulate.argtypes = [vp, vp, i64, i64]
+    lib.fobq_hessian_finalize.argtypes = [vp, vp]
+    lib.fobq_quantize_layer.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), ctypes.POINTER(FobqOut)]
+    lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
+    lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
+    lib.fobq_profile_enable.argtypes = [vp, i32]
+    lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
+    lib.fobq_profile_reset.argtypes = [vp]
+    for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_accumulate",
+                 "fobq_hessian_finalize", "fobq_quantize_layer", "fobq_spd_inverse", "fobq_sensitivity",
+                 "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+class FobqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"fobq status {code}: {msg}")
+        self.code = code
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, what: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what}: need a contiguous device tensor of {dtype}, got {t.dtype} on {t.device}")
+    return t.data_ptr()
+
+
+# ---- functions with the names of the C entry points -------------------------------------------
+def fobq_create(device: int = 0, stream: Optional[int] = None) -> int:
+    lib = load_library()
+    h = ctypes.c_void_p()
+    if stream is None:
+        stream = torch.cuda.current_stream(device).cuda_stream
+    rc = lib.fobq_create(ctypes.byref(h), device, ctypes.c_void_p(stream))
+    if rc != OK:
+        raise FobqError(rc, "fobq_create failed")
+    return h.value
+
+
+def fobq_destroy(ctx: int) -> None:
+    load_library().fobq_destroy(ctypes.c_void_p(ctx))
+
+
+def fobq_last_error(ctx: int) -> str:
+    return load_library().fobq_last_error(ctypes.c_void_p(ctx)).decode()
+
+
+def _check(ctx: int, rc: int) -> None:
+    if rc != OK:
+        raise FobqError(rc, fobq_last_error(ctx))
+
+
+def fobq_hessian_begin(ctx: int, d_col: int) -> None:
+    _check(ctx, load_library().fobq_hessian_begin(ctypes.c_void_p(ctx), d_col))
+
+
+def fobq_hessian_accumulate(ctx: int, X: torch.Tensor) -> None:
+    """X: device fp32, d_col x n, unit column stride (row stride = X.stride(0))."""
+    if not X.is_cuda or X.dtype != torch.float32 or X.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1):
+        raise TypeError("X must be a 2-D device fp32 tensor with unit column stride")
+    _check(ctx, load_library().fobq_hessian_accumulate(ctypes.c_void_p(ctx), ctypes.c_void_p(X.data_ptr()),
+                                                       X.shape[1], X.stride(0)))
+
+
+def fobq_hessian_finalize(ctx: int, H_out: Optional[torch.Tensor] = None) -> None:
+    _check(ctx, load_library().fobq_hessian_finalize(ctypes.c_void_p(ctx),
+                                                     ctypes.c_void_p(_ptr(H_out, torch.float64, "H_out"))))
+
+
+def _opts(bits, group, damp, damp_abs, order, block, stop_after, perm_in) -> FobqOpts:
+    return FobqOpts(bits, group, damp, damp_abs, order, block, stop_after, 0,
+                    _ptr(perm_in, torch.int32, "perm_in"))
+
+
+@dataclass
+class LayerOutput:
+    codes: torch.Tensor
+    scales: torch.Tensor
+    zeros: torch.Tensor
+    Q: torch.Tensor
+    perm: torch.Tensor
+    loss: torch.Tensor
+    W_work: Optional[torch.Tensor] = None
+    Hinv_work: Optional[torch.Tensor] = None
+
+
+def fobq_quantize_layer(ctx: int, W: torch.Tensor, H: Optional[torch.Tensor] = None, *, bits: int = 4,
+                        group: int = 0, damp: float = 0.01, damp_abs: float = 0.0,
+                        order: int = ORDER_SENSI_DESC, block: int = 0, stop_after: int = -1,
+                        perm_in: Optional[torch.Tensor] = None, debug: bool = False,
+                        out: Optional[LayerOutput] = None) -> LayerOutput:
+    """Allocates the outputs (unless `out` is given) and calls fobq_quantize_layer."""
+    if W.dim() != 2:
+        raise TypeError("W must be 2-D")
+    r, d = W.shape
+    dev = W.device
+    g = d // group if group > 0 and d % group == 0 else 1
+    if out is None:
+        out = LayerOutput(
+            codes=torch.empty((r, d), dtype=torch.uint8, device=dev),
+            scales=torch.empty((r, g), dtype=torch.float32, device=dev),
+            zeros=torch.empty((r, g), dtype=torch.float32, device=dev),
+            Q=torch.empty((r, d), dtype=torch.float32, device=dev),
+            perm=torch.empty((d,), dtype=torch.int32, device=dev),
+            loss=torch.empty((1,), dtype=torch.float64, device=dev),
+            W_work=torch.empty((r, d), dtype=torch.float64, device=dev) if debug else None,
+            Hinv_work=torch.empty((d, d), dtype=torch.float64, device=dev) if debug else None)
+    co = FobqOut(_ptr(out.codes, torch.uint8, "codes"), _ptr(out.scales, torch.float32, "scales"),
+                 _ptr(out.zeros, torch.float32, "zeros"), _ptr(out.Q, torch.float32, "Q"),
+                 _ptr(out.perm, torch.int32, "perm"), _ptr(out.W_work, torch.float64, "W_work"),
+                 _ptr(out.Hinv_work, torch.float64, "Hinv_work"), _ptr(out.loss, torch.float64, "loss"))
+    op = _opts(bits, group, damp, damp_abs, order, block, stop_after, perm_in)
+    rc = load_library().fobq_quantize_layer(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")),
+                                            r, d, ctypes.c_void_p(_ptr(H, torch.float64, "H")),
+                                            ctypes.byref(op), ctypes.byref(co))
+    _check(ctx, rc)
+    return out
+
+
+def fobq_spd_inverse(ctx: int, H: torch.Tensor) -> torch.Tensor:
+    d = H.shape[0]
+    Hinv = torch.empty((d, d), dtype=torch.float64, device=H.device)
+    _check(ctx, load_library().fobq_spd_inverse(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(H, torch.float64, "H")),
+                                                d, ctypes.c_void_p(Hinv.data_ptr())))
+    return Hinv
+
+
+def fobq_sensitivity(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 4, group: int = 0,
+                     order: int = ORDER_SENSI_DESC, perm_in: Optional[torch.Tensor] = None):
+    r, d = W.shape
+    S = torch.empty((d,), dtype=torch.float64, device=W.device)
+    perm = torch.empty((d,), dtype=torch.int32, device=W.device)
+    op = _opts(bits, group, 0.0, 0.0, order, 0, -1, perm_in)
+    rc = load_library().fobq_sensitivity(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")), r, d,
+                                         ctypes.c_void_p(_ptr(Hinv, torch.float64, "Hinv")), ctypes.byref(op),
+                                         ctypes.c_void_p(S.data_ptr()), ctypes.c_void_p(perm.data_ptr()))
+    _check(ctx, rc)
+    return S, perm
+
+
+def fobq_profile_enable(ctx: int, on: bool) -> None:
+    _check(ctx, load_library().fobq_profile_enable(ctypes.c_void_p(ctx), int(on)))
+
+
+def fobq_profile_get(ctx: int, stage: int):
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(ctx, load_library().fobq_profile_get(ctypes.c_void_p(ctx), stage, ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
+
+
+def fobq_profile_reset(ctx: int) -> None:
+    _check(ctx, load_library().fobq_profile_reset(ctypes.c_void_p(ctx)))
+
+
+class Ctx:
+    """Context manager around a fobq context bound to torch's current stream."""
+
+    def __init__(self, device: int = 0, stream: Optional[int] = None):
+        self.handle = fobq_create(device, stream)
+
+    def close(self) -> None:
+        if self.handle:
+            fobq_destroy(self.handle)
+            self.handle = 0
+
+    def __enter__(self) -> "Ctx":
+        return self
+
+    def __exit__(self, *exc) -> None:
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def hessian(self, X: torch.Tensor, chunk: Optional[int] = None, H_out: Optional[torch.Tensor] = None) -> None:
+        """begin / accumulate (optionally in column chunks) / finalize."""
+        fobq_hessian_begin(self.handle, X.shape[0])
+        n = X.shape[1]
+        step = n if not chunk else chunk
+        for lo in range(0, n, step):
+            fobq_hessian_accumulate(self.handle, X[:, lo:lo + step])
+        fobq_hessian_finalize(self.handle, H_out)
+
+    def quantize_layer(self, W: torch.Tensor, H: Optional[torch.Tensor] = None, **kw) -> LayerOutput:
+        return fobq_quantize_layer(self.handle, W, H, **kw)
+
+    def stage_ms(self):
+        return {name: fobq_profile_get(self.handle, i) for i, name in enumerate(STAGES)}

@@ -1,0 +1,472 @@
+// C ABI of libfobq: argument checks, workspace, and the order in which the
+// kernels of the path are enqueued.  No arithmetic of the method lives here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "fobq_internal.h"
+
+namespace fobq {
+
+int set_err(fobq_ctx* c, int code, const char* fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return code;
+}
+
+int hip_err(fobq_ctx* c, hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return FOBQ_OK;
+    if (e == hipErrorOutOfMemory) return set_err(c, FOBQ_ENOMEM, "%s: out of device memory", what);
+    return set_err(c, FOBQ_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static hipEvent_t take_event(fobq_ctx* c)
+{
+    if (!c->timer.pool.empty()) {
+        hipEvent_t e = c->timer.pool.back();
+        c->timer.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+StageScope::StageScope(fobq_ctx* c_, int stage_) : c(c_), stage(stage_)
+{
+    if (!c->profiling) return;
+    e0 = take_event(c);
+    e1 = take_event(c);
+    if (e0) (void)hipEventRecord(e0, c->stream);
+}
+
+StageScope::~StageScope()
+{
+    if (!c->profiling || !e0 || !e1) return;
+    (void)hipEventRecord(e1, c->stream);
+    c->timer.pending[stage].push_back({e0, e1});
+}
+
+static void fold_events(fobq_ctx* c)
+{
+    for (int st = 0; st < FOBQ_STAGE_COUNT; ++st) {
+        for (auto& pr : c->timer.pending[st]) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+                c->timer.ms[st] += ms;
+                c->timer.launches[st] += 1;
+            }
+            c->timer.pool.push_back(pr.first);
+            c->timer.pool.push_back(pr.second);
+        }
+        c->timer.pending[st].clear();
+    }
+}
+
+#define FOBQ_TRY(expr, what)                                   \
+    do {                                                       \
+        hipError_t e__ = (expr);                               \
+        if (e__ != hipSuccess) return hip_err(ctx, e__, what); \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        if (prev != dev) ok = (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+constexpr int64_t MAX_DCOL = 32768;
+constexpr int64_t MAX_DROW = 65535;
+
+enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
+
+static int ensure_factor_ws(fobq_ctx* ctx, int64_t d)
+{
+    const size_t dd = (size_t)d * d * sizeof(double);
+    FOBQ_TRY(ctx->Hd.ensure(dd), "workspace Hd");
+    FOBQ_TRY(ctx->Linv.ensure(dd), "workspace Linv");
+    FOBQ_TRY(ctx->T.ensure(dd), "workspace T");
+    FOBQ_TRY(ctx->Hinv.ensure(dd), "workspace Hinv");
+    FOBQ_TRY(ctx->U.ensure(dd), "workspace U");
+    FOBQ_TRY(ctx->Dblk.ensure((3 * 64 * 64 + 64) * sizeof(double)), "workspace Dblk");
+    FOBQ_TRY(ctx->scal.ensure(16 * sizeof(double)), "workspace scal");
+    FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
+    FOBQ_TRY(ctx->hdiag.ensure((size_t)d * sizeof(double)), "workspace hdiag");
+    return FOBQ_OK;
+}
+
+// damped H -> Hinv (upper tiles valid).  Enqueue only.
+static int enqueue_inverse(fobq_ctx* ctx, const double* H, int d, double damp, double damp_abs)
+{
+    hipStream_t s = ctx->stream;
+    int* flags = ctx->flags.as<int>();
+    double* Hd = ctx->Hd.as<double>();
+    double* L = ctx->U.as<double>();       // U is free until the elimination
+    double* Linv = ctx->Linv.as<double>();
+    {
+        StageScope sc(ctx, FOBQ_STAGE_CHOLESKY);
+        FOBQ_TRY(launch_damp(s, H, d, damp, damp_abs, Hd, ctx->scal.as<double>()), "damp");
+        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H), "cholesky");
+    }
+    {
+        StageScope sc(ctx, FOBQ_STAGE_INVERSE);
+        FOBQ_TRY(trtri_lower(ctx, L, d, Linv, ctx->T.as<double>()), "trtri");
+        FOBQ_TRY(lauum_upper(ctx, Linv, d, ctx->Hinv.as<double>()), "lauum");
+    }
+    return FOBQ_OK;
+}
+
+static int check_opts(fobq_ctx* ctx, const fobq_opts* o, int64_t d_col)
+{
+    if (!o) return set_err(ctx, FOBQ_EINVAL, "opts is NULL");
+    if (o->bits < 2 || o->bits > 8) return set_err(ctx, FOBQ_EINVAL, "bits must be in 2..8 (got %d)", o->bits);
+    if (o->group < 0 || (o->group > 0 && d_col % o->group != 0))
+        return set_err(ctx, FOBQ_EINVAL, "group (%d) must be 0 or divide d_col (%lld)", o->group, (long long)d_col);
+    if (!(o->damp >= 0.0) || !(o->damp_abs >= 0.0)) return set_err(ctx, FOBQ_EINVAL, "damp and damp_abs must be >= 0");
+    if (o->order < FOBQ_ORDER_NATURAL || o->order > FOBQ_ORDER_CUSTOM)
+        return set_err(ctx, FOBQ_EINVAL, "unknown order %d", o->order);
+    if (o->order == FOBQ_ORDER_CUSTOM && !o->perm_in) return set_err(ctx, FOBQ_EINVAL, "order CUSTOM needs perm_in");
+    if (o->block < 0 || o->block > 64) return set_err(ctx, FOBQ_EINVAL, "block must be in 0..64 (got %d)", o->block);
+    if (o->stop_after < -1 || o->stop_after > d_col)
+        return set_err(ctx, FOBQ_EINVAL, "stop_after must be in -1..d_col (got %d)", o->stop_after);
+    if (o->reserved != 0) return set_err(ctx, FOBQ_EINVAL, "reserved must be 0");
+    return FOBQ_OK;
+}
+
+static int check_shape(fobq_ctx* ctx, int64_t d_row, int64_t d_col)
+{
+    if (d_row < 1 || d_row > MAX_DROW) return set_err(ctx, FOBQ_EINVAL, "d_row must be in 1..%lld", (long long)MAX_DROW);
+    if (d_col < 1 || d_col > MAX_DCOL) return set_err(ctx, FOBQ_EINVAL, "d_col must be in 1..%lld", (long long)MAX_DCOL);
+    return FOBQ_OK;
+}
+
+// grid, scores, order.  Needs ctx->hdiag filled.  Enqueue only.
+static int enqueue_order(fobq_ctx* ctx, const float* W, int R, int d, const fobq_opts* o,
+                         float* scales_out, float* zeros_out)
+{
+    hipStream_t s = ctx->stream;
+    const int G = o->group > 0 ? d / o->group : 1;
+    FOBQ_TRY(ctx->scale.ensure((size_t)R * G * sizeof(double)), "workspace scale");
+    FOBQ_TRY(ctx->zero.ensure((size_t)R * G * sizeof(double)), "workspace zero");
+    FOBQ_TRY(ctx->S.ensure((size_t)d * sizeof(double)), "workspace S");
+    const int chunks = sens_chunks(R);
+    FOBQ_TRY(ctx->Spart.ensure((size_t)chunks * d * sizeof(double)), "workspace Spart");
+    FOBQ_TRY(ctx->perm.ensure((size_t)d * sizeof(int)), "workspace perm");
+    FOBQ_TRY(ctx->invperm.ensure((size_t)d * sizeof(int)), "workspace invperm");
+    StageScope sc(ctx, FOBQ_STAGE_ORDER);
+    FOBQ_TRY(launch_grid(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
+                         scales_out, zeros_out), "grid");
+    FOBQ_TRY(launch_sensitivity(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
+                                ctx->hdiag.as<double>(), ctx->Spart.as<double>(), chunks, ctx->S.as<double>()),
+             "sensitivity");
+    if (o->order == FOBQ_ORDER_NATURAL)
+        FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
+    else if (o->order == FOBQ_ORDER_SENSI_DESC)
+        FOBQ_TRY(launch_rank_sort(s, ctx->S.as<double>(), d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
+    else
+        FOBQ_TRY(launch_check_perm(s, o->perm_in, d, ctx->perm.as<int>(), ctx->invperm.as<int>(),
+                                   ctx->flags.as<int>() + FLAG_BADPERM), "order");
+    return FOBQ_OK;
+}
+
+static int read_flags(fobq_ctx* ctx)
+{
+    int h[FLAG_COUNT] = {0, 0, 0, 0};
+    FOBQ_TRY(hipMemcpyAsync(h, ctx->flags.p, sizeof h, hipMemcpyDeviceToHost, ctx->stream), "read status flags");
+    FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
+    if (h[FLAG_BADPERM]) return set_err(ctx, FOBQ_EINVAL, "perm_in is not a permutation of 0..d_col-1");
+    if (h[FLAG_NOTPD_H]) return set_err(ctx, FOBQ_ENOTPD, "damped Hessian is not positive definite (Cholesky pivot <= 0)");
+    if (h[FLAG_NOTPD_HINV]) return set_err(ctx, FOBQ_ENOTPD, "shared inverse Hessian lost positive definiteness (elimination pivot <= 0)");
+    return FOBQ_OK;
+}
+
+}  // namespace fobq
+
+using namespace fobq;
+
+extern "C" {
+
+int fobq_create(fobq_ctx** out, int device, void* hip_stream)
+{
+    if (!out) return FOBQ_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return FOBQ_EINVAL;
+    fobq_ctx* c = new (std::nothrow) fobq_ctx();
+    if (!c) return FOBQ_ENOMEM;
+    c->device = device;
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return FOBQ_OK;
+}
+
+int fobq_destroy(fobq_ctx* ctx)
+{
+    if (!ctx) return FOBQ_OK;
+    DeviceGuard g(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    fold_events(ctx);
+    for (hipEvent_t e : ctx->timer.pool) (void)hipEventDestroy(e);
+    DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
+                      &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
+                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow};
+    for (DevBuf* b : bufs) b->release();
+    delete ctx;
+    return FOBQ_OK;
+}
+
+const char* fobq_last_error(const fobq_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (d_col < 1 || d_col > MAX_DCOL) return set_err(ctx, FOBQ_EINVAL, "d_col must be in 1..%lld", (long long)MAX_DCOL);
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int splits = xxt_pick_splits((int)d_col);
+    const size_t dd = (size_t)d_col * d_col * sizeof(double);
+    FOBQ_TRY(ctx->Hpart.ensure(dd * splits), "workspace Hpart");
+    FOBQ_TRY(ctx->H.ensure(dd), "workspace H");
+    FOBQ_TRY(hipMemsetAsync(ctx->Hpart.p, 0, dd * splits, ctx->stream), "clear Hessian accumulator");
+    ctx->h_d = d_col;
+    ctx->h_n = 0;
+    ctx->h_splits = splits;
+    ctx->h_final = false;
+    ctx->err.clear();
+    return FOBQ_OK;
+}
+
+int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->h_d == 0 || ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "hessian_accumulate needs hessian_begin first");
+    if (!X) return set_err(ctx, FOBQ_EINVAL, "X is NULL");
+    if (n < 0 || ld < n) return set_err(ctx, FOBQ_EINVAL, "need 0 <= n <= ld (n=%lld ld=%lld)", (long long)n, (long long)ld);
+    if (n == 0) return FOBQ_OK;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    {
+        StageScope sc(ctx, FOBQ_STAGE_XXT);
+        FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits), "xxt");
+    }
+    ctx->h_n += n;
+    return FOBQ_OK;
+}
+
+int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->h_d == 0) return set_err(ctx, FOBQ_ESTATE, "hessian_finalize needs hessian_begin first");
+    if (ctx->h_n == 0) return set_err(ctx, FOBQ_ESTATE, "no calibration columns were accumulated");
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int d = (int)ctx->h_d;
+    {
+        StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
+        FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_splits, d,
+                                         2.0 / (double)ctx->h_n, ctx->H.as<double>()), "hessian finalize");
+        if (H_out)
+            FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice,
+                                    ctx->stream), "copy H");
+    }
+    ctx->h_final = true;
+    return FOBQ_OK;
+}
+
+int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d64, double* Hinv)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (!H || !Hinv) return set_err(ctx, FOBQ_EINVAL, "H or Hinv is NULL");
+    if (d64 < 1 || d64 > MAX_DCOL) return set_err(ctx, FOBQ_EINVAL, "d must be in 1..%lld", (long long)MAX_DCOL);
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int d = (int)d64;
+    int rc = ensure_factor_ws(ctx, d);
+    if (rc) return rc;
+    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
+    rc = enqueue_inverse(ctx, H, d, 0.0, 0.0);
+    if (rc) return rc;
+    // full symmetric copy out of the upper tiles
+    FOBQ_TRY(launch_hinv_work(ctx->stream, ctx->Hinv.as<double>(), d, 0, Hinv), "copy Hinv");
+    return read_flags(ctx);
+}
+
+int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
+                     const fobq_opts* opts, double* S, int32_t* perm)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (!W || !Hinv) return set_err(ctx, FOBQ_EINVAL, "W or Hinv is NULL");
+    int rc = check_shape(ctx, d_row, d_col);
+    if (rc) return rc;
+    rc = check_opts(ctx, opts, d_col);
+    if (rc) return rc;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int R = (int)d_row, d = (int)d_col;
+    FOBQ_TRY(ctx->hdiag.ensure((size_t)d * sizeof(double)), "workspace hdiag");
+    FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
+    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
+    FOBQ_TRY(launch_take_diag(ctx->stream, Hinv, d, ctx->hdiag.as<double>()), "diag");
+    rc = enqueue_order(ctx, W, R, d, opts, nullptr, nullptr);
+    if (rc) return rc;
+    if (S) FOBQ_TRY(hipMemcpyAsync(S, ctx->S.p, (size_t)d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy S");
+    if (perm) FOBQ_TRY(hipMemcpyAsync(perm, ctx->perm.p, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, ctx->stream), "copy perm");
+    return read_flags(ctx);
+}
+
+int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
+                        const fobq_opts* opts, const fobq_out* out)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (!W) return set_err(ctx, FOBQ_EINVAL, "W is NULL");
+    if (!out) return set_err(ctx, FOBQ_EINVAL, "out is NULL");
+    int rc = check_shape(ctx, d_row, d_col);
+    if (rc) return rc;
+    rc = check_opts(ctx, opts, d_col);
+    if (rc) return rc;
+    if (!H) {
+        if (!ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "H is NULL and no finalized Hessian is held by the context");
+        if (ctx->h_d != d_col)
+            return set_err(ctx, FOBQ_EINVAL, "accumulated Hessian has d_col=%lld, layer has %lld", (long long)ctx->h_d, (long long)d_col);
+        H = ctx->H.as<double>();
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    ctx->err.clear();
+
+    hipStream_t s = ctx->stream;
+    const int R = (int)d_row, d = (int)d_col;
+    const int G = opts->group > 0 ? d / opts->group : 1;
+    const int steps = opts->stop_after < 0 ? d : opts->stop_after;
+    const int block = opts->block == 0 ? 64 : opts->block;
+    const int Rp = (R + 63) / 64 * 64;
+    const size_t dd = (size_t)d * d * sizeof(double);
+
+    rc = ensure_factor_ws(ctx, d);
+    if (rc) return rc;
+    FOBQ_TRY(ctx->A.ensure(dd), "workspace A");
+    FOBQ_TRY(ctx->Un.ensure(dd), "workspace Un");
+    FOBQ_TRY(ctx->Wp.ensure((size_t)R * d * sizeof(double)), "workspace Wp");
+    FOBQ_TRY(ctx->DT.ensure((size_t)d * Rp * sizeof(double)), "workspace DT");
+    FOBQ_TRY(ctx->codesT.ensure((size_t)d * Rp), "workspace codesT");
+    FOBQ_TRY(ctx->lossrow.ensure((size_t)R * sizeof(double)), "workspace lossrow");
+    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), s), "clear flags");
+    FOBQ_TRY(hipMemsetAsync(ctx->lossrow.p, 0, (size_t)R * sizeof(double), s), "clear loss");
+
+    // damp, Cholesky, inverse
+    rc = enqueue_inverse(ctx, H, d, opts->damp, opts->damp_abs);
+    if (rc) return rc;
+    FOBQ_TRY(launch_take_diag(s, ctx->Hinv.as<double>(), d, ctx->hdiag.as<double>()), "diag");
+    // grid, column scores, order
+    rc = enqueue_order(ctx, W, R, d, opts, out->scales, out->zeros);
+    if (rc) return rc;
+    {
+        StageScope sc(ctx, FOBQ_STAGE_PERMUTE);
+        FOBQ_TRY(launch_gather(s, W, R, d, ctx->perm.as<int>(), ctx->Hinv.as<double>(), ctx->Wp.as<double>(),
+                               ctx->A.as<double>()), "permute");
+    }
+    double* A = ctx->A.as<double>();
+    double* Wp = ctx->Wp.as<double>();
+    const double* scale = ctx->scale.as<double>();
+    const double* zero = ctx->zero.as<double>();
+    const int* perm = ctx->perm.as<int>();
+    uint8_t* codesT = ctx->codesT.as<uint8_t>();
+    double* lossrow = ctx->lossrow.as<double>();
+
+    if (block == 1) {
+        // Eq. 9 / 11 and Eq. 12 one column at a time
+        StageScope sc(ctx, FOBQ_STAGE_COLUMNS);
+        for (int t = 0; t < steps; ++t)
+            FOBQ_TRY(launch_step(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits, codesT, Rp, lossrow),
+                     "column step");
+    } else {
+        double* U = ctx->U.as<double>();
+        double* Un = ctx->Un.as<double>();
+        double* DT = ctx->DT.as<double>();
+        {
+            StageScope sc(ctx, FOBQ_STAGE_ELIMINATE);
+            FOBQ_TRY(eliminate_blocked(ctx, A, d, steps, block, U, Un, ctx->flags.as<int>() + FLAG_NOTPD_HINV),
+                     "eliminate");
+        }
+        StageScope sc(ctx, FOBQ_STAGE_COLUMNS);
+        const int writeback = out->W_work ? 1 : 0;
+        for (int o = 0; o < steps; o += block) {
+            const int nb = (block < steps - o) ? block : steps - o;
+            FOBQ_TRY(launch_chain(s, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits, codesT, DT,
+                                  Rp, lossrow, writeback), "column block");
+            const int r = d - o - nb;
+            if (r <= 0) break;
+            // deferred compensation of the columns right of the block:
+            // W[:, o+nb:] -= D[:, block] * Un[block, o+nb:]
+            GemmP p;
+            p.M = R; p.N = r; p.K = nb;
+            p.A = DT + (int64_t)o * Rp; p.lda = Rp;
+            p.B = Un + (int64_t)o * d + (o + nb); p.ldb = d;
+            p.C = Wp + (o + nb); p.ldc = d;
+            p.alpha = -1.0; p.beta = 1.0;
+            FOBQ_TRY(gemm64(s, p, true, false), "column block update");
+        }
+    }
+    {
+        StageScope sc(ctx, FOBQ_STAGE_EMIT);
+        if (out->codes || out->Q)
+            FOBQ_TRY(launch_emit(s, codesT, Rp, R, d, steps, ctx->invperm.as<int>(), scale, zero, G, opts->group,
+                                 out->codes, out->Q), "emit");
+        if (out->loss) FOBQ_TRY(launch_loss(s, lossrow, R, out->loss), "loss");
+        if (out->perm)
+            FOBQ_TRY(hipMemcpyAsync(out->perm, perm, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, s), "copy perm");
+        if (out->W_work)
+            FOBQ_TRY(hipMemcpyAsync(out->W_work, Wp, (size_t)R * d * sizeof(double), hipMemcpyDeviceToDevice, s), "copy W_work");
+        if (out->Hinv_work) FOBQ_TRY(launch_hinv_work(s, A, d, steps, out->Hinv_work), "copy Hinv_work");
+    }
+    return read_flags(ctx);
+}
+
+int fobq_profile_enable(fobq_ctx* ctx, int on)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    ctx->profiling = on != 0;
+    return FOBQ_OK;
+}
+
+int fobq_profile_get(fobq_ctx* ctx, int stage, double* ms, int64_t* intervals)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (stage < 0 || stage >= FOBQ_STAGE_COUNT) return set_err(ctx, FOBQ_EINVAL, "unknown stage %d", stage);
+    DeviceGuard g(ctx->device);
+    FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
+    fold_events(ctx);
+    if (ms) *ms = ctx->timer.ms[stage];
+    if (intervals) *intervals = ctx->timer.launches[stage];
+    return FOBQ_OK;
+}
+
+int fobq_profile_reset(fobq_ctx* ctx)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    DeviceGuard g(ctx->device);
+    FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
+    fold_events(ctx);
+    for (int st = 0; st < FOBQ_STAGE_COUNT; ++st) {
+        ctx->timer.ms[st] = 0.0;
+        ctx->timer.launches[st] = 0;
+    }
+    return FOBQ_OK;
+}
+
+}  // extern "C"

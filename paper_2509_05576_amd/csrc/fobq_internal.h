@@ -1,0 +1,152 @@
+// Internal declarations shared by the translation units of libfobq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "fobq.h"
+
+namespace fobq {
+
+// ---------------------------------------------------------------------------
+// Device buffer owned by the context; grows, never shrinks.
+struct DevBuf {
+    void*  p = nullptr;
+    size_t cap = 0;
+    hipError_t ensure(size_t bytes) {
+        if (bytes <= cap) return hipSuccess;
+        if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
+        size_t want = (bytes + 255) & ~size_t(255);
+        hipError_t e = hipMalloc(&p, want);
+        if (e == hipSuccess) cap = want; else p = nullptr;
+        return e;
+    }
+    void release() { if (p) (void)hipFree(p); p = nullptr; cap = 0; }
+    template <class T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+// ---------------------------------------------------------------------------
+// Generic fp64 MFMA GEMM:  C = beta*C + alpha * op(A) * op(B), row-major.
+//   op(A) is M x K:  TA=false -> A[m*lda + k],  TA=true -> A[k*lda + m]
+//   op(B) is K x N:  TB=false -> B[k*ldb + n],  TB=true -> B[n*ldb + k]
+// Tiles of 64 x 64 per workgroup; tiles can be restricted to one triangle and
+// the K range of a tile can be restricted when an operand is triangular.
+enum { CMODE_ALL = 0, CMODE_LOWER = 1, CMODE_UPPER = 2 };
+enum { KMODE_FULL = 0,      // k in [0, K)
+       KMODE_GE_MAX_MN = 1, // k >= max(m0, n0)   (both operands zero above)
+       KMODE_GE_N = 2,      // k >= n0            (op(B) lower triangular)
+       KMODE_LT_M = 3 };    // k <  m0 + 64       (op(A) lower triangular)
+
+struct GemmP {
+    int M = 0, N = 0, K = 0;
+    const double* A = nullptr; int64_t lda = 0;
+    const double* B = nullptr; int64_t ldb = 0;
+    double* C = nullptr;       int64_t ldc = 0;
+    double* C2 = nullptr;              // optional second output: rowscale[m] * result
+    const double* rowscale = nullptr;
+    double alpha = 1.0, beta = 0.0;
+    int cmode = CMODE_ALL, kmode = KMODE_FULL;
+    // batching (blockIdx.z): element strides and per-batch clamps
+    int batches = 1;
+    int64_t sA = 0, sB = 0, sC = 0;
+    int Mtot = -1, mstep = 0;          // M_eff = min(M, Mtot - b*mstep) when Mtot >= 0
+    int Ktot = -1, kstep = 0;          // K_eff likewise
+};
+hipError_t gemm64(hipStream_t s, const GemmP& p, bool TA, bool TB);
+
+// ---------------------------------------------------------------------------
+// Stage timing (hipEvents on the context's stream), off by default.
+struct StageTimer {
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pending[FOBQ_STAGE_COUNT];
+    std::vector<hipEvent_t> pool;
+    double  ms[FOBQ_STAGE_COUNT] = {0};
+    int64_t launches[FOBQ_STAGE_COUNT] = {0};
+};
+
+}  // namespace fobq
+
+struct fobq_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+
+    // Hessian accumulation state
+    int64_t h_d = 0;        // d_col of the running accumulation (0 = none)
+    int64_t h_n = 0;        // calibration columns seen so far
+    int     h_splits = 0;   // split-K partial slabs in Hpart
+    bool    h_final = false;
+    fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
+    fobq::DevBuf H;         // d x d fp64, (2/N) X X^T, full symmetric
+
+    // factorization / elimination workspace (all d x d fp64 unless noted)
+    fobq::DevBuf Hd, Linv, T, Hinv, A, U, Un;
+    fobq::DevBuf Dblk;      // 3 x 64 x 64 fp64 + 64 fp64: diagonal-block scratch
+    fobq::DevBuf scal;      // a few fp64 scalars (lambda, loss)
+    fobq::DevBuf flags;     // int32 status flags written by kernels
+    // quantization workspace
+    fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
+    fobq::DevBuf DT;        // d x Rp fp64: (w - q) per processed column
+    fobq::DevBuf codesT;    // d x Rp u8
+    fobq::DevBuf scale, zero;   // d_row x G fp64
+    fobq::DevBuf S, Spart;  // d fp64, chunks x d fp64
+    fobq::DevBuf hdiag;     // d fp64
+    fobq::DevBuf perm, invperm; // d int32
+    fobq::DevBuf lossrow;   // d_row fp64
+
+    bool profiling = false;
+    fobq::StageTimer timer;
+};
+
+namespace fobq {
+
+int set_err(fobq_ctx* c, int code, const char* fmt, ...);
+int hip_err(fobq_ctx* c, hipError_t e, const char* what);
+
+struct StageScope {
+    fobq_ctx* c; int stage; hipEvent_t e0 = nullptr, e1 = nullptr;
+    StageScope(fobq_ctx* c_, int stage_);
+    ~StageScope();
+};
+
+// hessian.hip
+hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits);
+int xxt_pick_splits(int d);
+hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H);
+hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
+
+// factor.hip
+hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag);  // Hd = L L^T; Linv gets the diagonal-block inverses
+hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
+hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
+hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag);
+
+// quant.hip
+hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                       double* scale, double* zero, float* scales_out, float* zeros_out);
+hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag);
+hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                              const double* scale, const double* zero, const double* hdiag,
+                              double* Spart, int chunks, double* S);
+int sens_chunks(int R);
+hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm);
+hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm);
+hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm, int* invperm, int* flag);
+hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
+                         const double* Hinv_upper, double* Wp, double* A);
+hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
+                        const double* Un, const double* U, const double* scale, const double* zero,
+                        int G, int group, const int* perm, int bits,
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow, int writeback);
+hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
+                       const double* scale, const double* zero, int G, int group, const int* perm, int bits,
+                       uint8_t* codesT, int Rp, double* lossrow);
+hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int d, int steps,
+                       const int* invperm, const double* scale, const double* zero, int G, int group,
+                       uint8_t* codes, float* Q);
+hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss);
+hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
+hipError_t launch_fill_f64(hipStream_t s, double* p, int64_t n, double v);
+hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);
+
+}  // namespace fobq

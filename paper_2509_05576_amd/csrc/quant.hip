@@ -1,0 +1,499 @@
+// Grid, sensitivity, ordering, permutation and the column loop (Section 4.2).
+#include "fobq_internal.h"
+
+namespace fobq {
+
+// code = clamp(rint(w / scale) + zero, 0, maxq), rint = round half to even, all fp64
+__device__ __forceinline__ double grid_code(double w, double scale, double zero, double maxq)
+{
+    double c = rint(w / scale) + zero;
+    c = c < 0.0 ? 0.0 : c;
+    c = c > maxq ? maxq : c;
+    return c;
+}
+
+// ---------------------------------------------------------------------------
+// Min-max grid per (row, group) from the original W (Section 3, "fixed grid of
+// width Delta"): lo = min(min w, 0), hi = max(max w, 0), scale = (hi - lo) / maxq,
+// zero = rint(-lo / scale); an all-zero group gets scale 1, zero 0.
+// One wavefront per (row, group); min / max by wavefront shuffles.
+__global__ __launch_bounds__(256) void grid_kernel(const float* __restrict__ W, int R, int d, int gs, int G,
+                                                   double maxq, double* __restrict__ scale, double* __restrict__ zero,
+                                                   float* __restrict__ scales_out, float* __restrict__ zeros_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= (int64_t)R * G) return;
+    const int i = (int)(pair / G), g = (int)(pair % G);
+    const float* __restrict__ src = W + (int64_t)i * d + (int64_t)g * gs;
+    float lo = 0.f, hi = 0.f;
+    for (int j = lane; j < gs; j += 64) {
+        const float w = src[j];
+        lo = fminf(lo, w);
+        hi = fmaxf(hi, w);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+    }
+    if (lane == 0) {
+        double s = 1.0, z = 0.0;
+        if (hi != lo) {
+            s = ((double)hi - (double)lo) / maxq;
+            z = rint(-(double)lo / s);
+        }
+        scale[pair] = s;
+        zero[pair] = z;
+        if (scales_out) scales_out[pair] = (float)s;
+        if (zeros_out) zeros_out[pair] = (float)z;
+    }
+}
+
+hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                       double* scale, double* zero, float* scales_out, float* zeros_out)
+{
+    const int gs = group > 0 ? group : d;
+    const int G = group > 0 ? d / group : 1;
+    const int64_t pairs = (int64_t)R * G;
+    const double maxq = (double)((1 << bits) - 1);
+    hipLaunchKernelGGL(grid_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, W, R, d, gs, G, maxq,
+                       scale, zero, scales_out, zeros_out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void take_diag_kernel(const double* __restrict__ M, int d, double* __restrict__ diag)
+{
+    const int a = blockIdx.x * 256 + threadIdx.x;
+    if (a < d) diag[a] = M[(int64_t)a * d + a];
+}
+
+hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag)
+{
+    hipLaunchKernelGGL(take_diag_kernel, dim3((d + 255) / 256), dim3(256), 0, s, M, d, diag);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Column scores (Eq. 10 summed over rows, Section 4.2 steps 1-2):
+//   S_j = sum_i (quant(w_ij) - w_ij)^2 / (2 [Hinv]_jj)
+// Pass 1: thread = column, block row-chunk c sums rows [c*RC, (c+1)*RC).
+// Pass 2: chunks are added in index order, then divided by 2 [Hinv]_jj.
+constexpr int SENS_RC = 64;
+
+__global__ __launch_bounds__(256) void sens_partial_kernel(const float* __restrict__ W, int R, int d, int gs, int G,
+                                                           double maxq, const double* __restrict__ scale,
+                                                           const double* __restrict__ zero, double* __restrict__ Spart)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= d) return;
+    const int g = j / gs;
+    const int r0 = blockIdx.y * SENS_RC, r1 = min(R, r0 + SENS_RC);
+    double acc = 0.0;
+    for (int i = r0; i < r1; ++i) {
+        const double w = (double)W[(int64_t)i * d + j];
+        const double s = scale[(int64_t)i * G + g], z = zero[(int64_t)i * G + g];
+        const double q = s * (grid_code(w, s, z, maxq) - z);
+        acc += (q - w) * (q - w);
+    }
+    Spart[(int64_t)blockIdx.y * d + j] = acc;
+}
+
+__global__ __launch_bounds__(256) void sens_reduce_kernel(const double* __restrict__ Spart, int chunks, int d,
+                                                          const double* __restrict__ hdiag, double* __restrict__ S)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= d) return;
+    double acc = 0.0;
+    for (int c = 0; c < chunks; ++c) acc += Spart[(int64_t)c * d + j];
+    S[j] = acc / (2.0 * hdiag[j]);
+}
+
+int sens_chunks(int R) { return (R + SENS_RC - 1) / SENS_RC; }
+
+hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                              const double* scale, const double* zero, const double* hdiag,
+                              double* Spart, int chunks, double* S)
+{
+    const int gs = group > 0 ? group : d;
+    const int G = group > 0 ? d / group : 1;
+    const double maxq = (double)((1 << bits) - 1);
+    hipLaunchKernelGGL(sens_partial_kernel, dim3((d + 255) / 256, chunks), dim3(256), 0, s, W, R, d, gs, G, maxq,
+                       scale, zero, Spart);
+    hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, hdiag, S);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Order (Section 4.2 step 3): descending S, equal scores keep index order.
+// rank_j = #{k : S_k > S_j or (S_k == S_j and k < j)}; perm[rank_j] = j.
+// A score that is not finite compares as -infinity so that perm stays a permutation.
+__global__ __launch_bounds__(256) void rank_sort_kernel(const double* __restrict__ S, int d, int* __restrict__ perm,
+                                                        int* __restrict__ invperm)
+{
+    __shared__ double tile[256];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    double sj = (j < d) ? S[j] : 0.0;
+    if (!(sj == sj) || sj > 1.0e300 || sj < -1.0e300) sj = -1.0e308;
+    int rank = 0;
+    for (int base = 0; base < d; base += 256) {
+        const int k = base + threadIdx.x;
+        double sk = (k < d) ? S[k] : 0.0;
+        if (!(sk == sk) || sk > 1.0e300 || sk < -1.0e300) sk = -1.0e308;
+        __syncthreads();
+        tile[threadIdx.x] = sk;
+        __syncthreads();
+        const int lim = min(256, d - base);
+        for (int u = 0; u < lim; ++u) {
+            const double v = tile[u];
+            rank += (v > sj || (v == sj && base + u < j)) ? 1 : 0;
+        }
+    }
+    if (j < d) {
+        perm[rank] = j;
+        invperm[j] = rank;
+    }
+}
+
+hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm)
+{
+    hipLaunchKernelGGL(rank_sort_kernel, dim3((d + 255) / 256), dim3(256), 0, s, S, d, perm, invperm);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void iota_kernel(int d, int* __restrict__ perm, int* __restrict__ invperm)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < d) { perm[j] = j; invperm[j] = j; }
+}
+
+hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm)
+{
+    hipLaunchKernelGGL(iota_kernel, dim3((d + 255) / 256), dim3(256), 0, s, d, perm, invperm);
+    return hipGetLastError();
+}
+
+// Custom order: copy, and verify that it is a permutation of 0..d-1.  Entries out
+// of range are replaced by a valid index so that later gathers stay in bounds;
+// the flag makes the call fail.
+__global__ __launch_bounds__(256) void perm_copy_kernel(const int* __restrict__ perm_in, int d, int* __restrict__ perm,
+                                                        int* __restrict__ invperm, int* __restrict__ flag)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= d) return;
+    int j = perm_in[t];
+    if (j < 0 || j >= d) { *flag = 1; j = t; }
+    perm[t] = j;
+    invperm[j] = t;     // duplicates: last writer wins, detected by the check pass
+}
+
+__global__ __launch_bounds__(256) void perm_check_kernel(const int* __restrict__ perm, const int* __restrict__ invperm,
+                                                         int d, int* __restrict__ flag)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= d) return;
+    const int j = perm[t];
+    if (j < 0 || j >= d || invperm[j] != t) *flag = 1;
+}
+
+hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm, int* invperm, int* flag)
+{
+    // invperm starts at -1 so that an index that never appears is detected
+    (void)launch_fill_i32(s, invperm, d, -1);
+    hipLaunchKernelGGL(perm_copy_kernel, dim3((d + 255) / 256), dim3(256), 0, s, perm_in, d, perm, invperm, flag);
+    hipLaunchKernelGGL(perm_check_kernel, dim3((d + 255) / 256), dim3(256), 0, s, perm, invperm, d, flag);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Put W and Hinv into processing order (Section 4.2 step 3):
+//   Wp[i][t] = W[i][perm[t]] (widened),  A[a][b] = Hinv[perm[a]][perm[b]]
+// Hinv is read from its upper triangle.
+__global__ __launch_bounds__(256) void gather_w_kernel(const float* __restrict__ W, int R, int d,
+                                                       const int* __restrict__ perm, double* __restrict__ Wp)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.y;
+    if (t >= d) return;
+    int j = perm[t];
+    j = min(max(j, 0), d - 1);
+    Wp[(int64_t)i * d + t] = (double)W[(int64_t)i * d + j];
+}
+
+__global__ __launch_bounds__(256) void gather_h_kernel(const double* __restrict__ Hu, int d, const int* __restrict__ perm,
+                                                       double* __restrict__ A)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const int a = blockIdx.y;
+    if (b >= d) return;
+    int pa = perm[a], pb = perm[b];
+    pa = min(max(pa, 0), d - 1);
+    pb = min(max(pb, 0), d - 1);
+    const int lo = min(pa, pb), hi = max(pa, pb);
+    A[(int64_t)a * d + b] = Hu[(int64_t)lo * d + hi];
+}
+
+hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
+                         const double* Hinv_upper, double* Wp, double* A)
+{
+    hipLaunchKernelGGL(gather_w_kernel, dim3((d + 255) / 256, R), dim3(256), 0, s, W, R, d, perm, Wp);
+    hipLaunchKernelGGL(gather_h_kernel, dim3((d + 255) / 256, d), dim3(256), 0, s, Hinv_upper, d, perm, A);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Blocked column loop, the sequential part (Section 4.2 steps 4-5 inside one
+// block of nb <= 64 columns o .. o+nb-1).  One lane owns one row of W and keeps
+// the row's block entries in registers; rows never interact.  For each column j
+// of the block, in order:
+//   q    = quant(w_j)                         (all rows at once, one row per lane)
+//   diff = w_j - q ;  loss += diff^2 / (2 U[t,t])          (Eq. 10)
+//   w_k -= diff * Un[t, k]   for the later columns k of the block   (Eq. 9 / 11;
+//          e * Hinv[t,k] = (diff / U[t,t]) * U[t,k] = diff * Un[t,k])
+// diff is stored (DT) for the deferred rank-nb update of the columns right of the
+// block.  The register window slides: after step j, w[k] holds column j+1+k, so
+// the loop body has fixed register indices and stays rolled.  The pivot rows are
+// staged in LDS already shifted (uns[j][k] = Un[o+j][o+j+1+k], 0 past the block)
+// and are read as broadcasts.
+constexpr int CB = 64;
+
+__global__ __launch_bounds__(64) void chain_kernel(double* __restrict__ Wp, int R, int d, int o, int nb,
+                                                   const double* __restrict__ Un, const double* __restrict__ U,
+                                                   const double* __restrict__ scale, const double* __restrict__ zero,
+                                                   int G, int gs, const int* __restrict__ perm, double maxq,
+                                                   uint8_t* __restrict__ codesT, double* __restrict__ DT, int Rp,
+                                                   double* __restrict__ lossrow, int writeback)
+{
+    __shared__ double uns[CB][CB];
+    __shared__ double piv[CB];
+    __shared__ int grp[CB];
+    const int lane = threadIdx.x;
+    const int row = blockIdx.x * 64 + lane;
+    const bool active = row < R;
+    for (int j = 0; j < CB; ++j) {
+        // lane = shifted column index k; source column j+1+k
+        const int c = j + 1 + lane;
+        double v = 0.0;
+        if (j < nb && c < nb) v = Un[(int64_t)(o + j) * d + o + c];
+        uns[j][lane] = v;
+    }
+    if (lane < nb) {
+        piv[lane] = U[(int64_t)(o + lane) * d + o + lane];
+        int pj = perm[o + lane];
+        pj = min(max(pj, 0), d - 1);
+        grp[lane] = pj / gs;
+    } else {
+        piv[lane] = 1.0;
+        grp[lane] = 0;
+    }
+    double w[CB];
+    const int64_t rsafe = active ? row : 0;
+    double* __restrict__ wrow = Wp + rsafe * d + o;
+#pragma unroll
+    for (int k = 0; k < CB; ++k) w[k] = (k < nb) ? wrow[k] : 0.0;
+    __syncthreads();
+
+    double loss = 0.0;
+    const int64_t grow = rsafe * G;
+#pragma unroll 1
+    for (int j = 0; j < nb; ++j) {
+        const int g = grp[j];
+        const double s = scale[grow + g], z = zero[grow + g];
+        const double wj = w[0];
+        const double c = grid_code(wj, s, z, maxq);
+        const double q = s * (c - z);
+        const double diff = wj - q;
+        loss += diff * diff / (2.0 * piv[j]);
+        if (active) {
+            codesT[(int64_t)(o + j) * Rp + row] = (uint8_t)c;
+            DT[(int64_t)(o + j) * Rp + row] = diff;
+            if (writeback) wrow[j] = wj;
+        }
+#pragma unroll
+        for (int k = 0; k < CB - 1; ++k) w[k] = w[k + 1] - diff * uns[j][k];
+        w[CB - 1] = 0.0;
+    }
+    if (active) lossrow[row] += loss;
+}
+
+hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
+                        const double* Un, const double* U, const double* scale, const double* zero,
+                        int G, int group, const int* perm, int bits,
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow, int writeback)
+{
+    const int gs = group > 0 ? group : d;
+    const double maxq = (double)((1 << bits) - 1);
+    dim3 grid((R + 63) / 64), block(64);
+    hipLaunchKernelGGL(chain_kernel, grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm, maxq,
+                       codesT, DT, Rp, lossrow, writeback);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Unblocked column step t (Section 4.2 steps 4-5 with Eq. 9 / 11 and Eq. 12
+// literally, one launch per column): with p = A[t][t] (A = running shared Hinv in
+// processing order, upper triangle maintained),
+//   rows of W :  q = quant(W[i][t]); e = (W[i][t] - q) / p;  W[i][k] -= e * A[t][k]     k > t
+//   rows of A :  A[a][b] -= (A[t][a] / p) * A[t][b]                                    t < a <= b
+// blockIdx.y walks groups of 4 rows, first the R rows of W then the d-t-1 rows of
+// A; each wavefront takes one row; blockIdx.x walks strips of 256 columns right
+// of t.  Row t of A and column t of W are read-only during the step.
+constexpr int STEP_U = 4;
+
+__global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int R, int d, int t, double* __restrict__ A,
+                                                   const double* __restrict__ scale, const double* __restrict__ zero,
+                                                   int G, int gs, const int* __restrict__ perm, double maxq,
+                                                   uint8_t* __restrict__ codesT, int Rp, double* __restrict__ lossrow)
+{
+    const int lane = threadIdx.x & 63;
+    const int rid = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int c0 = t + 1 + blockIdx.x * (64 * STEP_U);
+    const double* __restrict__ rowt = A + (int64_t)t * d;
+    const double p = rowt[t];
+    if (rid < R) {
+        const int i = rid;
+        double* __restrict__ w = Wp + (int64_t)i * d;
+        int pj = perm[t];
+        pj = min(max(pj, 0), d - 1);
+        const int g = pj / gs;
+        const double s = scale[(int64_t)i * G + g], z = zero[(int64_t)i * G + g];
+        const double wt = w[t];
+        const double c = grid_code(wt, s, z, maxq);
+        const double q = s * (c - z);
+        const double diff = wt - q;
+        if (blockIdx.x == 0 && lane == 0) {
+            codesT[(int64_t)t * Rp + i] = (uint8_t)c;
+            lossrow[i] += diff * diff / (2.0 * p);
+        }
+        const double e = diff / p;
+#pragma unroll
+        for (int u = 0; u < STEP_U; ++u) {
+            const int k = c0 + u * 64 + lane;
+            if (k < d) w[k] -= e * rowt[k];
+        }
+    } else {
+        const int a = t + 1 + (rid - R);
+        if (a >= d) return;
+        if (c0 + 64 * STEP_U <= a) return;          // strip entirely left of the diagonal
+        double* __restrict__ ra = A + (int64_t)a * d;
+        const double f = rowt[a] / p;
+#pragma unroll
+        for (int u = 0; u < STEP_U; ++u) {
+            const int b = c0 + u * 64 + lane;
+            if (b >= a && b < d) ra[b] -= f * rowt[b];
+        }
+    }
+}
+
+hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
+                       const double* scale, const double* zero, int G, int group, const int* perm, int bits,
+                       uint8_t* codesT, int Rp, double* lossrow)
+{
+    const int gs = group > 0 ? group : d;
+    const double maxq = (double)((1 << bits) - 1);
+    const int r = d - t - 1;
+    const int strips = r > 0 ? (r + 64 * STEP_U - 1) / (64 * STEP_U) : 1;
+    const int rows = R + (r > 0 ? r : 0);
+    dim3 grid(strips, (rows + 3) / 4), block(256);
+    hipLaunchKernelGGL(step_kernel, grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq, codesT, Rp,
+                       lossrow);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Outputs in original column order: codes[i][c] and Q[i][c] = scale * (code - zero)
+// for the column c processed at step invperm[c] < steps; others get code 0, Q 0.
+__global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ codesT, int Rp, int R, int d, int steps,
+                                                   const int* __restrict__ invperm, const double* __restrict__ scale,
+                                                   const double* __restrict__ zero, int G, int gs,
+                                                   uint8_t* __restrict__ codes, float* __restrict__ Q)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.y;
+    if (c >= d) return;
+    int t = invperm[c];
+    uint8_t code = 0;
+    double q = 0.0;
+    if (t >= 0 && t < steps) {
+        code = codesT[(int64_t)t * Rp + i];
+        const int g = c / gs;
+        q = scale[(int64_t)i * G + g] * ((double)code - zero[(int64_t)i * G + g]);
+    }
+    if (codes) codes[(int64_t)i * d + c] = code;
+    if (Q) Q[(int64_t)i * d + c] = (float)q;
+}
+
+hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int d, int steps,
+                       const int* invperm, const double* scale, const double* zero, int G, int group,
+                       uint8_t* codes, float* Q)
+{
+    const int gs = group > 0 ? group : d;
+    hipLaunchKernelGGL(emit_kernel, dim3((d + 255) / 256, R), dim3(256), 0, s, codesT, Rp, R, d, steps, invperm,
+                       scale, zero, G, gs, codes, Q);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void loss_kernel(const double* __restrict__ lossrow, int R, double* __restrict__ loss)
+{
+    __shared__ double part[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < R; i += 256) s += lossrow[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = part[0];
+}
+
+hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss)
+{
+    hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, s, lossrow, R, loss);
+    return hipGetLastError();
+}
+
+// Running shared inverse after `steps` columns, processing order, full symmetric;
+// rows and columns of processed steps are 0.  A holds valid data on and above the
+// diagonal of the trailing square.
+__global__ __launch_bounds__(256) void hinv_work_kernel(const double* __restrict__ A, int d, int steps,
+                                                        double* __restrict__ out)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const int a = blockIdx.y;
+    if (b >= d) return;
+    double v = 0.0;
+    if (a >= steps && b >= steps) v = A[(int64_t)min(a, b) * d + max(a, b)];
+    out[(int64_t)a * d + b] = v;
+}
+
+hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out)
+{
+    hipLaunchKernelGGL(hinv_work_kernel, dim3((d + 255) / 256, d), dim3(256), 0, s, A, d, steps, out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_f64_kernel(double* __restrict__ p, int64_t n, double v)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ __launch_bounds__(256) void fill_i32_kernel(int* __restrict__ p, int64_t n, int v)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+hipError_t launch_fill_f64(hipStream_t s, double* p, int64_t n, double v)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_f64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+}  // namespace fobq

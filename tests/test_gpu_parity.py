@@ -1,0 +1,363 @@
+"""GPU parity: the HIP path (through the C ABI, via the ctypes binding) against
+the fp64 CPU oracle on the same seeded inputs.
+
+Bars (from the benchmark spec): integer codes -- at most 1e-3 of them may
+differ and none by more than one level (in practice both sides compute in fp64
+and the tests below see zero differences); scales / zeros within 1e-5
+relative; layer loss within 1e-3 relative.  Intermediate fp64 quantities (H,
+Hinv, S, W_work, Hinv_work) are compared at tolerances that follow from fp64
+rounding and the conditioning of the damped Hessian.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def fobq():
+    import paper_2509_05576_amd as f
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no CPU fallback exists)")
+    f.load_library()
+    return f
+
+
+@pytest.fixture()
+def ctx(fobq):
+    c = fobq.Ctx(0)
+    yield c
+    c.close()
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def _problem(r, d, n, seed, w_std=None):
+    rng = np.random.default_rng(seed)
+    std = w_std if w_std is not None else np.sqrt(2.0 / d)
+    W = (rng.standard_normal((r, d)) * std).astype(np.float32)
+    X = np.maximum(rng.standard_normal((d, n)), 0).astype(np.float32)
+    return W, X
+
+
+def _oracle_with_gpu_perm(W, H, gpu_perm, ref, **kw):
+    """Several processing orders are correct when two column scores tie to within
+    rounding.  If the GPU's order differs from the oracle's only at such ties the
+    oracle is re-run with the GPU's order; any other difference is a failure."""
+    if np.array_equal(gpu_perm, ref.perm):
+        return ref
+    assert sorted(gpu_perm.tolist()) == list(range(len(gpu_perm))), "GPU perm is not a permutation"
+    bad = np.nonzero(gpu_perm != ref.perm)[0]
+    for t in bad:
+        a, b = ref.S[ref.perm[t]], ref.S[gpu_perm[t]]
+        assert abs(a - b) <= 1e-9 * max(abs(a), abs(b)), f"order differs at step {t} beyond a rounding tie"
+    return oracle.quantize_layer(W, H=H, order_mode=oracle.ORDER_CUSTOM, perm=gpu_perm, **kw)
+
+
+def _compare_layer(out, ref, W, bits, exact=True):
+    codes = out.codes.cpu().numpy().astype(np.int64)
+    diff = codes != ref.codes
+    frac = diff.mean()
+    maxlev = np.abs(codes - ref.codes).max()
+    assert frac <= 1e-3, f"{frac:.2e} of codes differ"
+    assert maxlev <= 1, f"a code differs by {maxlev} levels"
+    if exact:
+        assert frac == 0.0, f"{diff.sum()} codes differ (fp64 on both sides: expected none)"
+    s = out.scales.cpu().numpy().astype(np.float64)
+    z = out.zeros.cpu().numpy().astype(np.float64)
+    assert np.allclose(s, ref.scales, rtol=1e-5, atol=0)
+    assert np.allclose(z, ref.zeros, rtol=1e-5, atol=0)
+    loss = float(out.loss.cpu()[0])
+    # absolute floor: when every weight sits on its grid (e.g. one column per row) the loss is
+    # rounding dust of order eps^2 |W|^2 and has no meaningful relative error
+    floor = 1e-24 * float(np.sum(W.astype(np.float64) ** 2))
+    assert abs(loss - ref.loss) <= 1e-3 * abs(ref.loss) + floor
+    Q = out.Q.cpu().numpy().astype(np.float64)
+    if frac == 0.0:
+        assert np.allclose(Q, ref.Q, rtol=1e-6, atol=1e-12)
+        assert abs(loss - ref.loss) <= 1e-9 * abs(ref.loss) + floor
+    return frac
+
+
+# --------------------------------------------------------------------------- stages
+@pytest.mark.parametrize("d,n,ld_pad,chunk", [(128, 512, 0, None), (200, 1000, 0, 256), (300, 777, 3, 100),
+                                              (64, 40, 0, None), (17, 5, 1, None)])
+def test_hessian_matches_oracle(fobq, ctx, d, n, ld_pad, chunk):
+    _say(f"hessian d={d} n={n} ld_pad={ld_pad} chunk={chunk}")
+    _, X = _problem(1, d, n, 100 + d)
+    ref = oracle.hessian(X)
+    Xd = torch.zeros((d, n + ld_pad), dtype=torch.float32, device="cuda")
+    Xd[:, :n] = _dev(X)
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.hessian(Xd[:, :n], chunk=chunk, H_out=H)
+    torch.cuda.synchronize()
+    Hh = H.cpu().numpy()
+    assert np.allclose(Hh, ref, rtol=1e-12, atol=1e-14)
+    assert np.array_equal(Hh, Hh.T)
+
+
+@pytest.mark.parametrize("d", [1, 7, 64, 65, 100, 128, 300, 1000])
+def test_spd_inverse_matches_oracle(fobq, ctx, d):
+    _say(f"spd_inverse d={d}")
+    _, X = _problem(1, d, max(2 * d, 8), 200 + d)
+    Hd, _ = oracle.damp(oracle.hessian(X), 0.01)
+    ref = oracle.spd_inverse(Hd)
+    got = fobq.fobq_spd_inverse(ctx.handle, _dev(Hd)).cpu().numpy()
+    scale = np.abs(ref).max()
+    assert np.max(np.abs(got - ref)) <= 1e-9 * scale
+    assert np.allclose(got @ Hd, np.eye(d), atol=1e-8)
+    assert np.array_equal(got, got.T)
+
+
+def test_spd_inverse_reports_non_pd(fobq, ctx):
+    _, X = _problem(1, 96, 32, 3)            # N < d: singular
+    H = oracle.hessian(X)
+    with pytest.raises(fobq.FobqError) as e:
+        fobq.fobq_spd_inverse(ctx.handle, _dev(H))
+    assert e.value.code == fobq.ENOTPD
+    # the context stays usable
+    Hd, _ = oracle.damp(H, 0.01)
+    got = fobq.fobq_spd_inverse(ctx.handle, _dev(Hd)).cpu().numpy()
+    assert np.allclose(got @ Hd, np.eye(96), atol=1e-8)
+
+
+@pytest.mark.parametrize("r,d,bits,group", [(64, 128, 4, 0), (33, 96, 3, 32), (130, 70, 8, 0), (5, 600, 2, 200)])
+def test_sensitivity_and_order_match_oracle(fobq, ctx, r, d, bits, group):
+    _say(f"sensitivity r={r} d={d} bits={bits} group={group}")
+    W, X = _problem(r, d, 3 * d, 300 + d)
+    Hd, _ = oracle.damp(oracle.hessian(X), 0.01)
+    Hinv = oracle.spd_inverse(Hd)
+    s, z = oracle.grid(W, bits, group)
+    S_ref = oracle.sensitivity(W, np.ascontiguousarray(np.diag(Hinv)), bits, group, s, z)
+    S, perm = fobq.fobq_sensitivity(ctx.handle, _dev(W), _dev(Hinv), bits=bits, group=group)
+    S = S.cpu().numpy()
+    assert np.allclose(S, S_ref, rtol=1e-12, atol=0)
+    # order: exactly the stable descending order of the GPU's own scores, and equal to the
+    # oracle's order wherever the scores are separated by more than rounding
+    p = perm.cpu().numpy()
+    assert np.array_equal(p, np.argsort(-S, kind="stable").astype(np.int32))
+    p_ref = oracle.order(S_ref)
+    if not np.array_equal(p, p_ref):
+        for t in np.nonzero(p != p_ref)[0]:
+            assert abs(S_ref[p_ref[t]] - S_ref[p[t]]) <= 1e-9 * abs(S_ref[p_ref[t]])
+
+
+# --------------------------------------------------------------------------- whole path, small
+SMALL = [
+    # r, d, n, bits, group, order, block
+    (64, 128, 512, 4, 0, 1, 0),
+    (64, 128, 512, 4, 0, 1, 1),
+    (70, 200, 450, 3, 0, 1, 0),       # ragged rows, ragged last block
+    (70, 200, 450, 3, 0, 1, 1),
+    (70, 200, 450, 3, 0, 1, 16),
+    (33, 192, 100, 4, 64, 1, 0),      # groups, N < d (rank deficient without damping)
+    (33, 192, 100, 4, 64, 0, 1),      # natural order, unblocked
+    (300, 320, 900, 8, 0, 1, 0),
+    (1, 64, 200, 2, 0, 1, 0),         # single row
+    (16, 1, 10, 4, 0, 1, 0),          # single column
+    (9, 63, 200, 5, 0, 0, 7),         # odd block width
+]
+
+
+@pytest.mark.parametrize("r,d,n,bits,group,order,block", SMALL)
+def test_quantize_layer_matches_oracle(fobq, ctx, r, d, n, bits, group, order, block):
+    _say(f"layer r={r} d={d} n={n} bits={bits} group={group} order={order} block={block}")
+    W, X = _problem(r, d, n, 400 + r + d + bits, w_std=0.05)
+    Xd = _dev(X)
+    ctx.hessian(Xd)
+    out = ctx.quantize_layer(_dev(W), bits=bits, group=group, order=order, block=block, damp=0.01)
+    ref = oracle.quantize_layer(W, X=X, bits=bits, group=group, order_mode=order)
+    ref = _oracle_with_gpu_perm(W, ref.H, out.perm.cpu().numpy(), ref, bits=bits, group=group)
+    _compare_layer(out, ref, W, bits)
+
+
+def test_custom_order_and_explicit_h(fobq, ctx):
+    W, X = _problem(40, 150, 400, 5, w_std=0.05)
+    H = oracle.hessian(X)
+    perm = np.random.default_rng(6).permutation(150).astype(np.int32)
+    out = ctx.quantize_layer(_dev(W), _dev(H), bits=4, order=fobq.ORDER_CUSTOM, perm_in=_dev(perm))
+    ref = oracle.quantize_layer(W, H=H, bits=4, order_mode=oracle.ORDER_CUSTOM, perm=perm)
+    assert np.array_equal(out.perm.cpu().numpy(), perm)
+    _compare_layer(out, ref, W, 4)
+
+
+def test_bad_custom_order_is_rejected(fobq, ctx):
+    W, X = _problem(8, 32, 100, 7)
+    H = _dev(oracle.hessian(X))
+    for bad in ([0] * 32, list(range(31)) + [40], list(range(31)) + [-1]):
+        with pytest.raises(fobq.FobqError) as e:
+            ctx.quantize_layer(_dev(W), H, order=fobq.ORDER_CUSTOM, perm_in=_dev(np.array(bad, dtype=np.int32)))
+        assert e.value.code == fobq.EINVAL
+
+
+def test_argument_errors(fobq, ctx):
+    W, X = _problem(8, 32, 100, 8)
+    Wd, H = _dev(W), _dev(oracle.hessian(X))
+    for kw in ({"bits": 1}, {"bits": 9}, {"group": 5}, {"block": 65}, {"stop_after": 33}, {"damp": -1.0},
+               {"order": 7}, {"order": fobq.ORDER_CUSTOM}):
+        with pytest.raises(fobq.FobqError) as e:
+            ctx.quantize_layer(Wd, H, **kw)
+        assert e.value.code == fobq.EINVAL, kw
+    with pytest.raises(fobq.FobqError) as e:       # no Hessian in the context
+        ctx.quantize_layer(Wd)
+    assert e.value.code == fobq.ESTATE
+    with pytest.raises(fobq.FobqError) as e:       # accumulate before begin
+        fobq.fobq_hessian_accumulate(ctx.handle, _dev(X))
+    assert e.value.code == fobq.ESTATE
+    ctx.hessian(_dev(X))
+    with pytest.raises(fobq.FobqError) as e:       # d_col mismatch with the accumulated Hessian
+        ctx.quantize_layer(_dev(W[:, :16].copy()))
+    assert e.value.code == fobq.EINVAL
+    ctx.quantize_layer(Wd)                          # and the context still works
+
+
+def test_rank_deficient_without_damping_is_enotpd(fobq, ctx):
+    W, X = _problem(8, 96, 32, 9)
+    ctx.hessian(_dev(X))
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.quantize_layer(_dev(W), damp=0.0)
+    assert e.value.code == fobq.ENOTPD
+    ctx.quantize_layer(_dev(W), damp=0.01)
+
+
+@pytest.mark.parametrize("block", [0, 1, 16])
+def test_stop_after_snapshots(fobq, ctx, block):
+    r, d, n = 37, 150, 400
+    W, X = _problem(r, d, n, 10, w_std=0.05)
+    H = oracle.hessian(X)
+    Hd_, Wd_ = _dev(H), _dev(W)
+    for t in [0, 1, 16, 64, 77, 149, 150]:
+        _say(f"snapshot block={block} t={t}")
+        out = ctx.quantize_layer(Wd_, Hd_, bits=4, block=block, stop_after=t, debug=True)
+        ref = oracle.quantize_layer(W, H=H, bits=4, steps=t)
+        p = out.perm.cpu().numpy()
+        ref = _oracle_with_gpu_perm(W, H, p, ref, bits=4, steps=t)
+        # running weights, processing order -> original order
+        Ww = np.empty((r, d))
+        Ww[:, p] = out.W_work.cpu().numpy()
+        assert np.allclose(Ww, ref.W_work, rtol=1e-9, atol=1e-12)
+        Hw = np.empty((d, d))
+        Hw[np.ix_(p, p)] = out.Hinv_work.cpu().numpy()
+        assert np.max(np.abs(Hw - ref.Hinv_work)) <= 1e-9 * np.abs(ref.Hinv).max()
+        codes = out.codes.cpu().numpy().astype(np.int64)
+        assert np.array_equal(codes, ref.codes)
+        assert abs(float(out.loss.cpu()[0]) - ref.loss) <= 1e-9 * abs(ref.loss) + 1e-300
+
+
+def test_blocked_and_unblocked_agree_and_runs_are_deterministic(fobq, ctx):
+    W, X = _problem(100, 260, 700, 11, w_std=0.05)
+    Wd_ = _dev(W)
+    ctx.hessian(_dev(X))
+    a = ctx.quantize_layer(Wd_, bits=4, block=0)
+    b = ctx.quantize_layer(Wd_, bits=4, block=1)
+    c = ctx.quantize_layer(Wd_, bits=4, block=0)
+    assert torch.equal(a.codes, b.codes)
+    assert torch.equal(a.codes, c.codes) and torch.equal(a.Q, c.Q) and torch.equal(a.loss, c.loss)
+    assert abs(float(a.loss[0]) - float(b.loss[0])) <= 1e-10 * float(a.loss[0])
+
+
+def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
+    # property that holds at any size: loss = (1/N)|(W-Q)X|^2 + lambda/2 |W-Q|^2, from X directly
+    W, X = _problem(50, 180, 500, 12, w_std=0.05)
+    ctx.hessian(_dev(X))
+    out = ctx.quantize_layer(_dev(W), bits=4)
+    Q = out.Q.cpu().numpy().astype(np.float64)
+    lam = 0.01 * np.mean(np.diag(oracle.hessian(X)))
+    dW = W.astype(np.float64) - Q
+    expect = oracle.output_error(W, Q, X) + 0.5 * lam * np.sum(dW ** 2)
+    assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-6 * expect
+
+
+# --------------------------------------------------------------------------- the benchmark configurations
+def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None):
+    spec = workloads.configs()[name]
+    _say(f"config {name}: generating inputs")
+    W = spec.make_w()
+    X = spec.make_x()
+    Xd = _dev(X)
+    _say(f"config {name}: GPU path")
+    ctx.hessian(Xd, chunk=chunk)
+    out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp, block=block)
+    del Xd
+    _say(f"config {name}: oracle")
+    H = oracle.hessian(X)
+    Hg = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
+    fobq.fobq_hessian_finalize(ctx.handle, Hg)
+    torch.cuda.synchronize()
+    assert np.allclose(Hg.cpu().numpy(), H, rtol=1e-11, atol=1e-13)
+    if rows is None:
+        ref = oracle.quantize_layer(W, H=H, bits=spec.bits, group=spec.group, damp_rel=spec.damp)
+        ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=spec.bits, group=spec.group,
+                                    damp_rel=spec.damp)
+        frac = _compare_layer(out, ref, W, spec.bits)
+    else:
+        # rows of W never interact once the order is fixed: the oracle quantizes a sample of rows
+        # under the order computed from ALL rows
+        Hd, _lam = oracle.damp(H, spec.damp)
+        Hinv = oracle.spd_inverse(Hd)
+        s, z = oracle.grid(W, spec.bits, spec.group)
+        S = oracle.sensitivity(W, np.ascontiguousarray(np.diag(Hinv)), spec.bits, spec.group, s, z)
+        p_ref = oracle.order(S)
+        p = out.perm.cpu().numpy()
+        if not np.array_equal(p, p_ref):
+            assert sorted(p.tolist()) == list(range(spec.d_col))
+            for t in np.nonzero(p != p_ref)[0]:
+                a, b = S[p_ref[t]], S[p[t]]
+                assert abs(a - b) <= 1e-9 * max(abs(a), abs(b))
+        sel = np.unique(np.linspace(0, spec.d_row - 1, rows).astype(int))
+        _say(f"config {name}: oracle column loop on {len(sel)} sampled rows")
+        ref = oracle.column_loop(np.ascontiguousarray(W[sel]), Hinv, p, spec.bits, spec.group,
+                                 np.ascontiguousarray(s[sel]), np.ascontiguousarray(z[sel]))
+        codes = out.codes.cpu().numpy().astype(np.int64)[sel]
+        diff = codes != ref.codes
+        frac = diff.mean()
+        assert frac <= 1e-3 and np.abs(codes - ref.codes).max() <= 1
+        assert frac == 0.0
+        assert np.allclose(out.scales.cpu().numpy(), s, rtol=1e-5)
+        assert np.allclose(out.zeros.cpu().numpy(), z, rtol=1e-5)
+        assert np.allclose(out.Q.cpu().numpy()[sel], ref.Q, rtol=1e-6, atol=1e-12)
+        # the loss over all rows, from the definition, with the GPU's Q
+        Q = out.Q.cpu().numpy().astype(np.float64)
+        expect = oracle.loss_eval(W, Q, Hd)
+        assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-3 * expect
+    _say(f"config {name}: {frac:.2e} of codes differ")
+
+
+def test_config_c1_tiny(fobq, ctx):
+    _run_config(fobq, ctx, "c1_tiny")
+    _run_config(fobq, ctx, "c1_tiny", block=1)
+
+
+def test_config_c2_resnet50_3x3(fobq, ctx):
+    _run_config(fobq, ctx, "c2_resnet50_3x3", chunk=6272)
+
+
+@pytest.mark.parametrize("name", ["c3a_expand_w8", "c3a_expand_w4"])
+def test_config_c3a(fobq, ctx, name):
+    _run_config(fobq, ctx, name)
+
+
+@pytest.mark.parametrize("name", ["c3b_fc_w8", "c3b_fc_w4"])
+def test_config_c3b(fobq, ctx, name):
+    _run_config(fobq, ctx, name)
+
+
+@pytest.mark.slow
+def test_config_c5_large_d(fobq, ctx):
+    _run_config(fobq, ctx, "c5_large_d", rows=64)
