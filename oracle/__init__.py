@@ -63,6 +63,11 @@ class OracleError(RuntimeError):
         self.code = code
 
 
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loops use."""
+    return int(_get().oracle_num_threads())
+
+
 def hessian(X: np.ndarray) -> np.ndarray:
     """H = (2/N) X X^T in fp64 from fp32 X (d_col x N)."""
     X = _f32(X)

@@ -37,11 +37,24 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORACLE_OK 0
 #define ORACLE_EINVAL -1
 #define ORACLE_ENOMEM -2
 #define ORACLE_ENOTPD -4
+
+/* Number of OpenMP threads the parallel loops below will use. */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* H = (2/N) X X^T, X given as fp32 d x N with row stride ld.  Full d x d. */
 int oracle_hessian(const float *X, int64_t d, int64_t N, int64_t ld, double *H)
