@@ -17,8 +17,18 @@ constexpr int NB = 64;
 constexpr int DLD = NB + 1;
 
 // ---------------------------------------------------------------------------
+// 64 x 64 diagonal blocks.  Both diagonal-block kernels use the same scheme: the
+// block lives in registers, thread (ti, tj) of a 16 x 16 grid owning the 4 x 4
+// micro-tile rows 4 ti.., columns 4 tj.. of the (full symmetric) block and of a
+// second 64 x 64 matrix X that starts as the identity.  Step k of the
+// factorization is a rank-1 update of both; the only data exchanged per step are
+// column k of the block and row k of X, through LDS, behind one barrier (the LDS
+// slots alternate with the parity of k so that one barrier per step is enough).
+// Applying the elementary eliminations to the identity yields the inverse of the
+// triangular factor in the same sweep.
+
 // Diagonal block of the Cholesky factorization.
-//   in : A[o:o+nb, o:o+nb] (lower triangle read)
+//   in : A[o:o+nb, o:o+nb] (symmetric; only the lower triangle is read)
 //   out: L[o:o+nb, o:o+nb] = L11 (lower, upper part zeroed)
 //        Linv[o:o+nb, o:o+nb] = L11^-1 (lower, upper part zeroed)
 //        Dinv (64 x 64, ld 64) = L11^-1 zero padded
@@ -28,51 +38,76 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
                                                         double* __restrict__ L, double* __restrict__ Linv,
                                                         double* __restrict__ Dinv, int* __restrict__ flag)
 {
-    __shared__ double a[NB][DLD];
-    __shared__ double x[NB][DLD];
+    __shared__ double col[2][NB];
+    __shared__ double xrow[2][NB];
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx / NB, j = idx % NB;
-        a[i][j] = (i < nb && j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
-        x[i][j] = 0.0;
-    }
-    __syncthreads();
-    for (int j = 0; j < nb; ++j) {
-        if (tid == 0) {
-            double piv = a[j][j];
-            if (!(piv > 0.0) || !(piv < 1.0e300)) { *flag = 1; piv = 1.0; }
-            a[j][j] = sqrt(piv);
+    const int ti = tid >> 4, tj = tid & 15;
+    const int i0 = ti * 4, j0 = tj * 4;
+    double a[4][4], x[4][4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int i = i0 + ii, j = j0 + jj;
+            double v = (i == j) ? 1.0 : 0.0;           // identity padding past nb
+            if (i < nb && j < nb) {
+                const int lo = min(i, j), hi = max(i, j);
+                v = A[(int64_t)(o + hi) * ld + o + lo];
+            }
+            a[ii][jj] = v;
+            x[ii][jj] = (i == j) ? 1.0 : 0.0;
+        }
+    // k = 4 kb + kk with kk unrolled, so that the micro-tile column / row handed to LDS
+    // has a compile-time register index (the tiles must stay in registers)
+    for (int kb = 0; kb < (nb + 3) / 4; ++kb) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = kb * 4 + kk, slot = kk & 1;
+        if (k >= nb) break;
+        if (tj == kb) {
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) col[slot][i0 + ii] = a[ii][kk];
+        }
+        if (ti == kb) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) xrow[slot][j0 + jj] = x[kk][jj];
         }
         __syncthreads();
-        const double ljj = a[j][j];
-        if (tid > j && tid < nb) a[tid][j] /= ljj;
-        __syncthreads();
-        const int rem = nb - j - 1;
-        for (int idx = tid; idx < rem * rem; idx += 256) {
-            const int i = j + 1 + idx / rem, k = j + 1 + idx % rem;
-            if (k <= i) a[i][k] -= a[i][j] * a[k][j];
+        double piv = col[slot][k];
+        if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
+        const double rs = 1.0 / sqrt(piv);
+        double li[4], lj[4], xs[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            li[u] = col[slot][i0 + u] * rs;
+            lj[u] = col[slot][j0 + u] * rs;
+            xs[u] = xrow[slot][j0 + u] * rs;
         }
-        __syncthreads();
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int i = i0 + ii, j = j0 + jj;
+                if (i > k && j > k) a[ii][jj] -= li[ii] * lj[jj];
+                else if (j == k && i >= k) a[ii][jj] = (i == k) ? piv * rs : li[ii];   // column k of L is final
+                if (i > k) x[ii][jj] -= li[ii] * xs[jj];
+                else if (i == k) x[ii][jj] = xs[jj];                                    // row k of L^-1 is final
+            }
+      }
     }
-    // column c of L11^-1 by forward substitution (one thread per column)
-    if (tid < nb) {
-        const int c = tid;
-        x[c][c] = 1.0 / a[c][c];
-        for (int i = c + 1; i < nb; ++i) {
-            double s = 0.0;
-            for (int k = c; k < i; ++k) s += a[i][k] * x[k][c];
-            x[i][c] = -s / a[i][i];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int i = i0 + ii, j = j0 + jj;
+            const bool in = i < nb && j < nb;
+            const double xv = (in && j <= i) ? x[ii][jj] : 0.0;
+            Dinv[i * NB + j] = xv;
+            if (in) {
+                L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? a[ii][jj] : 0.0;
+                Linv[(int64_t)(o + i) * ld + o + j] = xv;
+            }
         }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx / NB, j = idx % NB;
-        Dinv[idx] = x[i][j];
-        if (i < nb && j < nb) {
-            L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? a[i][j] : 0.0;
-            Linv[(int64_t)(o + i) * ld + o + j] = x[i][j];
-        }
-    }
 }
 
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag)
@@ -160,54 +195,98 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 //        G (64 x 64, ld 64)  = D U11^-T  (unit lower): pivot rows right of the
 //                              block are G * A[o:o+nb, o+nb:]
 //        rinv[j] = 1 / pivot_j
+// Same register scheme as chol_diag_kernel; X accumulates (U11^T)^-1, whose row k
+// before its division by the pivot is row k of G.
 __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ U, double* __restrict__ Un,
                                                         double* __restrict__ G, double* __restrict__ rinv,
                                                         int* __restrict__ flag)
 {
-    __shared__ double a[NB][DLD];
-    __shared__ double x[NB][DLD];
+    __shared__ double col[2][NB];
+    __shared__ double xrow[2][NB];
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx / NB, j = idx % NB;
-        a[i][j] = (j < nb && i <= j) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
-        x[i][j] = 0.0;
-    }
-    __syncthreads();
-    for (int j = 0; j < nb; ++j) {
-        if (tid == 0) {
-            const double piv = a[j][j];
-            if (!(piv > 0.0) || !(piv < 1.0e300)) { *flag = 1; a[j][j] = 1.0; }
+    const int ti = tid >> 4, tj = tid & 15;
+    const int i0 = ti * 4, j0 = tj * 4;
+    double a[4][4], x[4][4], g[4][4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int i = i0 + ii, j = j0 + jj;
+            double v = (i == j) ? 1.0 : 0.0;
+            if (i < nb && j < nb) {
+                const int lo = min(i, j), hi = max(i, j);
+                v = A[(int64_t)(o + lo) * ld + o + hi];      // upper triangle is the maintained one
+            }
+            a[ii][jj] = v;
+            x[ii][jj] = (i == j) ? 1.0 : 0.0;
+            g[ii][jj] = 0.0;
+        }
+    // k = 4 kb + kk with kk unrolled, so that the micro-tile column / row handed to LDS
+    // has a compile-time register index (the tiles must stay in registers)
+    for (int kb = 0; kb < (nb + 3) / 4; ++kb) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = kb * 4 + kk, slot = kk & 1;
+        if (k >= nb) break;
+        if (tj == kb) {
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) col[slot][i0 + ii] = a[ii][kk];
+        }
+        if (ti == kb) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) xrow[slot][j0 + jj] = x[kk][jj];
         }
         __syncthreads();
-        const double pinv = 1.0 / a[j][j];
-        const int rem = nb - j - 1;
-        for (int idx = tid; idx < rem * rem; idx += 256) {
-            const int r = j + 1 + idx / rem, k = j + 1 + idx % rem;
-            if (k >= r) a[r][k] -= a[j][r] * pinv * a[j][k];
+        double piv = col[slot][k];
+        if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
+        const double pinv = 1.0 / piv;
+        double ci[4], cj[4], xr[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            ci[u] = col[slot][i0 + u];
+            cj[u] = col[slot][j0 + u];
+            xr[u] = xrow[slot][j0 + u];
         }
-        __syncthreads();
+        if (tid == 0) rinv[k] = pinv;
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int i = i0 + ii, j = j0 + jj;
+                if (i > k && j > k) a[ii][jj] -= ci[ii] * pinv * cj[jj];
+                else if (i == k && j >= k) a[ii][jj] = (j == k) ? piv : cj[jj];   // pivot row k is final
+                if (i > k) x[ii][jj] -= ci[ii] * pinv * xr[jj];
+                else if (i == k) g[ii][jj] = xr[jj];                              // row k of G = D U11^-T
+            }
+      }
     }
-    // G = D * (U11^T)^-1: column c by forward substitution with Lh[i][k] = a[k][i]
-    if (tid < nb) {
-        const int c = tid;
-        x[c][c] = 1.0 / a[c][c];
-        for (int i = c + 1; i < nb; ++i) {
-            double s = 0.0;
-            for (int k = c; k < i; ++k) s += a[k][i] * x[k][c];
-            x[i][c] = -s / a[i][i];
+    if (tid < NB && tid >= nb) rinv[tid] = 0.0;
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int i = i0 + ii, j = j0 + jj;
+            const bool in = i < nb && j < nb;
+            G[i * NB + j] = (in && j <= i) ? g[ii][jj] : 0.0;
+            if (in && j >= i) {
+                U[(int64_t)(o + i) * ld + o + j] = a[ii][jj];
+            }
         }
+    // normalized pivot rows need the pivots of other threads' tiles: exchange through LDS
+    __syncthreads();
+    if (ti == tj) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) col[0][i0 + u] = a[u][u];
     }
     __syncthreads();
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx / NB, j = idx % NB;
-        G[idx] = (i < nb && j < nb) ? a[i][i] * x[i][j] : 0.0;
-        if (i < nb && j < nb && j >= i) {
-            U[(int64_t)(o + i) * ld + o + j] = a[i][j];
-            Un[(int64_t)(o + i) * ld + o + j] = a[i][j] / a[i][i];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int i = i0 + ii, j = j0 + jj;
+            if (i < nb && j < nb && j >= i) Un[(int64_t)(o + i) * ld + o + j] = a[ii][jj] / col[0][i];
         }
-    }
-    if (tid < NB) rinv[tid] = (tid < nb) ? 1.0 / a[tid][tid] : 0.0;
 }
 
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag)

@@ -257,6 +257,9 @@ hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int*
 // and are read as broadcasts.
 constexpr int CB = 64;
 
+// GROUPED: grids per (row, column group): the (scale, zero) pair of every block column is
+// staged in LDS up front so that no global load sits on the sequential chain.
+template <bool GROUPED>
 __global__ __launch_bounds__(64) void chain_kernel(double* __restrict__ Wp, int R, int d, int o, int nb,
                                                    const double* __restrict__ Un, const double* __restrict__ U,
                                                    const double* __restrict__ scale, const double* __restrict__ zero,
@@ -265,11 +268,14 @@ __global__ __launch_bounds__(64) void chain_kernel(double* __restrict__ Wp, int 
                                                    double* __restrict__ lossrow, int writeback)
 {
     __shared__ double uns[CB][CB];
-    __shared__ double piv[CB];
-    __shared__ int grp[CB];
+    __shared__ double hpiv[CB];                       // 1 / (2 U[t,t])
+    __shared__ double sc[GROUPED ? CB : 1][CB];
+    __shared__ double zr[GROUPED ? CB : 1][CB];
     const int lane = threadIdx.x;
     const int row = blockIdx.x * 64 + lane;
     const bool active = row < R;
+    const int64_t rsafe = active ? row : 0;
+    const int64_t grow = rsafe * G;
     for (int j = 0; j < CB; ++j) {
         // lane = shifted column index k; source column j+1+k
         const int c = j + 1 + lane;
@@ -277,33 +283,36 @@ __global__ __launch_bounds__(64) void chain_kernel(double* __restrict__ Wp, int 
         if (j < nb && c < nb) v = Un[(int64_t)(o + j) * d + o + c];
         uns[j][lane] = v;
     }
-    if (lane < nb) {
-        piv[lane] = U[(int64_t)(o + lane) * d + o + lane];
-        int pj = perm[o + lane];
-        pj = min(max(pj, 0), d - 1);
-        grp[lane] = pj / gs;
+    hpiv[lane] = (lane < nb) ? 0.5 / U[(int64_t)(o + lane) * d + o + lane] : 0.0;
+    double s0 = 1.0, z0 = 0.0;
+    if (GROUPED) {
+        for (int j = 0; j < nb; ++j) {
+            int pj = perm[o + j];
+            pj = min(max(pj, 0), d - 1);
+            const int g = pj / gs;
+            sc[j][lane] = scale[grow + g];
+            zr[j][lane] = zero[grow + g];
+        }
     } else {
-        piv[lane] = 1.0;
-        grp[lane] = 0;
+        s0 = scale[grow];
+        z0 = zero[grow];
     }
     double w[CB];
-    const int64_t rsafe = active ? row : 0;
     double* __restrict__ wrow = Wp + rsafe * d + o;
 #pragma unroll
     for (int k = 0; k < CB; ++k) w[k] = (k < nb) ? wrow[k] : 0.0;
     __syncthreads();
 
     double loss = 0.0;
-    const int64_t grow = rsafe * G;
 #pragma unroll 1
     for (int j = 0; j < nb; ++j) {
-        const int g = grp[j];
-        const double s = scale[grow + g], z = zero[grow + g];
+        const double s = GROUPED ? sc[j][lane] : s0;
+        const double z = GROUPED ? zr[j][lane] : z0;
         const double wj = w[0];
         const double c = grid_code(wj, s, z, maxq);
         const double q = s * (c - z);
         const double diff = wj - q;
-        loss += diff * diff / (2.0 * piv[j]);
+        loss += diff * diff * hpiv[j];
         if (active) {
             codesT[(int64_t)(o + j) * Rp + row] = (uint8_t)c;
             DT[(int64_t)(o + j) * Rp + row] = diff;
@@ -324,8 +333,12 @@ hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
     dim3 grid((R + 63) / 64), block(64);
-    hipLaunchKernelGGL(chain_kernel, grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm, maxq,
-                       codesT, DT, Rp, lossrow, writeback);
+    if (G > 1)
+        hipLaunchKernelGGL((chain_kernel<true>), grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm,
+                           maxq, codesT, DT, Rp, lossrow, writeback);
+    else
+        hipLaunchKernelGGL((chain_kernel<false>), grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm,
+                           maxq, codesT, DT, Rp, lossrow, writeback);
     return hipGetLastError();
 }
 
