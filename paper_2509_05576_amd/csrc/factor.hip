@@ -34,6 +34,8 @@ constexpr int DLD = NB + 1;
 //        Dinv (64 x 64, ld 64) = L11^-1 zero padded
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1
 //         so that the arithmetic stays finite; the caller reports ENOTPD).
+// Column k of L and row k of L^-1 are final at step k and are stored right then by
+// the threads that hold them.
 __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ L, double* __restrict__ Linv,
                                                         double* __restrict__ Dinv, int* __restrict__ flag)
@@ -53,9 +55,14 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
             if (i < nb && j < nb) {
                 const int lo = min(i, j), hi = max(i, j);
                 v = A[(int64_t)(o + hi) * ld + o + lo];
+                if (j > i) {                            // strictly upper part of the outputs is zero
+                    L[(int64_t)(o + i) * ld + o + j] = 0.0;
+                    Linv[(int64_t)(o + i) * ld + o + j] = 0.0;
+                }
             }
             a[ii][jj] = v;
             x[ii][jj] = (i == j) ? 1.0 : 0.0;
+            if (j > i || i >= nb || j >= nb) Dinv[i * NB + j] = 0.0;
         }
     // k = 4 kb + kk with kk unrolled, so that the micro-tile column / row handed to LDS
     // has a compile-time register index (the tiles must stay in registers)
@@ -75,39 +82,35 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
         __syncthreads();
         double piv = col[slot][k];
         if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
-        const double rs = 1.0 / sqrt(piv);
+        const double rs = rsqrt(piv);
         double li[4], lj[4], xs[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            li[u] = col[slot][i0 + u] * rs;
-            lj[u] = col[slot][j0 + u] * rs;
+            const double ci = col[slot][i0 + u] * rs;
+            li[u] = (i0 + u > k) ? ci : 0.0;           // rows <= k are finished: zero multiplier
+            lj[u] = (j0 + u > k) ? col[slot][j0 + u] * rs : 0.0;
             xs[u] = xrow[slot][j0 + u] * rs;
+            if (tj == kb) {                             // this thread holds column k: store L[:, k]
+                const int i = i0 + u;
+                if (i >= k && i < nb) L[(int64_t)(o + i) * ld + o + k] = (i == k) ? piv * rs : ci;
+            }
+            if (ti == kb) {                             // this thread holds row k of X: store L^-1[k, :]
+                const int j = j0 + u;
+                if (j <= k) {
+                    Linv[(int64_t)(o + k) * ld + o + j] = xs[u];
+                    Dinv[k * NB + j] = xs[u];
+                }
+            }
         }
 #pragma unroll
         for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
-                const int i = i0 + ii, j = j0 + jj;
-                if (i > k && j > k) a[ii][jj] -= li[ii] * lj[jj];
-                else if (j == k && i >= k) a[ii][jj] = (i == k) ? piv * rs : li[ii];   // column k of L is final
-                if (i > k) x[ii][jj] -= li[ii] * xs[jj];
-                else if (i == k) x[ii][jj] = xs[jj];                                    // row k of L^-1 is final
+                a[ii][jj] -= li[ii] * lj[jj];
+                x[ii][jj] -= li[ii] * xs[jj];
             }
       }
     }
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int i = i0 + ii, j = j0 + jj;
-            const bool in = i < nb && j < nb;
-            const double xv = (in && j <= i) ? x[ii][jj] : 0.0;
-            Dinv[i * NB + j] = xv;
-            if (in) {
-                L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? a[ii][jj] : 0.0;
-                Linv[(int64_t)(o + i) * ld + o + j] = xv;
-            }
-        }
 }
 
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag)
@@ -196,7 +199,8 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 //                              block are G * A[o:o+nb, o+nb:]
 //        rinv[j] = 1 / pivot_j
 // Same register scheme as chol_diag_kernel; X accumulates (U11^T)^-1, whose row k
-// before its division by the pivot is row k of G.
+// before its division by the pivot is row k of G.  Pivot row k and row k of G are
+// final at step k and are stored right then.
 __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ U, double* __restrict__ Un,
                                                         double* __restrict__ G, double* __restrict__ rinv,
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
     const int tid = threadIdx.x;
     const int ti = tid >> 4, tj = tid & 15;
     const int i0 = ti * 4, j0 = tj * 4;
-    double a[4][4], x[4][4], g[4][4];
+    double a[4][4], x[4][4];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
@@ -220,10 +224,9 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
             }
             a[ii][jj] = v;
             x[ii][jj] = (i == j) ? 1.0 : 0.0;
-            g[ii][jj] = 0.0;
+            if (j > i || i >= nb || j >= nb) G[i * NB + j] = 0.0;
         }
-    // k = 4 kb + kk with kk unrolled, so that the micro-tile column / row handed to LDS
-    // has a compile-time register index (the tiles must stay in registers)
+    if (tid < NB && tid >= nb) rinv[tid] = 0.0;
     for (int kb = 0; kb < (nb + 3) / 4; ++kb) {
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -241,52 +244,33 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
         double piv = col[slot][k];
         if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
         const double pinv = 1.0 / piv;
-        double ci[4], cj[4], xr[4];
+        if (tid == 0) rinv[k] = pinv;
+        double fi[4], cj[4], xr[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            ci[u] = col[slot][i0 + u];
-            cj[u] = col[slot][j0 + u];
+            fi[u] = (i0 + u > k) ? col[slot][i0 + u] * pinv : 0.0;   // rows <= k are finished
+            const double c = col[slot][j0 + u];                       // = A[k][j] by symmetry
+            cj[u] = (j0 + u > k) ? c : 0.0;
             xr[u] = xrow[slot][j0 + u];
+            const int j = j0 + u;
+            if (ti == kb) {                              // one thread row stores pivot row k and row k of G
+                if (j >= k && j < nb) {
+                    const double uv = (j == k) ? piv : c;
+                    U[(int64_t)(o + k) * ld + o + j] = uv;
+                    Un[(int64_t)(o + k) * ld + o + j] = (j == k) ? 1.0 : c * pinv;
+                }
+                if (j <= k) G[k * NB + j] = xr[u];
+            }
         }
-        if (tid == 0) rinv[k] = pinv;
 #pragma unroll
         for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
-                const int i = i0 + ii, j = j0 + jj;
-                if (i > k && j > k) a[ii][jj] -= ci[ii] * pinv * cj[jj];
-                else if (i == k && j >= k) a[ii][jj] = (j == k) ? piv : cj[jj];   // pivot row k is final
-                if (i > k) x[ii][jj] -= ci[ii] * pinv * xr[jj];
-                else if (i == k) g[ii][jj] = xr[jj];                              // row k of G = D U11^-T
+                a[ii][jj] -= fi[ii] * cj[jj];
+                x[ii][jj] -= fi[ii] * xr[jj];
             }
       }
     }
-    if (tid < NB && tid >= nb) rinv[tid] = 0.0;
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int i = i0 + ii, j = j0 + jj;
-            const bool in = i < nb && j < nb;
-            G[i * NB + j] = (in && j <= i) ? g[ii][jj] : 0.0;
-            if (in && j >= i) {
-                U[(int64_t)(o + i) * ld + o + j] = a[ii][jj];
-            }
-        }
-    // normalized pivot rows need the pivots of other threads' tiles: exchange through LDS
-    __syncthreads();
-    if (ti == tj) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) col[0][i0 + u] = a[u][u];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int i = i0 + ii, j = j0 + jj;
-            if (i < nb && j < nb && j >= i) Un[(int64_t)(o + i) * ld + o + j] = a[ii][jj] / col[0][i];
-        }
 }
 
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag)

@@ -243,86 +243,71 @@ hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int*
 
 // ---------------------------------------------------------------------------
 // Blocked column loop, the sequential part (Section 4.2 steps 4-5 inside one
-// block of nb <= 64 columns o .. o+nb-1).  One lane owns one row of W and keeps
-// the row's block entries in registers; rows never interact.  For each column j
-// of the block, in order:
-//   q    = quant(w_j)                         (all rows at once, one row per lane)
-//   diff = w_j - q ;  loss += diff^2 / (2 U[t,t])          (Eq. 10)
-//   w_k -= diff * Un[t, k]   for the later columns k of the block   (Eq. 9 / 11;
+// block of nb <= 64 columns o .. o+nb-1).  One wavefront owns one row of W; lane k
+// holds the row's entry in block column k, its grid (scale, zero), and the block's
+// pivot-row entries Un[o+j][o+k] for every j.  Rows never interact.  For each
+// column j of the block, in order:
+//   q    = quant(w_j)                                   (every row at once: one row per wavefront)
+//   diff = w_j - q ;  loss += diff^2 / (2 U[t,t])       (Eq. 10)
+//   w_k -= diff * Un[t, k]  for the later columns k     (Eq. 9 / 11;
 //          e * Hinv[t,k] = (diff / U[t,t]) * U[t,k] = diff * Un[t,k])
-// diff is stored (DT) for the deferred rank-nb update of the columns right of the
-// block.  The register window slides: after step j, w[k] holds column j+1+k, so
-// the loop body has fixed register indices and stays rolled.  The pivot rows are
-// staged in LDS already shifted (uns[j][k] = Un[o+j][o+j+1+k], 0 past the block)
-// and are read as broadcasts.
+// Every lane evaluates the quantizer on its own entry each step; lane j's result is
+// the one that counts and is broadcast with v_readlane.  The loop is fully
+// unrolled, so there is no memory access on the sequential chain.  diff is stored
+// (DT) for the deferred rank-nb update of the columns right of the block.
 constexpr int CB = 64;
+constexpr int CHAIN_WAVES = 4;
 
-// GROUPED: grids per (row, column group): the (scale, zero) pair of every block column is
-// staged in LDS up front so that no global load sits on the sequential chain.
-template <bool GROUPED>
-__global__ __launch_bounds__(64) void chain_kernel(double* __restrict__ Wp, int R, int d, int o, int nb,
-                                                   const double* __restrict__ Un, const double* __restrict__ U,
-                                                   const double* __restrict__ scale, const double* __restrict__ zero,
-                                                   int G, int gs, const int* __restrict__ perm, double maxq,
-                                                   uint8_t* __restrict__ codesT, double* __restrict__ DT, int Rp,
-                                                   double* __restrict__ lossrow, int writeback)
+__device__ __forceinline__ double readlane_f64(double v, int lane)
 {
-    __shared__ double uns[CB][CB];
-    __shared__ double hpiv[CB];                       // 1 / (2 U[t,t])
-    __shared__ double sc[GROUPED ? CB : 1][CB];
-    __shared__ double zr[GROUPED ? CB : 1][CB];
-    const int lane = threadIdx.x;
-    const int row = blockIdx.x * 64 + lane;
-    const bool active = row < R;
-    const int64_t rsafe = active ? row : 0;
-    const int64_t grow = rsafe * G;
-    for (int j = 0; j < CB; ++j) {
-        // lane = shifted column index k; source column j+1+k
-        const int c = j + 1 + lane;
-        double v = 0.0;
-        if (j < nb && c < nb) v = Un[(int64_t)(o + j) * d + o + c];
-        uns[j][lane] = v;
-    }
-    hpiv[lane] = (lane < nb) ? 0.5 / U[(int64_t)(o + lane) * d + o + lane] : 0.0;
-    double s0 = 1.0, z0 = 0.0;
-    if (GROUPED) {
-        for (int j = 0; j < nb; ++j) {
-            int pj = perm[o + j];
-            pj = min(max(pj, 0), d - 1);
-            const int g = pj / gs;
-            sc[j][lane] = scale[grow + g];
-            zr[j][lane] = zero[grow + g];
-        }
-    } else {
-        s0 = scale[grow];
-        z0 = zero[grow];
-    }
-    double w[CB];
-    double* __restrict__ wrow = Wp + rsafe * d + o;
-#pragma unroll
-    for (int k = 0; k < CB; ++k) w[k] = (k < nb) ? wrow[k] : 0.0;
-    __syncthreads();
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
 
-    double loss = 0.0;
-#pragma unroll 1
-    for (int j = 0; j < nb; ++j) {
-        const double s = GROUPED ? sc[j][lane] : s0;
-        const double z = GROUPED ? zr[j][lane] : z0;
-        const double wj = w[0];
-        const double c = grid_code(wj, s, z, maxq);
-        const double q = s * (c - z);
-        const double diff = wj - q;
-        loss += diff * diff * hpiv[j];
-        if (active) {
-            codesT[(int64_t)(o + j) * Rp + row] = (uint8_t)c;
-            DT[(int64_t)(o + j) * Rp + row] = diff;
-            if (writeback) wrow[j] = wj;
-        }
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
+    double* __restrict__ Wp, int R, int d, int o, int nb, const double* __restrict__ Un,
+    const double* __restrict__ U, const double* __restrict__ scale, const double* __restrict__ zero, int G, int gs,
+    const int* __restrict__ perm, double maxq, uint8_t* __restrict__ codesT, double* __restrict__ DT, int Rp,
+    double* __restrict__ lossrow)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * CHAIN_WAVES + (threadIdx.x >> 6);
+    if (row >= R) return;                    // whole wavefront leaves; no barriers in this kernel
+    const bool col_ok = lane < nb;
+    const int cl = col_ok ? lane : 0;        // safe column for address arithmetic
+    double* __restrict__ wptr = Wp + (int64_t)row * d + o + cl;
+    double w = *wptr;
+    int pj = perm[o + cl];
+    pj = min(max(pj, 0), d - 1);
+    const int64_t gi = (int64_t)row * G + pj / gs;
+    const double s = scale[gi], z = zero[gi];
+    const double hp = 0.5 / U[(int64_t)(o + cl) * d + o + cl];
+    double u[CB];
 #pragma unroll
-        for (int k = 0; k < CB - 1; ++k) w[k] = w[k + 1] - diff * uns[j][k];
-        w[CB - 1] = 0.0;
+    for (int j = 0; j < CB; ++j)
+        u[j] = (j < nb && lane > j && col_ok) ? Un[(int64_t)(o + j) * d + o + lane] : 0.0;
+
+    double mycode = 0.0, mydiff = 0.0;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        if (j < nb) {                        // uniform
+            const double c = grid_code(w, s, z, maxq);
+            const double df = w - s * (c - z);
+            const double dj = readlane_f64(df, j);
+            if (lane == j) { mycode = c; mydiff = df; }
+            w -= dj * u[j];                  // u[j] is 0 for lanes <= j: they keep the value they were quantized at
+        }
     }
-    if (active) lossrow[row] += loss;
+    if (col_ok) {
+        codesT[(int64_t)(o + lane) * Rp + row] = (uint8_t)mycode;
+        DT[(int64_t)(o + lane) * Rp + row] = mydiff;
+        *wptr = w;
+    }
+    double loss = col_ok ? mydiff * mydiff * hp : 0.0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
+    if (lane == 0) lossrow[row] += loss;
 }
 
 hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
@@ -330,15 +315,12 @@ hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         int G, int group, const int* perm, int bits,
                         uint8_t* codesT, double* DT, int Rp, double* lossrow, int writeback)
 {
+    (void)writeback;   // the running weights are always written back (coalesced, one store per lane)
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
-    dim3 grid((R + 63) / 64), block(64);
-    if (G > 1)
-        hipLaunchKernelGGL((chain_kernel<true>), grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm,
-                           maxq, codesT, DT, Rp, lossrow, writeback);
-    else
-        hipLaunchKernelGGL((chain_kernel<false>), grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm,
-                           maxq, codesT, DT, Rp, lossrow, writeback);
+    dim3 grid((R + CHAIN_WAVES - 1) / CHAIN_WAVES), block(64 * CHAIN_WAVES);
+    hipLaunchKernelGGL(chain_kernel, grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm, maxq,
+                       codesT, DT, Rp, lossrow);
     return hipGetLastError();
 }
 
