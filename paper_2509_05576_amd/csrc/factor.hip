@@ -14,18 +14,56 @@
 namespace fobq {
 
 constexpr int NB = 64;
-constexpr int DLD = NB + 1;
 
 // ---------------------------------------------------------------------------
-// 64 x 64 diagonal blocks.  Both diagonal-block kernels use the same scheme: the
-// block lives in registers, thread (ti, tj) of a 16 x 16 grid owning the 4 x 4
-// micro-tile rows 4 ti.., columns 4 tj.. of the (full symmetric) block and of a
-// second 64 x 64 matrix X that starts as the identity.  Step k of the
-// factorization is a rank-1 update of both; the only data exchanged per step are
-// column k of the block and row k of X, through LDS, behind one barrier (the LDS
-// slots alternate with the parity of k so that one barrier per step is enough).
-// Applying the elementary eliminations to the identity yields the inverse of the
-// triangular factor in the same sweep.
+// 64 x 64 diagonal blocks.  Both diagonal-block kernels keep the block in LDS and
+// work on it as a 4 x 4 grid of 16 x 16 tiles: the only sequential arithmetic is
+// the unblocked factorization of a 16 x 16 diagonal tile (one wavefront, one tile
+// row per lane, pivot rows broadcast with v_readlane, the tile's triangular
+// inverse obtained in the same sweep by applying the eliminations to the
+// identity); everything else -- panel, trailing update, assembly of the 64 x 64
+// triangular inverse from the tile inverses -- is 16 x 16 x 16 products on the
+// matrix cores (4 MFMAs each), one tile per wavefront.
+typedef double d4 __attribute__((ext_vector_type(4)));
+constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
+
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ d4 mfma4(double a, double b, d4 c)
+{
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// Assembly of the inverse X of a 64 x 64 lower triangular matrix T from the inverses of
+// its four 16 x 16 diagonal tiles (already in Xm):  X_ij = -X_ii sum_{m=j}^{i-1} T_im X_mj,
+// by distance from the diagonal.  tfetch(i, m, ks) returns this lane's A-operand element
+// of tile T_im for k-step ks, i.e. T_im[fr][4 ks + fq].
+template <class TF>
+__device__ __forceinline__ void assemble_inverse(double* Xm, TF tfetch, int wave, int fr, int fq)
+{
+    for (int dist = 1; dist < 4; ++dist) {
+        const int i = dist + wave, j = i - dist;
+        if (i < 4) {
+            d4 t = {0.0, 0.0, 0.0, 0.0};
+            for (int m = j; m < i; ++m)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    t = mfma4(tfetch(i, m, ks), Xm[(16 * m + 4 * ks + fq) * DL + 16 * j + fr], t);
+            // the accumulator layout (row 4 v + fq, column fr) is the B-operand layout of k-step v
+            d4 r = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) r = mfma4(Xm[(16 * i + fr) * DL + 16 * i + 4 * ks + fq], t[ks], r);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Xm[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = -r[v];
+        }
+        __syncthreads();
+    }
+}
 
 // Diagonal block of the Cholesky factorization.
 //   in : A[o:o+nb, o:o+nb] (symmetric; only the lower triangle is read)
@@ -34,82 +72,100 @@ constexpr int DLD = NB + 1;
 //        Dinv (64 x 64, ld 64) = L11^-1 zero padded
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1
 //         so that the arithmetic stays finite; the caller reports ENOTPD).
-// Column k of L and row k of L^-1 are final at step k and are stored right then by
-// the threads that hold them.
 __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ L, double* __restrict__ Linv,
                                                         double* __restrict__ Dinv, int* __restrict__ flag)
 {
-    __shared__ double col[2][NB];
-    __shared__ double xrow[2][NB];
-    const int tid = threadIdx.x;
-    const int ti = tid >> 4, tj = tid & 15;
-    const int i0 = ti * 4, j0 = tj * 4;
-    double a[4][4], x[4][4];
+    __shared__ double Am[NB * DL];
+    __shared__ double Xm[NB * DL];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 15, fq = lane >> 4;
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
+        if (i < nb && j < nb) v = (j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
+        Am[i * DL + j] = v;
+        Xm[i * DL + j] = 0.0;
+    }
+    __syncthreads();
+    for (int b = 0; b < 4; ++b) {
+        const int base = 16 * b;
+        if (wave == 0) {
+            // unblocked Cholesky of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of the
+            // symmetric tile and row r of X (starts as identity, ends as the tile's L^-1)
+            const int r = fr;
+            double a[16], x[16];
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
+            for (int j = 0; j < 16; ++j) {
+                a[j] = (j <= r) ? Am[(base + r) * DL + base + j] : Am[(base + j) * DL + base + r];
+                x[j] = (j == r) ? 1.0 : 0.0;
+            }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int i = i0 + ii, j = j0 + jj;
-            double v = (i == j) ? 1.0 : 0.0;           // identity padding past nb
-            if (i < nb && j < nb) {
-                const int lo = min(i, j), hi = max(i, j);
-                v = A[(int64_t)(o + hi) * ld + o + lo];
-                if (j > i) {                            // strictly upper part of the outputs is zero
-                    L[(int64_t)(o + i) * ld + o + j] = 0.0;
-                    Linv[(int64_t)(o + i) * ld + o + j] = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                double piv = readlane_f64(a[k], k);
+                if (!(piv > 0.0) || !(piv < 1.0e300)) { if (lane == 0) *flag = 1; piv = 1.0; }
+                const double rs = rsqrt(piv);
+                const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
+                const double lm = (r > k) ? t : 0.0;
+#pragma unroll
+                for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
+                a[k] = t;
+#pragma unroll
+                for (int c = 0; c <= k; ++c) {
+                    const double xs = readlane_f64(x[c], k) * rs;
+                    x[c] = (r == k) ? xs : x[c] - lm * xs;
                 }
             }
-            a[ii][jj] = v;
-            x[ii][jj] = (i == j) ? 1.0 : 0.0;
-            if (j > i || i >= nb || j >= nb) Dinv[i * NB + j] = 0.0;
-        }
-    // k = 4 kb + kk with kk unrolled, so that the micro-tile column / row handed to LDS
-    // has a compile-time register index (the tiles must stay in registers)
-    for (int kb = 0; kb < (nb + 3) / 4; ++kb) {
+            if (lane < 16) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int k = kb * 4 + kk, slot = kk & 1;
-        if (k >= nb) break;
-        if (tj == kb) {
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) col[slot][i0 + ii] = a[ii][kk];
-        }
-        if (ti == kb) {
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) xrow[slot][j0 + jj] = x[kk][jj];
+                for (int j = 0; j < 16; ++j) {
+                    Am[(base + r) * DL + base + j] = (j <= r) ? a[j] : 0.0;
+                    Xm[(base + r) * DL + base + j] = (j <= r) ? x[j] : 0.0;
+                }
+            }
         }
         __syncthreads();
-        double piv = col[slot][k];
-        if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
-        const double rs = rsqrt(piv);
-        double li[4], lj[4], xs[4];
+        // panel: L_ib = A_ib * Linv_bb^T for the tiles below the diagonal tile
+        {
+            const int i = b + 1 + wave;
+            if (i < 4) {
+                d4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const double ci = col[slot][i0 + u] * rs;
-            li[u] = (i0 + u > k) ? ci : 0.0;           // rows <= k are finished: zero multiplier
-            lj[u] = (j0 + u > k) ? col[slot][j0 + u] * rs : 0.0;
-            xs[u] = xrow[slot][j0 + u] * rs;
-            if (tj == kb) {                             // this thread holds column k: store L[:, k]
-                const int i = i0 + u;
-                if (i >= k && i < nb) L[(int64_t)(o + i) * ld + o + k] = (i == k) ? piv * rs : ci;
-            }
-            if (ti == kb) {                             // this thread holds row k of X: store L^-1[k, :]
-                const int j = j0 + u;
-                if (j <= k) {
-                    Linv[(int64_t)(o + k) * ld + o + j] = xs[u];
-                    Dinv[k * NB + j] = xs[u];
-                }
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = mfma4(Am[(16 * i + fr) * DL + base + 4 * ks + fq], Xm[(base + fr) * DL + base + 4 * ks + fq], acc);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + base + fr] = acc[v];
             }
         }
+        __syncthreads();
+        // trailing tiles: A_ij -= L_ib L_jb^T for b < j <= i
+        {
+            int t = 0;
+            for (int i = b + 1; i < 4; ++i)
+                for (int j = b + 1; j <= i; ++j, ++t) {
+                    if ((t & 3) != wave) continue;
+                    d4 acc;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
+                    for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                a[ii][jj] -= li[ii] * lj[jj];
-                x[ii][jj] -= li[ii] * xs[jj];
-            }
-      }
+                    for (int ks = 0; ks < 4; ++ks)
+                        acc = mfma4(-Am[(16 * i + fr) * DL + base + 4 * ks + fq], Am[(16 * j + fr) * DL + base + 4 * ks + fq], acc);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
+                }
+        }
+        __syncthreads();
+    }
+    assemble_inverse(Xm, [&](int i, int m, int ks) { return Am[(16 * i + fr) * DL + 16 * m + 4 * ks + fq]; }, wave, fr, fq);
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        const bool in = i < nb && j < nb;
+        const double xv = (in && j <= i) ? Xm[i * DL + j] : 0.0;
+        Dinv[idx] = xv;
+        if (in) {
+            L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? Am[i * DL + j] : 0.0;
+            Linv[(int64_t)(o + i) * ld + o + j] = xv;
+        }
     }
 }
 
@@ -191,86 +247,119 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 
 // ---------------------------------------------------------------------------
 // Diagonal block of the shared-Hinv elimination (Eq. 12 for nb consecutive steps
-// restricted to the block).  With A11 the current block and U11 its pivot rows,
-// A11 = U11^T D^-1 U11, D = diag(U11).
+// restricted to the block).  With A11 the current block, U11 its pivot rows,
+// D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
 //   out: U[o+j, o+j : o+nb]  = pivot row j inside the block
 //        Un = U / pivot
-//        G (64 x 64, ld 64)  = D U11^-T  (unit lower): pivot rows right of the
+//        G (64 x 64, ld 64)  = (Un11^T)^-1 (unit lower): pivot rows right of the
 //                              block are G * A[o:o+nb, o+nb:]
 //        rinv[j] = 1 / pivot_j
-// Same register scheme as chol_diag_kernel; X accumulates (U11^T)^-1, whose row k
-// before its division by the pivot is row k of G.  Pivot row k and row k of G are
-// final at step k and are stored right then.
+// Same tile scheme as chol_diag_kernel, without square roots.
 __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ U, double* __restrict__ Un,
                                                         double* __restrict__ G, double* __restrict__ rinv,
                                                         int* __restrict__ flag)
 {
-    __shared__ double col[2][NB];
-    __shared__ double xrow[2][NB];
-    const int tid = threadIdx.x;
-    const int ti = tid >> 4, tj = tid & 15;
-    const int i0 = ti * 4, j0 = tj * 4;
-    double a[4][4], x[4][4];
+    __shared__ double Am[NB * DL];     // current block (full symmetric); rows become pivot rows U
+    __shared__ double Um[NB * DL];     // Un
+    __shared__ double Xm[NB * DL];     // G
+    __shared__ double rv[NB];          // 1 / pivot
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 15, fq = lane >> 4;
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        double v = (i == j) ? 1.0 : 0.0;
+        if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
+        Am[i * DL + j] = v;
+        Um[i * DL + j] = 0.0;
+        Xm[i * DL + j] = 0.0;
+    }
+    __syncthreads();
+    for (int b = 0; b < 4; ++b) {
+        const int base = 16 * b;
+        if (wave == 0) {
+            // unblocked elimination of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of
+            // the symmetric tile and row r of X (identity -> (Un_bb^T)^-1)
+            const int r = fr;
+            double a[16], x[16], pinv[16];
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int i = i0 + ii, j = j0 + jj;
-            double v = (i == j) ? 1.0 : 0.0;
-            if (i < nb && j < nb) {
-                const int lo = min(i, j), hi = max(i, j);
-                v = A[(int64_t)(o + lo) * ld + o + hi];      // upper triangle is the maintained one
+            for (int j = 0; j < 16; ++j) {
+                a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+                x[j] = (j == r) ? 1.0 : 0.0;
             }
-            a[ii][jj] = v;
-            x[ii][jj] = (i == j) ? 1.0 : 0.0;
-            if (j > i || i >= nb || j >= nb) G[i * NB + j] = 0.0;
-        }
-    if (tid < NB && tid >= nb) rinv[tid] = 0.0;
-    for (int kb = 0; kb < (nb + 3) / 4; ++kb) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int k = kb * 4 + kk, slot = kk & 1;
-        if (k >= nb) break;
-        if (tj == kb) {
+            for (int k = 0; k < 16; ++k) {
+                double piv = readlane_f64(a[k], k);
+                if (!(piv > 0.0) || !(piv < 1.0e300)) { if (lane == 0) *flag = 1; piv = 1.0; }
+                pinv[k] = 1.0 / piv;
+                const double cr = (r == k) ? piv : a[k];          // A[k][r] = U[k][r] for r >= k
+                const double fm = (r > k) ? cr * pinv[k] : 0.0;   // Un[k][r]
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) col[slot][i0 + ii] = a[ii][kk];
-        }
-        if (ti == kb) {
+                for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
+                a[k] = cr;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) xrow[slot][j0 + jj] = x[kk][jj];
+                for (int c = 0; c <= k; ++c) x[c] -= fm * readlane_f64(x[c], k);
+            }
+            if (lane < 16) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    // lane r holds column r of the pivot rows: U[k][r] for k <= r
+                    if (k <= r) {
+                        Am[(base + k) * DL + base + r] = a[k];
+                        Um[(base + k) * DL + base + r] = (k == r) ? 1.0 : a[k] * pinv[k];
+                    }
+                    Xm[(base + r) * DL + base + k] = (k <= r) ? x[k] : 0.0;
+                    if (k == r) rv[base + k] = pinv[k];
+                }
+            }
         }
         __syncthreads();
-        double piv = col[slot][k];
-        if (!(piv > 0.0) || !(piv < 1.0e300)) { if (tid == 0) *flag = 1; piv = 1.0; }
-        const double pinv = 1.0 / piv;
-        if (tid == 0) rinv[k] = pinv;
-        double fi[4], cj[4], xr[4];
+        // pivot rows right of the diagonal tile: U_bj = G_bb * A_bj, Un_bj = D^-1 U_bj
+        {
+            const int j = b + 1 + wave;
+            if (j < 4) {
+                d4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            fi[u] = (i0 + u > k) ? col[slot][i0 + u] * pinv : 0.0;   // rows <= k are finished
-            const double c = col[slot][j0 + u];                       // = A[k][j] by symmetry
-            cj[u] = (j0 + u > k) ? c : 0.0;
-            xr[u] = xrow[slot][j0 + u];
-            const int j = j0 + u;
-            if (ti == kb) {                              // one thread row stores pivot row k and row k of G
-                if (j >= k && j < nb) {
-                    const double uv = (j == k) ? piv : c;
-                    U[(int64_t)(o + k) * ld + o + j] = uv;
-                    Un[(int64_t)(o + k) * ld + o + j] = (j == k) ? 1.0 : c * pinv;
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = mfma4(Xm[(base + fr) * DL + base + 4 * ks + fq], Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    Am[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
+                    Um[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v] * rv[base + 4 * v + fq];
                 }
-                if (j <= k) G[k * NB + j] = xr[u];
             }
         }
+        __syncthreads();
+        // trailing tiles: A_ij -= Un_bi^T U_bj for b < i <= j
+        {
+            int t = 0;
+            for (int i = b + 1; i < 4; ++i)
+                for (int j = i; j < 4; ++j, ++t) {
+                    if ((t & 3) != wave) continue;
+                    d4 acc;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
+                    for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                a[ii][jj] -= fi[ii] * cj[jj];
-                x[ii][jj] -= fi[ii] * xr[jj];
-            }
-      }
+                    for (int ks = 0; ks < 4; ++ks)
+                        acc = mfma4(-Um[(base + 4 * ks + fq) * DL + 16 * i + fr], Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
+                }
+        }
+        __syncthreads();
     }
+    // G = (Un11^T)^-1: tile T_im of Un11^T is Un_mi transposed
+    assemble_inverse(Xm, [&](int i, int m, int ks) { return Um[(16 * m + 4 * ks + fq) * DL + 16 * i + fr]; }, wave, fr, fq);
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        const bool in = i < nb && j < nb;
+        G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
+        if (in && j >= i) {
+            U[(int64_t)(o + i) * ld + o + j] = Am[i * DL + j];
+            Un[(int64_t)(o + i) * ld + o + j] = Um[i * DL + j];
+        }
+    }
+    if (tid < NB) rinv[tid] = (tid < nb) ? rv[tid] : 0.0;
 }
 
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag)

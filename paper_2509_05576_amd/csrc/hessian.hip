@@ -2,10 +2,17 @@
 //
 // xxt_kernel: fp32 X is read from HBM, staged through LDS as fp32, widened to
 // fp64 when the MFMA fragments are formed (products of two fp32 values are
-// exact in fp64), and accumulated with v_mfma_f64_16x16x4_f64.  Only tiles on
-// or below the diagonal are computed.  The calibration dimension is split over
-// blockIdx.y; each split owns its own d x d slab of partial sums, so the
-// result does not depend on the order in which workgroups finish.
+// exact in fp64), and accumulated with v_mfma_f64_16x16x4_f64.  Only the 128 x 128
+// tiles on or below the diagonal are computed.
+//
+// Work decomposition ("stream-K"): the work items are (tile, 32-column chunk of
+// the calibration dimension) pairs in tile-major order; a fixed number of
+// persistent workgroups each take one contiguous, equally long range of items, so
+// every workgroup does the same amount of MFMA work whatever d and n are.  A
+// range can cross tile boundaries; the part of a tile done by one workgroup is a
+// "piece".  Piece p of a tile is added into slab p of Hpart (XXT_SLABS slabs of
+// d x d), and exactly one workgroup owns a given (tile, piece) in a launch, so
+// the sums do not depend on the order in which workgroups finish.
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -14,7 +21,8 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 
 constexpr int XT = 128;          // tile edge
 constexpr int XK = 32;           // calibration columns per LDS stage
-constexpr int XLD = XK + 4;      // fp32 row stride in LDS: 16B-aligned rows, conflict-free fragment reads
+constexpr int XLD = XK + 4;      // fp32 row stride in LDS: 16B-aligned rows, conflict-free 16B fragment reads
+constexpr int XXT_WGS = 512;     // persistent workgroups: 2 per compute unit
 
 __device__ __forceinline__ void tile_decode(int t, int& I, int& J)
 {
@@ -26,124 +34,158 @@ __device__ __forceinline__ void tile_decode(int t, int& I, int& J)
     J = t - i * (i + 1) / 2;
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(256) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
-                                                  double* __restrict__ Hpart, int64_t kper)
+// FAST: X rows are 16-byte aligned (ld % 4 == 0, base aligned) -> float4 loads.
+template <bool FAST>
+__global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
+                                                     double* __restrict__ Hpart, int chunks, int64_t per_wg,
+                                                     int64_t total_items)
 {
-    int I, J;
-    tile_decode(blockIdx.x, I, J);
-    const int split = blockIdx.y;
-    const int64_t k_begin = (int64_t)split * kper;
-    const int64_t k_end = min(n, k_begin + kper);
-    if (k_begin >= k_end) return;
-    const int i0 = I * XT, j0 = J * XT;
-
-    __shared__ float As[XT][XLD];
-    __shared__ float Bs[XT][XLD];
+    __shared__ float As[2][XT][XLD];
+    __shared__ float Bs[2][XT][XLD];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = tid >> 3;          // 0..31: row within a group of 32 rows
     const int lk = (tid & 7) * 4;     // 0..28: first of 4 consecutive calibration columns
+    const int fr = lane & 15;         // fragment row
+    const int fk = (lane >> 4) * 4;   // fragment: 4 consecutive columns, one per k-step (the sum over k is order-free)
 
-    float4 pa[4], pb[4];
-    auto gload = [&](int64_t kk) {
+    int64_t item = (int64_t)blockIdx.x * per_wg;
+    const int64_t item_end = min(total_items, item + per_wg);
+
+    while (item < item_end) {
+        const int tile = (int)(item / chunks);
+        const int c_begin = (int)(item % chunks);
+        const int c_end = (int)min((int64_t)chunks, c_begin + (item_end - item));
+        // piece index of this range inside its tile: number of workgroup boundaries before it
+        const int64_t tile_first = (int64_t)tile * chunks;
+        const int piece = (int)(blockIdx.x - tile_first / per_wg);    // 0 for the workgroup whose range reaches the tile first
+        int I, J;
+        tile_decode(tile, I, J);
+        const int i0 = I * XT, j0 = J * XT;
+
+        // clamped row pointers: rows past d produce outputs that are never stored
+        const float* __restrict__ arow[4];
+        const float* __restrict__ brow[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int ra = i0 + lr + 32 * u, rb = j0 + lr + 32 * u;
-            const int64_t k = kk + lk;
-            float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
-            if (VEC && k + 3 < k_end) {
-                if (ra < d) va = *reinterpret_cast<const float4*>(X + (int64_t)ra * ld + k);
-                if (rb < d) vb = *reinterpret_cast<const float4*>(X + (int64_t)rb * ld + k);
-            } else {
-                if (ra < d) {
-                    const float* src = X + (int64_t)ra * ld;
-                    if (k + 0 < k_end) va.x = src[k + 0];
-                    if (k + 1 < k_end) va.y = src[k + 1];
-                    if (k + 2 < k_end) va.z = src[k + 2];
-                    if (k + 3 < k_end) va.w = src[k + 3];
+            arow[u] = X + (int64_t)min(i0 + lr + 32 * u, d - 1) * ld;
+            brow[u] = X + (int64_t)min(j0 + lr + 32 * u, d - 1) * ld;
+        }
+        float4 pa[4], pb[4];
+        auto gload = [&](int c) {
+            const int64_t k = (int64_t)c * XK + lk;
+            if (FAST && k + 3 < n) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    pa[u] = *reinterpret_cast<const float4*>(arow[u] + k);
+                    pb[u] = *reinterpret_cast<const float4*>(brow[u] + k);
                 }
-                if (rb < d) {
-                    const float* src = X + (int64_t)rb * ld;
-                    if (k + 0 < k_end) vb.x = src[k + 0];
-                    if (k + 1 < k_end) vb.y = src[k + 1];
-                    if (k + 2 < k_end) vb.z = src[k + 2];
-                    if (k + 3 < k_end) vb.w = src[k + 3];
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
+                    if (k + 0 < n) { va.x = arow[u][k + 0]; vb.x = brow[u][k + 0]; }
+                    if (k + 1 < n) { va.y = arow[u][k + 1]; vb.y = brow[u][k + 1]; }
+                    if (k + 2 < n) { va.z = arow[u][k + 2]; vb.z = brow[u][k + 2]; }
+                    if (k + 3 < n) { va.w = arow[u][k + 3]; vb.w = brow[u][k + 3]; }
+                    pa[u] = va;
+                    pb[u] = vb;
                 }
             }
-            pa[u] = va;
-            pb[u] = vb;
-        }
-    };
-    auto sstore = [&]() {
+        };
+        auto sstore = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            *reinterpret_cast<float4*>(&As[lr + 32 * u][lk]) = pa[u];
-            *reinterpret_cast<float4*>(&Bs[lr + 32 * u][lk]) = pb[u];
-        }
-    };
+            for (int u = 0; u < 4; ++u) {
+                *reinterpret_cast<float4*>(&As[buf][lr + 32 * u][lk]) = pa[u];
+                *reinterpret_cast<float4*>(&Bs[buf][lr + 32 * u][lk]) = pb[u];
+            }
+        };
 
-    d4 acc[4][4];
+        d4 acc[4][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+            for (int j = 0; j < 4; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
 
-    gload(k_begin);
-    for (int64_t kk = k_begin; kk < k_end; kk += XK) {
-        __syncthreads();          // previous stage fully consumed
-        sstore();
+        __syncthreads();              // LDS free (previous tile's last stage consumed)
+        gload(c_begin);
+        sstore(0);
         __syncthreads();
-        if (kk + XK < k_end) gload(kk + XK);
+        int cur = 0;
+        for (int c = c_begin; c < c_end; ++c) {
+            const bool more = c + 1 < c_end;
+            if (more) gload(c + 1);
 #pragma unroll
-        for (int ks = 0; ks < XK / 4; ++ks) {
-            double a[4], b[4];
+            for (int g = 0; g < XK / 16; ++g) {
+                float4 fa[4], fb[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = (double)As[wm * 64 + i * 16 + (lane & 15)][ks * 4 + (lane >> 4)];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = (double)Bs[wn * 64 + j * 16 + (lane & 15)][ks * 4 + (lane >> 4)];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i)
+                    fa[i] = *reinterpret_cast<const float4*>(&As[cur][wm * 64 + i * 16 + fr][g * 16 + fk]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-    }
-
-    double* __restrict__ out = Hpart + (int64_t)split * d * d;
+                    fb[j] = *reinterpret_cast<const float4*>(&Bs[cur][wn * 64 + j * 16 + fr][g * 16 + fk]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+                for (int ks = 0; ks < 4; ++ks) {
+                    double a[4], b[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+                    for (int i = 0; i < 4; ++i)
+                        a[i] = (double)(ks == 0 ? fa[i].x : ks == 1 ? fa[i].y : ks == 2 ? fa[i].z : fa[i].w);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gr = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4);
-                const int gc = j0 + wn * 64 + j * 16 + (lane & 15);
-                if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
+                    for (int j = 0; j < 4; ++j)
+                        b[j] = (double)(ks == 0 ? fb[j].x : ks == 1 ? fb[j].y : ks == 2 ? fb[j].z : fb[j].w);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
             }
+            if (more) sstore(cur ^ 1);
+            __syncthreads();
+            cur ^= 1;
+        }
+
+        double* __restrict__ out = Hpart + (int64_t)piece * d * d;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int gr = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4);
+                    const int gc = j0 + wn * 64 + j * 16 + (lane & 15);
+                    if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
+                }
+        item += c_end - c_begin;
+    }
 }
 
+// Number of d x d slabs of partial sums = the most pieces a tile can be cut into:
+// with XXT_WGS equal ranges over tiles * chunks items, a tile spans at most
+// ceil(XXT_WGS / tiles) ranges, plus one when it starts inside a range.
 int xxt_pick_splits(int d)
 {
     const int nt = (d + XT - 1) / XT;
-    const int tiles = nt * (nt + 1) / 2;
-    int s = (1024 + tiles - 1) / tiles;   // aim at ~4 workgroups per compute unit
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    return s;
+    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
+    return (int)((XXT_WGS + tiles - 1) / tiles) + 1;
 }
 
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
 {
     const int nt = (d + XT - 1) / XT;
-    const int tiles = nt * (nt + 1) / 2;
-    int64_t kper = (n + splits - 1) / splits;
-    kper = (kper + XK - 1) / XK * XK;
-    dim3 grid(tiles, splits), block(256);
-    const bool vec = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    if (vec) hipLaunchKernelGGL((xxt_kernel<true>), grid, block, 0, s, X, ld, d, n, Hpart, kper);
-    else     hipLaunchKernelGGL((xxt_kernel<false>), grid, block, 0, s, X, ld, d, n, Hpart, kper);
+    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
+    const int chunks = (int)((n + XK - 1) / XK);
+    const int64_t total = tiles * chunks;
+    // each workgroup's range must be long enough that no tile is cut into more than `splits` pieces
+    int64_t per_wg = (total + XXT_WGS - 1) / XXT_WGS;
+    const int64_t min_per = splits > 1 ? (chunks + splits - 2) / (splits - 1) : chunks;
+    if (per_wg < min_per) per_wg = min_per;
+    const int wgs = (int)((total + per_wg - 1) / per_wg);
+    dim3 grid(wgs), block(256);
+    const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    if (fast) hipLaunchKernelGGL((xxt_kernel<true>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total);
+    else      hipLaunchKernelGGL((xxt_kernel<false>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total);
     return hipGetLastError();
 }
 
