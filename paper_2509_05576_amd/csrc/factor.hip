@@ -92,36 +92,58 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
         const int base = 16 * b;
         if (wave == 0) {
             // unblocked Cholesky of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of the
-            // symmetric tile and row r of X (starts as identity, ends as the tile's L^-1)
+            // symmetric tile
             const int r = fr;
-            double a[16], x[16];
+            double a[16], rsv[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
+            for (int j = 0; j < 16; ++j)
                 a[j] = (j <= r) ? Am[(base + r) * DL + base + j] : Am[(base + j) * DL + base + r];
-                x[j] = (j == r) ? 1.0 : 0.0;
-            }
+            // the pivot of step k+1 is final as soon as column k+1 has been updated in step k, so
+            // that update is done first and the next reciprocal square root is started before the
+            // remaining updates of step k (they fill its latency)
+            bool bad = false;
+            double piv = readlane_f64(a[0], 0);
+            bad = bad || !(piv > 0.0) || !(piv < 1.0e300);
+            piv = bad ? 1.0 : piv;
+            double rs = rsqrt(piv);
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                double piv = readlane_f64(a[k], k);
-                if (!(piv > 0.0) || !(piv < 1.0e300)) { if (lane == 0) *flag = 1; piv = 1.0; }
-                const double rs = rsqrt(piv);
+                rsv[k] = rs;                                           // 1 / L[k][k]
                 const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
                 const double lm = (r > k) ? t : 0.0;
-#pragma unroll
-                for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
                 a[k] = t;
-#pragma unroll
-                for (int c = 0; c <= k; ++c) {
-                    const double xs = readlane_f64(x[c], k) * rs;
-                    x[c] = (r == k) ? xs : x[c] - lm * xs;
+                if (k + 1 < 16) {
+                    a[k + 1] -= lm * readlane_f64(t, k + 1);
+                    piv = readlane_f64(a[k + 1], k + 1);
+                    const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+                    bad = bad || b2;
+                    piv = b2 ? 1.0 : piv;
+                    rs = rsqrt(piv);
                 }
+#pragma unroll
+                for (int j = k + 2; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
+            }
+            if (bad && lane == 0) *flag = 1;
+            if (lane < 16) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) Am[(base + r) * DL + base + j] = (j <= r) ? a[j] : 0.0;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // the tile's inverse by forward substitution: lane c (mod 16) solves L x = e_c; the
+            // entries of L are wavefront-uniform LDS reads
+            double sv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sv[i] = (i == r) ? 1.0 : 0.0;
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                const double xm = sv[m] * rsv[m];
+                sv[m] = xm;
+#pragma unroll
+                for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + i) * DL + base + m] * xm;
             }
             if (lane < 16) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    Am[(base + r) * DL + base + j] = (j <= r) ? a[j] : 0.0;
-                    Xm[(base + r) * DL + base + j] = (j <= r) ? x[j] : 0.0;
-                }
+                for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + r] = sv[i];
             }
         }
         __syncthreads();
@@ -279,27 +301,35 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
         const int base = 16 * b;
         if (wave == 0) {
             // unblocked elimination of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of
-            // the symmetric tile and row r of X (identity -> (Un_bb^T)^-1)
+            // the symmetric tile
             const int r = fr;
-            double a[16], x[16], pinv[16];
+            double a[16], pinv[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
-                x[j] = (j == r) ? 1.0 : 0.0;
-            }
+            for (int j = 0; j < 16; ++j) a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+            // as in chol_diag_kernel: update column k+1 first, start the next reciprocal, then the rest
+            bool bad = false;
+            double piv = readlane_f64(a[0], 0);
+            bad = bad || !(piv > 0.0) || !(piv < 1.0e300);
+            piv = bad ? 1.0 : piv;
+            double pi = 1.0 / piv;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                double piv = readlane_f64(a[k], k);
-                if (!(piv > 0.0) || !(piv < 1.0e300)) { if (lane == 0) *flag = 1; piv = 1.0; }
-                pinv[k] = 1.0 / piv;
+                pinv[k] = pi;
                 const double cr = (r == k) ? piv : a[k];          // A[k][r] = U[k][r] for r >= k
-                const double fm = (r > k) ? cr * pinv[k] : 0.0;   // Un[k][r]
-#pragma unroll
-                for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
+                const double fm = (r > k) ? cr * pi : 0.0;        // Un[k][r]
                 a[k] = cr;
+                if (k + 1 < 16) {
+                    a[k + 1] -= fm * readlane_f64(cr, k + 1);
+                    piv = readlane_f64(a[k + 1], k + 1);
+                    const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+                    bad = bad || b2;
+                    piv = b2 ? 1.0 : piv;
+                    pi = 1.0 / piv;
+                }
 #pragma unroll
-                for (int c = 0; c <= k; ++c) x[c] -= fm * readlane_f64(x[c], k);
+                for (int j = k + 2; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
             }
+            if (bad && lane == 0) *flag = 1;
             if (lane < 16) {
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
@@ -308,9 +338,24 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
                         Am[(base + k) * DL + base + r] = a[k];
                         Um[(base + k) * DL + base + r] = (k == r) ? 1.0 : a[k] * pinv[k];
                     }
-                    Xm[(base + r) * DL + base + k] = (k <= r) ? x[k] : 0.0;
                     if (k == r) rv[base + k] = pinv[k];
                 }
+            }
+            __builtin_amdgcn_wave_barrier();
+            // G_bb = (Un_bb^T)^-1 (unit lower) by forward substitution: lane c (mod 16) solves
+            // Un_bb^T x = e_c; entry [i][m] of Un_bb^T is Un[m][i], a wavefront-uniform LDS read
+            double sv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sv[i] = (i == r) ? 1.0 : 0.0;
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                const double xm = sv[m];
+#pragma unroll
+                for (int i = m + 1; i < 16; ++i) sv[i] -= Um[(base + m) * DL + base + i] * xm;
+            }
+            if (lane < 16) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + r] = sv[i];
             }
         }
         __syncthreads();

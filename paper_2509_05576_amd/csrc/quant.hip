@@ -128,36 +128,46 @@ hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int b
 // Order (Section 4.2 step 3): descending S, equal scores keep index order.
 // rank_j = #{k : S_k > S_j or (S_k == S_j and k < j)}; perm[rank_j] = j.
 // A score that is not finite compares as -infinity so that perm stays a permutation.
-__global__ __launch_bounds__(256) void rank_sort_kernel(const double* __restrict__ S, int d, int* __restrict__ perm,
-                                                        int* __restrict__ invperm)
+__device__ __forceinline__ double sort_key(double v)
+{
+    return (!(v == v) || v > 1.0e300 || v < -1.0e300) ? -1.0e308 : v;
+}
+
+// blockIdx.x: 256 columns j; blockIdx.y: a slice of 256 comparison columns k.  Partial ranks are
+// integers, so adding them with atomics gives the same result in any order.
+__global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ S, int d, int* __restrict__ rank)
 {
     __shared__ double tile[256];
     const int j = blockIdx.x * 256 + threadIdx.x;
-    double sj = (j < d) ? S[j] : 0.0;
-    if (!(sj == sj) || sj > 1.0e300 || sj < -1.0e300) sj = -1.0e308;
-    int rank = 0;
-    for (int base = 0; base < d; base += 256) {
-        const int k = base + threadIdx.x;
-        double sk = (k < d) ? S[k] : 0.0;
-        if (!(sk == sk) || sk > 1.0e300 || sk < -1.0e300) sk = -1.0e308;
-        __syncthreads();
-        tile[threadIdx.x] = sk;
-        __syncthreads();
-        const int lim = min(256, d - base);
-        for (int u = 0; u < lim; ++u) {
-            const double v = tile[u];
-            rank += (v > sj || (v == sj && base + u < j)) ? 1 : 0;
-        }
+    const int base = blockIdx.y * 256;
+    const int k = base + threadIdx.x;
+    tile[threadIdx.x] = (k < d) ? sort_key(S[k]) : 0.0;
+    __syncthreads();
+    if (j >= d) return;
+    const double sj = sort_key(S[j]);
+    const int lim = min(256, d - base);
+    int cnt = 0;
+    for (int u = 0; u < lim; ++u) {
+        const double v = tile[u];
+        cnt += (v > sj || (v == sj && base + u < j)) ? 1 : 0;
     }
-    if (j < d) {
-        perm[rank] = j;
-        invperm[j] = rank;
-    }
+    if (cnt) atomicAdd(&rank[j], cnt);
+}
+
+__global__ __launch_bounds__(256) void rank_scatter_kernel(const int* __restrict__ rank, int d, int* __restrict__ perm)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < d) perm[min(max(rank[j], 0), d - 1)] = j;
 }
 
 hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm)
 {
-    hipLaunchKernelGGL(rank_sort_kernel, dim3((d + 255) / 256), dim3(256), 0, s, S, d, perm, invperm);
+    // invperm doubles as the rank array: invperm[j] = rank of column j = its step
+    hipError_t e = launch_fill_i32(s, invperm, d, 0);
+    if (e != hipSuccess) return e;
+    const int nb = (d + 255) / 256;
+    hipLaunchKernelGGL(rank_count_kernel, dim3(nb, nb), dim3(256), 0, s, S, d, invperm);
+    hipLaunchKernelGGL(rank_scatter_kernel, dim3(nb), dim3(256), 0, s, invperm, d, perm);
     return hipGetLastError();
 }
 
