@@ -25,7 +25,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
-PEAK_HBM_GBS = 8000.0
+# HBM bytes per xxt_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a plain device copy of X (profiles/xxt_kernel_c2_counters.txt); one launch per step only
+MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 4.33e9}
 
 
 def main() -> int:
@@ -37,6 +39,8 @@ def main() -> int:
     ap.add_argument("--block", type=int, default=0, help="0 = blocked (default), 1 = unblocked rank-1 path")
     ap.add_argument("--chunk", type=int, default=0, help="calibration columns per accumulate call (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run one plain device copy of X first (known bytes; calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the method shards by layers / rows, "
@@ -59,6 +63,11 @@ def main() -> int:
     Wd = torch.from_numpy(W).cuda()
     Xd = torch.from_numpy(X).cuda()
     torch.cuda.synchronize()
+
+    if args.copy_probe:
+        probe = Xd.clone()          # reads and writes X.numel() * 4 bytes
+        torch.cuda.synchronize()
+        del probe
 
     ctx = fobq.Ctx(0)
     out = None
@@ -95,7 +104,8 @@ def main() -> int:
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"kernel": "xxt_kernel", "bound": "mfma", "achieved": round(achieved, 3),
                 "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),
-                "traffic": None, "avg_launch_ms": round(avg_ms, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(spec.name) if launches_per_step == 1 else None,
+                "avg_launch_ms": round(avg_ms, 4),
                 "algorithmic_flops_per_launch": flops_per_launch}
 
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
