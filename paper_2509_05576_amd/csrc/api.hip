@@ -103,7 +103,7 @@ static int ensure_factor_ws(fobq_ctx* ctx, int64_t d)
     FOBQ_TRY(ctx->T.ensure(dd), "workspace T");
     FOBQ_TRY(ctx->Hinv.ensure(dd), "workspace Hinv");
     FOBQ_TRY(ctx->U.ensure(dd), "workspace U");
-    FOBQ_TRY(ctx->Dblk.ensure((3 * 64 * 64 + 64) * sizeof(double)), "workspace Dblk");
+    FOBQ_TRY(ctx->Dblk.ensure((4 * 64 * 64 + 128) * sizeof(double)), "workspace Dblk");
     FOBQ_TRY(ctx->scal.ensure(16 * sizeof(double)), "workspace scal");
     FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
     FOBQ_TRY(ctx->hdiag.ensure((size_t)d * sizeof(double)), "workspace hdiag");

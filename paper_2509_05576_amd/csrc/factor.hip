@@ -65,29 +65,17 @@ __device__ __forceinline__ void assemble_inverse(double* Xm, TF tfetch, int wave
     }
 }
 
-// Diagonal block of the Cholesky factorization.
-//   in : A[o:o+nb, o:o+nb] (symmetric; only the lower triangle is read)
-//   out: L[o:o+nb, o:o+nb] = L11 (lower, upper part zeroed)
-//        Linv[o:o+nb, o:o+nb] = L11^-1 (lower, upper part zeroed)
-//        Dinv (64 x 64, ld 64) = L11^-1 zero padded
-//   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1
-//         so that the arithmetic stays finite; the caller reports ENOTPD).
-__global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
-                                                        double* __restrict__ L, double* __restrict__ Linv,
-                                                        double* __restrict__ Dinv, int* __restrict__ flag)
+// Cholesky of the 64 x 64 block held in LDS.
+//   in : Am lower triangle = the block (identity padding past its size), Xm = 0
+//   out: Am = L (lower; the strictly upper parts of the diagonal 16 x 16 tiles are zeroed),
+//        Xm = L^-1 (lower)
+//   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1 so that
+//         the arithmetic stays finite; the caller reports ENOTPD).
+// Called by all 256 threads of the workgroup; ends with a barrier.
+__device__ __forceinline__ void chol_block(double* Am, double* Xm, int* __restrict__ flag)
 {
-    __shared__ double Am[NB * DL];
-    __shared__ double Xm[NB * DL];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx >> 6, j = idx & 63;
-        double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
-        if (i < nb && j < nb) v = (j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
-        Am[i * DL + j] = v;
-        Xm[i * DL + j] = 0.0;
-    }
-    __syncthreads();
     for (int b = 0; b < 4; ++b) {
         const int base = 16 * b;
         if (wave == 0) {
@@ -179,7 +167,13 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
         __syncthreads();
     }
     assemble_inverse(Xm, [&](int i, int m, int ks) { return Am[(16 * i + fr) * DL + 16 * m + 4 * ks + fq]; }, wave, fr, fq);
-    for (int idx = tid; idx < NB * NB; idx += 256) {
+}
+
+__device__ __forceinline__ void chol_block_store(const double* Am, const double* Xm, int64_t ld, int o, int nb,
+                                                 double* __restrict__ L, double* __restrict__ Linv,
+                                                 double* __restrict__ Dinv)
+{
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
         const double xv = (in && j <= i) ? Xm[i * DL + j] : 0.0;
@@ -191,32 +185,179 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
     }
 }
 
+// Diagonal block of the Cholesky factorization (stand-alone launch: first block, and every
+// block of the unfused path).
+//   in : A[o:o+nb, o:o+nb] (symmetric; only the lower triangle is read)
+//   out: L[o:o+nb, o:o+nb] = L11 (lower, upper part zeroed)
+//        Linv[o:o+nb, o:o+nb] = L11^-1 (lower, upper part zeroed)
+//        Dinv (64 x 64, ld 64) = L11^-1 zero padded
+__global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
+                                                        double* __restrict__ L, double* __restrict__ Linv,
+                                                        double* __restrict__ Dinv, int* __restrict__ flag)
+{
+    __shared__ double Am[NB * DL];
+    __shared__ double Xm[NB * DL];
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
+        if (i < nb && j < nb) v = (j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
+        Am[i * DL + j] = v;
+        Xm[i * DL + j] = 0.0;
+    }
+    __syncthreads();
+    chol_block(Am, Xm, flag);
+    chol_block_store(Am, Xm, ld, o, nb, L, Linv, Dinv);
+}
+
+// t = big (big + 1) / 2 + small, 0 <= small <= big
+__device__ __forceinline__ void tri_decode(int t, int& big, int& small)
+{
+    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while ((i + 1) * (i + 2) / 2 <= t) ++i;
+    while (i * (i + 1) / 2 > t) --i;
+    big = i;
+    small = t - i * (i + 1) / 2;
+}
+
+// One whole iteration of the blocked Cholesky factorization in a single launch.  The panel is
+// the 64 columns o .. o+63, whose diagonal block has already been factored (Dinv = L11^-1).
+// Workgroup (ti, tj), ti >= tj, owns the 64 x 64 tile (ti, tj) of the trailing matrix:
+//   1. it recomputes the two panel blocks it needs, L21_i = A21_i L11^-T and L21_j (three
+//      rank-64 MFMA products per tile instead of one, in exchange for not waiting on a
+//      separate panel launch); the tiles of the first tile column also store L21_i into L;
+//   2. A22(ti, tj) -= L21_i L21_j^T;
+//   3. workgroup 0 owns tile (0, 0), the next diagonal block: it does not write it back but
+//      factors it right away (chol_block) and stores L11, L11^-1 and Dinv_next for the next
+//      launch, overlapped with the other tiles of this launch.
+__global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
+                                                        const double* __restrict__ Dinv, double* __restrict__ L,
+                                                        double* __restrict__ Linv, double* __restrict__ Dinv_next,
+                                                        int* __restrict__ flag)
+{
+    __shared__ double lds[3 * NB * DL];
+    double* Gs = lds;
+    double* Pi = lds + NB * DL;
+    double* Pj = lds + 2 * NB * DL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int r0 = o + NB;
+    int ti, tj;
+    tri_decode(blockIdx.x, ti, tj);
+    const bool diag_tile = ti == tj;
+    const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
+
+#pragma unroll 4
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Gs[y * DL + x] = Dinv[y * NB + x];
+        const int gi = mi0 + y, gj = mj0 + y;
+        Pi[y * DL + x] = (gi < d) ? Hd[(int64_t)gi * d + o + x] : 0.0;
+        if (!diag_tile) Pj[y * DL + x] = (gj < d) ? Hd[(int64_t)gj * d + o + x] : 0.0;
+    }
+    d4 c[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+                c[i][j][v] = (gm < d && gn < d) ? Hd[(int64_t)gm * d + gn] : 0.0;
+            }
+    __syncthreads();
+
+    d4 li[2][2], lj[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; lj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+    for (int ks = 0; ks < 16; ++ks) {
+        double b[2], ai[2], aj[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = Gs[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            ai[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+            aj[i] = diag_tile ? 0.0 : Pj[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                li[i][j] = mfma4(ai[i], b[j], li[i][j]);
+                if (!diag_tile) lj[i][j] = mfma4(aj[i], b[j], lj[i][j]);
+            }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                Pi[m * DL + n] = li[i][j][v];
+                if (!diag_tile) Pj[m * DL + n] = lj[i][j][v];
+                if (tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[i][j][v];
+            }
+    __syncthreads();
+    const double* Qj = diag_tile ? Pi : Pj;
+    for (int ks = 0; ks < 16; ++ks) {
+        double a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = -Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = Qj[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+    }
+    if (blockIdx.x != 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+                    if (gm < d && gn < d) Hd[(int64_t)gm * d + gn] = c[i][j][v];
+                }
+        return;
+    }
+    // tile (0, 0): the next diagonal block, of size nbn
+    const int nbn = min(NB, d - r0);
+    __syncthreads();
+    double* Am = Pi;
+    double* Xm = Gs;
+    for (int idx = tid; idx < NB * NB; idx += 256) Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
+            }
+    __syncthreads();
+    chol_block(Am, Xm, flag);
+    chol_block_store(Am, Xm, d, r0, nbn, L, Linv, Dinv_next);
+}
+
+// H_d = L L^T.  One stand-alone launch for the first diagonal block, then one fused launch
+// per 64-column panel.
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag)
 {
     hipStream_t s = c->stream;
-    double* Dinv = c->Dblk.as<double>();
-    for (int o = 0; o < d; o += NB) {
-        const int nb = min(NB, d - o);
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), 0, s, Hd, (int64_t)d, o, nb, L, Linv, Dinv, flag);
-        const int r = d - o - nb;
-        if (r <= 0) break;
-        // L21 = A21 * L11^-T
-        GemmP p;
-        p.M = r; p.N = nb; p.K = nb;
-        p.A = Hd + (int64_t)(o + nb) * d + o; p.lda = d;
-        p.B = Dinv; p.ldb = NB;
-        p.C = L + (int64_t)(o + nb) * d + o; p.ldc = d;
-        hipError_t e = gemm64(s, p, false, true);
-        if (e != hipSuccess) return e;
-        // A22 -= L21 L21^T  (lower tiles)
-        GemmP q;
-        q.M = r; q.N = r; q.K = nb;
-        q.A = L + (int64_t)(o + nb) * d + o; q.lda = d;
-        q.B = q.A; q.ldb = d;
-        q.C = Hd + (int64_t)(o + nb) * d + (o + nb); q.ldc = d;
-        q.alpha = -1.0; q.beta = 1.0; q.cmode = CMODE_LOWER;
-        e = gemm64(s, q, false, true);
-        if (e != hipSuccess) return e;
+    double* Dinv[2] = {c->Dblk.as<double>(), c->Dblk.as<double>() + NB * NB};
+    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), 0, s, Hd, (int64_t)d, 0, min(NB, d), L, Linv, Dinv[0],
+                       flag);
+    int it = 0;
+    for (int o = 0; o + NB < d; o += NB, ++it) {
+        const int T = (d - o - NB + NB - 1) / NB;
+        hipLaunchKernelGGL(chol_iter_kernel, dim3(T * (T + 1) / 2), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                           Dinv[(it + 1) & 1], flag);
     }
     return hipGetLastError();
 }
@@ -268,35 +409,16 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 }
 
 // ---------------------------------------------------------------------------
-// Diagonal block of the shared-Hinv elimination (Eq. 12 for nb consecutive steps
-// restricted to the block).  With A11 the current block, U11 its pivot rows,
-// D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
-//   out: U[o+j, o+j : o+nb]  = pivot row j inside the block
-//        Un = U / pivot
-//        G (64 x 64, ld 64)  = (Un11^T)^-1 (unit lower): pivot rows right of the
-//                              block are G * A[o:o+nb, o+nb:]
-//        rinv[j] = 1 / pivot_j
-// Same tile scheme as chol_diag_kernel, without square roots.
-__global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
-                                                        double* __restrict__ U, double* __restrict__ Un,
-                                                        double* __restrict__ G, double* __restrict__ rinv,
-                                                        int* __restrict__ flag)
+// Shared-Hinv elimination (Eq. 12) of the 64 x 64 block held in LDS.  With A11 the block,
+// U11 its pivot rows, D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
+//   in : Am = the block, full symmetric (identity padding past its size), Um = Xm = 0
+//   out: Am upper triangle = U11 (pivot row j = row j), Um upper = Un11,
+//        Xm = G = (Un11^T)^-1 (unit lower), rv[j] = 1 / pivot_j
+// Called by all 256 threads of the workgroup; ends with a barrier.
+__device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, double* rv, int* __restrict__ flag)
 {
-    __shared__ double Am[NB * DL];     // current block (full symmetric); rows become pivot rows U
-    __shared__ double Um[NB * DL];     // Un
-    __shared__ double Xm[NB * DL];     // G
-    __shared__ double rv[NB];          // 1 / pivot
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int i = idx >> 6, j = idx & 63;
-        double v = (i == j) ? 1.0 : 0.0;
-        if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
-        Am[i * DL + j] = v;
-        Um[i * DL + j] = 0.0;
-        Xm[i * DL + j] = 0.0;
-    }
-    __syncthreads();
     for (int b = 0; b < 4; ++b) {
         const int base = 16 * b;
         if (wave == 0) {
@@ -395,7 +517,14 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
     }
     // G = (Un11^T)^-1: tile T_im of Un11^T is Un_mi transposed
     assemble_inverse(Xm, [&](int i, int m, int ks) { return Um[(16 * m + 4 * ks + fq) * DL + 16 * i + fr]; }, wave, fr, fq);
-    for (int idx = tid; idx < NB * NB; idx += 256) {
+}
+
+__device__ __forceinline__ void elim_block_store(const double* Am, const double* Um, const double* Xm, const double* rv,
+                                                 int64_t ld, int o, int nb, double* __restrict__ U,
+                                                 double* __restrict__ Un, double* __restrict__ G,
+                                                 double* __restrict__ rinv)
+{
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
         G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
@@ -404,14 +533,192 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
             Un[(int64_t)(o + i) * ld + o + j] = Um[i * DL + j];
         }
     }
-    if (tid < NB) rinv[tid] = (tid < nb) ? rv[tid] : 0.0;
+    if (threadIdx.x < NB) rinv[threadIdx.x] = (threadIdx.x < nb) ? rv[threadIdx.x] : 0.0;
 }
 
+// Diagonal block of the elimination (stand-alone launch).
+//   out: U[o+j, o+j : o+nb]  = pivot row j inside the block
+//        Un = U / pivot
+//        G (64 x 64, ld 64)  = (Un11^T)^-1: pivot rows right of the block are G * A[o:o+nb, o+nb:]
+//        rinv[j] = 1 / pivot_j
+__global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
+                                                        double* __restrict__ U, double* __restrict__ Un,
+                                                        double* __restrict__ G, double* __restrict__ rinv,
+                                                        int* __restrict__ flag)
+{
+    __shared__ double Am[NB * DL];
+    __shared__ double Um[NB * DL];
+    __shared__ double Xm[NB * DL];
+    __shared__ double rv[NB];
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+        const int i = idx >> 6, j = idx & 63;
+        double v = (i == j) ? 1.0 : 0.0;
+        if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
+        Am[i * DL + j] = v;
+        Um[i * DL + j] = 0.0;
+        Xm[i * DL + j] = 0.0;
+    }
+    __syncthreads();
+    elim_block(Am, Um, Xm, rv, flag);
+    elim_block_store(Am, Um, Xm, rv, ld, o, nb, U, Un, G, rinv);
+}
+
+// One whole iteration of the blocked shared-Hinv elimination in a single launch (same scheme
+// as chol_iter_kernel).  The panel is the 64 rows/columns o .. o+63 whose diagonal block has
+// been eliminated (G, rinv).  Workgroup (ti, tj), ti <= tj, owns tile (ti, tj) of the trailing
+// matrix (upper triangle):
+//   1. pivot rows right of the block for its two tile columns: U12_i = G A12_i, U12_j, and
+//      Un12 = D^-1 U12; the tiles of the first tile row also store them into U and Un;
+//   2. A22(ti, tj) -= Un12_i^T U12_j        (Eq. 12 for the 64 columns of the panel at once);
+//   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
+__global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, int d, int o,
+                                                        const double* __restrict__ G, const double* __restrict__ rinv,
+                                                        double* __restrict__ U, double* __restrict__ Un,
+                                                        double* __restrict__ G_next, double* __restrict__ rinv_next,
+                                                        int* __restrict__ flag)
+{
+    __shared__ double lds[3 * NB * DL + NB];
+    double* Gs = lds;
+    double* Pi = lds + NB * DL;
+    double* Pj = lds + 2 * NB * DL;
+    double* rs = lds + 3 * NB * DL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int r0 = o + NB;
+    int ti, tj;
+    tri_decode(blockIdx.x, tj, ti);          // ti <= tj
+    const bool diag_tile = ti == tj;
+    const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
+
+#pragma unroll 4
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Gs[y * DL + x] = G[y * NB + x];
+        Pi[y * DL + x] = (ci0 + x < d) ? A[(int64_t)(o + y) * d + ci0 + x] : 0.0;
+        if (!diag_tile) Pj[y * DL + x] = (cj0 + x < d) ? A[(int64_t)(o + y) * d + cj0 + x] : 0.0;
+    }
+    if (tid < NB) rs[tid] = rinv[tid];
+    d4 c[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
+                c[i][j][v] = (gm < d && gn < d) ? A[(int64_t)gm * d + gn] : 0.0;
+            }
+    __syncthreads();
+
+    d4 ui[2][2], uj[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { ui[i][j] = d4{0.0, 0.0, 0.0, 0.0}; uj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+    for (int ks = 0; ks < 16; ++ks) {
+        double a[2], bi[2], bj[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = Gs[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bi[j] = Pi[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+            bj[j] = diag_tile ? 0.0 : Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                ui[i][j] = mfma4(a[i], bi[j], ui[i][j]);
+                if (!diag_tile) uj[i][j] = mfma4(a[i], bj[j], uj[i][j]);
+            }
+    }
+    __syncthreads();
+    // Pi := Un12_i (rows scaled by 1 / pivot), Pj := U12_j
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                const double uiv = ui[i][j][v];
+                const double ujv = diag_tile ? uiv : uj[i][j][v];
+                Pi[m * DL + n] = uiv * rs[m];
+                Pj[m * DL + n] = ujv;
+                if (ti == 0 && cj0 + n < d) {
+                    U[(int64_t)(o + m) * d + cj0 + n] = ujv;
+                    Un[(int64_t)(o + m) * d + cj0 + n] = ujv * rs[m];
+                }
+            }
+    __syncthreads();
+    for (int ks = 0; ks < 16; ++ks) {
+        double a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = -Pi[(4 * ks + fq) * DL + wm * 32 + i * 16 + fr];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+    }
+    if (blockIdx.x != 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
+                    if (gm < d && gn < d) A[(int64_t)gm * d + gn] = c[i][j][v];
+                }
+        return;
+    }
+    // tile (0, 0): the next diagonal block, of size nbn
+    const int nbn = min(NB, d - r0);
+    __syncthreads();
+    double* Am = Pi;
+    double* Um = Pj;
+    double* Xm = Gs;
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
+        Um[(idx >> 6) * DL + (idx & 63)] = 0.0;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
+            }
+    __syncthreads();
+    elim_block(Am, Um, Xm, rs, flag);
+    elim_block_store(Am, Um, Xm, rs, d, r0, nbn, U, Un, G_next, rinv_next);
+}
+
+// Shared-Hinv elimination of the first `steps` columns, `block` columns at a time.
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag)
 {
     hipStream_t s = c->stream;
-    double* G = c->Dblk.as<double>() + NB * NB;
-    double* rinv = c->Dblk.as<double>() + 2 * NB * NB;
+    double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
+    double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
+    if (block == NB && steps == d) {
+        // one stand-alone launch for the first diagonal block, then one fused launch per panel
+        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un, Gb[0],
+                           rb[0], flag);
+        int it = 0;
+        for (int o = 0; o + NB < d; o += NB, ++it) {
+            const int T = (d - o - NB + NB - 1) / NB;
+            hipLaunchKernelGGL(elim_iter_kernel, dim3(T * (T + 1) / 2), dim3(256), 0, s, A, d, o, Gb[it & 1],
+                               rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
+        }
+        return hipGetLastError();
+    }
+    // general form (any block width, partial elimination): diagonal block, pivot rows, trailing update
+    double* G = Gb[0];
+    double* rinv = rb[0];
     for (int o = 0; o < steps; o += block) {
         const int nb = min(block, steps - o);
         hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, o, nb, U, Un, G, rinv, flag);

@@ -81,7 +81,7 @@ struct fobq_ctx {
 
     // factorization / elimination workspace (all d x d fp64 unless noted)
     fobq::DevBuf Hd, Linv, T, Hinv, A, U, Un;
-    fobq::DevBuf Dblk;      // 3 x 64 x 64 fp64 + 64 fp64: diagonal-block scratch
+    fobq::DevBuf Dblk;      // diagonal-block scratch: 2 x (64 x 64) L11^-1, 2 x (64 x 64) G, 2 x 64 reciprocal pivots
     fobq::DevBuf scal;      // a few fp64 scalars (lambda, loss)
     fobq::DevBuf flags;     // int32 status flags written by kernels
     // quantization workspace
