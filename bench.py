@@ -30,6 +30,55 @@ PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
 MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 4.33e9}
 
 
+def sweep(model: str, steps: int, warmup: int) -> int:
+    """Whole-model sweep: every layer of a ResNet-50- or YOLOv5s-shaped network (4-bit, per-row grids),
+    one layer after the other; activations are ReLU(N(0,1)) drawn on the device (torch generator, seed 0)."""
+    import torch
+
+    import paper_2509_05576_amd as fobq
+    import workloads
+
+    fobq.load_library()
+    layers = workloads.sweep_layers(model)
+    gen = torch.Generator(device="cuda")
+    ctx = fobq.Ctx(0)
+    per_layer = []
+    total_ms = 0.0
+    total_weights = 0
+    chunk_elems = 1 << 28                          # calibration columns are accumulated in chunks of <= 1 GiB
+    for spec in layers:
+        gen.manual_seed(spec.layer_index)
+        W = torch.randn((spec.d_row, spec.d_col), generator=gen, device="cuda") * (2.0 / spec.d_col) ** 0.5
+        X = torch.randn((spec.d_col, spec.n), generator=gen, device="cuda").relu_()
+        chunk = max(32, (chunk_elems // spec.d_col) // 32 * 32)
+        out = None
+        best = None
+        for it in range(warmup + steps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx.hessian(X, chunk=chunk)
+            out = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=out)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            if it >= warmup:
+                best = ms if best is None else min(best, ms)
+        per_layer.append({"layer": spec.name, "d_row": spec.d_row, "d_col": spec.d_col, "n": spec.n, "ms": round(best, 3)})
+        total_ms += best
+        total_weights += spec.weights
+        del W, X, out
+        torch.cuda.empty_cache()
+    ctx.close()
+    line = {"metric": f"whole-model quantization time, {model}-shaped network ({len(layers)} layers)",
+            "value": round(total_weights / (total_ms * 1e-3), 1), "unit": "weights/s", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": round(total_ms, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images",
+                       "weights": total_weights},
+            "whole_model_seconds": round(total_ms * 1e-3, 4), "per_layer": per_layer}
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +105,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 2
+    if args.workload in ("sweep_resnet50", "sweep_yolov5s"):
+        return sweep(args.workload[len("sweep_"):], min(args.steps, 3), min(args.warmup, 1))
     fobq.load_library()
     spec = workloads.configs()[args.workload]
     W = spec.make_w()

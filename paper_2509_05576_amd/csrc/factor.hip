@@ -34,6 +34,28 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
     return __hiloint2double(hi, lo);
 }
 
+// Reciprocal and reciprocal square root of a pivot (a normal, positive number): the hardware
+// approximation refined by two Newton steps, accurate to about one ulp.  Shorter dependent
+// chains than an IEEE division / square root, and these sit on the sequential path of the
+// tile factorizations.
+__device__ __forceinline__ double pivot_rcp(double x)
+{
+    double r = __builtin_amdgcn_rcp(x);
+    double e = fma(-x, r, 1.0);
+    r = fma(r, e, r);
+    e = fma(-x, r, 1.0);
+    return fma(r, e, r);
+}
+
+__device__ __forceinline__ double pivot_rsqrt(double x)
+{
+    double y = __builtin_amdgcn_rsq(x);
+    double e = fma(-(x * y), y, 1.0);
+    y = fma(0.5 * y, e, y);
+    e = fma(-(x * y), y, 1.0);
+    return fma(0.5 * y, e, y);
+}
+
 __device__ __forceinline__ d4 mfma4(double a, double b, d4 c)
 {
     return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
@@ -86,30 +108,26 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, int* __restri
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 a[j] = (j <= r) ? Am[(base + r) * DL + base + j] : Am[(base + j) * DL + base + r];
-            // the pivot of step k+1 is final as soon as column k+1 has been updated in step k, so
-            // that update is done first and the next reciprocal square root is started before the
-            // remaining updates of step k (they fill its latency)
+            // Each lane also keeps its own diagonal entry a[r][r] in `dg` and updates it locally
+            // (dg -= l_rk^2), so the pivot of step k+1 is available one fma after l_rk: the
+            // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
+            // rank-1 update of the rest of the tile fills the latency.
+            double dg = Am[(base + r) * DL + base + r];
             bool bad = false;
-            double piv = readlane_f64(a[0], 0);
-            bad = bad || !(piv > 0.0) || !(piv < 1.0e300);
-            piv = bad ? 1.0 : piv;
-            double rs = rsqrt(piv);
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
+                double piv = readlane_f64(dg, k);
+                const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+                bad = bad || b2;
+                piv = b2 ? 1.0 : piv;
+                const double rs = pivot_rsqrt(piv);
                 rsv[k] = rs;                                           // 1 / L[k][k]
                 const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
                 const double lm = (r > k) ? t : 0.0;
+                dg -= lm * lm;
                 a[k] = t;
-                if (k + 1 < 16) {
-                    a[k + 1] -= lm * readlane_f64(t, k + 1);
-                    piv = readlane_f64(a[k + 1], k + 1);
-                    const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-                    bad = bad || b2;
-                    piv = b2 ? 1.0 : piv;
-                    rs = rsqrt(piv);
-                }
 #pragma unroll
-                for (int j = k + 2; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
+                for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
             }
             if (bad && lane == 0) *flag = 1;
             if (lane < 16) {
@@ -229,15 +247,14 @@ __device__ __forceinline__ void tri_decode(int t, int& big, int& small)
 //   3. workgroup 0 owns tile (0, 0), the next diagonal block: it does not write it back but
 //      factors it right away (chol_block) and stores L11, L11^-1 and Dinv_next for the next
 //      launch, overlapped with the other tiles of this launch.
-__global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
+__global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
                                                         const double* __restrict__ Dinv, double* __restrict__ L,
                                                         double* __restrict__ Linv, double* __restrict__ Dinv_next,
                                                         int* __restrict__ flag)
 {
-    __shared__ double lds[3 * NB * DL];
-    double* Gs = lds;
-    double* Pi = lds + NB * DL;
-    double* Pj = lds + 2 * NB * DL;
+    __shared__ double lds[2 * NB * DL];      // two tiles: 2 workgroups per compute unit
+    double* Pi = lds;
+    double* Pj = lds + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
@@ -246,13 +263,21 @@ __global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd,
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
 
-#pragma unroll 4
+    // this lane's B-operand elements of L11^-T for all 16 k-steps, straight from global memory
+    // (32 KB shared by every workgroup of the launch: cache hits)
+    double gb[16][2];
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) gb[ks][j] = Dinv[(wn * 32 + j * 16 + fr) * NB + 4 * ks + fq];
+    // one round of loads (all in flight together), then the stores to LDS
+    double pa[16], pb[16];
+#pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int y = wave + 4 * u, x = lane;
-        Gs[y * DL + x] = Dinv[y * NB + x];
         const int gi = mi0 + y, gj = mj0 + y;
-        Pi[y * DL + x] = (gi < d) ? Hd[(int64_t)gi * d + o + x] : 0.0;
-        if (!diag_tile) Pj[y * DL + x] = (gj < d) ? Hd[(int64_t)gj * d + o + x] : 0.0;
+        pa[u] = (gi < d) ? Hd[(int64_t)gi * d + o + x] : 0.0;
+        pb[u] = (!diag_tile && gj < d) ? Hd[(int64_t)gj * d + o + x] : 0.0;
     }
     d4 c[2][2];
 #pragma unroll
@@ -264,6 +289,12 @@ __global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd,
                 const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
                 c[i][j][v] = (gm < d && gn < d) ? Hd[(int64_t)gm * d + gn] : 0.0;
             }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Pi[y * DL + x] = pa[u];
+        if (!diag_tile) Pj[y * DL + x] = pb[u];
+    }
     __syncthreads();
 
     d4 li[2][2], lj[2][2];
@@ -271,10 +302,11 @@ __global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd,
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; lj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         double b[2], ai[2], aj[2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Gs[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq];
+        for (int j = 0; j < 2; ++j) b[j] = gb[ks][j];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             ai[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
@@ -329,7 +361,7 @@ __global__ __launch_bounds__(256) void chol_iter_kernel(double* __restrict__ Hd,
     const int nbn = min(NB, d - r0);
     __syncthreads();
     double* Am = Pi;
-    double* Xm = Gs;
+    double* Xm = Pj;
     for (int idx = tid; idx < NB * NB; idx += 256) Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -411,11 +443,11 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 // ---------------------------------------------------------------------------
 // Shared-Hinv elimination (Eq. 12) of the 64 x 64 block held in LDS.  With A11 the block,
 // U11 its pivot rows, D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
-//   in : Am = the block, full symmetric (identity padding past its size), Um = Xm = 0
-//   out: Am upper triangle = U11 (pivot row j = row j), Um upper = Un11,
-//        Xm = G = (Un11^T)^-1 (unit lower), rv[j] = 1 / pivot_j
+//   in : Am = the block, full symmetric (identity padding past its size), Xm = 0
+//   out: Am upper triangle = U11 (pivot row j = row j), rv[j] = 1 / pivot_j
+//        (so Un11[i][j] = Am[i][j] * rv[i]),  Xm = G = (Un11^T)^-1 (unit lower)
 // Called by all 256 threads of the workgroup; ends with a barrier.
-__device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, double* rv, int* __restrict__ flag)
+__device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, int* __restrict__ flag)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
@@ -428,38 +460,30 @@ __device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, d
             double a[16], pinv[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
-            // as in chol_diag_kernel: update column k+1 first, start the next reciprocal, then the rest
+            // as in chol_block: every lane keeps its own diagonal entry in `dg`
+            double dg = Am[(base + r) * DL + base + r];
             bool bad = false;
-            double piv = readlane_f64(a[0], 0);
-            bad = bad || !(piv > 0.0) || !(piv < 1.0e300);
-            piv = bad ? 1.0 : piv;
-            double pi = 1.0 / piv;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
+                double piv = readlane_f64(dg, k);
+                const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+                bad = bad || b2;
+                piv = b2 ? 1.0 : piv;
+                const double pi = pivot_rcp(piv);
                 pinv[k] = pi;
                 const double cr = (r == k) ? piv : a[k];          // A[k][r] = U[k][r] for r >= k
                 const double fm = (r > k) ? cr * pi : 0.0;        // Un[k][r]
+                dg -= fm * cr;
                 a[k] = cr;
-                if (k + 1 < 16) {
-                    a[k + 1] -= fm * readlane_f64(cr, k + 1);
-                    piv = readlane_f64(a[k + 1], k + 1);
-                    const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-                    bad = bad || b2;
-                    piv = b2 ? 1.0 : piv;
-                    pi = 1.0 / piv;
-                }
 #pragma unroll
-                for (int j = k + 2; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
+                for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
             }
             if (bad && lane == 0) *flag = 1;
             if (lane < 16) {
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     // lane r holds column r of the pivot rows: U[k][r] for k <= r
-                    if (k <= r) {
-                        Am[(base + k) * DL + base + r] = a[k];
-                        Um[(base + k) * DL + base + r] = (k == r) ? 1.0 : a[k] * pinv[k];
-                    }
+                    if (k <= r) Am[(base + k) * DL + base + r] = a[k];
                     if (k == r) rv[base + k] = pinv[k];
                 }
             }
@@ -473,7 +497,7 @@ __device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, d
             for (int m = 0; m < 16; ++m) {
                 const double xm = sv[m];
 #pragma unroll
-                for (int i = m + 1; i < 16; ++i) sv[i] -= Um[(base + m) * DL + base + i] * xm;
+                for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + m) * DL + base + i] * pinv[m] * xm;
             }
             if (lane < 16) {
 #pragma unroll
@@ -490,10 +514,7 @@ __device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, d
                 for (int ks = 0; ks < 4; ++ks)
                     acc = mfma4(Xm[(base + fr) * DL + base + 4 * ks + fq], Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    Am[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
-                    Um[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v] * rv[base + 4 * v + fq];
-                }
+                for (int v = 0; v < 4; ++v) Am[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
             }
         }
         __syncthreads();
@@ -508,7 +529,8 @@ __device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, d
                     for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
-                        acc = mfma4(-Um[(base + 4 * ks + fq) * DL + 16 * i + fr], Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
+                        acc = mfma4(-Am[(base + 4 * ks + fq) * DL + 16 * i + fr] * rv[base + 4 * ks + fq],
+                                    Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
                 }
@@ -516,10 +538,11 @@ __device__ __forceinline__ void elim_block(double* Am, double* Um, double* Xm, d
         __syncthreads();
     }
     // G = (Un11^T)^-1: tile T_im of Un11^T is Un_mi transposed
-    assemble_inverse(Xm, [&](int i, int m, int ks) { return Um[(16 * m + 4 * ks + fq) * DL + 16 * i + fr]; }, wave, fr, fq);
+    assemble_inverse(Xm, [&](int i, int m, int ks) {
+        return Am[(16 * m + 4 * ks + fq) * DL + 16 * i + fr] * rv[16 * m + 4 * ks + fq]; }, wave, fr, fq);
 }
 
-__device__ __forceinline__ void elim_block_store(const double* Am, const double* Um, const double* Xm, const double* rv,
+__device__ __forceinline__ void elim_block_store(const double* Am, const double* Xm, const double* rv,
                                                  int64_t ld, int o, int nb, double* __restrict__ U,
                                                  double* __restrict__ Un, double* __restrict__ G,
                                                  double* __restrict__ rinv)
@@ -530,7 +553,7 @@ __device__ __forceinline__ void elim_block_store(const double* Am, const double*
         G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
         if (in && j >= i) {
             U[(int64_t)(o + i) * ld + o + j] = Am[i * DL + j];
-            Un[(int64_t)(o + i) * ld + o + j] = Um[i * DL + j];
+            Un[(int64_t)(o + i) * ld + o + j] = (i == j) ? 1.0 : Am[i * DL + j] * rv[i];
         }
     }
     if (threadIdx.x < NB) rinv[threadIdx.x] = (threadIdx.x < nb) ? rv[threadIdx.x] : 0.0;
@@ -547,7 +570,6 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
                                                         int* __restrict__ flag)
 {
     __shared__ double Am[NB * DL];
-    __shared__ double Um[NB * DL];
     __shared__ double Xm[NB * DL];
     __shared__ double rv[NB];
     for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
@@ -555,12 +577,11 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
         double v = (i == j) ? 1.0 : 0.0;
         if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
         Am[i * DL + j] = v;
-        Um[i * DL + j] = 0.0;
         Xm[i * DL + j] = 0.0;
     }
     __syncthreads();
-    elim_block(Am, Um, Xm, rv, flag);
-    elim_block_store(Am, Um, Xm, rv, ld, o, nb, U, Un, G, rinv);
+    elim_block(Am, Xm, rv, flag);
+    elim_block_store(Am, Xm, rv, ld, o, nb, U, Un, G, rinv);
 }
 
 // One whole iteration of the blocked shared-Hinv elimination in a single launch (same scheme
@@ -571,17 +592,16 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
 //      Un12 = D^-1 U12; the tiles of the first tile row also store them into U and Un;
 //   2. A22(ti, tj) -= Un12_i^T U12_j        (Eq. 12 for the 64 columns of the panel at once);
 //   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
-__global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, int d, int o,
+__global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ A, int d, int o,
                                                         const double* __restrict__ G, const double* __restrict__ rinv,
                                                         double* __restrict__ U, double* __restrict__ Un,
                                                         double* __restrict__ G_next, double* __restrict__ rinv_next,
                                                         int* __restrict__ flag)
 {
-    __shared__ double lds[3 * NB * DL + NB];
-    double* Gs = lds;
-    double* Pi = lds + NB * DL;
-    double* Pj = lds + 2 * NB * DL;
-    double* rs = lds + 3 * NB * DL;
+    __shared__ double lds[2 * NB * DL + NB];   // two tiles: 2 workgroups per compute unit
+    double* Pi = lds;
+    double* Pj = lds + NB * DL;
+    double* rs = lds + 2 * NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
@@ -590,14 +610,21 @@ __global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, 
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
 
-#pragma unroll 4
+    // this lane's A-operand elements of G for all 16 k-steps, straight from global memory
+    double ga[16][2];
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) ga[ks][i] = G[(wm * 32 + i * 16 + fr) * NB + 4 * ks + fq];
+    // one round of loads (all in flight together), then the stores to LDS
+    double pa[16], pb[16];
+#pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int y = wave + 4 * u, x = lane;
-        Gs[y * DL + x] = G[y * NB + x];
-        Pi[y * DL + x] = (ci0 + x < d) ? A[(int64_t)(o + y) * d + ci0 + x] : 0.0;
-        if (!diag_tile) Pj[y * DL + x] = (cj0 + x < d) ? A[(int64_t)(o + y) * d + cj0 + x] : 0.0;
+        pa[u] = (ci0 + x < d) ? A[(int64_t)(o + y) * d + ci0 + x] : 0.0;
+        pb[u] = (!diag_tile && cj0 + x < d) ? A[(int64_t)(o + y) * d + cj0 + x] : 0.0;
     }
-    if (tid < NB) rs[tid] = rinv[tid];
+    const double rsv = (tid < NB) ? rinv[tid] : 0.0;
     d4 c[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -608,6 +635,13 @@ __global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, 
                 const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
                 c[i][j][v] = (gm < d && gn < d) ? A[(int64_t)gm * d + gn] : 0.0;
             }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Pi[y * DL + x] = pa[u];
+        if (!diag_tile) Pj[y * DL + x] = pb[u];
+    }
+    if (tid < NB) rs[tid] = rsv;
     __syncthreads();
 
     d4 ui[2][2], uj[2][2];
@@ -615,10 +649,11 @@ __global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) { ui[i][j] = d4{0.0, 0.0, 0.0, 0.0}; uj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         double a[2], bi[2], bj[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = Gs[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+        for (int i = 0; i < 2; ++i) a[i] = ga[ks][i];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             bi[j] = Pi[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
@@ -678,12 +713,7 @@ __global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, 
     const int nbn = min(NB, d - r0);
     __syncthreads();
     double* Am = Pi;
-    double* Um = Pj;
-    double* Xm = Gs;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
-        Um[(idx >> 6) * DL + (idx & 63)] = 0.0;
-    }
+    double* Xm = Pj;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -692,10 +722,11 @@ __global__ __launch_bounds__(256) void elim_iter_kernel(double* __restrict__ A, 
             for (int v = 0; v < 4; ++v) {
                 const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
                 Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
+                Xm[m * DL + n] = 0.0;
             }
     __syncthreads();
-    elim_block(Am, Um, Xm, rs, flag);
-    elim_block_store(Am, Um, Xm, rs, d, r0, nbn, U, Un, G_next, rinv_next);
+    elim_block(Am, Xm, rs, flag);
+    elim_block_store(Am, Xm, rs, d, r0, nbn, U, Un, G_next, rinv_next);
 }
 
 // Shared-Hinv elimination of the first `steps` columns, `block` columns at a time.

@@ -275,6 +275,32 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
     return __hiloint2double(hi, lo);
 }
 
+// The 64 sequential steps of one row.  EXACT = false forms the quotient w / s as w * (1 / s)
+// (the product is within 2 ulp of the true quotient, so rint of it can differ from
+// rint(w / s) only when it lies within 2 ulp of a half-integer) and reports through `suspect`
+// whether any lane came that close; EXACT = true uses the true division.  The dependent chain
+// per step is: multiply, rint, max, min, fma, readlane, fma.
+template <bool EXACT>
+__device__ __forceinline__ void chain_steps(double& w, const double (&u)[64], double s, double z, double maxq, int nb,
+                                            int lane, double& mycode, double& mydiff, bool& suspect)
+{
+    const double rcp_s = 1.0 / s;
+    const double lo = -z, hi = maxq - z;          // clamp(c + z, 0, maxq) - z = clamp(c, -z, maxq - z)
+#pragma unroll
+    for (int j = 0; j < 64; ++j) {
+        if (j < nb) {                             // uniform
+            const double tq = EXACT ? w / s : w * rcp_s;
+            const double c0 = rint(tq);
+            if (!EXACT) suspect = suspect || (fabs(fabs(tq - c0) - 0.5) < 1.0e-9 * fmax(1.0, fabs(tq)));
+            const double cz = fmin(fmax(c0, lo), hi);        // code - zero
+            const double df = w - s * cz;
+            const double dj = readlane_f64(df, j);
+            if (lane == j) { mycode = cz + z; mydiff = df; }
+            w -= dj * u[j];                       // u[j] is 0 for lanes <= j: they keep the value they were quantized at
+        }
+    }
+}
+
 __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
     double* __restrict__ Wp, int R, int d, int o, int nb, const double* __restrict__ Un,
     const double* __restrict__ U, const double* __restrict__ scale, const double* __restrict__ zero, int G, int gs,
@@ -287,7 +313,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
     const bool col_ok = lane < nb;
     const int cl = col_ok ? lane : 0;        // safe column for address arithmetic
     double* __restrict__ wptr = Wp + (int64_t)row * d + o + cl;
-    double w = *wptr;
+    const double w0 = *wptr;
     int pj = perm[o + cl];
     pj = min(max(pj, 0), d - 1);
     const int64_t gi = (int64_t)row * G + pj / gs;
@@ -298,16 +324,12 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
     for (int j = 0; j < CB; ++j)
         u[j] = (j < nb && lane > j && col_ok) ? Un[(int64_t)(o + j) * d + o + lane] : 0.0;
 
-    double mycode = 0.0, mydiff = 0.0;
-#pragma unroll
-    for (int j = 0; j < CB; ++j) {
-        if (j < nb) {                        // uniform
-            const double c = grid_code(w, s, z, maxq);
-            const double df = w - s * (c - z);
-            const double dj = readlane_f64(df, j);
-            if (lane == j) { mycode = c; mydiff = df; }
-            w -= dj * u[j];                  // u[j] is 0 for lanes <= j: they keep the value they were quantized at
-        }
+    double w = w0, mycode = 0.0, mydiff = 0.0;
+    bool suspect = false;
+    chain_steps<false>(w, u, s, z, maxq, nb, lane, mycode, mydiff, suspect);
+    if (__any(suspect)) {                    // wavefront-uniform; practically never taken
+        w = w0;
+        chain_steps<true>(w, u, s, z, maxq, nb, lane, mycode, mydiff, suspect);
     }
     if (col_ok) {
         codesT[(int64_t)(o + lane) * Rp + row] = (uint8_t)mycode;
@@ -341,10 +363,15 @@ hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
 //   rows of W :  q = quant(W[i][t]); e = (W[i][t] - q) / p;  W[i][k] -= e * A[t][k]     k > t
 //   rows of A :  A[a][b] -= (A[t][a] / p) * A[t][b]                                    t < a <= b
 // blockIdx.y walks groups of 4 rows, first the R rows of W then the d-t-1 rows of
-// A; each wavefront takes one row; blockIdx.x walks strips of 256 columns right
-// of t.  Row t of A and column t of W are read-only during the step.
-constexpr int STEP_U = 4;
+// A; each wavefront takes one row; blockIdx.x walks strips of 1024 columns whose
+// boundaries are fixed multiples of 1024, so that with an even d every lane can move
+// 16 bytes at a time.  Row t of A and column t of W are read-only during the step.
+// This is the streaming, HBM-bound form: every step reads and writes the whole
+// remaining part of W and of the upper triangle of A.
+constexpr int STEP_SW = 1024;                  // columns per strip
+constexpr int STEP_U = STEP_SW / 128;          // 16-byte pairs per lane
 
+template <bool VEC2>
 __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int R, int d, int t, double* __restrict__ A,
                                                    const double* __restrict__ scale, const double* __restrict__ zero,
                                                    int G, int gs, const int* __restrict__ perm, double maxq,
@@ -352,17 +379,21 @@ __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int 
 {
     const int lane = threadIdx.x & 63;
     const int rid = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int c0 = t + 1 + blockIdx.x * (64 * STEP_U);
+    const int strip0 = (t + 1) / STEP_SW;
+    const int c_base = (strip0 + blockIdx.x) * STEP_SW;
     const double* __restrict__ rowt = A + (int64_t)t * d;
     const double p = rowt[t];
+    double* __restrict__ row;      // the row this wavefront updates
+    double f;                      // row[k] -= f * rowt[k]
+    int first;                     // first column to update
     if (rid < R) {
         const int i = rid;
-        double* __restrict__ w = Wp + (int64_t)i * d;
+        row = Wp + (int64_t)i * d;
         int pj = perm[t];
         pj = min(max(pj, 0), d - 1);
         const int g = pj / gs;
         const double s = scale[(int64_t)i * G + g], z = zero[(int64_t)i * G + g];
-        const double wt = w[t];
+        const double wt = row[t];
         const double c = grid_code(wt, s, z, maxq);
         const double q = s * (c - z);
         const double diff = wt - q;
@@ -370,22 +401,55 @@ __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int 
             codesT[(int64_t)t * Rp + i] = (uint8_t)c;
             lossrow[i] += diff * diff / (2.0 * p);
         }
-        const double e = diff / p;
-#pragma unroll
-        for (int u = 0; u < STEP_U; ++u) {
-            const int k = c0 + u * 64 + lane;
-            if (k < d) w[k] -= e * rowt[k];
-        }
+        f = diff / p;
+        first = t + 1;
     } else {
         const int a = t + 1 + (rid - R);
         if (a >= d) return;
-        if (c0 + 64 * STEP_U <= a) return;          // strip entirely left of the diagonal
-        double* __restrict__ ra = A + (int64_t)a * d;
-        const double f = rowt[a] / p;
+        if (c_base + STEP_SW <= a) return;          // strip entirely left of the diagonal
+        row = A + (int64_t)a * d;
+        f = rowt[a] / p;
+        first = a;
+    }
+    if (VEC2) {
+        // all loads first (16 in flight per lane), then the updates
+        double2 v[STEP_U], r[STEP_U];
 #pragma unroll
         for (int u = 0; u < STEP_U; ++u) {
-            const int b = c0 + u * 64 + lane;
-            if (b >= a && b < d) ra[b] -= f * rowt[b];
+            const int k = c_base + u * 128 + 2 * lane;
+            v[u] = make_double2(0.0, 0.0);
+            r[u] = make_double2(0.0, 0.0);
+            if (k + 1 >= first && k < d) {           // d is even: k + 1 < d as well
+                v[u] = *reinterpret_cast<const double2*>(row + k);
+                r[u] = *reinterpret_cast<const double2*>(rowt + k);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < STEP_U; ++u) {
+            const int k = c_base + u * 128 + 2 * lane;
+            if (k + 1 >= first && k < d) {
+                if (k >= first) {
+                    v[u].x -= f * r[u].x;
+                    v[u].y -= f * r[u].y;
+                    *reinterpret_cast<double2*>(row + k) = v[u];
+                } else {
+                    row[k + 1] = v[u].y - f * r[u].y;   // pair straddles the first column
+                }
+            }
+        }
+    } else {
+        double v[2 * STEP_U], r[2 * STEP_U];
+#pragma unroll
+        for (int u = 0; u < 2 * STEP_U; ++u) {
+            const int k = c_base + u * 64 + lane;
+            const bool ok = k >= first && k < d;
+            v[u] = ok ? row[k] : 0.0;
+            r[u] = ok ? rowt[k] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 2 * STEP_U; ++u) {
+            const int k = c_base + u * 64 + lane;
+            if (k >= first && k < d) row[k] = v[u] - f * r[u];
         }
     }
 }
@@ -397,11 +461,16 @@ hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
     const int r = d - t - 1;
-    const int strips = r > 0 ? (r + 64 * STEP_U - 1) / (64 * STEP_U) : 1;
+    const int strip0 = (t + 1) / STEP_SW;
+    const int strips = r > 0 ? (d - 1) / STEP_SW - strip0 + 1 : 1;
     const int rows = R + (r > 0 ? r : 0);
     dim3 grid(strips, (rows + 3) / 4), block(256);
-    hipLaunchKernelGGL(step_kernel, grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq, codesT, Rp,
-                       lossrow);
+    if (d % 2 == 0)
+        hipLaunchKernelGGL((step_kernel<true>), grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq,
+                           codesT, Rp, lossrow);
+    else
+        hipLaunchKernelGGL((step_kernel<false>), grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq,
+                           codesT, Rp, lossrow);
     return hipGetLastError();
 }
 
