@@ -285,8 +285,8 @@ def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
 
 
 # --------------------------------------------------------------------------- the benchmark configurations
-def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None):
-    spec = workloads.configs()[name]
+def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None, spec=None):
+    spec = spec if spec is not None else workloads.configs()[name]
     _say(f"config {name}: generating inputs")
     W = spec.make_w()
     X = spec.make_x()
@@ -361,3 +361,21 @@ def test_config_c3b(fobq, ctx, name):
 @pytest.mark.slow
 def test_config_c5_large_d(fobq, ctx):
     _run_config(fobq, ctx, "c5_large_d", rows=64)
+
+
+# config 4 (whole-model sweep): parity on layers of the sweep that add something the other
+# configs do not -- ragged d_col (147), ragged d_row (255), a very long calibration set
+# accumulated in chunks, d_col = 4608 with N barely above d_col, and N << d_col.
+SWEEP_CASES = [
+    ("resnet50", "resnet50_64x147_n1605632_0", 1 << 18),
+    ("yolov5s", "yolov5s_255x128_n819200_0", 200000),
+    ("resnet50", "resnet50_512x4608_n6272_0", None),
+    ("resnet50", "resnet50_1000x2048_n128_0", None),
+]
+
+
+@pytest.mark.slow
+@pytest.mark.parametrize("model,layer,chunk", SWEEP_CASES)
+def test_config_c4_sweep_layers(fobq, ctx, model, layer, chunk):
+    spec = next(l for l in workloads.sweep_layers(model) if l.name == layer)
+    _run_config(fobq, ctx, layer, rows=None if spec.d_col < 4000 else 96, chunk=chunk, spec=spec)
