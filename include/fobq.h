@@ -44,11 +44,18 @@ typedef enum {
     FOBQ_ESTATE = -5  /* call sequence error (e.g. accumulate before begin)                 */
 } fobq_status;
 
-/* Column processing order (Section 4.2, step 3; Table 3 "No Sorting"). */
+/* Column processing order (Section 4.2, step 3).  The other keys and directions are the
+ * ones of the ordering ablation (Section 4.1, Table 3: "err", "w", "sensi" x "des", "asc",
+ * "No Sorting"), aggregated per column.  Equal keys keep index order. */
 typedef enum {
-    FOBQ_ORDER_NATURAL = 0,    /* columns 0, 1, 2, ...                                       */
-    FOBQ_ORDER_SENSI_DESC = 1, /* by S_j = sum_i L_q(w_ij), descending; ties keep index order */
-    FOBQ_ORDER_CUSTOM = 2      /* caller-supplied permutation perm_in                         */
+    FOBQ_ORDER_NATURAL = 0,    /* columns 0, 1, 2, ... ("No Sorting")                         */
+    FOBQ_ORDER_SENSI_DESC = 1, /* by S_j = sum_i L_q(w_ij), descending (the paper's method)   */
+    FOBQ_ORDER_CUSTOM = 2,     /* caller-supplied permutation perm_in                         */
+    FOBQ_ORDER_ERR_DESC = 3,   /* by sum_i (quant(w_ij) - w_ij)^2, descending                 */
+    FOBQ_ORDER_W_DESC = 4,     /* by sum_i w_ij^2, descending                                 */
+    FOBQ_ORDER_SENSI_ASC = 5,  /* ascending variants                                          */
+    FOBQ_ORDER_ERR_ASC = 6,
+    FOBQ_ORDER_W_ASC = 7
 } fobq_order;
 
 typedef struct {
@@ -130,8 +137,9 @@ int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_
 int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d, double* Hinv);
 
 /* Column scores and order (Section 4.2 steps 1-3) from W and the diagonal of
- * Hinv (device fp64 d x d): S (device fp64 d_col, may be NULL) and perm (device
- * int32 d_col, may be NULL) for opts->order.  Uses opts->bits, group, order,
+ * Hinv (device fp64 d x d): S (device fp64 d_col, may be NULL; the sort key of
+ * opts->order, S_j for NATURAL and CUSTOM) and perm (device int32 d_col, may be
+ * NULL) for opts->order.  Uses opts->bits, group, order,
  * perm_in.  Synchronises. */
 int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                      const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);

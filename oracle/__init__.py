@@ -117,11 +117,29 @@ def sensitivity(W: np.ndarray, Hinv_diag: np.ndarray, bits: int, group: int,
     return S
 
 
-def order(S: np.ndarray) -> np.ndarray:
+def order(S: np.ndarray, ascending: bool = False) -> np.ndarray:
     S = np.ascontiguousarray(S, dtype=np.float64)
     perm = np.empty(S.shape[0], dtype=np.int32)
-    _chk(_get().oracle_order(_p(S), ctypes.c_int64(S.shape[0]), _p(perm)), "oracle_order")
+    _chk(_get().oracle_order_dir(_p(S), ctypes.c_int64(S.shape[0]), ctypes.c_int(int(ascending)), _p(perm)),
+         "oracle_order_dir")
     return perm
+
+
+KEY_SENSI, KEY_ERR, KEY_W = 0, 1, 2
+
+
+def column_key(W: np.ndarray, Hinv_diag: np.ndarray, bits: int, group: int, scale: np.ndarray,
+               zero: np.ndarray, kind: int) -> np.ndarray:
+    """Sort key per column: KEY_SENSI = S_j, KEY_ERR = summed squared quantization error,
+    KEY_W = summed squared weight."""
+    W = _f32(W)
+    r, d = W.shape
+    hd = np.ascontiguousarray(Hinv_diag, dtype=np.float64)
+    key = np.empty(d, dtype=np.float64)
+    _chk(_get().oracle_column_key(_p(W), ctypes.c_int64(r), ctypes.c_int64(d), _p(hd), ctypes.c_int(bits),
+                                  ctypes.c_int64(group), _p(scale), _p(zero), ctypes.c_int(kind), _p(key)),
+         "oracle_column_key")
+    return key
 
 
 @dataclass
@@ -177,6 +195,9 @@ def output_error(W: np.ndarray, Q: np.ndarray, X: np.ndarray) -> float:
 
 
 ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM = 0, 1, 2
+ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC = 3, 4, 5, 6, 7
+_ORDER_KEYS = {ORDER_SENSI_DESC: (KEY_SENSI, False), ORDER_ERR_DESC: (KEY_ERR, False), ORDER_W_DESC: (KEY_W, False),
+               ORDER_SENSI_ASC: (KEY_SENSI, True), ORDER_ERR_ASC: (KEY_ERR, True), ORDER_W_ASC: (KEY_W, True)}
 
 
 @dataclass
@@ -213,6 +234,10 @@ def quantize_layer(W: np.ndarray, X: Optional[np.ndarray] = None, H: Optional[np
         p = np.arange(W.shape[1], dtype=np.int32)
     elif order_mode == ORDER_SENSI_DESC:
         p = order(S)
+    elif order_mode in _ORDER_KEYS:
+        kind, asc = _ORDER_KEYS[order_mode]
+        S = column_key(W, np.ascontiguousarray(np.diag(Hinv)), bits, group, scale, zero, kind)
+        p = order(S, asc)
     else:
         p = np.ascontiguousarray(perm, dtype=np.int32)
     res = column_loop(W, Hinv, p, bits, group, scale, zero, steps)

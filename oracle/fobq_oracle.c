@@ -23,6 +23,9 @@
  *   oracle_sensitivity    Section 3, Eq. 10 and Section 4.2 steps 1-2:
  *                         L = (quant(w) - w)^2 / (2 [Hinv]_jj), S_j = sum_i L_ij.
  *   oracle_order          Section 4.2 step 3: columns by S_j, descending.
+ *   oracle_column_key,    Section 4.1 and Table 3: the other sort keys of the ablation
+ *   oracle_order_dir      ("err" = summed squared quantization error, "w" = summed squared
+ *                         weight, "sensi" = S_j) and both directions ("des", "asc").
  *   oracle_column_loop    Section 4.2 steps 4-5 with Eq. 9 (row form of Eq. 11)
  *                         and Eq. 12: quantize a whole column, push the error
  *                         into the columns not yet quantized, eliminate the
@@ -208,8 +211,38 @@ int oracle_sensitivity(const float *W, int64_t d_row, int64_t d_col, const doubl
     return ORACLE_OK;
 }
 
-/* perm = columns by S descending; equal scores keep the smaller index first. */
-int oracle_order(const double *S, int64_t d, int32_t *perm)
+/* Column sort keys of the ordering ablation (Section 4.1, Table 3), aggregated per column
+ * as in Section 4.2 step 2.  kind 0 "sensi": sum_i (quant(w) - w)^2 / (2 Hinv_jj);
+ * kind 1 "err": sum_i (quant(w) - w)^2;  kind 2 "w": sum_i w^2. */
+int oracle_column_key(const float *W, int64_t d_row, int64_t d_col, const double *Hinv_diag, int bits,
+                      int64_t group, const double *scale, const double *zero, int kind, double *key)
+{
+    if (!W || !scale || !zero || !key || kind < 0 || kind > 2) return ORACLE_EINVAL;
+    if (kind == 0) return oracle_sensitivity(W, d_row, d_col, Hinv_diag, bits, group, scale, zero, key);
+    const int64_t G = groups_of(d_col, group);
+    const int64_t gs = group > 0 ? group : d_col;
+    const double maxq = ldexp(1.0, bits) - 1.0;
+    for (int64_t j = 0; j < d_col; ++j) {
+        const int64_t g = j / gs;
+        double s = 0.0;
+        for (int64_t i = 0; i < d_row; ++i) {
+            const double w = (double)W[i * d_col + j];
+            if (kind == 1) {
+                const double q = grid_value(grid_code(w, scale[i * G + g], zero[i * G + g], maxq),
+                                            scale[i * G + g], zero[i * G + g]);
+                s += (q - w) * (q - w);
+            } else {
+                s += w * w;
+            }
+        }
+        key[j] = s;
+    }
+    return ORACLE_OK;
+}
+
+/* perm = columns by key, descending (ascending = 0) or ascending (ascending = 1); equal keys
+ * keep the smaller index first. */
+int oracle_order_dir(const double *S, int64_t d, int ascending, int32_t *perm)
 {
     if (!S || !perm || d <= 0) return ORACLE_EINVAL;
     for (int64_t j = 0; j < d; ++j) perm[j] = (int32_t)j;
@@ -217,13 +250,19 @@ int oracle_order(const double *S, int64_t d, int32_t *perm)
     for (int64_t a = 1; a < d; ++a) {
         int32_t v = perm[a];
         int64_t b = a - 1;
-        while (b >= 0 && S[perm[b]] < S[v]) {
+        while (b >= 0 && (ascending ? S[perm[b]] > S[v] : S[perm[b]] < S[v])) {
             perm[b + 1] = perm[b];
             --b;
         }
         perm[b + 1] = v;
     }
     return ORACLE_OK;
+}
+
+/* perm = columns by S descending; equal scores keep the smaller index first. */
+int oracle_order(const double *S, int64_t d, int32_t *perm)
+{
+    return oracle_order_dir(S, d, 0, perm);
 }
 
 /*

@@ -138,7 +138,7 @@ static int check_opts(fobq_ctx* ctx, const fobq_opts* o, int64_t d_col)
     if (o->group < 0 || (o->group > 0 && d_col % o->group != 0))
         return set_err(ctx, FOBQ_EINVAL, "group (%d) must be 0 or divide d_col (%lld)", o->group, (long long)d_col);
     if (!(o->damp >= 0.0) || !(o->damp_abs >= 0.0)) return set_err(ctx, FOBQ_EINVAL, "damp and damp_abs must be >= 0");
-    if (o->order < FOBQ_ORDER_NATURAL || o->order > FOBQ_ORDER_CUSTOM)
+    if (o->order < FOBQ_ORDER_NATURAL || o->order > FOBQ_ORDER_W_ASC)
         return set_err(ctx, FOBQ_EINVAL, "unknown order %d", o->order);
     if (o->order == FOBQ_ORDER_CUSTOM && !o->perm_in) return set_err(ctx, FOBQ_EINVAL, "order CUSTOM needs perm_in");
     if (o->block < 0 || o->block > 64) return set_err(ctx, FOBQ_EINVAL, "block must be in 0..64 (got %d)", o->block);
@@ -171,13 +171,18 @@ static int enqueue_order(fobq_ctx* ctx, const float* W, int R, int d, const fobq
     StageScope sc(ctx, FOBQ_STAGE_ORDER);
     FOBQ_TRY(launch_grid(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
                          scales_out, zeros_out), "grid");
+    // sort key: 0 "sensi", 1 "err", 2 "w" (Section 4.1, Table 3)
+    const int kind = (o->order == FOBQ_ORDER_ERR_DESC || o->order == FOBQ_ORDER_ERR_ASC) ? 1
+                   : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
+    const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC;
     FOBQ_TRY(launch_sensitivity(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                                ctx->hdiag.as<double>(), ctx->Spart.as<double>(), chunks, ctx->S.as<double>()),
+                                ctx->hdiag.as<double>(), ctx->Spart.as<double>(), chunks, ctx->S.as<double>(), kind),
              "sensitivity");
     if (o->order == FOBQ_ORDER_NATURAL)
         FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
-    else if (o->order == FOBQ_ORDER_SENSI_DESC)
-        FOBQ_TRY(launch_rank_sort(s, ctx->S.as<double>(), d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
+    else if (o->order != FOBQ_ORDER_CUSTOM)
+        FOBQ_TRY(launch_rank_sort(s, ctx->S.as<double>(), d, ctx->perm.as<int>(), ctx->invperm.as<int>(), ascending),
+                 "order");
     else
         FOBQ_TRY(launch_check_perm(s, o->perm_in, d, ctx->perm.as<int>(), ctx->invperm.as<int>(),
                                    ctx->flags.as<int>() + FLAG_BADPERM), "order");

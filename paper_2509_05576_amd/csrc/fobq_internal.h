@@ -127,9 +127,9 @@ hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, in
 hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag);
 hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
                               const double* scale, const double* zero, const double* hdiag,
-                              double* Spart, int chunks, double* S);
+                              double* Spart, int chunks, double* S, int kind);
 int sens_chunks(int R);
-hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm);
+hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm, int ascending);
 hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm);
 hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm, int* invperm, int* flag);
 hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,

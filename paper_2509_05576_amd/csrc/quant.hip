@@ -81,9 +81,12 @@ hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag)
 // Pass 2: chunks are added in index order, then divided by 2 [Hinv]_jj.
 constexpr int SENS_RC = 64;
 
+// kind 0 / 1: sum of squared quantization errors ("sensi" divides by 2 [Hinv]_jj in pass 2, "err" does
+// not); kind 2: sum of squared weights ("w").  Section 4.1, Table 3.
 __global__ __launch_bounds__(256) void sens_partial_kernel(const float* __restrict__ W, int R, int d, int gs, int G,
                                                            double maxq, const double* __restrict__ scale,
-                                                           const double* __restrict__ zero, double* __restrict__ Spart)
+                                                           const double* __restrict__ zero, double* __restrict__ Spart,
+                                                           int kind)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= d) return;
@@ -94,39 +97,41 @@ __global__ __launch_bounds__(256) void sens_partial_kernel(const float* __restri
         const double w = (double)W[(int64_t)i * d + j];
         const double s = scale[(int64_t)i * G + g], z = zero[(int64_t)i * G + g];
         const double q = s * (grid_code(w, s, z, maxq) - z);
-        acc += (q - w) * (q - w);
+        acc += (kind == 2) ? w * w : (q - w) * (q - w);
     }
     Spart[(int64_t)blockIdx.y * d + j] = acc;
 }
 
 __global__ __launch_bounds__(256) void sens_reduce_kernel(const double* __restrict__ Spart, int chunks, int d,
-                                                          const double* __restrict__ hdiag, double* __restrict__ S)
+                                                          const double* __restrict__ hdiag, double* __restrict__ S,
+                                                          int kind)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= d) return;
     double acc = 0.0;
     for (int c = 0; c < chunks; ++c) acc += Spart[(int64_t)c * d + j];
-    S[j] = acc / (2.0 * hdiag[j]);
+    S[j] = (kind == 0) ? acc / (2.0 * hdiag[j]) : acc;
 }
 
 int sens_chunks(int R) { return (R + SENS_RC - 1) / SENS_RC; }
 
 hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
                               const double* scale, const double* zero, const double* hdiag,
-                              double* Spart, int chunks, double* S)
+                              double* Spart, int chunks, double* S, int kind)
 {
     const int gs = group > 0 ? group : d;
     const int G = group > 0 ? d / group : 1;
     const double maxq = (double)((1 << bits) - 1);
     hipLaunchKernelGGL(sens_partial_kernel, dim3((d + 255) / 256, chunks), dim3(256), 0, s, W, R, d, gs, G, maxq,
-                       scale, zero, Spart);
-    hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, hdiag, S);
+                       scale, zero, Spart, kind);
+    hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, hdiag, S, kind);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-// Order (Section 4.2 step 3): descending S, equal scores keep index order.
-// rank_j = #{k : S_k > S_j or (S_k == S_j and k < j)}; perm[rank_j] = j.
+// Order (Section 4.2 step 3): descending S (or ascending), equal scores keep index order.
+// rank_j = #{k : S_k before S_j or (S_k == S_j and k < j)}; perm[rank_j] = j.  Ascending order
+// is the descending order of the negated keys.
 // A score that is not finite compares as -infinity so that perm stays a permutation.
 __device__ __forceinline__ double sort_key(double v)
 {
@@ -135,16 +140,17 @@ __device__ __forceinline__ double sort_key(double v)
 
 // blockIdx.x: 256 columns j; blockIdx.y: a slice of 256 comparison columns k.  Partial ranks are
 // integers, so adding them with atomics gives the same result in any order.
-__global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ S, int d, int* __restrict__ rank)
+__global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ S, int d, int* __restrict__ rank,
+                                                         double sign)
 {
     __shared__ double tile[256];
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int base = blockIdx.y * 256;
     const int k = base + threadIdx.x;
-    tile[threadIdx.x] = (k < d) ? sort_key(S[k]) : 0.0;
+    tile[threadIdx.x] = (k < d) ? sort_key(sign * S[k]) : 0.0;
     __syncthreads();
     if (j >= d) return;
-    const double sj = sort_key(S[j]);
+    const double sj = sort_key(sign * S[j]);
     const int lim = min(256, d - base);
     int cnt = 0;
     for (int u = 0; u < lim; ++u) {
@@ -160,13 +166,13 @@ __global__ __launch_bounds__(256) void rank_scatter_kernel(const int* __restrict
     if (j < d) perm[min(max(rank[j], 0), d - 1)] = j;
 }
 
-hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm)
+hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm, int ascending)
 {
     // invperm doubles as the rank array: invperm[j] = rank of column j = its step
     hipError_t e = launch_fill_i32(s, invperm, d, 0);
     if (e != hipSuccess) return e;
     const int nb = (d + 255) / 256;
-    hipLaunchKernelGGL(rank_count_kernel, dim3(nb, nb), dim3(256), 0, s, S, d, invperm);
+    hipLaunchKernelGGL(rank_count_kernel, dim3(nb, nb), dim3(256), 0, s, S, d, invperm, ascending ? -1.0 : 1.0);
     hipLaunchKernelGGL(rank_scatter_kernel, dim3(nb), dim3(256), 0, s, invperm, d, perm);
     return hipGetLastError();
 }

@@ -187,6 +187,23 @@ def test_quantize_layer_matches_oracle(fobq, ctx, r, d, n, bits, group, order, b
     _compare_layer(out, ref, W, bits)
 
 
+@pytest.mark.parametrize("order", [3, 4, 5, 6, 7])
+def test_ablation_orders_match_oracle(fobq, ctx, order):
+    # the sort keys and directions of the ordering ablation (Section 4.1, Table 3)
+    _say(f"order {order}")
+    W, X = _problem(48, 170, 500, 30 + order, w_std=0.05)
+    H = oracle.hessian(X)
+    out = ctx.quantize_layer(_dev(W), _dev(H), bits=4, order=order)
+    ref = oracle.quantize_layer(W, H=H, bits=4, order_mode=order)
+    ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=4)
+    _compare_layer(out, ref, W, 4)
+    kind, asc = oracle._ORDER_KEYS[order]
+    key = oracle.column_key(W, np.diag(ref.Hinv).copy(), 4, 0, ref.scales, ref.zeros, kind)
+    S, perm = fobq.fobq_sensitivity(ctx.handle, _dev(W), _dev(ref.Hinv), bits=4, order=order)
+    assert np.allclose(S.cpu().numpy(), key, rtol=1e-12)
+    assert np.array_equal(perm.cpu().numpy(), out.perm.cpu().numpy())
+
+
 def test_custom_order_and_explicit_h(fobq, ctx):
     W, X = _problem(40, 150, 400, 5, w_std=0.05)
     H = oracle.hessian(X)
@@ -210,7 +227,7 @@ def test_argument_errors(fobq, ctx):
     W, X = _problem(8, 32, 100, 8)
     Wd, H = _dev(W), _dev(oracle.hessian(X))
     for kw in ({"bits": 1}, {"bits": 9}, {"group": 5}, {"block": 65}, {"stop_after": 33}, {"damp": -1.0},
-               {"order": 7}, {"order": fobq.ORDER_CUSTOM}):
+               {"order": 8}, {"order": -1}, {"order": fobq.ORDER_CUSTOM}):
         with pytest.raises(fobq.FobqError) as e:
             ctx.quantize_layer(Wd, H, **kw)
         assert e.value.code == fobq.EINVAL, kw

@@ -328,3 +328,43 @@ def test_column_loop_rejects_bad_perm():
     with pytest.raises(oracle.OracleError):
         oracle.quantize_layer(W, X=X, bits=4, order_mode=oracle.ORDER_CUSTOM,
                               perm=np.array([0, 1, 1, 2], dtype=np.int32))
+
+
+# ---------------------------------------------------------------- other sort keys (Section 4.1, Table 3)
+def test_column_keys_against_numpy():
+    W, X = _problem(9, 13, 60, 21)
+    s, z = oracle.grid(W, 3, 0)
+    hd = np.linspace(0.5, 4.0, 13)
+    Wd = W.astype(np.float64)
+    q = s * (np.clip(np.rint(Wd / s) + z, 0, 7) - z)
+    err = ((q - Wd) ** 2).sum(0)
+    assert np.allclose(oracle.column_key(W, hd, 3, 0, s, z, oracle.KEY_ERR), err, rtol=1e-13)
+    assert np.allclose(oracle.column_key(W, hd, 3, 0, s, z, oracle.KEY_W), (Wd ** 2).sum(0), rtol=1e-13)
+    assert np.allclose(oracle.column_key(W, hd, 3, 0, s, z, oracle.KEY_SENSI), err / (2 * hd), rtol=1e-13)
+
+
+def test_order_directions_are_stable():
+    S = np.array([1.0, 3.0, 2.0, 3.0, 0.5, 2.0])
+    assert list(oracle.order(S, ascending=True)) == [4, 0, 2, 5, 1, 3]
+    assert list(oracle.order(S, ascending=False)) == [1, 3, 2, 5, 0, 4]
+    rng = np.random.default_rng(22)
+    S = rng.integers(0, 5, 300).astype(np.float64)          # many ties
+    assert np.array_equal(oracle.order(S, True), np.argsort(S, kind="stable"))
+    assert np.array_equal(oracle.order(S, False), np.argsort(-S, kind="stable"))
+
+
+@pytest.mark.parametrize("mode", [oracle.ORDER_ERR_DESC, oracle.ORDER_W_DESC, oracle.ORDER_SENSI_ASC,
+                                  oracle.ORDER_ERR_ASC, oracle.ORDER_W_ASC])
+def test_every_order_is_the_custom_order_of_its_own_permutation(mode):
+    W, X = _problem(6, 15, 70, 23)
+    H = oracle.hessian(X)
+    a = oracle.quantize_layer(W, H=H, bits=4, order_mode=mode)
+    kind, asc = oracle._ORDER_KEYS[mode]
+    key = oracle.column_key(W, np.diag(a.Hinv).copy(), 4, 0, a.scales, a.zeros, kind)
+    expect = np.argsort(key if asc else -key, kind="stable").astype(np.int32)
+    assert np.array_equal(a.perm, expect)
+    b = oracle.quantize_layer(W, H=H, bits=4, order_mode=oracle.ORDER_CUSTOM, perm=expect)
+    assert np.array_equal(a.codes, b.codes) and np.isclose(a.loss, b.loss, rtol=1e-12)
+    # the loss identity holds for any order
+    dW = W.astype(np.float64) - a.Q
+    assert np.isclose(a.loss, 0.5 * np.trace(dW @ a.H_damped @ dW.T), rtol=1e-9)
