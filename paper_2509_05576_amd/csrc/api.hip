@@ -42,19 +42,35 @@ static hipEvent_t take_event(fobq_ctx* c)
     return e;
 }
 
-StageScope::StageScope(fobq_ctx* c_, int stage_) : c(c_), stage(stage_)
+StageScope::StageScope(fobq_ctx* c_, int stage_, hipStream_t on) : c(c_), stage(stage_), st(on ? on : c_->stream)
 {
     if (!c->profiling) return;
     e0 = take_event(c);
     e1 = take_event(c);
-    if (e0) (void)hipEventRecord(e0, c->stream);
+    if (e0) (void)hipEventRecord(e0, st);
 }
 
 StageScope::~StageScope()
 {
     if (!c->profiling || !e0 || !e1) return;
-    (void)hipEventRecord(e1, c->stream);
+    (void)hipEventRecord(e1, st);
     c->timer.pending[stage].push_back({e0, e1});
+}
+
+// events (no timing) that order the side stream behind the context's stream and back
+static int ensure_sync_events(fobq_ctx* c, size_t n)
+{
+    if (!c->side && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) {
+        c->side = nullptr;
+        return set_err(c, FOBQ_EHIP, "cannot create the side stream");
+    }
+    while (c->sync_ev.size() < n) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+            return set_err(c, FOBQ_EHIP, "cannot create an event");
+        c->sync_ev.push_back(e);
+    }
+    return FOBQ_OK;
 }
 
 static void fold_events(fobq_ctx* c)
@@ -227,6 +243,11 @@ int fobq_destroy(fobq_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     fold_events(ctx);
     for (hipEvent_t e : ctx->timer.pool) (void)hipEventDestroy(e);
+    if (ctx->side) {
+        (void)hipStreamSynchronize(ctx->side);
+        (void)hipStreamDestroy(ctx->side);
+    }
+    for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
                       &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
                       &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow};
@@ -403,29 +424,45 @@ int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_
         double* U = ctx->U.as<double>();
         double* Un = ctx->Un.as<double>();
         double* DT = ctx->DT.as<double>();
+        // Eq. 12 does not involve W: the elimination runs ahead on the context's stream and the
+        // column loop follows on the side stream, block k as soon as the pivot rows of block k exist
+        // (both are chains of short dependent launches that leave most of the GPU idle).
+        const int nblocks = (steps + block - 1) / block;
+        rc = ensure_sync_events(ctx, (size_t)nblocks + 2);
+        if (rc) return rc;
+        hipStream_t side = ctx->side;
+        std::vector<hipEvent_t> rows_ready(ctx->sync_ev.begin(), ctx->sync_ev.begin() + nblocks);
+        hipEvent_t ev_start = ctx->sync_ev[nblocks], ev_done = ctx->sync_ev[nblocks + 1];
+        FOBQ_TRY(hipEventRecord(ev_start, s), "event");
+        FOBQ_TRY(hipStreamWaitEvent(side, ev_start, 0), "stream wait");
         {
             StageScope sc(ctx, FOBQ_STAGE_ELIMINATE);
-            FOBQ_TRY(eliminate_blocked(ctx, A, d, steps, block, U, Un, ctx->flags.as<int>() + FLAG_NOTPD_HINV),
-                     "eliminate");
+            FOBQ_TRY(eliminate_blocked(ctx, A, d, steps, block, U, Un, ctx->flags.as<int>() + FLAG_NOTPD_HINV,
+                                       &rows_ready), "eliminate");
         }
-        StageScope sc(ctx, FOBQ_STAGE_COLUMNS);
-        const int writeback = out->W_work ? 1 : 0;
-        for (int o = 0; o < steps; o += block) {
-            const int nb = (block < steps - o) ? block : steps - o;
-            FOBQ_TRY(launch_chain(s, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits, codesT, DT,
-                                  Rp, lossrow, writeback), "column block");
-            const int r = d - o - nb;
-            if (r <= 0) break;
-            // deferred compensation of the columns right of the block:
-            // W[:, o+nb:] -= D[:, block] * Un[block, o+nb:]
-            GemmP p;
-            p.M = R; p.N = r; p.K = nb;
-            p.A = DT + (int64_t)o * Rp; p.lda = Rp;
-            p.B = Un + (int64_t)o * d + (o + nb); p.ldb = d;
-            p.C = Wp + (o + nb); p.ldc = d;
-            p.alpha = -1.0; p.beta = 1.0;
-            FOBQ_TRY(gemm64(s, p, true, false), "column block update");
+        {
+            StageScope sc(ctx, FOBQ_STAGE_COLUMNS, side);
+            int k = 0;
+            for (int o = 0; o < steps; o += block, ++k) {
+                const int nb = (block < steps - o) ? block : steps - o;
+                FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[k], 0), "stream wait");
+                FOBQ_TRY(launch_chain(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
+                                      codesT, DT, Rp, lossrow), "column block");
+                const int r = d - o - nb;
+                if (r <= 0) break;
+                // deferred compensation of the columns right of the block:
+                // W[:, o+nb:] -= D[:, block] * Un[block, o+nb:]
+                GemmP p;
+                p.M = R; p.N = r; p.K = nb;
+                p.A = DT + (int64_t)o * Rp; p.lda = Rp;
+                p.B = Un + (int64_t)o * d + (o + nb); p.ldb = d;
+                p.C = Wp + (o + nb); p.ldc = d;
+                p.alpha = -1.0; p.beta = 1.0;
+                FOBQ_TRY(gemm64(side, p, true, false), "column block update");
+            }
         }
+        FOBQ_TRY(hipEventRecord(ev_done, side), "event");
+        FOBQ_TRY(hipStreamWaitEvent(s, ev_done, 0), "stream wait");
     }
     {
         StageScope sc(ctx, FOBQ_STAGE_EMIT);

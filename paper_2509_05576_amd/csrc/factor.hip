@@ -730,9 +730,13 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
 }
 
 // Shared-Hinv elimination of the first `steps` columns, `block` columns at a time.
-hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag)
+hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag,
+                             const std::vector<hipEvent_t>* rows_ready)
 {
     hipStream_t s = c->stream;
+    auto ready = [&](int k) {
+        if (rows_ready && k < (int)rows_ready->size()) (void)hipEventRecord((*rows_ready)[k], s);
+    };
     double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
     if (block == NB && steps == d) {
@@ -744,17 +748,20 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
             const int T = (d - o - NB + NB - 1) / NB;
             hipLaunchKernelGGL(elim_iter_kernel, dim3(T * (T + 1) / 2), dim3(256), 0, s, A, d, o, Gb[it & 1],
                                rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
+            ready(it);          // rows of block `it` complete (its diagonal part came from the previous launch)
         }
+        ready(it);              // last block: only a diagonal part
         return hipGetLastError();
     }
     // general form (any block width, partial elimination): diagonal block, pivot rows, trailing update
     double* G = Gb[0];
     double* rinv = rb[0];
-    for (int o = 0; o < steps; o += block) {
+    int it = 0;
+    for (int o = 0; o < steps; o += block, ++it) {
         const int nb = min(block, steps - o);
         hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, o, nb, U, Un, G, rinv, flag);
         const int r = d - o - nb;
-        if (r <= 0) break;
+        if (r <= 0) { ready(it); break; }
         // pivot rows right of the block: U12 = G * A12, Un12 = D^-1 U12
         GemmP p;
         p.M = nb; p.N = r; p.K = nb;
@@ -773,6 +780,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
         q.alpha = -1.0; q.beta = 1.0; q.cmode = CMODE_UPPER;
         e = gemm64(s, q, true, false);
         if (e != hipSuccess) return e;
+        ready(it);
     }
     return hipGetLastError();
 }

@@ -94,6 +94,11 @@ struct fobq_ctx {
     fobq::DevBuf perm, invperm; // d int32
     fobq::DevBuf lossrow;   // d_row fp64
 
+    // second stream: the column loop of block k only needs the pivot rows of blocks <= k, so it
+    // runs behind the shared-Hinv elimination on its own stream, ordered by one event per block
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> sync_ev;
+
     bool profiling = false;
     fobq::StageTimer timer;
 };
@@ -104,8 +109,8 @@ int set_err(fobq_ctx* c, int code, const char* fmt, ...);
 int hip_err(fobq_ctx* c, hipError_t e, const char* what);
 
 struct StageScope {
-    fobq_ctx* c; int stage; hipEvent_t e0 = nullptr, e1 = nullptr;
-    StageScope(fobq_ctx* c_, int stage_);
+    fobq_ctx* c; int stage; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr;
+    StageScope(fobq_ctx* c_, int stage_, hipStream_t on = nullptr);   // on == nullptr: the context's stream
     ~StageScope();
 };
 
@@ -119,7 +124,10 @@ hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, doubl
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag);  // Hd = L L^T; Linv gets the diagonal-block inverses
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
 hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
-hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag);
+// `rows_ready` (may be null): rows_ready[k] is recorded on the context's stream once the pivot rows of
+// block k (rows k*block .. of U and Un) are complete
+hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag,
+                             const std::vector<hipEvent_t>* rows_ready);
 
 // quant.hip
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
@@ -137,7 +145,7 @@ hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int*
 hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         const double* Un, const double* U, const double* scale, const double* zero,
                         int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow, int writeback);
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow);
 hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
                        const double* scale, const double* zero, int G, int group, const int* perm, int bits,
                        uint8_t* codesT, int Rp, double* lossrow);
@@ -146,7 +154,6 @@ hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int 
                        uint8_t* codes, float* Q);
 hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss);
 hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
-hipError_t launch_fill_f64(hipStream_t s, double* p, int64_t n, double v);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);
 
 }  // namespace fobq

@@ -351,9 +351,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
 hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         const double* Un, const double* U, const double* scale, const double* zero,
                         int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow, int writeback)
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow)
 {
-    (void)writeback;   // the running weights are always written back (coalesced, one store per lane)
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
     dim3 grid((R + CHAIN_WAVES - 1) / CHAIN_WAVES), block(64 * CHAIN_WAVES);
@@ -553,21 +552,10 @@ hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, do
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void fill_f64_kernel(double* __restrict__ p, int64_t n, double v)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
-}
 __global__ __launch_bounds__(256) void fill_i32_kernel(int* __restrict__ p, int64_t n, int v)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = v;
-}
-hipError_t launch_fill_f64(hipStream_t s, double* p, int64_t n, double v)
-{
-    if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_f64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
-    return hipGetLastError();
 }
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v)
 {
