@@ -24,14 +24,19 @@ constexpr int XK = 32;           // calibration columns per LDS stage
 constexpr int XLD = XK + 4;      // fp32 row stride in LDS: 16B-aligned rows, conflict-free 16B fragment reads
 constexpr int XXT_WGS = 512;     // persistent workgroups: 2 per compute unit
 
-__device__ __forceinline__ void tile_decode(int t, int& I, int& J)
+// Order of the lower-triangle tiles: tile rows are taken in pairs (2r, 2r + 1) and a pair is walked
+// column by column, (2r, J), (2r + 1, J), (2r, J + 1), ...  Consecutive tiles of the order then share a
+// panel of X: the column panel J with the tile just before or after, the row panel with the tile two
+// places away.  Pair r starts at index 2 r^2 + r and has 4 r + 3 tiles; an odd last row stands alone.
+__device__ __forceinline__ void tile_decode(int t, int nt, int& I, int& J)
 {
-    // t = I (I + 1) / 2 + J, 0 <= J <= I
-    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((i + 1) * (i + 2) / 2 <= t) ++i;
-    while (i * (i + 1) / 2 > t) --i;
-    I = i;
-    J = t - i * (i + 1) / 2;
+    int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.25f);
+    while (2 * (r + 1) * (r + 1) + (r + 1) <= t) ++r;
+    while (2 * r * r + r > t) --r;
+    const int u = t - (2 * r * r + r);
+    if (2 * r + 1 >= nt) { I = 2 * r; J = u; }                       // unpaired last row
+    else if (u < 4 * r + 2) { I = 2 * r + (u & 1); J = u >> 1; }
+    else { I = 2 * r + 1; J = 2 * r + 1; }                           // diagonal tile of the second row
 }
 
 // FAST: X rows are 16-byte aligned (ld % 4 == 0, base aligned) -> float4 loads.
@@ -50,7 +55,15 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
     const int fr = lane & 15;         // fragment row
     const int fk = (lane >> 4) * 4;   // fragment: 4 consecutive columns, one per k-step (the sum over k is order-free)
 
-    int64_t item = (int64_t)blockIdx.x * per_wg;
+    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD one contiguous run of ranges, so
+    // that the workgroups sharing an L2 work on neighbouring tiles (which share panels of X) at almost
+    // the same position of the calibration dimension.
+    const int nx = 8, gq = (int)gridDim.x / nx, grem = (int)gridDim.x % nx;
+    const int xcd = (int)blockIdx.x % nx;
+    const int vb = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+    const int nt = (d + XT - 1) / XT;
+
+    int64_t item = (int64_t)vb * per_wg;
     const int64_t item_end = min(total_items, item + per_wg);
 
     while (item < item_end) {
@@ -59,9 +72,9 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
         const int c_end = (int)min((int64_t)chunks, c_begin + (item_end - item));
         // piece index of this range inside its tile: number of workgroup boundaries before it
         const int64_t tile_first = (int64_t)tile * chunks;
-        const int piece = (int)(blockIdx.x - tile_first / per_wg);    // 0 for the workgroup whose range reaches the tile first
+        const int piece = (int)(vb - tile_first / per_wg);    // 0 for the workgroup whose range reaches the tile first
         int I, J;
-        tile_decode(tile, I, J);
+        tile_decode(tile, nt, I, J);
         const int i0 = I * XT, j0 = J * XT;
 
         // clamped row pointers: rows past d produce outputs that are never stored
