@@ -17,13 +17,15 @@ constexpr int NB = 64;
 
 // ---------------------------------------------------------------------------
 // 64 x 64 diagonal blocks.  Both diagonal-block kernels keep the block in LDS and
-// work on it as a 4 x 4 grid of 16 x 16 tiles: the only sequential arithmetic is
-// the unblocked factorization of a 16 x 16 diagonal tile (one wavefront, one tile
-// row per lane, pivot rows broadcast with v_readlane, the tile's triangular
-// inverse obtained in the same sweep by applying the eliminations to the
-// identity); everything else -- panel, trailing update, assembly of the 64 x 64
-// triangular inverse from the tile inverses -- is 16 x 16 x 16 products on the
-// matrix cores (4 MFMAs each), one tile per wavefront.
+// work on it as a 4 x 4 grid of 16 x 16 tiles.  The only sequential arithmetic is
+// the unblocked sweep over the 16 pivots of a diagonal tile: one wavefront, one
+// row (Cholesky) or column (elimination) of the whole block per lane, so the same
+// sweep also produces the tiles below (right of) the diagonal tile; pivot rows are
+// broadcast with v_readlane.  The triangular inverse of a diagonal tile is a
+// forward substitution done by a second wavefront while the first one already
+// sweeps the next tile.  Everything else -- trailing update, assembly of the
+// 64 x 64 triangular inverse from the tile inverses -- is 16 x 16 x 16 products on
+// the matrix cores (4 MFMAs each), one tile per wavefront.
 typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
 
@@ -61,130 +63,151 @@ __device__ __forceinline__ d4 mfma4(double a, double b, d4 c)
     return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
-// Assembly of the inverse X of a 64 x 64 lower triangular matrix T from the inverses of
-// its four 16 x 16 diagonal tiles (already in Xm):  X_ij = -X_ii sum_{m=j}^{i-1} T_im X_mj,
-// by distance from the diagonal.  tfetch(i, m, ks) returns this lane's A-operand element
-// of tile T_im for k-step ks, i.e. T_im[fr][4 ks + fq].
+// One off-diagonal 16 x 16 tile of the inverse X of a 64 x 64 lower triangular matrix T:
+//   X_ij = -X_ii sum_{m=j}^{i-1} T_im X_mj        (X_ii and the X_mj already in Xm).
+// tfetch(i, m, ks) returns this lane's A-operand element of tile T_im for k-step ks, i.e.
+// T_im[fr][4 ks + fq].  One wavefront.
 template <class TF>
-__device__ __forceinline__ void assemble_inverse(double* Xm, TF tfetch, int wave, int fr, int fq)
+__device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, int fr, int fq)
 {
-    for (int dist = 1; dist < 4; ++dist) {
-        const int i = dist + wave, j = i - dist;
-        if (i < 4) {
-            d4 t = {0.0, 0.0, 0.0, 0.0};
-            for (int m = j; m < i; ++m)
+    d4 t = {0.0, 0.0, 0.0, 0.0};
+    for (int m = j; m < i; ++m)
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    t = mfma4(tfetch(i, m, ks), Xm[(16 * m + 4 * ks + fq) * DL + 16 * j + fr], t);
-            // the accumulator layout (row 4 v + fq, column fr) is the B-operand layout of k-step v
-            d4 r = {0.0, 0.0, 0.0, 0.0};
+        for (int ks = 0; ks < 4; ++ks)
+            t = mfma4(tfetch(i, m, ks), Xm[(16 * m + 4 * ks + fq) * DL + 16 * j + fr], t);
+    // the accumulator layout (row 4 v + fq, column fr) is the B-operand layout of k-step v
+    d4 r = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) r = mfma4(Xm[(16 * i + fr) * DL + 16 * i + 4 * ks + fq], t[ks], r);
+    for (int ks = 0; ks < 4; ++ks) r = mfma4(Xm[(16 * i + fr) * DL + 16 * i + 4 * ks + fq], t[ks], r);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Xm[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = -r[v];
-        }
+    for (int v = 0; v < 4; ++v) Xm[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = -r[v];
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Schedule shared by chol_block and elim_block.  sweep(b): pivots of diagonal tile b and the
+// tiles below / right of it; tinv(b): triangular inverse of diagonal tile b into Xm;
+// trail(b): update of the tiles behind tile row/column b; tf: tile fetch for inv_tile.
+//   interval      wavefront 0   wavefront 1        wavefront 2
+//   b = 0..3      sweep(b)      tinv(b-1)          X_10 (b = 3)
+//   (after each of b = 0..2: trail(b) on all wavefronts)
+//   then          tinv(3)       X_21, X_20
+//   then          X_30          X_31               X_32
+// Called by all 256 threads of the workgroup; ends with a barrier.
+template <class SW, class TI, class TR, class TF>
+__device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR trail, TF tf)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int fr = lane & 15, fq = lane >> 4;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        if (wave == 0) sweep(b);
+        else if (wave == 1 && b > 0) tinv(b - 1);
+        else if (wave == 2 && b == 3) inv_tile(Xm, tf, 1, 0, fr, fq);
         __syncthreads();
+        if (b < 3) {
+            trail(b);
+            __syncthreads();
+        }
     }
+    if (wave == 0) tinv(3);
+    else if (wave == 1) {
+        inv_tile(Xm, tf, 2, 1, fr, fq);
+        inv_tile(Xm, tf, 2, 0, fr, fq);
+    }
+    __syncthreads();
+    if (wave < 3) inv_tile(Xm, tf, 3, wave, fr, fq);
+    __syncthreads();
 }
 
 // Cholesky of the 64 x 64 block held in LDS.
 //   in : Am lower triangle = the block (identity padding past its size), Xm = 0
 //   out: Am = L (lower; the strictly upper parts of the diagonal 16 x 16 tiles are zeroed),
-//        Xm = L^-1 (lower)
+//        Xm = L^-1 (lower);  rq (64 doubles of LDS) is scratch: 1 / L[k][k]
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1 so that
 //         the arithmetic stays finite; the caller reports ENOTPD).
 // Called by all 256 threads of the workgroup; ends with a barrier.
-__device__ __forceinline__ void chol_block(double* Am, double* Xm, int* __restrict__ flag)
+__device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, int* __restrict__ flag)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    for (int b = 0; b < 4; ++b) {
-        const int base = 16 * b;
-        if (wave == 0) {
-            // unblocked Cholesky of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of the
-            // symmetric tile
-            const int r = fr;
-            double a[16], rsv[16];
+
+    // Right-looking Cholesky of the 16 columns base .. base+15 of the block over all rows
+    // >= base: lane rho holds row rho.  Rows inside the diagonal tile (0 <= r < 16) hold the
+    // symmetric tile row; rows below it (r >= 16) get their part of L in the same sweep
+    // (l_rho,k = (a_rho,k - sum l l) / l_kk); rows above (r < 0) idle on harmless values.
+    auto sweep = [&](int b) {
+        const int base = 16 * b, rho = lane, r = rho - base;
+        double a[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                a[j] = (j <= r) ? Am[(base + r) * DL + base + j] : Am[(base + j) * DL + base + r];
-            // Each lane also keeps its own diagonal entry a[r][r] in `dg` and updates it locally
-            // (dg -= l_rk^2), so the pivot of step k+1 is available one fma after l_rk: the
-            // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
-            // rank-1 update of the rest of the tile fills the latency.
-            double dg = Am[(base + r) * DL + base + r];
-            bool bad = false;
+        for (int j = 0; j < 16; ++j) a[j] = (j <= r) ? Am[rho * DL + base + j] : Am[(base + j) * DL + rho];
+        // Each lane of the tile also keeps its own diagonal entry in `dg` and updates it locally
+        // (dg -= l_rk^2), so the pivot of step k+1 is available one fma after l_rk: the
+        // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
+        // rank-1 update of the rest fills the latency.
+        double dg = Am[rho * DL + rho];
+        double own = 0.0;
+        bool bad = false;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                double piv = readlane_f64(dg, k);
-                const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-                bad = bad || b2;
-                piv = b2 ? 1.0 : piv;
-                const double rs = pivot_rsqrt(piv);
-                rsv[k] = rs;                                           // 1 / L[k][k]
-                const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
-                const double lm = (r > k) ? t : 0.0;
-                dg -= lm * lm;
-                a[k] = t;
+        for (int k = 0; k < 16; ++k) {
+            double piv = readlane_f64(dg, base + k);
+            const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+            bad = bad || b2;
+            piv = b2 ? 1.0 : piv;
+            const double rs = pivot_rsqrt(piv);                    // 1 / L[k][k]
+            own = (r == k) ? rs : own;
+            const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
+            const double lm = (r > k) ? t : 0.0;
+            dg -= lm * lm;
+            a[k] = t;
 #pragma unroll
-                for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, j);
-            }
-            if (bad && lane == 0) *flag = 1;
-            if (lane < 16) {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) Am[(base + r) * DL + base + j] = (j <= r) ? a[j] : 0.0;
-            }
-            __builtin_amdgcn_wave_barrier();
-            // the tile's inverse by forward substitution: lane c (mod 16) solves L x = e_c; the
-            // entries of L are wavefront-uniform LDS reads
-            double sv[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sv[i] = (i == r) ? 1.0 : 0.0;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                const double xm = sv[m] * rsv[m];
-                sv[m] = xm;
-#pragma unroll
-                for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + i) * DL + base + m] * xm;
-            }
-            if (lane < 16) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + r] = sv[i];
-            }
+            for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, base + j);
         }
-        __syncthreads();
-        // panel: L_ib = A_ib * Linv_bb^T for the tiles below the diagonal tile
-        {
-            const int i = b + 1 + wave;
-            if (i < 4) {
-                d4 acc = {0.0, 0.0, 0.0, 0.0};
+        if (bad && lane == 0) *flag = 1;
+        if (r >= 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) Am[rho * DL + base + j] = (j <= r) ? a[j] : 0.0;
+            if (r < 16) rq[rho] = own;
+        }
+    };
+    // the diagonal tile's inverse by forward substitution: lane c (mod 16) solves L x = e_c;
+    // the entries of L and the pivot reciprocals are wavefront-uniform LDS reads
+    auto tinv = [&](int b) {
+        const int base = 16 * b, c = fr;
+        double sv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sv[i] = (i == c) ? 1.0 : 0.0;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const double xm = sv[m] * rq[base + m];
+            sv[m] = xm;
+#pragma unroll
+            for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + i) * DL + base + m] * xm;
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + c] = sv[i];
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    // trailing tiles: A_ij -= L_ib L_jb^T for b < j <= i
+    auto trail = [&](int b) {
+        const int base = 16 * b;
+        int t = 0;
+        for (int i = b + 1; i < 4; ++i)
+            for (int j = b + 1; j <= i; ++j, ++t) {
+                if ((t & 3) != wave) continue;
+                d4 acc;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    acc = mfma4(Am[(16 * i + fr) * DL + base + 4 * ks + fq], Xm[(base + fr) * DL + base + 4 * ks + fq], acc);
+                    acc = mfma4(-Am[(16 * i + fr) * DL + base + 4 * ks + fq], Am[(16 * j + fr) * DL + base + 4 * ks + fq], acc);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + base + fr] = acc[v];
+                for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
             }
-        }
-        __syncthreads();
-        // trailing tiles: A_ij -= L_ib L_jb^T for b < j <= i
-        {
-            int t = 0;
-            for (int i = b + 1; i < 4; ++i)
-                for (int j = b + 1; j <= i; ++j, ++t) {
-                    if ((t & 3) != wave) continue;
-                    d4 acc;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        acc = mfma4(-Am[(16 * i + fr) * DL + base + 4 * ks + fq], Am[(16 * j + fr) * DL + base + 4 * ks + fq], acc);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
-                }
-        }
-        __syncthreads();
-    }
-    assemble_inverse(Xm, [&](int i, int m, int ks) { return Am[(16 * i + fr) * DL + 16 * m + 4 * ks + fq]; }, wave, fr, fq);
+    };
+    block_schedule(Xm, sweep, tinv, trail,
+                   [&](int i, int m, int ks) { return Am[(16 * i + fr) * DL + 16 * m + 4 * ks + fq]; });
 }
 
 __device__ __forceinline__ void chol_block_store(const double* Am, const double* Xm, int64_t ld, int o, int nb,
@@ -215,6 +238,7 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
 {
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
+    __shared__ double rq[NB];
     for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
         const int i = idx >> 6, j = idx & 63;
         double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
@@ -223,7 +247,7 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict
         Xm[i * DL + j] = 0.0;
     }
     __syncthreads();
-    chol_block(Am, Xm, flag);
+    chol_block(Am, Xm, rq, flag);
     chol_block_store(Am, Xm, ld, o, nb, L, Linv, Dinv);
 }
 
@@ -252,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
                                                         double* __restrict__ Linv, double* __restrict__ Dinv_next,
                                                         int* __restrict__ flag)
 {
-    __shared__ double lds[2 * NB * DL];      // two tiles: 2 workgroups per compute unit
+    __shared__ double lds[2 * NB * DL + NB];  // two tiles: 2 workgroups per compute unit
     double* Pi = lds;
     double* Pj = lds + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -373,7 +397,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
                 Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
             }
     __syncthreads();
-    chol_block(Am, Xm, flag);
+    chol_block(Am, Xm, lds + 2 * NB * DL, flag);
     chol_block_store(Am, Xm, d, r0, nbn, L, Linv, Dinv_next);
 }
 
@@ -451,95 +475,83 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    for (int b = 0; b < 4; ++b) {
-        const int base = 16 * b;
-        if (wave == 0) {
-            // unblocked elimination of the 16 x 16 diagonal tile; lane r (mod 16) holds row r of
-            // the symmetric tile
-            const int r = fr;
-            double a[16], pinv[16];
+
+    // Elimination of the 16 pivots base .. base+15 over all columns >= base: lane c holds
+    // column c of the 16 pivot rows.  Columns inside the diagonal tile (0 <= r < 16) hold the
+    // symmetric tile column; columns right of it (r >= 16) get their part of the pivot rows
+    // in the same sweep; columns left of it (r < 0) idle on harmless values.
+    auto sweep = [&](int b) {
+        const int base = 16 * b, c = lane, r = c - base;
+        double a[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
-            // as in chol_block: every lane keeps its own diagonal entry in `dg`
-            double dg = Am[(base + r) * DL + base + r];
-            bool bad = false;
+        for (int j = 0; j < 16; ++j) a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+        // as in chol_block: every lane of the tile keeps its own diagonal entry in `dg`
+        double dg = Am[c * DL + c];
+        double own = 0.0;
+        bool bad = false;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                double piv = readlane_f64(dg, k);
-                const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-                bad = bad || b2;
-                piv = b2 ? 1.0 : piv;
-                const double pi = pivot_rcp(piv);
-                pinv[k] = pi;
-                const double cr = (r == k) ? piv : a[k];          // A[k][r] = U[k][r] for r >= k
-                const double fm = (r > k) ? cr * pi : 0.0;        // Un[k][r]
-                dg -= fm * cr;
-                a[k] = cr;
+        for (int k = 0; k < 16; ++k) {
+            double piv = readlane_f64(dg, base + k);
+            const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
+            bad = bad || b2;
+            piv = b2 ? 1.0 : piv;
+            const double pi = pivot_rcp(piv);
+            own = (r == k) ? pi : own;
+            const double cr = (r == k) ? piv : a[k];          // A[k][c] = U[k][c] for c >= k
+            const double fm = (r > k) ? cr * pi : 0.0;        // Un[k][c]
+            dg -= fm * cr;
+            a[k] = cr;
 #pragma unroll
-                for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, j);
-            }
-            if (bad && lane == 0) *flag = 1;
-            if (lane < 16) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    // lane r holds column r of the pivot rows: U[k][r] for k <= r
-                    if (k <= r) Am[(base + k) * DL + base + r] = a[k];
-                    if (k == r) rv[base + k] = pinv[k];
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-            // G_bb = (Un_bb^T)^-1 (unit lower) by forward substitution: lane c (mod 16) solves
-            // Un_bb^T x = e_c; entry [i][m] of Un_bb^T is Un[m][i], a wavefront-uniform LDS read
-            double sv[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sv[i] = (i == r) ? 1.0 : 0.0;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                const double xm = sv[m];
-#pragma unroll
-                for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + m) * DL + base + i] * pinv[m] * xm;
-            }
-            if (lane < 16) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + r] = sv[i];
-            }
+            for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, base + j);
         }
-        __syncthreads();
-        // pivot rows right of the diagonal tile: U_bj = G_bb * A_bj, Un_bj = D^-1 U_bj
-        {
-            const int j = b + 1 + wave;
-            if (j < 4) {
-                d4 acc = {0.0, 0.0, 0.0, 0.0};
+        if (bad && lane == 0) *flag = 1;
+        if (r >= 0) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (k <= r) Am[(base + k) * DL + c] = a[k];   // U[k][c] for k <= c
+            if (r < 16) rv[c] = own;
+        }
+    };
+    // G_bb = (Un_bb^T)^-1 (unit lower) by forward substitution: lane c (mod 16) solves
+    // Un_bb^T x = e_c; entry [i][m] of Un_bb^T is Un[m][i], a wavefront-uniform LDS read
+    auto tinv = [&](int b) {
+        const int base = 16 * b, c = fr;
+        double sv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sv[i] = (i == c) ? 1.0 : 0.0;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const double xm = sv[m] * rv[base + m];
+#pragma unroll
+            for (int i = m + 1; i < 16; ++i) sv[i] -= Am[(base + m) * DL + base + i] * xm;
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Xm[(base + i) * DL + base + c] = sv[i];
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    // trailing tiles: A_ij -= Un_bi^T U_bj for b < i <= j
+    auto trail = [&](int b) {
+        const int base = 16 * b;
+        int t = 0;
+        for (int i = b + 1; i < 4; ++i)
+            for (int j = i; j < 4; ++j, ++t) {
+                if ((t & 3) != wave) continue;
+                d4 acc;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    acc = mfma4(Xm[(base + fr) * DL + base + 4 * ks + fq], Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
+                    acc = mfma4(-Am[(base + 4 * ks + fq) * DL + 16 * i + fr] * rv[base + 4 * ks + fq],
+                                Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) Am[(base + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
+                for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
             }
-        }
-        __syncthreads();
-        // trailing tiles: A_ij -= Un_bi^T U_bj for b < i <= j
-        {
-            int t = 0;
-            for (int i = b + 1; i < 4; ++i)
-                for (int j = i; j < 4; ++j, ++t) {
-                    if ((t & 3) != wave) continue;
-                    d4 acc;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        acc = mfma4(-Am[(base + 4 * ks + fq) * DL + 16 * i + fr] * rv[base + 4 * ks + fq],
-                                    Am[(base + 4 * ks + fq) * DL + 16 * j + fr], acc);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr] = acc[v];
-                }
-        }
-        __syncthreads();
-    }
+    };
     // G = (Un11^T)^-1: tile T_im of Un11^T is Un_mi transposed
-    assemble_inverse(Xm, [&](int i, int m, int ks) {
-        return Am[(16 * m + 4 * ks + fq) * DL + 16 * i + fr] * rv[16 * m + 4 * ks + fq]; }, wave, fr, fq);
+    block_schedule(Xm, sweep, tinv, trail, [&](int i, int m, int ks) {
+        return Am[(16 * m + 4 * ks + fq) * DL + 16 * i + fr] * rv[16 * m + 4 * ks + fq]; });
 }
 
 __device__ __forceinline__ void elim_block_store(const double* Am, const double* Xm, const double* rv,
