@@ -210,6 +210,17 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
                    [&](int i, int m, int ks) { return Am[(16 * i + fr) * DL + 16 * m + 4 * ks + fq]; });
 }
 
+// Fragment layout of a 64 x 64 block inverse M that the next launch uses as an MFMA operand:
+//   F[((w * 16 + ks) * 2 + h) * 64 + lane] = M[w * 32 + h * 16 + (lane & 15)][4 * ks + (lane >> 4)]
+// so that the 64 lanes of a wavefront read 512 contiguous bytes per operand element instead of
+// 16 scattered 32-byte pieces.  frag_source returns the (row, column) of M stored at F[idx].
+__device__ __forceinline__ void frag_source(int idx, int& row, int& col)
+{
+    const int lane = idx & 63, h = (idx >> 6) & 1, ks = (idx >> 7) & 15, w = idx >> 11;
+    row = w * 32 + h * 16 + (lane & 15);
+    col = 4 * ks + (lane >> 4);
+}
+
 __device__ __forceinline__ void chol_block_store(const double* Am, const double* Xm, int64_t ld, int o, int nb,
                                                  double* __restrict__ L, double* __restrict__ Linv,
                                                  double* __restrict__ Dinv)
@@ -218,7 +229,9 @@ __device__ __forceinline__ void chol_block_store(const double* Am, const double*
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
         const double xv = (in && j <= i) ? Xm[i * DL + j] : 0.0;
-        Dinv[idx] = xv;
+        int fi, fj;
+        frag_source(idx, fi, fj);
+        Dinv[idx] = (fi < nb && fj <= fi) ? Xm[fi * DL + fj] : 0.0;     // fj <= fi < nb
         if (in) {
             L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? Am[i * DL + j] : 0.0;
             Linv[(int64_t)(o + i) * ld + o + j] = xv;
@@ -231,7 +244,7 @@ __device__ __forceinline__ void chol_block_store(const double* Am, const double*
 //   in : A[o:o+nb, o:o+nb] (symmetric; only the lower triangle is read)
 //   out: L[o:o+nb, o:o+nb] = L11 (lower, upper part zeroed)
 //        Linv[o:o+nb, o:o+nb] = L11^-1 (lower, upper part zeroed)
-//        Dinv (64 x 64, ld 64) = L11^-1 zero padded
+//        Dinv (4096 doubles) = L11^-1 zero padded, in the fragment layout
 __global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ L, double* __restrict__ Linv,
                                                         double* __restrict__ Dinv, int* __restrict__ flag)
@@ -293,15 +306,17 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) gb[ks][j] = Dinv[(wn * 32 + j * 16 + fr) * NB + 4 * ks + fq];
+        for (int j = 0; j < 2; ++j) gb[ks][j] = Dinv[((wn * 16 + ks) * 2 + j) * 64 + lane];
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int y = wave + 4 * u, x = lane;
         const int gi = mi0 + y, gj = mj0 + y;
-        pa[u] = (gi < d) ? Hd[(int64_t)gi * d + o + x] : 0.0;
-        pb[u] = (!diag_tile && gj < d) ? Hd[(int64_t)gj * d + o + x] : 0.0;
+        // Rows past d are read from row d - 1 (clamped address, no branch per load): they only
+        // reach outputs past d, which are never stored or are replaced by the identity padding.
+        pa[u] = Hd[(int64_t)min(gi, d - 1) * d + o + x];
+        pb[u] = Hd[(int64_t)min(diag_tile ? gi : gj, d - 1) * d + o + x];
     }
     d4 c[2][2];
 #pragma unroll
@@ -311,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
-                c[i][j][v] = (gm < d && gn < d) ? Hd[(int64_t)gm * d + gn] : 0.0;
+                c[i][j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
             }
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
@@ -557,12 +572,17 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
 __device__ __forceinline__ void elim_block_store(const double* Am, const double* Xm, const double* rv,
                                                  int64_t ld, int o, int nb, double* __restrict__ U,
                                                  double* __restrict__ Un, double* __restrict__ G,
-                                                 double* __restrict__ rinv)
+                                                 double* __restrict__ Gf, double* __restrict__ rinv)
 {
     for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
-        G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
+        if (G) G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
+        if (Gf) {
+            int fi, fj;
+            frag_source(idx, fi, fj);
+            Gf[idx] = (fi < nb && fj <= fi) ? Xm[fi * DL + fj] : 0.0;
+        }
         if (in && j >= i) {
             U[(int64_t)(o + i) * ld + o + j] = Am[i * DL + j];
             Un[(int64_t)(o + i) * ld + o + j] = (i == j) ? 1.0 : Am[i * DL + j] * rv[i];
@@ -574,12 +594,13 @@ __device__ __forceinline__ void elim_block_store(const double* Am, const double*
 // Diagonal block of the elimination (stand-alone launch).
 //   out: U[o+j, o+j : o+nb]  = pivot row j inside the block
 //        Un = U / pivot
-//        G (64 x 64, ld 64)  = (Un11^T)^-1: pivot rows right of the block are G * A[o:o+nb, o+nb:]
+//        G (64 x 64, ld 64)  = (Un11^T)^-1: pivot rows right of the block are G * A[o:o+nb, o+nb:];
+//        Gf = the same in the fragment layout (either may be null)
 //        rinv[j] = 1 / pivot_j
 __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ U, double* __restrict__ Un,
-                                                        double* __restrict__ G, double* __restrict__ rinv,
-                                                        int* __restrict__ flag)
+                                                        double* __restrict__ G, double* __restrict__ Gf,
+                                                        double* __restrict__ rinv, int* __restrict__ flag)
 {
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
@@ -593,12 +614,12 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
     }
     __syncthreads();
     elim_block(Am, Xm, rv, flag);
-    elim_block_store(Am, Xm, rv, ld, o, nb, U, Un, G, rinv);
+    elim_block_store(Am, Xm, rv, ld, o, nb, U, Un, G, Gf, rinv);
 }
 
 // One whole iteration of the blocked shared-Hinv elimination in a single launch (same scheme
 // as chol_iter_kernel).  The panel is the 64 rows/columns o .. o+63 whose diagonal block has
-// been eliminated (G, rinv).  Workgroup (ti, tj), ti <= tj, owns tile (ti, tj) of the trailing
+// been eliminated (G in the fragment layout, rinv).  Workgroup (ti, tj), ti <= tj, owns tile (ti, tj) of the trailing
 // matrix (upper triangle):
 //   1. pivot rows right of the block for its two tile columns: U12_i = G A12_i, U12_j, and
 //      Un12 = D^-1 U12; the tiles of the first tile row also store them into U and Un;
@@ -627,14 +648,16 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) ga[ks][i] = G[(wm * 32 + i * 16 + fr) * NB + 4 * ks + fq];
+        for (int i = 0; i < 2; ++i) ga[ks][i] = G[((wm * 16 + ks) * 2 + i) * 64 + lane];
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int y = wave + 4 * u, x = lane;
-        pa[u] = (ci0 + x < d) ? A[(int64_t)(o + y) * d + ci0 + x] : 0.0;
-        pb[u] = (!diag_tile && cj0 + x < d) ? A[(int64_t)(o + y) * d + cj0 + x] : 0.0;
+        // Columns past d are read from column d - 1 (clamped address, no branch per load): they
+        // only reach outputs past d, which are never stored or are replaced by the identity padding.
+        pa[u] = A[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
+        pb[u] = A[(int64_t)(o + y) * d + min((diag_tile ? ci0 : cj0) + x, d - 1)];
     }
     const double rsv = (tid < NB) ? rinv[tid] : 0.0;
     d4 c[2][2];
@@ -645,7 +668,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
-                c[i][j][v] = (gm < d && gn < d) ? A[(int64_t)gm * d + gn] : 0.0;
+                c[i][j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
             }
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
@@ -738,7 +761,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
             }
     __syncthreads();
     elim_block(Am, Xm, rs, flag);
-    elim_block_store(Am, Xm, rs, d, r0, nbn, U, Un, G_next, rinv_next);
+    elim_block_store(Am, Xm, rs, d, r0, nbn, U, Un, nullptr, G_next, rinv_next);
 }
 
 // Shared-Hinv elimination of the first `steps` columns, `block` columns at a time.
@@ -753,8 +776,8 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
     if (block == NB && steps == d) {
         // one stand-alone launch for the first diagonal block, then one fused launch per panel
-        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un, Gb[0],
-                           rb[0], flag);
+        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un,
+                           (double*)nullptr, Gb[0], rb[0], flag);
         int it = 0;
         for (int o = 0; o + NB < d; o += NB, ++it) {
             const int T = (d - o - NB + NB - 1) / NB;
@@ -771,7 +794,8 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     int it = 0;
     for (int o = 0; o < steps; o += block, ++it) {
         const int nb = min(block, steps - o);
-        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, o, nb, U, Un, G, rinv, flag);
+        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, o, nb, U, Un, G,
+                           (double*)nullptr, rinv, flag);
         const int r = d - o - nb;
         if (r <= 0) { ready(it); break; }
         // pivot rows right of the block: U12 = G * A12, Un12 = D^-1 U12
