@@ -169,6 +169,26 @@ def column_loop(W: np.ndarray, Hinv: np.ndarray, perm: np.ndarray, bits: int, gr
     return LoopResult(codes, Q, Ww, Hw, loss.value)
 
 
+def column_loop_dynamic(W: np.ndarray, Hinv: np.ndarray, bits: int, group: int, scale: np.ndarray,
+                        zero: np.ndarray, steps: Optional[int] = None):
+    """Column loop with the order chosen step by step (largest current score first).
+    Returns (LoopResult, perm)."""
+    W = _f32(W)
+    r, d = W.shape
+    Hw = np.array(Hinv, dtype=np.float64, order="C", copy=True)
+    perm = np.empty(d, dtype=np.int32)
+    steps = d if steps is None else steps
+    codes = np.empty((r, d), dtype=np.int64)
+    Q = np.empty((r, d), dtype=np.float64)
+    Ww = np.empty((r, d), dtype=np.float64)
+    loss = ctypes.c_double(0.0)
+    _chk(_get().oracle_column_loop_dynamic(_p(W), ctypes.c_int64(r), ctypes.c_int64(d), _p(Hw), _p(perm),
+                                           ctypes.c_int(bits), ctypes.c_int64(group), _p(scale), _p(zero),
+                                           ctypes.c_int64(steps), _p(codes), _p(Q), _p(Ww), ctypes.byref(loss)),
+         "oracle_column_loop_dynamic")
+    return LoopResult(codes, Q, Ww, Hw, loss.value), perm
+
+
 def loss_eval(W: np.ndarray, Q: np.ndarray, H: np.ndarray) -> float:
     """1/2 tr((W - Q) H (W - Q)^T)."""
     W = _f32(W)
@@ -196,6 +216,7 @@ def output_error(W: np.ndarray, Q: np.ndarray, X: np.ndarray) -> float:
 
 ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM = 0, 1, 2
 ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC = 3, 4, 5, 6, 7
+ORDER_SENSI_DYNAMIC = 8
 _ORDER_KEYS = {ORDER_SENSI_DESC: (KEY_SENSI, False), ORDER_ERR_DESC: (KEY_ERR, False), ORDER_W_DESC: (KEY_W, False),
                ORDER_SENSI_ASC: (KEY_SENSI, True), ORDER_ERR_ASC: (KEY_ERR, True), ORDER_W_ASC: (KEY_W, True)}
 
@@ -238,6 +259,10 @@ def quantize_layer(W: np.ndarray, X: Optional[np.ndarray] = None, H: Optional[np
         kind, asc = _ORDER_KEYS[order_mode]
         S = column_key(W, np.ascontiguousarray(np.diag(Hinv)), bits, group, scale, zero, kind)
         p = order(S, asc)
+    elif order_mode == ORDER_SENSI_DYNAMIC:
+        res, p = column_loop_dynamic(W, Hinv, bits, group, scale, zero, steps)
+        return LayerResult(res.codes, scale, zero, res.Q, p, res.loss, H, Hd, Hinv, S,
+                           res.W_work, res.Hinv_work, lam)
     else:
         p = np.ascontiguousarray(perm, dtype=np.int32)
     res = column_loop(W, Hinv, p, bits, group, scale, zero, steps)

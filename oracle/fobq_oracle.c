@@ -284,12 +284,13 @@ int oracle_order(const double *S, int64_t d, int32_t *perm)
  * value they had when they were quantized), Hinv (running; rows and columns of
  * processed indices are set to 0), loss.
  */
-int oracle_column_loop(const float *W, int64_t d_row, int64_t d_col, double *Hinv,
-                       const int32_t *perm, int bits, int64_t group,
-                       const double *scale, const double *zero, int64_t steps,
-                       int64_t *codes, double *Q, double *Wwork, double *loss)
+static int column_loop_impl(const float *W, int64_t d_row, int64_t d_col, double *Hinv,
+                            const int32_t *perm, int32_t *perm_dyn, int bits, int64_t group,
+                            const double *scale, const double *zero, int64_t steps,
+                            int64_t *codes, double *Q, double *Wwork, double *loss)
 {
-    if (!W || !Hinv || !perm || !scale || !zero || !codes || !Q || !Wwork || !loss) return ORACLE_EINVAL;
+    if (!W || !Hinv || (!perm && !perm_dyn) || !scale || !zero || !codes || !Q || !Wwork || !loss)
+        return ORACLE_EINVAL;
     if (steps < 0 || steps > d_col) return ORACLE_EINVAL;
     const int64_t d = d_col;
     const int64_t G = groups_of(d_col, group);
@@ -298,7 +299,11 @@ int oracle_column_loop(const float *W, int64_t d_row, int64_t d_col, double *Hin
     unsigned char *done = (unsigned char *)calloc((size_t)d, 1);
     double *rowj = (double *)malloc((size_t)d * sizeof(double));
     double *lossrow = (double *)calloc((size_t)d_row, sizeof(double));
-    if (!done || !rowj || !lossrow) { free(done); free(rowj); free(lossrow); return ORACLE_ENOMEM; }
+    double *score = (double *)calloc((size_t)d, sizeof(double));
+    if (!done || !rowj || !lossrow || !score) {
+        free(done); free(rowj); free(lossrow); free(score);
+        return ORACLE_ENOMEM;
+    }
     for (int64_t i = 0; i < d_row * d_col; ++i) {
         Wwork[i] = (double)W[i];
         Q[i] = 0.0;
@@ -306,7 +311,32 @@ int oracle_column_loop(const float *W, int64_t d_row, int64_t d_col, double *Hin
     }
     int status = ORACLE_OK;
     for (int64_t t = 0; t < steps; ++t) {
-        const int64_t j = perm[t];
+        int64_t j;
+        if (perm_dyn) {
+            /* Dynamic order: the scores of Eq. 10 are recomputed from the current weights and the
+             * current shared inverse; the column with the largest score is next (the first such
+             * column in index order when several are equal). */
+#pragma omp parallel for schedule(static)
+            for (int64_t k = 0; k < d; ++k) {
+                if (done[k]) continue;
+                const int64_t gk = k / gs;
+                const double hkk = Hinv[k * d + k];
+                double sk = 0.0;
+                for (int64_t i = 0; i < d_row; ++i) {
+                    const double w = Wwork[i * d + k];
+                    const double s = scale[i * G + gk], z = zero[i * G + gk];
+                    const double diff = grid_value(grid_code(w, s, z, maxq), s, z) - w;
+                    sk += diff * diff / (2.0 * hkk);
+                }
+                score[k] = sk;
+            }
+            j = -1;
+            for (int64_t k = 0; k < d; ++k)
+                if (!done[k] && (j < 0 || score[k] > score[j])) j = k;
+            perm_dyn[t] = (int32_t)j;
+        } else {
+            j = perm[t];
+        }
         if (j < 0 || j >= d || done[j]) { status = ORACLE_EINVAL; break; }
         const double hjj = Hinv[j * d + j];
         if (!(hjj > 0.0)) { status = ORACLE_ENOTPD; break; }
@@ -344,10 +374,44 @@ int oracle_column_loop(const float *W, int64_t d_row, int64_t d_col, double *Hin
     double total = 0.0;
     for (int64_t i = 0; i < d_row; ++i) total += lossrow[i];
     *loss = total;
+    if (perm_dyn) {
+        /* columns not reached (steps < d_col) follow in index order */
+        int64_t t = steps;
+        for (int64_t k = 0; k < d && status == ORACLE_OK; ++k)
+            if (!done[k]) perm_dyn[t++] = (int32_t)k;
+    }
     free(done);
     free(rowj);
     free(lossrow);
+    free(score);
     return status;
+}
+
+int oracle_column_loop(const float *W, int64_t d_row, int64_t d_col, double *Hinv,
+                       const int32_t *perm, int bits, int64_t group,
+                       const double *scale, const double *zero, int64_t steps,
+                       int64_t *codes, double *Q, double *Wwork, double *loss)
+{
+    if (!perm) return ORACLE_EINVAL;
+    return column_loop_impl(W, d_row, d_col, Hinv, perm, NULL, bits, group, scale, zero, steps,
+                            codes, Q, Wwork, loss);
+}
+
+/*
+ * The same loop with the order decided step by step (the reading of Section 5 in which the
+ * sorting is repeated for every column): before each step the scores S_k of Eq. 10 are
+ * recomputed for every column not yet processed, from the current (compensated) weights and
+ * the diagonal of the current shared inverse, and the column with the largest score is taken.
+ * perm_out[t] receives the column processed at step t.
+ */
+int oracle_column_loop_dynamic(const float *W, int64_t d_row, int64_t d_col, double *Hinv,
+                               int32_t *perm_out, int bits, int64_t group,
+                               const double *scale, const double *zero, int64_t steps,
+                               int64_t *codes, double *Q, double *Wwork, double *loss)
+{
+    if (!perm_out) return ORACLE_EINVAL;
+    return column_loop_impl(W, d_row, d_col, Hinv, NULL, perm_out, bits, group, scale, zero, steps,
+                            codes, Q, Wwork, loss);
 }
 
 /* 1/2 tr((W - Q) H (W - Q)^T), H fp64 d x d. */

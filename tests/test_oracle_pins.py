@@ -368,3 +368,70 @@ def test_every_order_is_the_custom_order_of_its_own_permutation(mode):
     # the loss identity holds for any order
     dW = W.astype(np.float64) - a.Q
     assert np.isclose(a.loss, 0.5 * np.trace(dW @ a.H_damped @ dW.T), rtol=1e-9)
+
+
+# ---------------------------------------------------------------- dynamic order (Section 5: sorting repeated per column)
+def test_dynamic_order_is_the_custom_order_of_its_own_permutation():
+    W, X = _problem(7, 14, 80, 24)
+    a = oracle.quantize_layer(W, X=X, bits=3, order_mode=oracle.ORDER_SENSI_DYNAMIC)
+    assert sorted(a.perm) == list(range(14))
+    b = oracle.quantize_layer(W, X=X, bits=3, order_mode=oracle.ORDER_CUSTOM, perm=a.perm)
+    assert np.array_equal(a.codes, b.codes) and np.array_equal(a.Q, b.Q) and a.loss == b.loss
+    # first choice = largest initial score = first column of the static order
+    assert a.perm[0] == oracle.quantize_layer(W, X=X, bits=3).perm[0]
+
+
+@pytest.mark.parametrize("group", [0, 3])
+def test_dynamic_order_takes_the_column_with_the_largest_loss_term(group):
+    """Eq. 10 is the loss a column incurs when it is quantized now.  At every step, processing any
+    other remaining column next would add a smaller (or equal) term to the loss: checked through the
+    loss accumulated by the static loop run on each alternative order (an independent route to the
+    same number: the loop's own (w - q)^2 / (2 Hinv_tt), not the score routine)."""
+    d = 6
+    W, X = _problem(5, d, 40, 25)
+    H = oracle.hessian(X)
+    a = oracle.quantize_layer(W, H=H, bits=3, group=group, order_mode=oracle.ORDER_SENSI_DYNAMIC)
+    for t in range(d):
+        done = list(a.perm[:t])
+        before = oracle.quantize_layer(W, H=H, bits=3, group=group, order_mode=oracle.ORDER_CUSTOM,
+                                       perm=a.perm, steps=t).loss if t else 0.0
+        gains = {}
+        for cand in range(d):
+            if cand in done:
+                continue
+            rest = [k for k in range(d) if k not in done and k != cand]
+            p = np.array(done + [cand] + rest, dtype=np.int32)
+            gains[cand] = oracle.quantize_layer(W, H=H, bits=3, group=group, order_mode=oracle.ORDER_CUSTOM,
+                                                perm=p, steps=t + 1).loss - before
+        best = max(gains.values())
+        assert gains[int(a.perm[t])] >= best * (1 - 1e-9)
+        # and the choice is strict here (no ties in this problem), so it is the unique argmax
+        assert int(a.perm[t]) == max(gains, key=gains.get)
+
+
+def test_dynamic_order_equals_static_order_without_compensation():
+    # X with orthogonal rows: H diagonal, no compensation, the diagonal of Hinv never changes,
+    # so the scores of the remaining columns never change either.
+    rng = np.random.default_rng(26)
+    d = 9
+    Qm, _ = np.linalg.qr(rng.standard_normal((32, d)))
+    X = (Qm.T * np.linspace(1.0, 3.0, d)[:, None]).astype(np.float32)
+    W = (rng.standard_normal((6, d)) * 0.1).astype(np.float32)
+    H = np.diag(np.diag(oracle.hessian(X)))            # exactly diagonal
+    a = oracle.quantize_layer(W, H=H, bits=4, order_mode=oracle.ORDER_SENSI_DYNAMIC)
+    b = oracle.quantize_layer(W, H=H, bits=4, order_mode=oracle.ORDER_SENSI_DESC)
+    assert np.array_equal(a.perm, b.perm) and np.array_equal(a.codes, b.codes)
+
+
+def test_dynamic_order_breaks_ties_by_index_and_honours_steps():
+    # two identical columns with identical statistics: the smaller index goes first
+    rng = np.random.default_rng(27)
+    W = (rng.standard_normal((4, 5)) * 0.1).astype(np.float32)
+    W[:, 3] = W[:, 1]
+    H = np.eye(5) * 2.0
+    a = oracle.quantize_layer(W, H=H, bits=2, damp_rel=0.0, order_mode=oracle.ORDER_SENSI_DYNAMIC)
+    assert list(a.perm).index(1) + 1 == list(a.perm).index(3)
+    part = oracle.quantize_layer(W, H=H, bits=2, damp_rel=0.0, order_mode=oracle.ORDER_SENSI_DYNAMIC, steps=2)
+    assert np.array_equal(part.perm[:2], a.perm[:2])
+    assert sorted(part.perm) == list(range(5)) and list(part.perm[2:]) == sorted(part.perm[2:])
+    assert np.all(part.Q[:, part.perm[2:]] == 0.0)
