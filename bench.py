@@ -173,7 +173,8 @@ def main() -> int:
                "seconds": round(cpu_s, 2), "codes_differ_vs_gpu": float((codes != ref.codes).mean())}
 
     line = {
-        "metric": "weights quantized per second, whole layer path (ResNet-50 3x3 shape)",
+        "metric": "weights quantized per second, whole layer path"
+                  + (" (ResNet-50 3x3 shape)" if spec.name == "c2_resnet50_3x3" else f" ({spec.name})"),
         "value": round(value, 1), "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",

@@ -55,7 +55,11 @@ typedef enum {
     FOBQ_ORDER_W_DESC = 4,     /* by sum_i w_ij^2, descending                                 */
     FOBQ_ORDER_SENSI_ASC = 5,  /* ascending variants                                          */
     FOBQ_ORDER_ERR_ASC = 6,
-    FOBQ_ORDER_W_ASC = 7
+    FOBQ_ORDER_W_ASC = 7,
+    FOBQ_ORDER_SENSI_DYNAMIC = 8 /* Section 5 read literally (sorting repeated for every column): before   */
+                                 /* each step S_j is recomputed from the current weights and the current */
+                                 /* shared inverse and the largest is taken (smaller index among equals); */
+                                 /* always runs one column per launch, `block` is ignored                 */
 } fobq_order;
 
 typedef struct {

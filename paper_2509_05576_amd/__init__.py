@@ -5,7 +5,7 @@ from .binding import (  # noqa: F401
     FobqError, Ctx, LayerOutput,
     OK, EINVAL, ENOMEM, EHIP, ENOTPD, ESTATE,
     ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM,
-    ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC,
+    ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC, ORDER_SENSI_DYNAMIC,
     STAGES, lib_path, load_library,
     fobq_create, fobq_destroy, fobq_last_error,
     fobq_hessian_begin, fobq_hessian_accumulate, fobq_hessian_finalize,

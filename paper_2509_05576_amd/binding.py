@@ -14,6 +14,7 @@ import torch
 OK, EINVAL, ENOMEM, EHIP, ENOTPD, ESTATE = 0, -1, -2, -3, -4, -5
 ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM = 0, 1, 2
 ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC = 3, 4, 5, 6, 7
+ORDER_SENSI_DYNAMIC = 8
 STAGES = ("xxt", "finalize", "cholesky", "inverse", "order", "permute", "eliminate", "columns", "emit")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

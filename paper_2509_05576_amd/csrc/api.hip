@@ -154,7 +154,7 @@ static int check_opts(fobq_ctx* ctx, const fobq_opts* o, int64_t d_col)
     if (o->group < 0 || (o->group > 0 && d_col % o->group != 0))
         return set_err(ctx, FOBQ_EINVAL, "group (%d) must be 0 or divide d_col (%lld)", o->group, (long long)d_col);
     if (!(o->damp >= 0.0) || !(o->damp_abs >= 0.0)) return set_err(ctx, FOBQ_EINVAL, "damp and damp_abs must be >= 0");
-    if (o->order < FOBQ_ORDER_NATURAL || o->order > FOBQ_ORDER_W_ASC)
+    if (o->order < FOBQ_ORDER_NATURAL || o->order > FOBQ_ORDER_SENSI_DYNAMIC)
         return set_err(ctx, FOBQ_EINVAL, "unknown order %d", o->order);
     if (o->order == FOBQ_ORDER_CUSTOM && !o->perm_in) return set_err(ctx, FOBQ_EINVAL, "order CUSTOM needs perm_in");
     if (o->block < 0 || o->block > 64) return set_err(ctx, FOBQ_EINVAL, "block must be in 0..64 (got %d)", o->block);
@@ -190,11 +190,12 @@ static int enqueue_order(fobq_ctx* ctx, const float* W, int R, int d, const fobq
     // sort key: 0 "sensi", 1 "err", 2 "w" (Section 4.1, Table 3)
     const int kind = (o->order == FOBQ_ORDER_ERR_DESC || o->order == FOBQ_ORDER_ERR_ASC) ? 1
                    : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
-    const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC;
+    const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC && o->order <= FOBQ_ORDER_W_ASC;
     FOBQ_TRY(launch_sensitivity(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
                                 ctx->hdiag.as<double>(), ctx->Spart.as<double>(), chunks, ctx->S.as<double>(), kind),
              "sensitivity");
-    if (o->order == FOBQ_ORDER_NATURAL)
+    // the dynamic order starts from the identity and exchanges columns step by step
+    if (o->order == FOBQ_ORDER_NATURAL || o->order == FOBQ_ORDER_SENSI_DYNAMIC)
         FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
     else if (o->order != FOBQ_ORDER_CUSTOM)
         FOBQ_TRY(launch_rank_sort(s, ctx->S.as<double>(), d, ctx->perm.as<int>(), ctx->invperm.as<int>(), ascending),
@@ -268,7 +269,7 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
     const size_t dd = (size_t)d_col * d_col * sizeof(double);
     FOBQ_TRY(ctx->Hpart.ensure(dd * splits), "workspace Hpart");
     FOBQ_TRY(ctx->H.ensure(dd), "workspace H");
-    FOBQ_TRY(hipMemsetAsync(ctx->Hpart.p, 0, dd * splits, ctx->stream), "clear Hessian accumulator");
+    ctx->h_zeroed = 0;      // slabs are cleared when a launch first needs them
     ctx->h_d = d_col;
     ctx->h_n = 0;
     ctx->h_splits = splits;
@@ -286,6 +287,13 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     if (n == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
+    if (need > ctx->h_zeroed) {
+        const size_t dd = (size_t)ctx->h_d * ctx->h_d * sizeof(double);
+        FOBQ_TRY(hipMemsetAsync(ctx->Hpart.as<char>() + dd * ctx->h_zeroed, 0, dd * (need - ctx->h_zeroed), ctx->stream),
+                 "clear Hessian accumulator");
+        ctx->h_zeroed = need;
+    }
     {
         StageScope sc(ctx, FOBQ_STAGE_XXT);
         FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits), "xxt");
@@ -304,7 +312,7 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
     const int d = (int)ctx->h_d;
     {
         StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
-        FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_splits, d,
+        FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d,
                                          2.0 / (double)ctx->h_n, ctx->H.as<double>()), "hessian finalize");
         if (H_out)
             FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice,
@@ -341,6 +349,8 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     if (rc) return rc;
     rc = check_opts(ctx, opts, d_col);
     if (rc) return rc;
+    if (perm && opts->order == FOBQ_ORDER_SENSI_DYNAMIC)
+        return set_err(ctx, FOBQ_EINVAL, "the dynamic order is only known after the column loop (fobq_quantize_layer returns it)");
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int R = (int)d_row, d = (int)d_col;
@@ -379,7 +389,8 @@ int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_
     const int R = (int)d_row, d = (int)d_col;
     const int G = opts->group > 0 ? d / opts->group : 1;
     const int steps = opts->stop_after < 0 ? d : opts->stop_after;
-    const int block = opts->block == 0 ? 64 : opts->block;
+    const bool dynamic = opts->order == FOBQ_ORDER_SENSI_DYNAMIC;
+    const int block = dynamic ? 1 : (opts->block == 0 ? 64 : opts->block);   // re-sorting needs W after every column
     const int Rp = (R + 63) / 64 * 64;
     const size_t dd = (size_t)d * d * sizeof(double);
 
@@ -410,16 +421,21 @@ int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_
     double* Wp = ctx->Wp.as<double>();
     const double* scale = ctx->scale.as<double>();
     const double* zero = ctx->zero.as<double>();
-    const int* perm = ctx->perm.as<int>();
+    int* perm = ctx->perm.as<int>();
     uint8_t* codesT = ctx->codesT.as<uint8_t>();
     double* lossrow = ctx->lossrow.as<double>();
 
     if (block == 1) {
         // Eq. 9 / 11 and Eq. 12 one column at a time
         StageScope sc(ctx, FOBQ_STAGE_COLUMNS);
-        for (int t = 0; t < steps; ++t)
+        for (int t = 0; t < steps; ++t) {
+            if (dynamic)
+                FOBQ_TRY(launch_dyn_select(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits,
+                                           ctx->Spart.as<double>(), sens_chunks(R)), "column choice");
             FOBQ_TRY(launch_step(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits, codesT, Rp, lossrow),
                      "column step");
+        }
+        if (dynamic) FOBQ_TRY(launch_invert_perm(s, perm, d, ctx->invperm.as<int>()), "order");
     } else {
         double* U = ctx->U.as<double>();
         double* Un = ctx->Un.as<double>();

@@ -75,6 +75,7 @@ struct fobq_ctx {
     int64_t h_d = 0;        // d_col of the running accumulation (0 = none)
     int64_t h_n = 0;        // calibration columns seen so far
     int     h_splits = 0;   // split-K partial slabs in Hpart
+    int     h_zeroed = 0;   // slabs of Hpart cleared (and possibly written) since hessian_begin
     bool    h_final = false;
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
     fobq::DevBuf H;         // d x d fp64, (2/N) X X^T, full symmetric
@@ -117,6 +118,7 @@ struct StageScope {
 // hessian.hip
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits);
 int xxt_pick_splits(int d);
+int xxt_slabs_touched(int d, int64_t n, int splits);
 hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H);
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
 
@@ -146,6 +148,9 @@ hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         const double* Un, const double* U, const double* scale, const double* zero,
                         int G, int group, const int* perm, int bits,
                         uint8_t* codesT, double* DT, int Rp, double* lossrow);
+hipError_t launch_invert_perm(hipStream_t s, const int* perm, int d, int* invperm);
+hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, double* A, const double* scale,
+                             const double* zero, int G, int group, int* perm, int bits, double* Spart, int chunks);
 hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
                        const double* scale, const double* zero, int G, int group, const int* perm, int bits,
                        uint8_t* codesT, int Rp, double* lossrow);

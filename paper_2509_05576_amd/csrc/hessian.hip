@@ -184,7 +184,8 @@ int xxt_pick_splits(int d)
     return (int)((XXT_WGS + tiles - 1) / tiles) + 1;
 }
 
-hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
+// length of one workgroup's range of (tile, chunk) items
+static int64_t xxt_range(int d, int64_t n, int splits, int* chunks_out)
 {
     const int nt = (d + XT - 1) / XT;
     const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
@@ -194,6 +195,27 @@ hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t 
     int64_t per_wg = (total + XXT_WGS - 1) / XXT_WGS;
     const int64_t min_per = splits > 1 ? (chunks + splits - 2) / (splits - 1) : chunks;
     if (per_wg < min_per) per_wg = min_per;
+    *chunks_out = chunks;
+    return per_wg;
+}
+
+// Slabs a launch over n calibration columns can write to (the rest of Hpart is not touched):
+// a tile of `chunks` items meets at most ceil(chunks / range) + 1 ranges.
+int xxt_slabs_touched(int d, int64_t n, int splits)
+{
+    int chunks;
+    const int64_t per_wg = xxt_range(d, n, splits, &chunks);
+    const int64_t p = (chunks + per_wg - 1) / per_wg + 1;
+    return (int)(p < splits ? p : splits);
+}
+
+hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
+{
+    const int nt = (d + XT - 1) / XT;
+    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
+    int chunks;
+    const int64_t per_wg = xxt_range(d, n, splits, &chunks);
+    const int64_t total = tiles * chunks;
     const int wgs = (int)((total + per_wg - 1) / per_wg);
     dim3 grid(wgs), block(256);
     const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);

@@ -459,6 +459,111 @@ __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Dynamic order (the reading of Section 5 in which the sorting is repeated for every
+// column): before step t the scores of Eq. 10 are recomputed for the columns at
+// positions t .. d-1 from the current weights and the diagonal of the current shared
+// inverse, and the column with the largest score is swapped into position t.
+//
+// Pass 1 (dyn_score_kernel): thread = position, block row-chunk c sums the squared
+// quantization errors of rows [c*SENS_RC, (c+1)*SENS_RC).
+// Pass 2 (dyn_select_kernel, one workgroup): chunks are added in index order and divided
+// by 2 [Hinv]_kk; the largest score wins, the smaller original column index among equal
+// scores; then positions t and the winner's are exchanged in W (columns), in the upper
+// triangle of the running inverse (rows and columns) and in perm.
+__global__ __launch_bounds__(256) void dyn_score_kernel(const double* __restrict__ Wp, int R, int d, int t, int gs,
+                                                        int G, double maxq, const double* __restrict__ scale,
+                                                        const double* __restrict__ zero,
+                                                        const int* __restrict__ perm, double* __restrict__ Spart)
+{
+    const int k = t + blockIdx.x * 256 + threadIdx.x;
+    if (k >= d) return;
+    const int g = min(max(perm[k], 0), d - 1) / gs;
+    const int r0 = blockIdx.y * SENS_RC, r1 = min(R, r0 + SENS_RC);
+    double acc = 0.0;
+    for (int i = r0; i < r1; ++i) {
+        const double w = Wp[(int64_t)i * d + k];
+        const double s = scale[(int64_t)i * G + g], z = zero[(int64_t)i * G + g];
+        const double q = s * (grid_code(w, s, z, maxq) - z);
+        acc += (q - w) * (q - w);
+    }
+    Spart[(int64_t)blockIdx.y * d + k] = acc;
+}
+
+__global__ __launch_bounds__(1024) void dyn_select_kernel(double* __restrict__ Wp, int R, int d, int t,
+                                                          double* __restrict__ A, const double* __restrict__ Spart,
+                                                          int chunks, int* __restrict__ perm)
+{
+    __shared__ double bs[1024];
+    __shared__ int bo[1024], bp[1024];
+    const int tid = threadIdx.x;
+    // a score that is not a number is never taken; position t stands in when none qualifies
+    double best = -1.0;
+    int borig = 0x7fffffff, bpos = -1;
+    for (int k = t + tid; k < d; k += 1024) {
+        double acc = 0.0;
+        for (int c = 0; c < chunks; ++c) acc += Spart[(int64_t)c * d + k];
+        const double sc = acc / (2.0 * A[(int64_t)k * d + k]);
+        const int orig = perm[k];
+        if (sc > best || (sc == best && orig < borig)) { best = sc; borig = orig; bpos = k; }
+    }
+    bs[tid] = best; bo[tid] = borig; bp[tid] = bpos;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if (tid < w) {
+            const double s2 = bs[tid + w];
+            const int o2 = bo[tid + w];
+            if (bp[tid + w] >= 0 && (bp[tid] < 0 || s2 > bs[tid] || (s2 == bs[tid] && o2 < bo[tid]))) {
+                bs[tid] = s2; bo[tid] = o2; bp[tid] = bp[tid + w];
+            }
+        }
+        __syncthreads();
+    }
+    const int c = bp[0] < 0 ? t : bp[0];
+    if (c == t) return;
+    // exchange positions t < c
+    if (tid == 0) { const int a = perm[t]; perm[t] = perm[c]; perm[c] = a; }
+    for (int i = tid; i < R; i += 1024) {
+        const double a = Wp[(int64_t)i * d + t];
+        Wp[(int64_t)i * d + t] = Wp[(int64_t)i * d + c];
+        Wp[(int64_t)i * d + c] = a;
+    }
+    // symmetric exchange in the upper triangle; rows and columns left of t are no longer read
+    for (int m = t + tid; m < d; m += 1024) {
+        if (m == c) continue;
+        double *x, *y;
+        if (m == t) { x = A + (int64_t)t * d + t; y = A + (int64_t)c * d + c; }           // diagonal entries
+        else if (m < c) { x = A + (int64_t)t * d + m; y = A + (int64_t)m * d + c; }       // [t][m] <-> [m][c]
+        else { x = A + (int64_t)t * d + m; y = A + (int64_t)c * d + m; }                  // [t][m] <-> [c][m]
+        const double a = *x;
+        *x = *y;
+        *y = a;
+    }
+}
+
+__global__ __launch_bounds__(256) void invert_perm_kernel(const int* __restrict__ perm, int d, int* __restrict__ invperm)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < d) invperm[min(max(perm[t], 0), d - 1)] = t;
+}
+
+hipError_t launch_invert_perm(hipStream_t s, const int* perm, int d, int* invperm)
+{
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((d + 255) / 256), dim3(256), 0, s, perm, d, invperm);
+    return hipGetLastError();
+}
+
+hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, double* A, const double* scale,
+                             const double* zero, int G, int group, int* perm, int bits, double* Spart, int chunks)
+{
+    const int gs = group > 0 ? group : d;
+    const double maxq = (double)((1 << bits) - 1);
+    hipLaunchKernelGGL(dyn_score_kernel, dim3((d - t + 255) / 256, chunks), dim3(256), 0, s, Wp, R, d, t, gs, G, maxq,
+                       scale, zero, perm, Spart);
+    hipLaunchKernelGGL(dyn_select_kernel, dim3(1), dim3(1024), 0, s, Wp, R, d, t, A, Spart, chunks, perm);
+    return hipGetLastError();
+}
+
 hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
                        const double* scale, const double* zero, int G, int group, const int* perm, int bits,
                        uint8_t* codesT, int Rp, double* lossrow)

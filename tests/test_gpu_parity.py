@@ -204,6 +204,29 @@ def test_ablation_orders_match_oracle(fobq, ctx, order):
     assert np.array_equal(perm.cpu().numpy(), out.perm.cpu().numpy())
 
 
+@pytest.mark.parametrize("r,d,n,bits,group,stop", [(48, 170, 500, 4, 0, -1), (33, 96, 300, 3, 32, -1),
+                                                   (20, 130, 400, 4, 0, 57), (70, 1100, 2500, 4, 0, -1)])
+def test_dynamic_order_matches_oracle(fobq, ctx, r, d, n, bits, group, stop):
+    # Section 5 read literally: the scores are recomputed and the order decided before every column
+    _say(f"dynamic order r={r} d={d} bits={bits} group={group} stop_after={stop}")
+    W, X = _problem(r, d, n, 600 + r + d, w_std=0.05)
+    H = oracle.hessian(X)
+    out = ctx.quantize_layer(_dev(W), _dev(H), bits=bits, group=group, order=fobq.ORDER_SENSI_DYNAMIC,
+                             stop_after=stop)
+    steps = d if stop < 0 else stop
+    ref = oracle.quantize_layer(W, H=H, bits=bits, group=group, order_mode=oracle.ORDER_SENSI_DYNAMIC, steps=steps)
+    perm = out.perm.cpu().numpy()
+    assert sorted(perm.tolist()) == list(range(d))
+    assert np.array_equal(perm[:steps], ref.perm[:steps])
+    _compare_layer(out, ref, W, bits)
+    # the static order is a different one on these inputs (otherwise this test shows nothing)
+    assert not np.array_equal(ref.perm, oracle.quantize_layer(W, H=H, bits=bits, group=group).perm)
+    with pytest.raises(fobq.FobqError) as e:
+        fobq.fobq_sensitivity(ctx.handle, _dev(W), _dev(ref.Hinv), bits=bits, group=group,
+                              order=fobq.ORDER_SENSI_DYNAMIC)
+    assert e.value.code == fobq.EINVAL
+
+
 def test_custom_order_and_explicit_h(fobq, ctx):
     W, X = _problem(40, 150, 400, 5, w_std=0.05)
     H = oracle.hessian(X)
@@ -227,7 +250,7 @@ def test_argument_errors(fobq, ctx):
     W, X = _problem(8, 32, 100, 8)
     Wd, H = _dev(W), _dev(oracle.hessian(X))
     for kw in ({"bits": 1}, {"bits": 9}, {"group": 5}, {"block": 65}, {"stop_after": 33}, {"damp": -1.0},
-               {"order": 8}, {"order": -1}, {"order": fobq.ORDER_CUSTOM}):
+               {"order": 9}, {"order": -1}, {"order": fobq.ORDER_CUSTOM}):
         with pytest.raises(fobq.FobqError) as e:
             ctx.quantize_layer(Wd, H, **kw)
         assert e.value.code == fobq.EINVAL, kw
@@ -373,6 +396,20 @@ def test_config_c3a(fobq, ctx, name):
 @pytest.mark.parametrize("name", ["c3b_fc_w8", "c3b_fc_w4"])
 def test_config_c3b(fobq, ctx, name):
     _run_config(fobq, ctx, name)
+
+
+@pytest.mark.parametrize("name", ["c1_tiny", pytest.param("c3a_expand_w4", marks=pytest.mark.slow)])
+def test_config_with_dynamic_order(fobq, ctx, name):
+    spec = workloads.configs()[name]
+    _say(f"config {name}, dynamic order")
+    W, X = spec.make_w(), spec.make_x()
+    ctx.hessian(_dev(X))
+    out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp,
+                             order=fobq.ORDER_SENSI_DYNAMIC)
+    ref = oracle.quantize_layer(W, X=X, bits=spec.bits, group=spec.group, damp_rel=spec.damp,
+                                order_mode=oracle.ORDER_SENSI_DYNAMIC)
+    assert np.array_equal(out.perm.cpu().numpy(), ref.perm)
+    _compare_layer(out, ref, W, spec.bits)
 
 
 @pytest.mark.slow
