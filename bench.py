@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_resnet50_3x3")
     ap.add_argument("--block", type=int, default=0, help="0 = blocked (default), 1 = unblocked rank-1 path")
     ap.add_argument("--chunk", type=int, default=0, help="calibration columns per accumulate call (0 = all)")
+    ap.add_argument("--from-maps", action="store_true",
+                    help="conv workloads: accumulate the Hessian straight from the feature maps "
+                         "(fobq_hessian_accumulate_conv) instead of the unfolded X")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain device copy of X first (known bytes; calibrates HBM byte counters)")
@@ -113,6 +116,12 @@ def main() -> int:
     X = spec.make_x()
     Wd = torch.from_numpy(W).cuda()
     Xd = torch.from_numpy(X).cuda()
+    Md = None
+    if args.from_maps:
+        if spec.conv is None:
+            print(f"bench.py: workload {spec.name} is not a convolution", file=sys.stderr)
+            return 2
+        Md = torch.from_numpy(spec.make_maps()).cuda()
     torch.cuda.synchronize()
 
     if args.copy_probe:
@@ -125,7 +134,10 @@ def main() -> int:
 
     def step():
         nonlocal out
-        ctx.hessian(Xd, chunk=args.chunk or None)
+        if Md is not None:
+            ctx.hessian_conv(Md, spec.conv[3], 1, spec.conv[4])
+        else:
+            ctx.hessian(Xd, chunk=args.chunk or None)
         out = ctx.quantize_layer(Wd, bits=spec.bits, group=spec.group, damp=spec.damp, block=args.block, out=out)
 
     for _ in range(args.warmup):
@@ -180,7 +192,8 @@ def main() -> int:
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{spec.name}: W {spec.d_row}x{spec.d_col} fp32, X {spec.d_col}x{spec.n} fp32, "
                                f"{spec.bits}-bit, group {spec.group}, damp {spec.damp}, sensitivity order",
-                   "block": args.block or 64, "accumulate_calls_per_step": launches_per_step},
+                   "block": args.block or 64, "accumulate_calls_per_step": launches_per_step,
+                   "hessian_input": "feature maps (implicit unfold)" if args.from_maps else "unfolded X"},
         "stages_ms": stage_ms,
         "roofline": roofline,
         "cpu_baseline": cpu,

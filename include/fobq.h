@@ -116,6 +116,21 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
 int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
 
 /*
+ * The same accumulation for a k x k convolution, straight from its input feature maps
+ * (Section 6.1: the quantized layers are convolutions; their X is the unfolded input).
+ * Equivalent to fobq_hessian_accumulate on X = unfold(maps) without materialising X, where
+ *   row    c * k * k + ky * k + kx   (the column order of a weight matrix W[out][c][ky][kx])
+ *   column image * ho * wo + y * wo + x,  ho = (h + 2 pad - k) / stride + 1, wo likewise
+ *   X[row][column] = maps[image][y * stride + ky - pad][x * stride + kx - pad][c], 0 outside the map.
+ * maps: device fp32, n_img x h x w x c, channels innermost (NHWC).  d_col of fobq_hessian_begin
+ * must equal c * k * k; 1 <= k <= 64, 1 <= stride <= 64, 0 <= pad < k.  N grows by n_img * ho * wo (< 2^31 per call).  One accumulation uses
+ * either this call (always with the same c and k) or fobq_hessian_accumulate, not both (ESTATE).
+ * Enqueues work and returns; maps must stay valid until the stream reaches that work.
+ */
+int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img, int64_t h, int64_t w,
+                                 int64_t c, int32_t k, int32_t stride, int32_t pad);
+
+/*
  * Quantize one layer (Section 4.2, steps 1-5):
  *   damp H and invert it through its Cholesky factor (Section 5 item 1,
  *   Section 6.1); freeze the min-max grid of every row / group from W;

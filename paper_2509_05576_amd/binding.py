@@ -58,6 +58,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_last_error.restype = ctypes.c_char_p
     lib.fobq_hessian_begin.argtypes = [vp, i64]
     lib.fobq_hessian_accumulate.argtypes = [vp, vp, i64, i64]
+    lib.fobq_hessian_accumulate_conv.argtypes = [vp, vp, i64, i64, i64, i64, i32, i32, i32]
     lib.fobq_hessian_finalize.argtypes = [vp, vp]
     lib.fobq_quantize_layer.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), ctypes.POINTER(FobqOut)]
     lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
@@ -122,6 +123,15 @@ def fobq_hessian_accumulate(ctx: int, X: torch.Tensor) -> None:
         raise TypeError("X must be a 2-D device fp32 tensor with unit column stride")
     _check(ctx, load_library().fobq_hessian_accumulate(ctypes.c_void_p(ctx), ctypes.c_void_p(X.data_ptr()),
                                                        X.shape[1], X.stride(0)))
+
+
+def fobq_hessian_accumulate_conv(ctx: int, maps: torch.Tensor, k: int, stride: int = 1, pad: int = 0) -> None:
+    """maps: device fp32, images x h x w x channels, contiguous (channels innermost)."""
+    if not maps.is_cuda or maps.dtype != torch.float32 or maps.dim() != 4 or not maps.is_contiguous():
+        raise TypeError("maps must be a contiguous 4-D device fp32 tensor (images, h, w, channels)")
+    n, h, w, c = maps.shape
+    _check(ctx, load_library().fobq_hessian_accumulate_conv(ctypes.c_void_p(ctx), ctypes.c_void_p(maps.data_ptr()),
+                                                            n, h, w, c, k, stride, pad))
 
 
 def fobq_hessian_finalize(ctx: int, H_out: Optional[torch.Tensor] = None) -> None:
@@ -244,6 +254,16 @@ class Ctx:
         step = n if not chunk else chunk
         for lo in range(0, n, step):
             fobq_hessian_accumulate(self.handle, X[:, lo:lo + step])
+        fobq_hessian_finalize(self.handle, H_out)
+
+    def hessian_conv(self, maps: torch.Tensor, k: int, stride: int = 1, pad: int = 0,
+                     images_per_call: Optional[int] = None, H_out: Optional[torch.Tensor] = None) -> None:
+        """begin / accumulate_conv (optionally a few images per call) / finalize for a k x k convolution."""
+        fobq_hessian_begin(self.handle, maps.shape[3] * k * k)
+        n = maps.shape[0]
+        step = n if not images_per_call else images_per_call
+        for lo in range(0, n, step):
+            fobq_hessian_accumulate_conv(self.handle, maps[lo:lo + step], k, stride, pad)
         fobq_hessian_finalize(self.handle, H_out)
 
     def quantize_layer(self, W: torch.Tensor, H: Optional[torch.Tensor] = None, **kw) -> LayerOutput:

@@ -251,7 +251,7 @@ int fobq_destroy(fobq_ctx* ctx)
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
                       &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
-                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow};
+                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->zero_word};
     for (DevBuf* b : bufs) b->release();
     delete ctx;
     return FOBQ_OK;
@@ -270,11 +270,26 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
     FOBQ_TRY(ctx->Hpart.ensure(dd * splits), "workspace Hpart");
     FOBQ_TRY(ctx->H.ensure(dd), "workspace H");
     ctx->h_zeroed = 0;      // slabs are cleared when a launch first needs them
+    ctx->h_conv_c = 0;      // plain or convolution mode is fixed by the first accumulate call
+    ctx->h_conv_k = 0;
     ctx->h_d = d_col;
     ctx->h_n = 0;
     ctx->h_splits = splits;
     ctx->h_final = false;
     ctx->err.clear();
+    return FOBQ_OK;
+}
+
+// clears the slabs of Hpart that a launch over n calibration columns can touch for the first time
+static int clear_slabs(fobq_ctx* ctx, int64_t n)
+{
+    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
+    if (need > ctx->h_zeroed) {
+        const size_t dd = (size_t)ctx->h_d * ctx->h_d * sizeof(double);
+        FOBQ_TRY(hipMemsetAsync(ctx->Hpart.as<char>() + dd * ctx->h_zeroed, 0, dd * (need - ctx->h_zeroed), ctx->stream),
+                 "clear Hessian accumulator");
+        ctx->h_zeroed = need;
+    }
     return FOBQ_OK;
 }
 
@@ -284,21 +299,64 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     if (ctx->h_d == 0 || ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "hessian_accumulate needs hessian_begin first");
     if (!X) return set_err(ctx, FOBQ_EINVAL, "X is NULL");
     if (n < 0 || ld < n) return set_err(ctx, FOBQ_EINVAL, "need 0 <= n <= ld (n=%lld ld=%lld)", (long long)n, (long long)ld);
+    if (ctx->h_conv_c > 0)
+        return set_err(ctx, FOBQ_ESTATE, "this accumulation was started with fobq_hessian_accumulate_conv");
     if (n == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
-    if (need > ctx->h_zeroed) {
-        const size_t dd = (size_t)ctx->h_d * ctx->h_d * sizeof(double);
-        FOBQ_TRY(hipMemsetAsync(ctx->Hpart.as<char>() + dd * ctx->h_zeroed, 0, dd * (need - ctx->h_zeroed), ctx->stream),
-                 "clear Hessian accumulator");
-        ctx->h_zeroed = need;
-    }
+    int rc = clear_slabs(ctx, n);
+    if (rc) return rc;
+    ctx->h_conv_c = -1;
     {
         StageScope sc(ctx, FOBQ_STAGE_XXT);
         FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits), "xxt");
     }
     ctx->h_n += n;
+    return FOBQ_OK;
+}
+
+int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img, int64_t h, int64_t w, int64_t c,
+                                 int32_t k, int32_t stride, int32_t pad)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->h_d == 0 || ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "hessian_accumulate_conv needs hessian_begin first");
+    if (!maps) return set_err(ctx, FOBQ_EINVAL, "maps is NULL");
+    if (n_img < 0 || h < 1 || w < 1 || c < 1 || k < 1 || stride < 1 || pad < 0 || h > (1 << 20) || w > (1 << 20) ||
+        k > 64 || pad > 64 || stride > 64)
+        return set_err(ctx, FOBQ_EINVAL, "bad convolution geometry");
+    if (c * (int64_t)k * k != ctx->h_d)
+        return set_err(ctx, FOBQ_EINVAL, "channels * k * k = %lld does not match d_col = %lld", (long long)(c * (int64_t)k * k),
+                       (long long)ctx->h_d);
+    const int64_t ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
+    if (h + 2 * pad < k || w + 2 * pad < k || ho < 1 || wo < 1)
+        return set_err(ctx, FOBQ_EINVAL, "the kernel does not fit the padded map");
+    if (pad >= k) return set_err(ctx, FOBQ_EINVAL, "pad must be smaller than k (every window must touch the map)");
+    if (((int64_t)k * w + k) * c >= (1ll << 31))
+        return set_err(ctx, FOBQ_EINVAL, "k rows of the map (k * w * c elements) must stay below 2^31 elements");
+    if (ho * wo >= (1ll << 31) || n_img * ho * wo >= (1ll << 31))
+        return set_err(ctx, FOBQ_EINVAL, "more than 2^31 - 1 output pixels in one call: accumulate in several calls");
+    if (ctx->h_conv_c < 0)
+        return set_err(ctx, FOBQ_ESTATE, "this accumulation was started with fobq_hessian_accumulate");
+    if (ctx->h_conv_c > 0 && (ctx->h_conv_c != c || ctx->h_conv_k != k))
+        return set_err(ctx, FOBQ_ESTATE, "channels and kernel size must stay the same within one accumulation");
+    const int64_t npix = n_img * ho * wo;
+    if (npix == 0) return FOBQ_OK;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    int rc = clear_slabs(ctx, npix);
+    if (rc) return rc;
+    if (!ctx->zero_word.p) {
+        FOBQ_TRY(ctx->zero_word.ensure(256), "workspace zero word");
+        FOBQ_TRY(hipMemsetAsync(ctx->zero_word.p, 0, 256, ctx->stream), "clear zero word");
+    }
+    ctx->h_conv_c = (int)c;
+    ctx->h_conv_k = k;
+    {
+        StageScope sc(ctx, FOBQ_STAGE_XXT);
+        FOBQ_TRY(launch_xxt_conv(ctx->stream, maps, ctx->zero_word.as<float>(), (int)h, (int)w, (int)c, k, stride, pad, (int)ho, (int)wo, npix,
+                                 ctx->Hpart.as<double>(), ctx->h_splits), "xxt (convolution)");
+    }
+    ctx->h_n += npix;
     return FOBQ_OK;
 }
 
@@ -313,7 +371,8 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
     {
         StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
         FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d,
-                                         2.0 / (double)ctx->h_n, ctx->H.as<double>()), "hessian finalize");
+                                         2.0 / (double)ctx->h_n, ctx->H.as<double>(), ctx->h_conv_c > 0 ? ctx->h_conv_c : 0,
+                                         ctx->h_conv_k * ctx->h_conv_k), "hessian finalize");
         if (H_out)
             FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice,
                                     ctx->stream), "copy H");

@@ -77,7 +77,11 @@ struct fobq_ctx {
     int     h_splits = 0;   // split-K partial slabs in Hpart
     int     h_zeroed = 0;   // slabs of Hpart cleared (and possibly written) since hessian_begin
     bool    h_final = false;
+    int     h_conv_c = 0;   // > 0: accumulation in convolution mode with this many channels ...
+    int     h_conv_k = 0;   // ... and this kernel size; -1 in h_conv_c: plain mode
+
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
+    fobq::DevBuf zero_word; // 256 bytes of zeros: what the convolution loader reads for padding
     fobq::DevBuf H;         // d x d fp64, (2/N) X X^T, full symmetric
 
     // factorization / elimination workspace (all d x d fp64 unless noted)
@@ -119,7 +123,10 @@ struct StageScope {
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits);
 int xxt_pick_splits(int d);
 int xxt_slabs_touched(int d, int64_t n, int splits);
-hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H);
+hipError_t launch_xxt_conv(hipStream_t s, const float* maps, const float* zero_word, int h, int w, int c, int k,
+                           int stride, int pad, int ho, int wo, int64_t npix, double* Hpart, int splits);
+hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
+                                   int conv_c, int conv_kk);
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
 
 // factor.hip

@@ -13,11 +13,48 @@
 // "piece".  Piece p of a tile is added into slab p of Hpart (XXT_SLABS slabs of
 // d x d), and exactly one workgroup owns a given (tile, piece) in a launch, so
 // the sums do not depend on the order in which workgroups finish.
+//
+// Convolution mode: the same kernel with a loader that reads the unfolded input of a k x k
+// convolution straight from NHWC feature maps (X is never materialised).  Row (c, ky, kx) of
+// X, column (image, y, x) is maps[image][y*stride + ky - pad][x*stride + kx - pad][c] or 0
+// outside the map.  Inside the kernel the rows are taken tap-major (row' = (ky*k + kx)*C + c)
+// so that consecutive rows are consecutive channels, which NHWC stores contiguously; the
+// finalize kernel of this mode puts H back into the (c, ky, kx) order.
 #include "fobq_internal.h"
 
 namespace fobq {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
+
+// n / dv for 0 <= n < 2^32 and a divisor fixed at launch: q = (t + ((n - t) >> s1)) >> s2 with
+// t = umulhi(m, n)  (division by an invariant integer through multiplication).
+struct FastDiv { uint32_t m; int s1, s2; };
+
+static FastDiv fastdiv_make(uint32_t dv)
+{
+    FastDiv f;
+    int L = 0;
+    while ((1ull << L) < dv) ++L;
+    f.m = (uint32_t)(((1ull << 32) * ((1ull << L) - dv)) / dv + 1);
+    f.s1 = L < 1 ? L : 1;
+    f.s2 = L > 1 ? L - 1 : 0;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f)
+{
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
+struct ConvP {
+    const float* zero;  // device word holding +0.0
+    int h, w, c, k, stride, pad, ho, wo;
+    FastDiv div_img;    // by ho * wo
+    FastDiv div_row;    // by wo
+    FastDiv div_c;      // by c
+    FastDiv div_k;      // by k
+};
 
 constexpr int XT = 128;          // tile edge
 constexpr int XK = 32;           // calibration columns per LDS stage
@@ -39,12 +76,15 @@ __device__ __forceinline__ void tile_decode(int t, int nt, int& I, int& J)
     else { I = 2 * r + 1; J = 2 * r + 1; }                           // diagonal tile of the second row
 }
 
-// FAST: X rows are 16-byte aligned (ld % 4 == 0, base aligned) -> float4 loads.
-template <bool FAST>
+// MODE 0: X rows are 16-byte aligned (ld % 4 == 0, base aligned) -> float4 loads.
+// MODE 1: any ld / alignment.  MODE 2: X = feature maps, n = images * ho * wo (convolution mode).
+template <int MODE>
 __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
                                                      double* __restrict__ Hpart, int chunks, int64_t per_wg,
-                                                     int64_t total_items)
+                                                     int64_t total_items, ConvP cp)
 {
+    constexpr bool FAST = MODE == 0;
+    constexpr bool CONV = MODE == 2;
     __shared__ float As[2][XT][XLD];
     __shared__ float Bs[2][XT][XLD];
 
@@ -54,6 +94,7 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
     const int lk = (tid & 7) * 4;     // 0..28: first of 4 consecutive calibration columns
     const int fr = lane & 15;         // fragment row
     const int fk = (lane >> 4) * 4;   // fragment: 4 consecutive columns, one per k-step (the sum over k is order-free)
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value, known to be wavefront-uniform
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD one contiguous run of ranges, so
     // that the workgroups sharing an L2 work on neighbouring tiles (which share panels of X) at almost
@@ -77,16 +118,98 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
         tile_decode(tile, nt, I, J);
         const int i0 = I * XT, j0 = J * XT;
 
-        // clamped row pointers: rows past d produce outputs that are never stored
+        // plain modes: clamped row pointers (rows past d produce outputs that are never stored);
+        // thread = (row lr + 32 u, 4 consecutive columns)
         const float* __restrict__ arow[4];
         const float* __restrict__ brow[4];
+        // convolution mode: thread = (rows lane + 64 q, pixels 8 wave + j): a load covers 64
+        // consecutive channels (256 contiguous bytes) of ONE pixel, so the pixel's decoding and its
+        // window origin are wavefront-uniform (scalar unit) and only the tap test is per lane.
+        // Per tile: this thread's two rows of each operand as (ky, kx) and the offset of
+        // (ky, kx, channel) from the window's top-left element.  Rows past d stand in as row d - 1.
+        int offA[2], offB[2], kyA[2], kxA[2], kyB[2], kxB[2];
+        if (CONV) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            arow[u] = X + (int64_t)min(i0 + lr + 32 * u, d - 1) * ld;
-            brow[u] = X + (int64_t)min(j0 + lr + 32 * u, d - 1) * ld;
+            for (int q = 0; q < 2; ++q) {
+                const int ra = min(i0 + lane + 64 * q, d - 1), rb = min(j0 + lane + 64 * q, d - 1);
+                const uint32_t ta = fastdiv((uint32_t)ra, cp.div_c), tb = fastdiv((uint32_t)rb, cp.div_c);
+                kyA[q] = (int)fastdiv(ta, cp.div_k);
+                kyB[q] = (int)fastdiv(tb, cp.div_k);
+                kxA[q] = (int)ta - kyA[q] * cp.k;
+                kxB[q] = (int)tb - kyB[q] * cp.k;
+                offA[q] = (kyA[q] * cp.w + kxA[q]) * cp.c + (ra - (int)ta * cp.c);
+                offB[q] = (kyB[q] * cp.w + kxB[q]) * cp.c + (rb - (int)tb * cp.c);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                arow[u] = X + (int64_t)min(i0 + lr + 32 * u, d - 1) * ld;
+                brow[u] = X + (int64_t)min(j0 + lr + 32 * u, d - 1) * ld;
+            }
         }
         float4 pa[4], pb[4];
+        // Convolution mode: the loads of pixel j (0..7) of chunk c for this thread's rows; called
+        // with j = 0, 1, ..., 7 in this order.  Pixel 0 is decoded in full (two divisions by
+        // invariant integers), the others by stepping (image, y, x) one pixel on.  All of it is
+        // wavefront-uniform, i.e. scalar-unit work.
+        int px_img = 0, px_yo = 0, px_xo = 0;
+        auto gload_px = [&](int c, int j) {
+            float* fa = reinterpret_cast<float*>(pa);
+            float* fb = reinterpret_cast<float*>(pb);
+            const int64_t p = (int64_t)c * XK + 8 * wave_s + j;
+            const bool pv = p < n;
+            if (j == 0) {
+                const uint32_t pc = (uint32_t)min(p, n - 1);
+                const uint32_t img = fastdiv(pc, cp.div_img);
+                const uint32_t rem = pc - img * (uint32_t)(cp.ho * cp.wo);
+                const uint32_t yo = fastdiv(rem, cp.div_row);
+                px_img = (int)img;
+                px_yo = (int)yo;
+                px_xo = (int)(rem - yo * (uint32_t)cp.wo);
+            } else if (pv) {
+                ++px_xo;
+                if (px_xo == cp.wo) { px_xo = 0; ++px_yo; }
+                if (px_yo == cp.ho) { px_yo = 0; ++px_img; }
+            }
+            const int ytop = px_yo * cp.stride - cp.pad;
+            const int xtop = px_xo * cp.stride - cp.pad;
+            // Window origin (may lie in the padding: only offsets of elements inside the map are
+            // added to it).  All arithmetic on the vector unit takes cycles from the fp64 matrix
+            // instructions (the kernel slows down by what the vector instructions add), so the
+            // common case is kept to one address add per element: when the whole window lies
+            // inside the map (scalar test) no per-lane test is needed.
+            const float* __restrict__ win = X + (((int64_t)px_img * cp.h + ytop) * cp.w + xtop) * cp.c;
+            if (!pv) {
+                // past the last pixel: the padding of the calibration dimension must be zero
+#pragma unroll
+                for (int q = 0; q < 2; ++q) { fa[q * 8 + j] = 0.f; fb[q * 8 + j] = 0.f; }
+            } else if (ytop >= 0 && xtop >= 0 && ytop + cp.k <= cp.h && xtop + cp.k <= cp.w) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    fa[q * 8 + j] = win[offA[q]];
+                    fb[q * 8 + j] = win[offB[q]];
+                }
+            } else {
+                // window crosses the border: an element outside the map (zero padding) is read from
+                // a word that holds +0.0 instead, so that no arithmetic depends on the loaded value
+                // before it is stored to LDS and the loads stay in flight across the MFMA section
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const bool va = ((unsigned)(ytop + kyA[q]) < (unsigned)cp.h) &
+                                    ((unsigned)(xtop + kxA[q]) < (unsigned)cp.w);
+                    const bool vb2 = ((unsigned)(ytop + kyB[q]) < (unsigned)cp.h) &
+                                     ((unsigned)(xtop + kxB[q]) < (unsigned)cp.w);
+                    fa[q * 8 + j] = *(va ? win + offA[q] : cp.zero);
+                    fb[q * 8 + j] = *(vb2 ? win + offB[q] : cp.zero);
+                }
+            }
+        };
         auto gload = [&](int c) {
+            if (CONV) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) gload_px(c, j);
+                return;
+            }
             const int64_t k = (int64_t)c * XK + lk;
             if (FAST && k + 3 < n) {
 #pragma unroll
@@ -108,6 +231,17 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             }
         };
         auto sstore = [&](int buf) {
+            if (CONV) {
+                // 8 consecutive pixels of a row: two 16-byte stores per row
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave]) = pa[2 * q];
+                    *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave + 4]) = pa[2 * q + 1];
+                    *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave]) = pb[2 * q];
+                    *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave + 4]) = pb[2 * q + 1];
+                }
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 *reinterpret_cast<float4*>(&As[buf][lr + 32 * u][lk]) = pa[u];
@@ -128,7 +262,11 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
         int cur = 0;
         for (int c = c_begin; c < c_end; ++c) {
             const bool more = c + 1 < c_end;
-            if (more) gload(c + 1);
+            // plain modes: 8 wide loads, issued up front.  Convolution mode: one pixel's loads per
+            // group of 16 MFMAs (after the last chunk of a range the same chunk is simply loaded
+            // again and not stored).
+            if (!CONV && more) gload(c + 1);
+            const int cn = more ? c + 1 : c;
 #pragma unroll
             for (int g = 0; g < XK / 16; ++g) {
                 float4 fa[4], fb[4];
@@ -152,6 +290,7 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+                    if (CONV) gload_px(cn, g * 4 + ks);
                 }
             }
             if (more) sstore(cur ^ 1);
@@ -219,8 +358,33 @@ hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t 
     const int wgs = (int)((total + per_wg - 1) / per_wg);
     dim3 grid(wgs), block(256);
     const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    if (fast) hipLaunchKernelGGL((xxt_kernel<true>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total);
-    else      hipLaunchKernelGGL((xxt_kernel<false>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total);
+    ConvP none{};
+    if (fast) hipLaunchKernelGGL((xxt_kernel<0>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, none);
+    else      hipLaunchKernelGGL((xxt_kernel<1>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, none);
+    return hipGetLastError();
+}
+
+// Convolution mode: maps is n_img x h x w x c (NHWC), d = c k^2, one calibration column per
+// output pixel; npix = n_img * ho * wo < 2^31; zero_word points to at least 4 bytes of zeros.
+hipError_t launch_xxt_conv(hipStream_t s, const float* maps, const float* zero_word, int h, int w, int c, int k,
+                           int stride, int pad, int ho, int wo, int64_t npix, double* Hpart, int splits)
+{
+    const int d = c * k * k;
+    const int nt = (d + XT - 1) / XT;
+    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
+    int chunks;
+    const int64_t per_wg = xxt_range(d, npix, splits, &chunks);
+    const int64_t total = tiles * chunks;
+    const int wgs = (int)((total + per_wg - 1) / per_wg);
+    ConvP cp;
+    cp.zero = zero_word;
+    cp.h = h; cp.w = w; cp.c = c; cp.k = k; cp.stride = stride; cp.pad = pad; cp.ho = ho; cp.wo = wo;
+    cp.div_img = fastdiv_make((uint32_t)(ho * wo));
+    cp.div_row = fastdiv_make((uint32_t)wo);
+    cp.div_c = fastdiv_make((uint32_t)c);
+    cp.div_k = fastdiv_make((uint32_t)k);
+    hipLaunchKernelGGL((xxt_kernel<2>), dim3(wgs), dim3(256), 0, s, maps, (int64_t)0, d, npix, Hpart, chunks, per_wg,
+                       total, cp);
     return hipGetLastError();
 }
 
@@ -238,10 +402,32 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __r
     H[(int64_t)b * d + a] = s;
 }
 
-hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H)
+// Convolution mode: the slabs are in tap-major row order; H is written in (c, ky, kx) order.
+__global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double* __restrict__ Hpart, int splits, int d,
+                                                                    double factor, double* __restrict__ H, int c,
+                                                                    int kk)
+{
+    const int b = blockIdx.x * 16 + (threadIdx.x & 15);
+    const int a = blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (a >= d || b >= d || b > a) return;
+    const int ai = (a % kk) * c + a / kk, bi = (b % kk) * c + b / kk;
+    const int hi = max(ai, bi), lo = min(ai, bi);
+    double s = 0.0;
+    for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * d * d + (int64_t)hi * d + lo];
+    s *= factor;
+    H[(int64_t)a * d + b] = s;
+    H[(int64_t)b * d + a] = s;
+}
+
+// conv_c > 0: the slabs were accumulated in convolution mode with conv_c channels and conv_kk taps
+hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
+                                   int conv_c, int conv_kk)
 {
     dim3 grid((d + 15) / 16, (d + 15) / 16), block(256);
-    hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, d, factor, H);
+    if (conv_c > 0)
+        hipLaunchKernelGGL(hessian_finalize_conv_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, conv_c, conv_kk);
+    else
+        hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, d, factor, H);
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "fobq.h")).read()
     names = sorted(set(re.findall(r"^(?:int|const char\*)\s+(fobq_[a-z_0-9]+)\s*\(", header, flags=re.M)))
     assert {"fobq_create", "fobq_destroy", "fobq_last_error", "fobq_hessian_begin", "fobq_hessian_accumulate",
-            "fobq_hessian_finalize", "fobq_quantize_layer", "fobq_spd_inverse", "fobq_sensitivity",
+            "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer", "fobq_spd_inverse", "fobq_sensitivity",
             "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"libfobq.so does not export {n}"
@@ -36,6 +36,7 @@ def test_null_context_is_rejected_without_touching_a_gpu():
     null = ctypes.c_void_p(None)
     assert lib.fobq_hessian_begin(null, 8) == fobq.EINVAL
     assert lib.fobq_hessian_accumulate(null, null, 1, 1) == fobq.EINVAL
+    assert lib.fobq_hessian_accumulate_conv(null, null, 1, 1, 1, 1, 1, 1, 0) == fobq.EINVAL
     assert lib.fobq_hessian_finalize(null, null) == fobq.EINVAL
     assert lib.fobq_quantize_layer(null, null, 1, 1, null, None, None) == fobq.EINVAL
     assert lib.fobq_spd_inverse(null, null, 1, null) == fobq.EINVAL

@@ -112,6 +112,58 @@ def test_hessian_matches_oracle(fobq, ctx, d, n, ld_pad, chunk):
     assert np.array_equal(Hh, Hh.T)
 
 
+@pytest.mark.parametrize("n,h,w,c,k,stride,pad,per_call", [
+    (3, 9, 7, 5, 3, 1, 1, None),        # ragged everything, one tile
+    (2, 8, 8, 16, 1, 1, 0, None),       # 1 x 1 convolution: X is the maps themselves
+    (4, 11, 10, 7, 3, 2, 1, 3),         # stride 2, images split over two calls
+    (2, 13, 13, 3, 6, 2, 2, None),      # the 6 x 6 stride-2 stem shape
+    (3, 10, 10, 130, 3, 1, 1, 2),       # d = 1170: 10 tile rows, ragged last tile, taps change inside a tile
+    (1, 5, 5, 4, 5, 1, 0, None),        # kernel covers the whole map: one output pixel per image
+    (5, 12, 9, 8, 3, 2, 1, 2),          # channels % 4 == 0 (16-byte loads), stride 2, three calls
+    (2, 9, 9, 132, 3, 1, 1, None),      # channels % 4 == 0, d = 1188: several tiles, ragged last tile
+])
+def test_hessian_from_feature_maps_matches_oracle(fobq, ctx, n, h, w, c, k, stride, pad, per_call):
+    # the Hessian of a k x k convolution accumulated straight from NHWC maps equals the
+    # Hessian of the unfolded input (the definition, written out on the CPU)
+    _say(f"hessian_conv n={n} h={h} w={w} c={c} k={k} stride={stride} pad={pad}")
+    rng = np.random.default_rng(n * 1000 + h * 100 + c)
+    maps = np.maximum(rng.standard_normal((n, h, w, c)), 0).astype(np.float32)
+    X = workloads.im2col(maps, k, stride, pad)
+    ref = oracle.hessian(X)
+    d = c * k * k
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.hessian_conv(_dev(maps), k, stride, pad, images_per_call=per_call, H_out=H)
+    torch.cuda.synchronize()
+    Hh = H.cpu().numpy()
+    assert np.allclose(Hh, ref, rtol=1e-12, atol=1e-14)
+    assert np.array_equal(Hh, Hh.T)
+
+
+def test_hessian_conv_argument_and_state_errors(fobq, ctx):
+    maps = _dev(np.ones((2, 6, 6, 4), dtype=np.float32))
+    X = _dev(np.ones((36, 10), dtype=np.float32))
+    fobq.fobq_hessian_begin(ctx.handle, 36)
+    for kw in ({"k": 2}, {"k": 3, "stride": 0}, {"k": 3, "pad": -1}):
+        with pytest.raises(fobq.FobqError) as e:
+            fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, **kw)
+        assert e.value.code == fobq.EINVAL
+    with pytest.raises(fobq.FobqError) as e:      # 7 x 7 kernel does not fit a 6 x 6 map
+        fobq.fobq_hessian_begin(ctx.handle, 4 * 49)
+        fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, 7)
+    assert e.value.code == fobq.EINVAL
+    fobq.fobq_hessian_begin(ctx.handle, 36)
+    fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, 3, 1, 1)
+    with pytest.raises(fobq.FobqError) as e:      # plain and convolution calls do not mix
+        fobq.fobq_hessian_accumulate(ctx.handle, X)
+    assert e.value.code == fobq.ESTATE
+    fobq.fobq_hessian_begin(ctx.handle, 36)
+    fobq.fobq_hessian_accumulate(ctx.handle, X)
+    with pytest.raises(fobq.FobqError) as e:
+        fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, 3, 1, 1)
+    assert e.value.code == fobq.ESTATE
+    fobq.fobq_hessian_finalize(ctx.handle)
+
+
 @pytest.mark.parametrize("d", [1, 7, 64, 65, 100, 128, 300, 1000])
 def test_spd_inverse_matches_oracle(fobq, ctx, d):
     _say(f"spd_inverse d={d}")
@@ -332,7 +384,14 @@ def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None, spec=None):
     X = spec.make_x()
     Xd = _dev(X)
     _say(f"config {name}: GPU path")
-    ctx.hessian(Xd, chunk=chunk)
+    if chunk is not None:
+        # accumulation over several calls gives the same Hessian as one call (up to summation order)
+        ctx.hessian(Xd, chunk=chunk)
+        Hc = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
+        fobq.fobq_hessian_finalize(ctx.handle, Hc)
+        torch.cuda.synchronize()
+        Hc = Hc.cpu().numpy()
+    ctx.hessian(Xd)          # one launch over all calibration columns: the configuration bench.py times
     out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp, block=block)
     del Xd
     _say(f"config {name}: oracle")
@@ -341,6 +400,8 @@ def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None, spec=None):
     fobq.fobq_hessian_finalize(ctx.handle, Hg)
     torch.cuda.synchronize()
     assert np.allclose(Hg.cpu().numpy(), H, rtol=1e-11, atol=1e-13)
+    if chunk is not None:
+        assert np.allclose(Hc, H, rtol=1e-11, atol=1e-13)
     if rows is None:
         ref = oracle.quantize_layer(W, H=H, bits=spec.bits, group=spec.group, damp_rel=spec.damp)
         ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=spec.bits, group=spec.group,
@@ -386,6 +447,26 @@ def test_config_c1_tiny(fobq, ctx):
 
 def test_config_c2_resnet50_3x3(fobq, ctx):
     _run_config(fobq, ctx, "c2_resnet50_3x3", chunk=6272)
+
+
+def test_config_c2_hessian_from_feature_maps(fobq, ctx):
+    # config 2 with the Hessian accumulated from the 128 x 14 x 14 x 256 maps instead of the
+    # unfolded 2304 x 25088 matrix: same H, same codes
+    spec = workloads.configs()["c2_resnet50_3x3"]
+    _images, _side, _ch, k, pad = spec.conv
+    _say("config c2 from feature maps")
+    maps = spec.make_maps()
+    W = spec.make_w()
+    X = workloads.im2col(maps, k, 1, pad)
+    H = oracle.hessian(X)
+    Hg = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
+    ctx.hessian_conv(_dev(maps), k, 1, pad, H_out=Hg)
+    out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp)
+    assert np.allclose(Hg.cpu().numpy(), H, rtol=1e-11, atol=1e-13)
+    ref = oracle.quantize_layer(W, H=H, bits=spec.bits, group=spec.group, damp_rel=spec.damp)
+    ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=spec.bits, group=spec.group,
+                                damp_rel=spec.damp)
+    _compare_layer(out, ref, W, spec.bits)
 
 
 @pytest.mark.parametrize("name", ["c3a_expand_w8", "c3a_expand_w4"])

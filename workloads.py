@@ -126,12 +126,18 @@ class LayerSpec:
         return normal_f32((self.d_row, self.d_col), std, self.seed,
                           STREAM_W + 16 * self.layer_index)
 
+    def make_maps(self) -> np.ndarray:
+        """Input feature maps (images, side, side, channels) of a conv recipe."""
+        assert self.conv is not None
+        images, side, ch, _k, _pad = self.conv
+        return relu_normal_f32((images, side, side, ch), self.seed, STREAM_ACT + 16 * self.layer_index)
+
     def make_x(self, n: Optional[int] = None) -> np.ndarray:
         """X (d_col x n).  For conv recipes n must be the full N."""
         stream = STREAM_ACT + 16 * self.layer_index
         if self.conv is not None:
-            images, side, ch, k, pad = self.conv
-            maps = relu_normal_f32((images, side, side, ch), self.seed, stream)
+            _images, _side, _ch, k, pad = self.conv
+            maps = self.make_maps()
             x = im2col(maps, k, 1, pad)
             assert x.shape == (self.d_col, self.n), (x.shape, self.d_col, self.n)
             return x
