@@ -123,7 +123,9 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
  *   column image * ho * wo + y * wo + x,  ho = (h + 2 pad - k) / stride + 1, wo likewise
  *   X[row][column] = maps[image][y * stride + ky - pad][x * stride + kx - pad][c], 0 outside the map.
  * maps: device fp32, n_img x h x w x c, channels innermost (NHWC).  d_col of fobq_hessian_begin
- * must equal c * k * k; 1 <= k <= 64, 1 <= stride <= 64, 0 <= pad < k.  N grows by n_img * ho * wo (< 2^31 per call).  One accumulation uses
+ * must equal c * k * k; 1 <= k <= 64, 1 <= stride <= 64, 0 <= pad <= 64.  The context keeps a
+ * zero-padded copy of the maps of one call ((n_img + 1) (h + 2 pad) (w + 2 pad) c floats of scratch):
+ * pass fewer images per call to bound it.  N grows by n_img * ho * wo (< 2^31 per call).  One accumulation uses
  * either this call (always with the same c and k) or fobq_hessian_accumulate, not both (ESTATE).
  * Enqueues work and returns; maps must stay valid until the stream reaches that work.
  */

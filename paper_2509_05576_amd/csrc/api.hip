@@ -251,7 +251,7 @@ int fobq_destroy(fobq_ctx* ctx)
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
                       &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
-                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->zero_word};
+                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
     for (DevBuf* b : bufs) b->release();
     delete ctx;
     return FOBQ_OK;
@@ -330,10 +330,10 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     const int64_t ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
     if (h + 2 * pad < k || w + 2 * pad < k || ho < 1 || wo < 1)
         return set_err(ctx, FOBQ_EINVAL, "the kernel does not fit the padded map");
-    if (pad >= k) return set_err(ctx, FOBQ_EINVAL, "pad must be smaller than k (every window must touch the map)");
-    if (((int64_t)k * w + k) * c >= (1ll << 31))
-        return set_err(ctx, FOBQ_EINVAL, "k rows of the map (k * w * c elements) must stay below 2^31 elements");
-    if (ho * wo >= (1ll << 31) || n_img * ho * wo >= (1ll << 31))
+    const int64_t hp = h + 2 * pad, wp = w + 2 * pad;
+    if ((k * wp + k) * c >= (1ll << 31))
+        return set_err(ctx, FOBQ_EINVAL, "k rows of the padded map (k * (w + 2 pad) * c elements) must stay below 2^31 elements");
+    if (ho * wo >= (1ll << 31) - 64 || n_img * ho * wo >= (1ll << 31) - 64)
         return set_err(ctx, FOBQ_EINVAL, "more than 2^31 - 1 output pixels in one call: accumulate in several calls");
     if (ctx->h_conv_c < 0)
         return set_err(ctx, FOBQ_ESTATE, "this accumulation was started with fobq_hessian_accumulate");
@@ -345,16 +345,16 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     int rc = clear_slabs(ctx, npix);
     if (rc) return rc;
-    if (!ctx->zero_word.p) {
-        FOBQ_TRY(ctx->zero_word.ensure(256), "workspace zero word");
-        FOBQ_TRY(hipMemsetAsync(ctx->zero_word.p, 0, 256, ctx->stream), "clear zero word");
-    }
+    FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
     ctx->h_conv_c = (int)c;
     ctx->h_conv_k = k;
     {
+        // the padded copy is stream-ordered: a later call reuses the buffer only after this launch
+        FOBQ_TRY(launch_pad_maps(ctx->stream, maps, (int)n_img, (int)h, (int)w, (int)c, pad, ctx->maps_pad.as<float>()),
+                 "pad maps");
         StageScope sc(ctx, FOBQ_STAGE_XXT);
-        FOBQ_TRY(launch_xxt_conv(ctx->stream, maps, ctx->zero_word.as<float>(), (int)h, (int)w, (int)c, k, stride, pad, (int)ho, (int)wo, npix,
-                                 ctx->Hpart.as<double>(), ctx->h_splits), "xxt (convolution)");
+        FOBQ_TRY(launch_xxt_conv(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, k, stride,
+                                 (int)ho, (int)wo, npix, ctx->Hpart.as<double>(), ctx->h_splits), "xxt (convolution)");
     }
     ctx->h_n += npix;
     return FOBQ_OK;

@@ -81,7 +81,7 @@ struct fobq_ctx {
     int     h_conv_k = 0;   // ... and this kernel size; -1 in h_conv_c: plain mode
 
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
-    fobq::DevBuf zero_word; // 256 bytes of zeros: what the convolution loader reads for padding
+    fobq::DevBuf maps_pad;  // zero-padded copy of the feature maps of one accumulate_conv call (+ 1 zero image)
     fobq::DevBuf H;         // d x d fp64, (2/N) X X^T, full symmetric
 
     // factorization / elimination workspace (all d x d fp64 unless noted)
@@ -123,8 +123,9 @@ struct StageScope {
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits);
 int xxt_pick_splits(int d);
 int xxt_slabs_touched(int d, int64_t n, int splits);
-hipError_t launch_xxt_conv(hipStream_t s, const float* maps, const float* zero_word, int h, int w, int c, int k,
-                           int stride, int pad, int ho, int wo, int64_t npix, double* Hpart, int splits);
+hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, int w, int c, int pad, float* out);
+hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
+                           int ho, int wo, int64_t npix, double* Hpart, int splits);
 hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
                                    int conv_c, int conv_kk);
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);

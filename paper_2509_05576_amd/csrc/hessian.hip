@@ -17,9 +17,12 @@
 // Convolution mode: the same kernel with a loader that reads the unfolded input of a k x k
 // convolution straight from NHWC feature maps (X is never materialised).  Row (c, ky, kx) of
 // X, column (image, y, x) is maps[image][y*stride + ky - pad][x*stride + kx - pad][c] or 0
-// outside the map.  Inside the kernel the rows are taken tap-major (row' = (ky*k + kx)*C + c)
-// so that consecutive rows are consecutive channels, which NHWC stores contiguously; the
-// finalize kernel of this mode puts H back into the (c, ky, kx) order.
+// outside the map.  pad_maps_kernel first writes a zero-padded copy of the maps with one extra
+// all-zero image at the end, so that every window lies inside the copy (no per-element test)
+// and the columns past the last pixel read zeros from the extra image (no branch).  Inside the
+// kernel the rows are taken tap-major (row' = (ky*k + kx)*C + c) so that consecutive rows are
+// consecutive channels, which NHWC stores contiguously; the finalize kernel of this mode puts
+// H back into the (c, ky, kx) order.
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -48,13 +51,41 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f)
 }
 
 struct ConvP {
-    const float* zero;  // device word holding +0.0
-    int h, w, c, k, stride, pad, ho, wo;
+    int hp, wp, c, k, stride, ho, wo;   // hp, wp: height and width of the padded copy
+    int64_t zero_origin;                // element offset of the all-zero image
     FastDiv div_img;    // by ho * wo
     FastDiv div_row;    // by wo
     FastDiv div_c;      // by c
     FastDiv div_k;      // by k
 };
+
+// out: (n_img + 1) x hp x wp x c, hp = h + 2 pad, wp = w + 2 pad; image n_img is all zeros
+__global__ __launch_bounds__(256) void pad_maps_kernel(const float* __restrict__ maps, int n_img, int h, int w, int c,
+                                                       int pad, float* __restrict__ out, int64_t total)
+{
+    const int hp = h + 2 * pad, wp = w + 2 * pad;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int ch = (int)(idx % c);
+        int64_t r = idx / c;
+        const int x = (int)(r % wp) - pad;
+        r /= wp;
+        const int y = (int)(r % hp) - pad;
+        const int64_t img = r / hp;
+        float v = 0.f;
+        if (img < n_img && (unsigned)y < (unsigned)h && (unsigned)x < (unsigned)w)
+            v = maps[((img * h + y) * w + x) * c + ch];
+        out[idx] = v;
+    }
+}
+
+hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, int w, int c, int pad, float* out)
+{
+    const int64_t total = (int64_t)(n_img + 1) * (h + 2 * pad) * (w + 2 * pad) * c;
+    const int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(pad_maps_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, maps, n_img, h,
+                       w, c, pad, out, total);
+    return hipGetLastError();
+}
 
 constexpr int XT = 128;          // tile edge
 constexpr int XK = 32;           // calibration columns per LDS stage
@@ -124,21 +155,18 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
         const float* __restrict__ brow[4];
         // convolution mode: thread = (rows lane + 64 q, pixels 8 wave + j): a load covers 64
         // consecutive channels (256 contiguous bytes) of ONE pixel, so the pixel's decoding and its
-        // window origin are wavefront-uniform (scalar unit) and only the tap test is per lane.
-        // Per tile: this thread's two rows of each operand as (ky, kx) and the offset of
-        // (ky, kx, channel) from the window's top-left element.  Rows past d stand in as row d - 1.
-        int offA[2], offB[2], kyA[2], kxA[2], kyB[2], kxB[2];
+        // window origin are wavefront-uniform (scalar unit).  Per tile: the offset of this thread's
+        // two rows (ky, kx, channel) of each operand from the window's top-left element in the
+        // padded copy.  Rows past d stand in as row d - 1.
+        uint32_t offA[2], offB[2];
         if (CONV) {
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const int ra = min(i0 + lane + 64 * q, d - 1), rb = min(j0 + lane + 64 * q, d - 1);
                 const uint32_t ta = fastdiv((uint32_t)ra, cp.div_c), tb = fastdiv((uint32_t)rb, cp.div_c);
-                kyA[q] = (int)fastdiv(ta, cp.div_k);
-                kyB[q] = (int)fastdiv(tb, cp.div_k);
-                kxA[q] = (int)ta - kyA[q] * cp.k;
-                kxB[q] = (int)tb - kyB[q] * cp.k;
-                offA[q] = (kyA[q] * cp.w + kxA[q]) * cp.c + (ra - (int)ta * cp.c);
-                offB[q] = (kyB[q] * cp.w + kxB[q]) * cp.c + (rb - (int)tb * cp.c);
+                const uint32_t kya = fastdiv(ta, cp.div_k), kyb = fastdiv(tb, cp.div_k);
+                offA[q] = (kya * cp.wp + (ta - kya * cp.k)) * cp.c + ((uint32_t)ra - ta * cp.c);
+                offB[q] = (kyb * cp.wp + (tb - kyb * cp.k)) * cp.c + ((uint32_t)rb - tb * cp.c);
             }
         } else {
 #pragma unroll
@@ -150,58 +178,39 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
         float4 pa[4], pb[4];
         // Convolution mode: the loads of pixel j (0..7) of chunk c for this thread's rows; called
         // with j = 0, 1, ..., 7 in this order.  Pixel 0 is decoded in full (two divisions by
-        // invariant integers), the others by stepping (image, y, x) one pixel on.  All of it is
-        // wavefront-uniform, i.e. scalar-unit work.
+        // invariant integers), the others by stepping (image, y, x) one pixel on; a pixel past the
+        // last one takes the all-zero image.  All of it is wavefront-uniform, i.e. scalar-unit
+        // work with no branch: arithmetic on the vector unit takes cycles from the fp64 matrix
+        // instructions (the kernel slows down by what the vector instructions add).
         int px_img = 0, px_yo = 0, px_xo = 0;
         auto gload_px = [&](int c, int j) {
             float* fa = reinterpret_cast<float*>(pa);
             float* fb = reinterpret_cast<float*>(pb);
-            const int64_t p = (int64_t)c * XK + 8 * wave_s + j;
-            const bool pv = p < n;
+            const int p = c * XK + 8 * wave_s + j;               // < 2^31 (checked by the caller)
+            const bool pv = p < (int)n;
             if (j == 0) {
-                const uint32_t pc = (uint32_t)min(p, n - 1);
+                const uint32_t pc = (uint32_t)min(p, (int)n - 1);
                 const uint32_t img = fastdiv(pc, cp.div_img);
                 const uint32_t rem = pc - img * (uint32_t)(cp.ho * cp.wo);
                 const uint32_t yo = fastdiv(rem, cp.div_row);
                 px_img = (int)img;
                 px_yo = (int)yo;
                 px_xo = (int)(rem - yo * (uint32_t)cp.wo);
-            } else if (pv) {
-                ++px_xo;
-                if (px_xo == cp.wo) { px_xo = 0; ++px_yo; }
-                if (px_yo == cp.ho) { px_yo = 0; ++px_img; }
-            }
-            const int ytop = px_yo * cp.stride - cp.pad;
-            const int xtop = px_xo * cp.stride - cp.pad;
-            // Window origin (may lie in the padding: only offsets of elements inside the map are
-            // added to it).  All arithmetic on the vector unit takes cycles from the fp64 matrix
-            // instructions (the kernel slows down by what the vector instructions add), so the
-            // common case is kept to one address add per element: when the whole window lies
-            // inside the map (scalar test) no per-lane test is needed.
-            const float* __restrict__ win = X + (((int64_t)px_img * cp.h + ytop) * cp.w + xtop) * cp.c;
-            if (!pv) {
-                // past the last pixel: the padding of the calibration dimension must be zero
-#pragma unroll
-                for (int q = 0; q < 2; ++q) { fa[q * 8 + j] = 0.f; fb[q * 8 + j] = 0.f; }
-            } else if (ytop >= 0 && xtop >= 0 && ytop + cp.k <= cp.h && xtop + cp.k <= cp.w) {
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    fa[q * 8 + j] = win[offA[q]];
-                    fb[q * 8 + j] = win[offB[q]];
-                }
             } else {
-                // window crosses the border: an element outside the map (zero padding) is read from
-                // a word that holds +0.0 instead, so that no arithmetic depends on the loaded value
-                // before it is stored to LDS and the loads stay in flight across the MFMA section
+                ++px_xo;
+                const bool wx = px_xo == cp.wo;
+                px_xo = wx ? 0 : px_xo;
+                px_yo += wx ? 1 : 0;
+                const bool wy = px_yo == cp.ho;
+                px_yo = wy ? 0 : px_yo;
+                px_img += wy ? 1 : 0;
+            }
+            const int64_t origin = (((int64_t)px_img * cp.hp + px_yo * cp.stride) * cp.wp + px_xo * cp.stride) * cp.c;
+            const float* __restrict__ win = X + (pv ? origin : cp.zero_origin);
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const bool va = ((unsigned)(ytop + kyA[q]) < (unsigned)cp.h) &
-                                    ((unsigned)(xtop + kxA[q]) < (unsigned)cp.w);
-                    const bool vb2 = ((unsigned)(ytop + kyB[q]) < (unsigned)cp.h) &
-                                     ((unsigned)(xtop + kxB[q]) < (unsigned)cp.w);
-                    fa[q * 8 + j] = *(va ? win + offA[q] : cp.zero);
-                    fb[q * 8 + j] = *(vb2 ? win + offB[q] : cp.zero);
-                }
+            for (int q = 0; q < 2; ++q) {
+                fa[q * 8 + j] = win[offA[q]];
+                fb[q * 8 + j] = win[offB[q]];
             }
         };
         auto gload = [&](int c) {
@@ -364,10 +373,10 @@ hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t 
     return hipGetLastError();
 }
 
-// Convolution mode: maps is n_img x h x w x c (NHWC), d = c k^2, one calibration column per
-// output pixel; npix = n_img * ho * wo < 2^31; zero_word points to at least 4 bytes of zeros.
-hipError_t launch_xxt_conv(hipStream_t s, const float* maps, const float* zero_word, int h, int w, int c, int k,
-                           int stride, int pad, int ho, int wo, int64_t npix, double* Hpart, int splits)
+// Convolution mode: padded = the copy written by launch_pad_maps ((n_img + 1) x hp x wp x c),
+// d = c k^2, one calibration column per output pixel; npix = n_img * ho * wo < 2^31 - 64.
+hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
+                           int ho, int wo, int64_t npix, double* Hpart, int splits)
 {
     const int d = c * k * k;
     const int nt = (d + XT - 1) / XT;
@@ -377,13 +386,13 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* maps, const float* zero_w
     const int64_t total = tiles * chunks;
     const int wgs = (int)((total + per_wg - 1) / per_wg);
     ConvP cp;
-    cp.zero = zero_word;
-    cp.h = h; cp.w = w; cp.c = c; cp.k = k; cp.stride = stride; cp.pad = pad; cp.ho = ho; cp.wo = wo;
+    cp.hp = hp; cp.wp = wp; cp.c = c; cp.k = k; cp.stride = stride; cp.ho = ho; cp.wo = wo;
+    cp.zero_origin = (int64_t)n_img * hp * wp * c;
     cp.div_img = fastdiv_make((uint32_t)(ho * wo));
     cp.div_row = fastdiv_make((uint32_t)wo);
     cp.div_c = fastdiv_make((uint32_t)c);
     cp.div_k = fastdiv_make((uint32_t)k);
-    hipLaunchKernelGGL((xxt_kernel<2>), dim3(wgs), dim3(256), 0, s, maps, (int64_t)0, d, npix, Hpart, chunks, per_wg,
+    hipLaunchKernelGGL((xxt_kernel<2>), dim3(wgs), dim3(256), 0, s, padded, (int64_t)0, d, npix, Hpart, chunks, per_wg,
                        total, cp);
     return hipGetLastError();
 }
