@@ -91,6 +91,9 @@ def main() -> int:
                     help="conv workloads: accumulate the Hessian straight from the feature maps "
                          "(fobq_hessian_accumulate_conv) instead of the unfolded X")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--obq-rows", type=int, default=0,
+                    help="with the CPU baseline: also run the per-row OBQ baseline (own inverse Hessian per row) "
+                         "of the oracle on this many rows and report its cost and loss next to FastOBQ's")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain device copy of X first (known bytes; calibrates HBM byte counters)")
     args = ap.parse_args()
@@ -183,6 +186,19 @@ def main() -> int:
         cpu = {"value": round(weights / cpu_s, 1), "unit": "weights/s", "cores": oracle.num_threads(),
                "kind": "oracle", "sample": f"the whole {spec.name} layer once ({cpu_s:.1f} s): H, inverse, order, column loop",
                "seconds": round(cpu_s, 2), "codes_differ_vs_gpu": float((codes != ref.codes).mean())}
+        if args.obq_rows > 0:
+            # the paper's comparison (OBQ vs FastOBQ, Tables 1-2 "Time") on this synthetic layer, CPU oracle only
+            nr = min(args.obq_rows, spec.d_row)
+            t = time.perf_counter()
+            ob = oracle.obq_rows(W, ref.Hinv, spec.bits, spec.group, ref.scales, ref.zeros, rows=(0, nr))
+            obq_s = time.perf_counter() - t
+            dW = W[:nr].astype(np.float64) - ref.Q[:nr]
+            fast_loss = 0.5 * float(np.einsum("ij,jk,ik->", dW, ref.H_damped, dW))
+            cpu["obq"] = {"rows": nr, "seconds": round(obq_s, 2),
+                          "est_layer_seconds": round(obq_s * spec.d_row / nr, 1),
+                          "obq_over_fastobq_time": round(obq_s * spec.d_row / nr / cpu_s, 1),
+                          "obq_over_fastobq_gpu_time": round(obq_s * spec.d_row / nr / (ms_per_step * 1e-3), 1),
+                          "fastobq_over_obq_loss_same_rows": round(fast_loss / float(ob.lossrow[:nr].sum()), 4)}
 
     line = {
         "metric": "weights quantized per second, whole layer path"

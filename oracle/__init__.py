@@ -189,6 +189,32 @@ def column_loop_dynamic(W: np.ndarray, Hinv: np.ndarray, bits: int, group: int, 
     return LoopResult(codes, Q, Ww, Hw, loss.value), perm
 
 
+@dataclass
+class ObqResult:
+    codes: np.ndarray      # int64 d_row x d_col (only rows[0]:rows[1] are meaningful)
+    Q: np.ndarray
+    order: np.ndarray      # int32 d_row x d_col: per row, the index processed at each step
+    lossrow: np.ndarray    # fp64 d_row
+    rows: tuple
+
+
+def obq_rows(W: np.ndarray, Hinv: np.ndarray, bits: int, group: int, scale: np.ndarray, zero: np.ndarray,
+             rows: Optional[tuple] = None) -> ObqResult:
+    """The per-row baseline (own inverse Hessian and own order per row, smallest loss term first)."""
+    W = _f32(W)
+    r, d = W.shape
+    lo, hi = (0, r) if rows is None else rows
+    Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
+    codes = np.zeros((r, d), dtype=np.int64)
+    Q = np.zeros((r, d), dtype=np.float64)
+    order_ = np.zeros((r, d), dtype=np.int32)
+    lossrow = np.zeros(r, dtype=np.float64)
+    _chk(_get().oracle_obq_rows(_p(W), ctypes.c_int64(r), ctypes.c_int64(d), _p(Hinv), ctypes.c_int(bits),
+                                ctypes.c_int64(group), _p(scale), _p(zero), ctypes.c_int64(lo), ctypes.c_int64(hi),
+                                _p(codes), _p(Q), _p(order_), _p(lossrow)), "oracle_obq_rows")
+    return ObqResult(codes, Q, order_, lossrow, (lo, hi))
+
+
 def loss_eval(W: np.ndarray, Q: np.ndarray, H: np.ndarray) -> float:
     """1/2 tr((W - Q) H (W - Q)^T)."""
     W = _f32(W)

@@ -414,6 +414,90 @@ int oracle_column_loop_dynamic(const float *W, int64_t d_row, int64_t d_col, dou
                             codes, Q, Wwork, loss);
 }
 
+/*
+ * The baseline the method is derived from (Section 4.2, first paragraphs): OBQ quantizes every
+ * row on its own.  Each row keeps its own copy of the inverse Hessian, picks at every step the
+ * not-yet-quantized weight with the SMALLEST loss term (quant(w_p) - w_p)^2 / (2 [Hinv]_pp)
+ * (Eq. 10; the first such weight in index order when several are equal), quantizes it,
+ * compensates the rest of the row (Eq. 9 / 11) and eliminates index p from the row's own
+ * inverse (Eq. 12).  Cost O(d_row d_col^3) against O(d_col^3 + d_row d_col^2) of the shared-inverse
+ * loop above.  Same frozen grid, same arithmetic per step as oracle_column_loop.
+ *
+ * row_begin .. row_end: the rows to process (a sample of rows is enough to measure the per-row
+ * cost and loss; rows do not interact).  Outputs are full d_row x d_col arrays of which only those
+ * rows are written; order (may be NULL) receives, per row, the index processed at each step;
+ * lossrow (d_row) the row's accumulated loss.
+ */
+int oracle_obq_rows(const float *W, int64_t d_row, int64_t d_col, const double *Hinv0,
+                    int bits, int64_t group, const double *scale, const double *zero,
+                    int64_t row_begin, int64_t row_end,
+                    int64_t *codes, double *Q, int32_t *order, double *lossrow)
+{
+    if (!W || !Hinv0 || !scale || !zero || !codes || !Q || !lossrow) return ORACLE_EINVAL;
+    if (row_begin < 0 || row_end > d_row || row_begin > row_end) return ORACLE_EINVAL;
+    const int64_t d = d_col;
+    const int64_t G = groups_of(d_col, group);
+    const int64_t gs = group > 0 ? group : d_col;
+    const double maxq = ldexp(1.0, bits) - 1.0;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = row_begin; i < row_end; ++i) {
+        double *Hc = (double *)malloc((size_t)d * d * sizeof(double));
+        double *w = (double *)malloc((size_t)d * sizeof(double));
+        double *rowj = (double *)malloc((size_t)d * sizeof(double));
+        unsigned char *done = (unsigned char *)calloc((size_t)d, 1);
+        if (!Hc || !w || !rowj || !done) {
+#pragma omp critical
+            status = ORACLE_ENOMEM;
+            free(Hc); free(w); free(rowj); free(done);
+            continue;
+        }
+        memcpy(Hc, Hinv0, (size_t)d * d * sizeof(double));
+        for (int64_t k = 0; k < d; ++k) w[k] = (double)W[i * d + k];
+        double loss = 0.0;
+        for (int64_t t = 0; t < d; ++t) {
+            int64_t j = -1;
+            double best = 0.0;
+            for (int64_t k = 0; k < d; ++k) {
+                if (done[k]) continue;
+                const double s = scale[i * G + k / gs], z = zero[i * G + k / gs];
+                const double diff = grid_value(grid_code(w[k], s, z, maxq), s, z) - w[k];
+                const double sk = diff * diff / (2.0 * Hc[k * d + k]);
+                if (j < 0 || sk < best) { j = k; best = sk; }
+            }
+            const double hjj = Hc[j * d + j];
+            if (!(hjj > 0.0)) {
+#pragma omp critical
+                status = ORACLE_ENOTPD;
+                break;
+            }
+            for (int64_t k = 0; k < d; ++k) rowj[k] = Hc[j * d + k];
+            done[j] = 1;
+            if (order) order[i * d + t] = (int32_t)j;
+            const double s = scale[i * G + j / gs], z = zero[i * G + j / gs];
+            const double c = grid_code(w[j], s, z, maxq);
+            const double q = grid_value(c, s, z);
+            codes[i * d + j] = (int64_t)c;
+            Q[i * d + j] = q;
+            const double diff = w[j] - q;
+            loss += diff * diff / (2.0 * hjj);
+            const double e = diff / hjj;
+            for (int64_t k = 0; k < d; ++k)
+                if (!done[k]) w[k] -= e * rowj[k];
+            for (int64_t a = 0; a < d; ++a) {
+                if (done[a]) continue;
+                const double f = rowj[a] / hjj;
+                double *ra = Hc + a * d;
+                for (int64_t b = 0; b < d; ++b)
+                    if (!done[b]) ra[b] -= f * rowj[b];
+            }
+        }
+        lossrow[i] = loss;
+        free(Hc); free(w); free(rowj); free(done);
+    }
+    return status;
+}
+
 /* 1/2 tr((W - Q) H (W - Q)^T), H fp64 d x d. */
 int oracle_loss_eval(const float *W, const double *Q, const double *H, int64_t d_row, int64_t d_col,
                      double *loss)

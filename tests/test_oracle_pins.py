@@ -435,3 +435,54 @@ def test_dynamic_order_breaks_ties_by_index_and_honours_steps():
     assert np.array_equal(part.perm[:2], a.perm[:2])
     assert sorted(part.perm) == list(range(5)) and list(part.perm[2:]) == sorted(part.perm[2:])
     assert np.all(part.Q[:, part.perm[2:]] == 0.0)
+
+
+# ---------------------------------------------------------------- per-row OBQ baseline (Section 4.2, first paragraphs)
+def test_obq_row_is_the_shared_loop_on_that_row_with_the_rows_own_order():
+    """Rows never interact, so OBQ on row i must equal the (pinned) shared-inverse loop run on the
+    single row i with the order OBQ chose for it: same codes, same values, same loss."""
+    W, X = _problem(5, 12, 70, 31)
+    base = oracle.quantize_layer(W, X=X, bits=3, group=4)
+    o = oracle.obq_rows(W, base.Hinv, 3, 4, base.scales, base.zeros)
+    for i in range(5):
+        assert sorted(o.order[i]) == list(range(12))
+        one = oracle.column_loop(W[i:i + 1], base.Hinv, o.order[i], 3, 4, base.scales[i:i + 1], base.zeros[i:i + 1])
+        assert np.array_equal(o.codes[i], one.codes[0])
+        assert np.array_equal(o.Q[i], one.Q[0])
+        assert np.isclose(o.lossrow[i], one.loss, rtol=1e-13)
+    # the loss identity holds per row whatever the order
+    dW = W.astype(np.float64) - o.Q
+    assert np.allclose(o.lossrow, 0.5 * np.einsum("ij,jk,ik->i", dW, base.H_damped, dW), rtol=1e-9)
+
+
+def test_obq_takes_the_weight_with_the_smallest_loss_term():
+    d = 6
+    W, X = _problem(2, d, 40, 32)
+    base = oracle.quantize_layer(W, X=X, bits=3)
+    o = oracle.obq_rows(W, base.Hinv, 3, 0, base.scales, base.zeros)
+    i = 1
+    for t in range(d):
+        done = list(o.order[i][:t])
+        before = oracle.column_loop(W[i:i + 1], base.Hinv, o.order[i], 3, 0, base.scales[i:i + 1],
+                                    base.zeros[i:i + 1], steps=t).loss if t else 0.0
+        gains = {}
+        for cand in range(d):
+            if cand in done:
+                continue
+            rest = [k for k in range(d) if k not in done and k != cand]
+            p = np.array(done + [cand] + rest, dtype=np.int32)
+            gains[cand] = oracle.column_loop(W[i:i + 1], base.Hinv, p, 3, 0, base.scales[i:i + 1],
+                                             base.zeros[i:i + 1], steps=t + 1).loss - before
+        assert int(o.order[i][t]) == min(gains, key=gains.get)
+
+
+def test_obq_row_range_and_diagonal_case():
+    rng = np.random.default_rng(33)
+    W = (rng.standard_normal((4, 7)) * 0.1).astype(np.float32)
+    H = np.diag(np.linspace(1.0, 2.0, 7))
+    base = oracle.quantize_layer(W, H=H, bits=4, damp_rel=0.0)
+    part = oracle.obq_rows(W, base.Hinv, 4, 0, base.scales, base.zeros, rows=(1, 3))
+    full = oracle.obq_rows(W, base.Hinv, 4, 0, base.scales, base.zeros)
+    assert np.array_equal(part.codes[1:3], full.codes[1:3]) and np.all(part.codes[[0, 3]] == 0)
+    # diagonal H: no compensation, every order gives plain round-to-nearest
+    assert np.array_equal(full.codes, base.codes)
