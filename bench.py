@@ -28,6 +28,8 @@ PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
 # HBM bytes per xxt_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain device copy of X (profiles/xxt_kernel_c2_counters.txt); one launch per step only
 MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 2.92e9}
+# the same for step_kernel (--block 1), average per launch (profiles/step_kernel_c5_block1.txt)
+MEASURED_STEP_TRAFFIC_BYTES = {"c5_large_d": 1.349e8}
 
 
 def sweep(model: str, steps: int, warmup: int) -> int:
@@ -175,6 +177,19 @@ def main() -> int:
                 "algorithmic_flops_per_launch": flops_per_launch}
 
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
+    if args.block == 1:
+        # the literal rank-1 path: step_kernel (one launch per column) dominates and is HBM-bound.
+        # Algorithmic bytes per layer: fp64 W read + write and the upper triangle of the fp64 running
+        # inverse read + write, 8 R d^2 + (8/3) d^3; one launch = one column.  The launches are timed
+        # together (HIP events around the stage on the library's stream), so launch gaps are included.
+        R, d = spec.d_row, spec.d_col
+        bytes_per_launch = (8.0 * R * d * d + 8.0 / 3.0 * d ** 3) / d
+        col_ms, _ = stages["columns"]
+        avg_ms = col_ms / (args.steps * d)
+        ach = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": "step_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
+                    "frac": round(ach / 8000.0, 4), "traffic": MEASURED_STEP_TRAFFIC_BYTES.get(spec.name),
+                    "avg_launch_ms": round(avg_ms, 6), "algorithmic_bytes_per_launch": bytes_per_launch}
 
     cpu = None
     if not args.no_cpu_baseline:
