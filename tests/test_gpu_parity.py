@@ -376,6 +376,56 @@ def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
     assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-6 * expect
 
 
+def test_maximum_d_row(fobq, ctx):
+    # the largest d_row the library accepts, checked against the oracle in full
+    r, d = 65535, 96
+    _say(f"maximum d_row: {r} x {d}")
+    W, X = _problem(r, d, 400, 13, w_std=0.05)
+    H = oracle.hessian(X)
+    out = ctx.quantize_layer(_dev(W), _dev(H), bits=4, group=32)
+    ref = oracle.quantize_layer(W, H=H, bits=4, group=32)
+    ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=4, group=32)
+    _compare_layer(out, ref, W, 4)
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.quantize_layer(torch.zeros((65536, 8), dtype=torch.float32, device="cuda"),
+                           torch.eye(8, dtype=torch.float64, device="cuda"))
+    assert e.value.code == fobq.EINVAL
+
+
+@pytest.mark.slow
+@pytest.mark.parametrize("d", [16384, 32768])
+def test_large_d_col_properties(fobq, ctx, d):
+    """d_col far beyond what the oracle can follow (32768 is the largest the library accepts): the
+    properties that hold at any size.  The order is a permutation, the codes are on the grid, and the
+    loss accumulated step by step equals 1/2 tr(dW H_d dW^T) evaluated from the Hessian -- which only
+    holds if the inverse, the elimination and every compensation step are right."""
+    r, n = 8, 2048
+    _say(f"large d_col: {r} x {d}, N = {n}")
+    rng = np.random.default_rng(d)
+    X = torch.from_numpy(np.maximum(rng.standard_normal((d, n)), 0).astype(np.float32)).cuda()
+    W = torch.from_numpy((rng.standard_normal((r, d)) * 0.02).astype(np.float32)).cuda()
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.hessian(X, H_out=H)
+    _say("large d_col: quantize")
+    out = ctx.quantize_layer(W, bits=4, damp=0.01)
+    _say("large d_col: checks")
+    perm = out.perm.cpu().numpy()
+    assert np.array_equal(np.sort(perm), np.arange(d))
+    assert int(out.codes.max()) <= 15
+    lam = 0.01 * float(torch.diagonal(H).mean())
+    dW = W.double() - out.Q.double()
+    expect = 0.5 * float(((dW @ H) * dW).sum()) + 0.5 * lam * float((dW * dW).sum())
+    loss = float(out.loss.cpu()[0])
+    assert abs(loss - expect) <= 1e-6 * expect, (loss, expect)
+    # Q is what the codes say
+    G = out.scales.shape[1]
+    q = out.scales.double() * (out.codes.double().reshape(r, G, -1).permute(2, 0, 1) - out.zeros.double())
+    assert torch.allclose(q.permute(1, 2, 0).reshape(r, d), out.Q.double(), rtol=1e-6, atol=1e-12)
+    with pytest.raises(fobq.FobqError) as e:
+        fobq.fobq_hessian_begin(ctx.handle, 32769)
+    assert e.value.code == fobq.EINVAL
+
+
 # --------------------------------------------------------------------------- the benchmark configurations
 def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None, spec=None):
     spec = spec if spec is not None else workloads.configs()[name]
