@@ -87,10 +87,21 @@ hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, i
     return hipGetLastError();
 }
 
-constexpr int XT = 128;          // tile edge
+// Tile edge XT: 128 (each of the 4 wavefronts owns 64 x 64 = 4 x 4 MFMA tiles) or, for small d where
+// 128-wide tiles are mostly padding, 64 (32 x 32 = 2 x 2 MFMA tiles per wavefront; twice the operand
+// traffic and conversions per MFMA, but up to 4x less padding).
 constexpr int XK = 32;           // calibration columns per LDS stage
 constexpr int XLD = XK + 4;      // fp32 row stride in LDS: 16B-aligned rows, conflict-free 16B fragment reads
-constexpr int XXT_WGS = 512;     // persistent workgroups: 2 per compute unit
+constexpr int xxt_wgs(int xt) { return xt == 128 ? 512 : 1024; }   // persistent workgroups: 2 or 4 per compute unit
+
+// 64-wide tiles when they cut the padded area (tiles on or below the diagonal) by more than the ~20 % that
+// the smaller tile costs in matrix-pipe efficiency.
+static int xxt_tile(int d)
+{
+    const int64_t n128 = (d + 127) / 128, n64 = (d + 63) / 64;
+    const int64_t a128 = n128 * (n128 + 1) / 2 * 128 * 128, a64 = n64 * (n64 + 1) / 2 * 64 * 64;
+    return a64 * 6 < a128 * 5 ? 64 : 128;
+}
 
 // Order of the lower-triangle tiles: tile rows are taken in pairs (2r, 2r + 1) and a pair is walked
 // column by column, (2r, J), (2r + 1, J), (2r, J + 1), ...  Consecutive tiles of the order then share a
@@ -109,13 +120,16 @@ __device__ __forceinline__ void tile_decode(int t, int nt, int& I, int& J)
 
 // MODE 0: X rows are 16-byte aligned (ld % 4 == 0, base aligned) -> float4 loads.
 // MODE 1: any ld / alignment.  MODE 2: X = feature maps, n = images * ho * wo (convolution mode).
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
+template <int MODE, int XT>
+__global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
                                                      double* __restrict__ Hpart, int chunks, int64_t per_wg,
                                                      int64_t total_items, ConvP cp)
 {
     constexpr bool FAST = MODE == 0;
     constexpr bool CONV = MODE == 2;
+    constexpr int RG = XT / 32;       // groups of 32 rows per operand tile (plain loader: one float4 per group)
+    constexpr int WT = XT / 2;        // edge of a wavefront's part of the tile
+    constexpr int MT = WT / 16;       // MFMA tiles per edge of that part
     __shared__ float As[2][XT][XLD];
     __shared__ float Bs[2][XT][XLD];
 
@@ -151,17 +165,18 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
 
         // plain modes: clamped row pointers (rows past d produce outputs that are never stored);
         // thread = (row lr + 32 u, 4 consecutive columns)
-        const float* __restrict__ arow[4];
-        const float* __restrict__ brow[4];
+        const float* __restrict__ arow[RG];
+        const float* __restrict__ brow[RG];
         // convolution mode: thread = (rows lane + 64 q, pixels 8 wave + j): a load covers 64
         // consecutive channels (256 contiguous bytes) of ONE pixel, so the pixel's decoding and its
         // window origin are wavefront-uniform (scalar unit).  Per tile: the offset of this thread's
         // two rows (ky, kx, channel) of each operand from the window's top-left element in the
         // padded copy.  Rows past d stand in as row d - 1.
-        uint32_t offA[2], offB[2];
+        constexpr int QN = XT / 64;    // rows per operand and thread in convolution mode
+        uint32_t offA[QN], offB[QN];
         if (CONV) {
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < QN; ++q) {
                 const int ra = min(i0 + lane + 64 * q, d - 1), rb = min(j0 + lane + 64 * q, d - 1);
                 const uint32_t ta = fastdiv((uint32_t)ra, cp.div_c), tb = fastdiv((uint32_t)rb, cp.div_c);
                 const uint32_t kya = fastdiv(ta, cp.div_k), kyb = fastdiv(tb, cp.div_k);
@@ -170,12 +185,12 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             }
         } else {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < RG; ++u) {
                 arow[u] = X + (int64_t)min(i0 + lr + 32 * u, d - 1) * ld;
                 brow[u] = X + (int64_t)min(j0 + lr + 32 * u, d - 1) * ld;
             }
         }
-        float4 pa[4], pb[4];
+        float4 pa[RG], pb[RG];
         // Convolution mode: the loads of pixel j (0..7) of chunk c for this thread's rows; called
         // with j = 0, 1, ..., 7 in this order.  Pixel 0 is decoded in full (two divisions by
         // invariant integers), the others by stepping (image, y, x) one pixel on; a pixel past the
@@ -208,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             const int64_t origin = (((int64_t)px_img * cp.hp + px_yo * cp.stride) * cp.wp + px_xo * cp.stride) * cp.c;
             const float* __restrict__ win = X + (pv ? origin : cp.zero_origin);
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < QN; ++q) {
                 fa[q * 8 + j] = win[offA[q]];
                 fb[q * 8 + j] = win[offB[q]];
             }
@@ -222,13 +237,13 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             const int64_t k = (int64_t)c * XK + lk;
             if (FAST && k + 3 < n) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < RG; ++u) {
                     pa[u] = *reinterpret_cast<const float4*>(arow[u] + k);
                     pb[u] = *reinterpret_cast<const float4*>(brow[u] + k);
                 }
             } else {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < RG; ++u) {
                     float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
                     if (k + 0 < n) { va.x = arow[u][k + 0]; vb.x = brow[u][k + 0]; }
                     if (k + 1 < n) { va.y = arow[u][k + 1]; vb.y = brow[u][k + 1]; }
@@ -243,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             if (CONV) {
                 // 8 consecutive pixels of a row: two 16-byte stores per row
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
+                for (int q = 0; q < QN; ++q) {
                     *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave]) = pa[2 * q];
                     *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave + 4]) = pa[2 * q + 1];
                     *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave]) = pb[2 * q];
@@ -252,17 +267,17 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
                 return;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < RG; ++u) {
                 *reinterpret_cast<float4*>(&As[buf][lr + 32 * u][lk]) = pa[u];
                 *reinterpret_cast<float4*>(&Bs[buf][lr + 32 * u][lk]) = pb[u];
             }
         };
 
-        d4 acc[4][4];
+        d4 acc[MT][MT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+            for (int j = 0; j < MT; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
 
         __syncthreads();              // LDS free (previous tile's last stage consumed)
         gload(c_begin);
@@ -278,26 +293,26 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
             const int cn = more ? c + 1 : c;
 #pragma unroll
             for (int g = 0; g < XK / 16; ++g) {
-                float4 fa[4], fb[4];
+                float4 fa[MT], fb[MT];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    fa[i] = *reinterpret_cast<const float4*>(&As[cur][wm * 64 + i * 16 + fr][g * 16 + fk]);
+                for (int i = 0; i < MT; ++i)
+                    fa[i] = *reinterpret_cast<const float4*>(&As[cur][wm * WT + i * 16 + fr][g * 16 + fk]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    fb[j] = *reinterpret_cast<const float4*>(&Bs[cur][wn * 64 + j * 16 + fr][g * 16 + fk]);
+                for (int j = 0; j < MT; ++j)
+                    fb[j] = *reinterpret_cast<const float4*>(&Bs[cur][wn * WT + j * 16 + fr][g * 16 + fk]);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    double a[4], b[4];
+                    double a[MT], b[MT];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < MT; ++i)
                         a[i] = (double)(ks == 0 ? fa[i].x : ks == 1 ? fa[i].y : ks == 2 ? fa[i].z : fa[i].w);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < MT; ++j)
                         b[j] = (double)(ks == 0 ? fb[j].x : ks == 1 ? fb[j].y : ks == 2 ? fb[j].z : fb[j].w);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < MT; ++i)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
+                        for (int j = 0; j < MT; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
                     if (CONV) gload_px(cn, g * 4 + ks);
                 }
@@ -309,13 +324,13 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
 
         double* __restrict__ out = Hpart + (int64_t)piece * d * d;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < MT; ++j)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int gr = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4);
-                    const int gc = j0 + wn * 64 + j * 16 + (lane & 15);
+                    const int gr = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4);
+                    const int gc = j0 + wn * WT + j * 16 + (lane & 15);
                     if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
                 }
         item += c_end - c_begin;
@@ -323,24 +338,26 @@ __global__ __launch_bounds__(256, 2) void xxt_kernel(const float* __restrict__ X
 }
 
 // Number of d x d slabs of partial sums = the most pieces a tile can be cut into:
-// with XXT_WGS equal ranges over tiles * chunks items, a tile spans at most
-// ceil(XXT_WGS / tiles) ranges, plus one when it starts inside a range.
+// with W equal ranges over tiles * chunks items, a tile spans at most ceil(W / tiles) ranges,
+// plus one when it starts inside a range.
 int xxt_pick_splits(int d)
 {
-    const int nt = (d + XT - 1) / XT;
+    const int xt = xxt_tile(d);
+    const int nt = (d + xt - 1) / xt;
     const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
-    return (int)((XXT_WGS + tiles - 1) / tiles) + 1;
+    return (int)((xxt_wgs(xt) + tiles - 1) / tiles) + 1;
 }
 
 // length of one workgroup's range of (tile, chunk) items
 static int64_t xxt_range(int d, int64_t n, int splits, int* chunks_out)
 {
-    const int nt = (d + XT - 1) / XT;
+    const int xt = xxt_tile(d);
+    const int nt = (d + xt - 1) / xt;
     const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
     const int chunks = (int)((n + XK - 1) / XK);
     const int64_t total = tiles * chunks;
     // each workgroup's range must be long enough that no tile is cut into more than `splits` pieces
-    int64_t per_wg = (total + XXT_WGS - 1) / XXT_WGS;
+    int64_t per_wg = (total + xxt_wgs(xt) - 1) / xxt_wgs(xt);
     const int64_t min_per = splits > 1 ? (chunks + splits - 2) / (splits - 1) : chunks;
     if (per_wg < min_per) per_wg = min_per;
     *chunks_out = chunks;
@@ -357,19 +374,29 @@ int xxt_slabs_touched(int d, int64_t n, int splits)
     return (int)(p < splits ? p : splits);
 }
 
+template <int MODE>
+static void xxt_launch(hipStream_t s, int xt, int wgs, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
+                       int chunks, int64_t per_wg, int64_t total, const ConvP& cp)
+{
+    if (xt == 128)
+        hipLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, cp);
+    else
+        hipLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, cp);
+}
+
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
 {
-    const int nt = (d + XT - 1) / XT;
+    const int xt = xxt_tile(d);
+    const int nt = (d + xt - 1) / xt;
     const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
     int chunks;
     const int64_t per_wg = xxt_range(d, n, splits, &chunks);
     const int64_t total = tiles * chunks;
     const int wgs = (int)((total + per_wg - 1) / per_wg);
-    dim3 grid(wgs), block(256);
     const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     ConvP none{};
-    if (fast) hipLaunchKernelGGL((xxt_kernel<0>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, none);
-    else      hipLaunchKernelGGL((xxt_kernel<1>), grid, block, 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, none);
+    if (fast) xxt_launch<0>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none);
+    else      xxt_launch<1>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none);
     return hipGetLastError();
 }
 
@@ -379,7 +406,8 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
                            int ho, int wo, int64_t npix, double* Hpart, int splits)
 {
     const int d = c * k * k;
-    const int nt = (d + XT - 1) / XT;
+    const int xt = xxt_tile(d);
+    const int nt = (d + xt - 1) / xt;
     const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
     int chunks;
     const int64_t per_wg = xxt_range(d, npix, splits, &chunks);
@@ -392,8 +420,7 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
     cp.div_row = fastdiv_make((uint32_t)wo);
     cp.div_c = fastdiv_make((uint32_t)c);
     cp.div_k = fastdiv_make((uint32_t)k);
-    hipLaunchKernelGGL((xxt_kernel<2>), dim3(wgs), dim3(256), 0, s, padded, (int64_t)0, d, npix, Hpart, chunks, per_wg,
-                       total, cp);
+    xxt_launch<2>(s, xt, wgs, padded, 0, d, npix, Hpart, chunks, per_wg, total, cp);
     return hipGetLastError();
 }
 
