@@ -123,7 +123,7 @@ __device__ __forceinline__ void tile_decode(int t, int nt, int& I, int& J)
 template <int MODE, int XT>
 __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
                                                      double* __restrict__ Hpart, int chunks, int64_t per_wg,
-                                                     int64_t total_items, ConvP cp)
+                                                     int64_t total_items, int classes, ConvP cp)
 {
     constexpr bool FAST = MODE == 0;
     constexpr bool CONV = MODE == 2;
@@ -146,18 +146,54 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
     // the same position of the calibration dimension.
     const int nx = 8, gq = (int)gridDim.x / nx, grem = (int)gridDim.x % nx;
     const int xcd = (int)blockIdx.x % nx;
-    const int vb = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+    const int vpos = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+    // Position vpos in that XCD-contiguous order -> range index vb, class-major: when a tile is cut
+    // into `classes` pieces, the ranges vb = c, c + classes, c + 2 classes, ... cover the same part
+    // of the calibration dimension of consecutive tiles, and only they can share fetches; ordering
+    // the ranges by (vb mod classes, vb) puts up to 64 of them on one XCD instead of 64 / classes.
+    int vb = vpos;
+    if (classes > 1) {
+        int cls = 0, before = 0;
+        for (;;) {
+            const int cnt = ((int)gridDim.x - cls + classes - 1) / classes;   // ranges with vb mod classes == cls
+            if (vpos < before + cnt) break;
+            before += cnt;
+            ++cls;
+        }
+        vb = cls + classes * (vpos - before);
+    }
     const int nt = (d + XT - 1) / XT;
 
-    int64_t item = (int64_t)vb * per_wg;
-    const int64_t item_end = min(total_items, item + per_wg);
+    // This workgroup's range of items [g0, g1) and its pieces (one per tile it touches).  All
+    // workgroups start together and advance one chunk per step, so chunk k is best visited at step
+    // k mod per_wg: workgroups on neighbouring tiles (which share panels of X and, thanks to the
+    // mapping above, an L2) then read the same columns of X at the same time.  A range inside one
+    // tile therefore starts at its chunk whose index is a multiple of per_wg and wraps around; a range
+    // over two tiles takes the head of the later tile (chunks 0 ...) before the tail of the earlier
+    // one.  The order of the sum over chunks is free; it stays fixed, so results are reproducible.
+    const int64_t g0 = (int64_t)vb * per_wg;
+    const int64_t g1 = min(total_items, g0 + per_wg);
+    if (g0 >= g1) return;
+    const int t_first = (int)(g0 / chunks), t_last = (int)((g1 - 1) / chunks);
+    const int npieces = t_last - t_first + 1;
 
-    while (item < item_end) {
-        const int tile = (int)(item / chunks);
-        const int c_begin = (int)(item % chunks);
-        const int c_end = (int)min((int64_t)chunks, c_begin + (item_end - item));
-        // piece index of this range inside its tile: number of workgroup boundaries before it
+    for (int pi = 0; pi < npieces; ++pi) {
+        const int tile = npieces == 2 ? t_last - pi : t_first + pi;
         const int64_t tile_first = (int64_t)tile * chunks;
+        const int c_begin = (int)(max(g0, tile_first) - tile_first);
+        const int c_end = (int)(min(g1, tile_first + chunks) - tile_first);
+        const int len = c_end - c_begin;
+        int rot = 0;
+        if (npieces == 1) {
+            const int64_t aligned = (c_begin + per_wg - 1) / per_wg * per_wg;
+            if (aligned < c_end) rot = (int)(aligned - c_begin);
+        }
+        auto chunk_at = [&](int i) {
+            int c = i + rot;
+            if (c >= len) c -= len;
+            return c_begin + c;
+        };
+        // piece index of this range inside its tile: number of workgroup boundaries before it
         const int piece = (int)(vb - tile_first / per_wg);    // 0 for the workgroup whose range reaches the tile first
         int I, J;
         tile_decode(tile, nt, I, J);
@@ -280,17 +316,17 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
             for (int j = 0; j < MT; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
 
         __syncthreads();              // LDS free (previous tile's last stage consumed)
-        gload(c_begin);
+        gload(chunk_at(0));
         sstore(0);
         __syncthreads();
         int cur = 0;
-        for (int c = c_begin; c < c_end; ++c) {
-            const bool more = c + 1 < c_end;
+        for (int ci = 0; ci < len; ++ci) {
+            const bool more = ci + 1 < len;
             // plain modes: 8 wide loads, issued up front.  Convolution mode: one pixel's loads per
             // group of 16 MFMAs (after the last chunk of a range the same chunk is simply loaded
             // again and not stored).
-            if (!CONV && more) gload(c + 1);
-            const int cn = more ? c + 1 : c;
+            const int cn = chunk_at(more ? ci + 1 : ci);
+            if (!CONV && more) gload(cn);
 #pragma unroll
             for (int g = 0; g < XK / 16; ++g) {
                 float4 fa[MT], fb[MT];
@@ -333,7 +369,6 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
                     const int gc = j0 + wn * WT + j * 16 + (lane & 15);
                     if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
                 }
-        item += c_end - c_begin;
     }
 }
 
@@ -378,10 +413,15 @@ template <int MODE>
 static void xxt_launch(hipStream_t s, int xt, int wgs, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
                        int chunks, int64_t per_wg, int64_t total, const ConvP& cp)
 {
+    // pieces per tile, rounded: the number of classes of ranges (see the kernel)
+    int classes = (int)((chunks + per_wg / 2) / per_wg);
+    classes = classes < 1 ? 1 : (classes > wgs ? wgs : classes);
     if (xt == 128)
-        hipLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, cp);
+        hipLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total,
+                           classes, cp);
     else
-        hipLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total, cp);
+        hipLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total,
+                           classes, cp);
 }
 
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
