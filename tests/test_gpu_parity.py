@@ -376,6 +376,30 @@ def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
     assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-6 * expect
 
 
+def test_non_finite_inputs_do_not_break_the_context(fobq, ctx):
+    # NaN / Inf in the inputs are not rejected on the host; they must neither fault nor poison later calls
+    W, X = _problem(20, 130, 400, 14, w_std=0.05)
+    H = oracle.hessian(X)
+    Xbad = X.copy()
+    Xbad[5, 7] = np.nan
+    ctx.hessian(_dev(Xbad))
+    with pytest.raises(fobq.FobqError) as e:          # H has a NaN row: no positive pivot
+        ctx.quantize_layer(_dev(W), bits=4)
+    assert e.value.code == fobq.ENOTPD
+    Wbad = W.copy()
+    Wbad[3, 10] = np.nan
+    Wbad[4, 11] = np.inf
+    out = ctx.quantize_layer(_dev(Wbad), _dev(H), bits=4)        # returns; the order is still a permutation
+    assert sorted(out.perm.cpu().numpy().tolist()) == list(range(130))
+    good = [i for i in range(20) if i not in (3, 4)]
+    assert torch.isfinite(out.Q[good]).all()
+    # and the context still gives the right answer afterwards
+    out = ctx.quantize_layer(_dev(W), _dev(H), bits=4)
+    ref = oracle.quantize_layer(W, H=H, bits=4)
+    ref = _oracle_with_gpu_perm(W, H, out.perm.cpu().numpy(), ref, bits=4)
+    _compare_layer(out, ref, W, 4)
+
+
 def test_maximum_d_row(fobq, ctx):
     # the largest d_row the library accepts, checked against the oracle in full
     r, d = 65535, 96
