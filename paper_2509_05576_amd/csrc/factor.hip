@@ -37,25 +37,23 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
 }
 
 // Reciprocal and reciprocal square root of a pivot (a normal, positive number): the hardware
-// approximation refined by two Newton steps, accurate to about one ulp.  Shorter dependent
-// chains than an IEEE division / square root, and these sit on the sequential path of the
-// tile factorizations.
+// approximation r0 (good to about 2^-24) with one third-order correction,
+//   1/x       = r0 (1 + e + e^2 + ...),            e = 1 - x r0
+//   1/sqrt(x) = y0 (1 + e/2 + 3 e^2 / 8 + ...),    e = 1 - x y0^2
+// accurate to about one ulp (measured 1.00 / 1.24 ulp, the same as two Newton steps).  Four / five
+// dependent operations: these sit on the sequential path of the tile sweeps.
 __device__ __forceinline__ double pivot_rcp(double x)
 {
-    double r = __builtin_amdgcn_rcp(x);
-    double e = fma(-x, r, 1.0);
-    r = fma(r, e, r);
-    e = fma(-x, r, 1.0);
-    return fma(r, e, r);
+    const double r0 = __builtin_amdgcn_rcp(x);
+    const double e = fma(-x, r0, 1.0);
+    return fma(r0 * e, 1.0 + e, r0);
 }
 
 __device__ __forceinline__ double pivot_rsqrt(double x)
 {
-    double y = __builtin_amdgcn_rsq(x);
-    double e = fma(-(x * y), y, 1.0);
-    y = fma(0.5 * y, e, y);
-    e = fma(-(x * y), y, 1.0);
-    return fma(0.5 * y, e, y);
+    const double y0 = __builtin_amdgcn_rsq(x);
+    const double e = fma(-(x * y0), y0, 1.0);
+    return fma(y0 * e, fma(0.375, e, 0.5), y0);
 }
 
 __device__ __forceinline__ d4 mfma4(double a, double b, d4 c)
