@@ -150,6 +150,23 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
 int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                         const double* H, const fobq_opts* opts, const fobq_out* out);
 
+/*
+ * The same in two halves, for callers that keep several contexts busy at once (layers are
+ * independent of each other, Section 3; most of a layer's work is a chain of short dependent
+ * launches that leaves the GPU nearly idle, so layers on different contexts / streams overlap well):
+ *   fobq_quantize_layer_enqueue  checks the arguments, enqueues all work and returns without
+ *                                waiting; W, H, perm_in and the outputs must stay valid until
+ *                                fobq_finish returns.  Only Hessian accumulation for the next
+ *                                layer may be called on the context before fobq_finish (ESTATE
+ *                                otherwise).
+ *   fobq_finish                  synchronises the context's stream and reports the enqueued
+ *                                layer's device-detected failures (ENOTPD, bad permutation);
+ *                                with nothing enqueued it only synchronises.
+ */
+int fobq_quantize_layer_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
+                                const double* H, const fobq_opts* opts, const fobq_out* out);
+int fobq_finish(fobq_ctx* ctx);
+
 /* ---- stage-level entry points (test and benchmark hooks) ------------------ */
 
 /* Hinv = H^-1 for symmetric positive definite H via H = L L^T, L^-1, L^-T L^-1

@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_hessian_accumulate_conv.argtypes = [vp, vp, i64, i64, i64, i64, i32, i32, i32]
     lib.fobq_hessian_finalize.argtypes = [vp, vp]
     lib.fobq_quantize_layer.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), ctypes.POINTER(FobqOut)]
+    lib.fobq_quantize_layer_enqueue.argtypes = lib.fobq_quantize_layer.argtypes
+    lib.fobq_finish.argtypes = [vp]
     lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
     lib.fobq_profile_enable.argtypes = [vp, i32]
@@ -160,8 +162,10 @@ def fobq_quantize_layer(ctx: int, W: torch.Tensor, H: Optional[torch.Tensor] = N
                         group: int = 0, damp: float = 0.01, damp_abs: float = 0.0,
                         order: int = ORDER_SENSI_DESC, block: int = 0, stop_after: int = -1,
                         perm_in: Optional[torch.Tensor] = None, debug: bool = False,
-                        out: Optional[LayerOutput] = None) -> LayerOutput:
-    """Allocates the outputs (unless `out` is given) and calls fobq_quantize_layer."""
+                        out: Optional[LayerOutput] = None, wait: bool = True) -> LayerOutput:
+    """Allocates the outputs (unless `out` is given) and calls fobq_quantize_layer, or, with
+    wait=False, fobq_quantize_layer_enqueue: the outputs are then valid after fobq_finish(ctx), and
+    W, H, perm_in must be kept alive until then."""
     if W.dim() != 2:
         raise TypeError("W must be 2-D")
     r, d = W.shape
@@ -182,11 +186,16 @@ def fobq_quantize_layer(ctx: int, W: torch.Tensor, H: Optional[torch.Tensor] = N
                  _ptr(out.perm, torch.int32, "perm"), _ptr(out.W_work, torch.float64, "W_work"),
                  _ptr(out.Hinv_work, torch.float64, "Hinv_work"), _ptr(out.loss, torch.float64, "loss"))
     op = _opts(bits, group, damp, damp_abs, order, block, stop_after, perm_in)
-    rc = load_library().fobq_quantize_layer(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")),
-                                            r, d, ctypes.c_void_p(_ptr(H, torch.float64, "H")),
-                                            ctypes.byref(op), ctypes.byref(co))
+    lib = load_library()
+    fn = lib.fobq_quantize_layer if wait else lib.fobq_quantize_layer_enqueue
+    rc = fn(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")), r, d,
+            ctypes.c_void_p(_ptr(H, torch.float64, "H")), ctypes.byref(op), ctypes.byref(co))
     _check(ctx, rc)
     return out
+
+
+def fobq_finish(ctx: int) -> None:
+    _check(ctx, load_library().fobq_finish(ctypes.c_void_p(ctx)))
 
 
 def fobq_spd_inverse(ctx: int, H: torch.Tensor) -> torch.Tensor:
@@ -268,6 +277,9 @@ class Ctx:
 
     def quantize_layer(self, W: torch.Tensor, H: Optional[torch.Tensor] = None, **kw) -> LayerOutput:
         return fobq_quantize_layer(self.handle, W, H, **kw)
+
+    def finish(self) -> None:
+        fobq_finish(self.handle)
 
     def stage_ms(self):
         return {name: fobq_profile_get(self.handle, i) for i, name in enumerate(STAGES)}

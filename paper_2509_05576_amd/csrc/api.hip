@@ -384,6 +384,7 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
 int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d64, double* Hinv)
 {
     if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending) return set_err(ctx, FOBQ_ESTATE, "an enqueued layer is waiting for fobq_finish");
     if (!H || !Hinv) return set_err(ctx, FOBQ_EINVAL, "H or Hinv is NULL");
     if (d64 < 1 || d64 > MAX_DCOL) return set_err(ctx, FOBQ_EINVAL, "d must be in 1..%lld", (long long)MAX_DCOL);
     DeviceGuard g(ctx->device);
@@ -403,6 +404,7 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
                      const fobq_opts* opts, double* S, int32_t* perm)
 {
     if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending) return set_err(ctx, FOBQ_ESTATE, "an enqueued layer is waiting for fobq_finish");
     if (!W || !Hinv) return set_err(ctx, FOBQ_EINVAL, "W or Hinv is NULL");
     int rc = check_shape(ctx, d_row, d_col);
     if (rc) return rc;
@@ -424,10 +426,13 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     return read_flags(ctx);
 }
 
-int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
-                        const fobq_opts* opts, const fobq_out* out)
+// everything of fobq_quantize_layer except the final synchronisation and status read
+static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
+                            const fobq_opts* opts, const fobq_out* out)
 {
     if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending)
+        return set_err(ctx, FOBQ_ESTATE, "a layer enqueued with fobq_quantize_layer_enqueue is waiting for fobq_finish");
     if (!W) return set_err(ctx, FOBQ_EINVAL, "W is NULL");
     if (!out) return set_err(ctx, FOBQ_EINVAL, "out is NULL");
     int rc = check_shape(ctx, d_row, d_col);
@@ -551,6 +556,36 @@ int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_
             FOBQ_TRY(hipMemcpyAsync(out->W_work, Wp, (size_t)R * d * sizeof(double), hipMemcpyDeviceToDevice, s), "copy W_work");
         if (out->Hinv_work) FOBQ_TRY(launch_hinv_work(s, A, d, steps, out->Hinv_work), "copy Hinv_work");
     }
+    return FOBQ_OK;
+}
+
+int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
+                        const fobq_opts* opts, const fobq_out* out)
+{
+    int rc = quantize_enqueue(ctx, W, d_row, d_col, H, opts, out);
+    if (rc) return rc;
+    return read_flags(ctx);
+}
+
+int fobq_quantize_layer_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
+                                const fobq_opts* opts, const fobq_out* out)
+{
+    int rc = quantize_enqueue(ctx, W, d_row, d_col, H, opts, out);
+    if (rc) return rc;
+    ctx->pending = true;
+    return FOBQ_OK;
+}
+
+int fobq_finish(fobq_ctx* ctx)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    if (!ctx->pending) {
+        FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
+        return FOBQ_OK;
+    }
+    ctx->pending = false;
     return read_flags(ctx);
 }
 

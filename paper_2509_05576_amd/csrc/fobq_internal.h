@@ -104,6 +104,7 @@ struct fobq_ctx {
     hipStream_t side = nullptr;
     std::vector<hipEvent_t> sync_ev;
 
+    bool pending = false;   // a layer was enqueued without the final status read (fobq_finish outstanding)
     bool profiling = false;
     fobq::StageTimer timer;
 };

@@ -25,7 +25,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "fobq.h")).read()
     names = sorted(set(re.findall(r"^(?:int|const char\*)\s+(fobq_[a-z_0-9]+)\s*\(", header, flags=re.M)))
     assert {"fobq_create", "fobq_destroy", "fobq_last_error", "fobq_hessian_begin", "fobq_hessian_accumulate",
-            "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer", "fobq_spd_inverse", "fobq_sensitivity",
+            "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
+            "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
             "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"libfobq.so does not export {n}"
@@ -39,6 +40,8 @@ def test_null_context_is_rejected_without_touching_a_gpu():
     assert lib.fobq_hessian_accumulate_conv(null, null, 1, 1, 1, 1, 1, 1, 0) == fobq.EINVAL
     assert lib.fobq_hessian_finalize(null, null) == fobq.EINVAL
     assert lib.fobq_quantize_layer(null, null, 1, 1, null, None, None) == fobq.EINVAL
+    assert lib.fobq_quantize_layer_enqueue(null, null, 1, 1, null, None, None) == fobq.EINVAL
+    assert lib.fobq_finish(null) == fobq.EINVAL
     assert lib.fobq_spd_inverse(null, null, 1, null) == fobq.EINVAL
     assert lib.fobq_profile_enable(null, 1) == fobq.EINVAL
     assert lib.fobq_destroy(null) == fobq.OK

@@ -376,6 +376,41 @@ def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
     assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-6 * expect
 
 
+def test_enqueue_and_finish_on_several_contexts(fobq, ctx):
+    # independent layers in flight on three contexts / streams at once give the results of the blocking call
+    probs = [_problem(40 + 10 * i, 150 + 40 * i, 500, 40 + i, w_std=0.05) for i in range(3)]
+    streams = [torch.cuda.Stream() for _ in probs]
+    ctxs = [fobq.Ctx(0, stream=s.cuda_stream) for s in streams]
+    torch.cuda.synchronize()
+    keep, outs = [], []
+    for c, (W, X) in zip(ctxs, probs):
+        Wd_, Xd = _dev(W), _dev(X)
+        keep.append((Wd_, Xd))
+        torch.cuda.synchronize()                     # inputs were produced on torch's stream
+        c.hessian(Xd)
+        outs.append(c.quantize_layer(Wd_, bits=4, wait=False))
+    with pytest.raises(fobq.FobqError) as e:        # one layer per context until fobq_finish
+        ctxs[0].quantize_layer(keep[0][0], bits=4, wait=False)
+    assert e.value.code == fobq.ESTATE
+    for c in ctxs:
+        c.finish()
+    for (W, X), out in zip(probs, outs):
+        ref = oracle.quantize_layer(W, X=X, bits=4)
+        ref = _oracle_with_gpu_perm(W, ref.H, out.perm.cpu().numpy(), ref, bits=4)
+        _compare_layer(out, ref, W, 4)
+    # a failure detected on the device is reported by fobq_finish
+    _, Xs = _problem(1, 96, 32, 3)
+    ctxs[0].hessian(_dev(Xs))
+    Ws = _dev(np.ones((4, 96), dtype=np.float32))
+    ctxs[0].quantize_layer(Ws, bits=4, damp=0.0, wait=False)
+    with pytest.raises(fobq.FobqError) as e:
+        ctxs[0].finish()
+    assert e.value.code == fobq.ENOTPD
+    ctxs[0].finish()                                 # nothing pending: synchronises, no error
+    for c in ctxs:
+        c.close()
+
+
 def test_non_finite_inputs_do_not_break_the_context(fobq, ctx):
     # NaN / Inf in the inputs are not rejected on the host; they must neither fault nor poison later calls
     W, X = _problem(20, 130, 400, 14, w_std=0.05)
