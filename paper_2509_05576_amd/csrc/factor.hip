@@ -298,13 +298,18 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
 
-    // this lane's B-operand elements of L11^-T for all 16 k-steps, straight from global memory
+    // Panel product L21 = A21 L11^-T: L11^-1 is lower triangular, so the 16 columns of column tile ct
+    // (of 4) only need the k-steps 0 .. 4 ct + 3.  The wavefronts with wn = 0 take the column tiles
+    // 0 and 3, those with wn = 1 the tiles 1 and 2: 20 of 32 (k-step, tile) pairs each.
+    const int ct[2] = {wn, 3 - wn};
+    // this lane's B-operand elements of L11^-T for those k-steps, straight from global memory
     // (32 KB shared by every workgroup of the launch: cache hits)
     double gb[16][2];
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) gb[ks][j] = Dinv[((wn * 16 + ks) * 2 + j) * 64 + lane];
+        for (int j = 0; j < 2; ++j)
+            gb[ks][j] = (ks <= 4 * ct[j] + 3) ? Dinv[(((ct[j] >> 1) * 16 + ks) * 2 + (ct[j] & 1)) * 64 + lane] : 0.0;
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
@@ -350,12 +355,14 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
             aj[i] = diag_tile ? 0.0 : Pj[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            if (ks > 4 * ct[j] + 3) continue;          // wavefront-uniform: the rest of L11^-T's rows is zero
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int i = 0; i < 2; ++i) {
                 li[i][j] = mfma4(ai[i], b[j], li[i][j]);
                 if (!diag_tile) lj[i][j] = mfma4(aj[i], b[j], lj[i][j]);
             }
+        }
     }
     __syncthreads();
 #pragma unroll
@@ -364,7 +371,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                const int m = wm * 32 + i * 16 + 4 * v + fq, n = ct[j] * 16 + fr;
                 Pi[m * DL + n] = li[i][j][v];
                 if (!diag_tile) Pj[m * DL + n] = lj[i][j][v];
                 if (tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[i][j][v];
@@ -641,12 +648,17 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
 
-    // this lane's A-operand elements of G for all 16 k-steps, straight from global memory
+    // Pivot rows U12 = G A12: G is lower triangular, so the 16 rows of row tile rt (of 4) only need
+    // the k-steps 0 .. 4 rt + 3.  The wavefronts with wm = 0 take the row tiles 0 and 3, those with
+    // wm = 1 the tiles 1 and 2: 20 of 32 (k-step, tile) pairs each.
+    const int rt[2] = {wm, 3 - wm};
+    // this lane's A-operand elements of G for those k-steps, straight from global memory
     double ga[16][2];
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) ga[ks][i] = G[((wm * 16 + ks) * 2 + i) * 64 + lane];
+        for (int i = 0; i < 2; ++i)
+            ga[ks][i] = (ks <= 4 * rt[i] + 3) ? G[(((rt[i] >> 1) * 16 + ks) * 2 + (rt[i] & 1)) * 64 + lane] : 0.0;
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
@@ -693,12 +705,14 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
             bj[j] = diag_tile ? 0.0 : Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
+            if (ks > 4 * rt[i] + 3) continue;          // wavefront-uniform: the rest of G's rows is zero
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 ui[i][j] = mfma4(a[i], bi[j], ui[i][j]);
                 if (!diag_tile) uj[i][j] = mfma4(a[i], bj[j], uj[i][j]);
             }
+        }
     }
     __syncthreads();
     // Pi := Un12_i (rows scaled by 1 / pivot), Pj := U12_j
@@ -708,7 +722,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                const int m = rt[i] * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
                 const double uiv = ui[i][j][v];
                 const double ujv = diag_tile ? uiv : uj[i][j][v];
                 Pi[m * DL + n] = uiv * rs[m];
