@@ -107,6 +107,9 @@ struct DeviceGuard {
 };
 
 constexpr int64_t MAX_DCOL = 32768;
+// inverse tiles fused into the factorization launches: 0.31 vs 0.37 ms at d = 512, 1.38 vs 1.68 ms at 2304,
+// even at 4608 (5.38 vs 5.29 ms), slower beyond (26.2 vs 22.0 ms at 8192: three products per tile against one)
+constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
 
 enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
@@ -134,14 +137,21 @@ static int enqueue_inverse(fobq_ctx* ctx, const double* H, int d, double damp, d
     double* Hd = ctx->Hd.as<double>();
     double* L = ctx->U.as<double>();       // U is free until the elimination
     double* Linv = ctx->Linv.as<double>();
+    bool fused = false;
     {
         StageScope sc(ctx, FOBQ_STAGE_CHOLESKY);
         FOBQ_TRY(launch_damp(s, H, d, damp, damp_abs, Hd, ctx->scal.as<double>()), "damp");
-        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H), "cholesky");
+        // the triangular inverse rides along with the factorization (tiles in the shadow of its critical
+        // path) while the launches are small; for large d the extra tiles would slow the launches down by
+        // more than the separate recursive-doubling inverse costs
+        const bool fused_inverse = d <= FUSED_INVERSE_MAX_D;
+        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H, fused_inverse ? ctx->T.as<double>() : nullptr),
+                 "cholesky");
+        fused = fused_inverse;
     }
     {
         StageScope sc(ctx, FOBQ_STAGE_INVERSE);
-        FOBQ_TRY(trtri_lower(ctx, L, d, Linv, ctx->T.as<double>()), "trtri");
+        if (!fused) FOBQ_TRY(trtri_lower(ctx, L, d, Linv, ctx->T.as<double>()), "trtri");
         FOBQ_TRY(lauum_upper(ctx, Linv, d, ctx->Hinv.as<double>()), "lauum");
     }
     return FOBQ_OK;

@@ -272,6 +272,125 @@ __device__ __forceinline__ void tri_decode(int t, int& big, int& small)
     small = t - i * (i + 1) / 2;
 }
 
+// Triangular inverse alongside the factorization (right-looking): with S_ij = sum_{m=j}^{i-1} L_im Linv_mj
+// the blocks of L^-1 below the diagonal are Linv_ij = -Linv_ii S_ij.  In the launch of panel p, once
+// per tile (i, j), i > p >= j:
+//     L_ip    = A_ip Linv_pp^T                      (the same panel product as the trailing tiles)
+//     Linv_pj = -Linv_pp S_pj  (j < p),  Linv_pp    (j = p)     -- S_pj is complete after launch p - 1
+//     S_ij   += L_ip Linv_pj                        (first touched, from zero, when j = p)
+// and the tiles of row i = p + 1 store Linv_pj.  S lives in Sacc (d x d, lower blocks); the last block
+// row of L^-1 is finished by the caller.  These tiles run in the shadow of workgroup 0, like the
+// trailing tiles, so the inverse costs no launches of its own.
+__device__ __forceinline__ void chol_inverse_tile(double* lds, const double* __restrict__ Hd, int d, int o, int it,
+                                                  int jt, const double* __restrict__ Dinv,
+                                                  double* __restrict__ Linv, double* __restrict__ Sacc)
+{
+    double* Pi = lds;
+    double* Pj = lds + NB * DL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int mi0 = NB * it, n0 = NB * jt;
+    const bool at_panel = n0 == o;                     // j = p
+    const int ct[2] = {wn, 3 - wn};                     // column tiles of the panel product (see chol_iter_kernel)
+    const int rt[2] = {wm, 3 - wm};                     // row tiles of Linv_pp S_pj
+    double gb[16][2], ga[16][2];
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            gb[ks][j] = (ks <= 4 * ct[j] + 3) ? Dinv[(((ct[j] >> 1) * 16 + ks) * 2 + (ct[j] & 1)) * 64 + lane] : 0.0;
+            ga[ks][j] = (!at_panel && ks <= 4 * rt[j] + 3) ? Dinv[(((rt[j] >> 1) * 16 + ks) * 2 + (rt[j] & 1)) * 64 + lane] : 0.0;
+        }
+    double pa[16], pb[16];
+    const double* __restrict__ src = at_panel ? Linv + (int64_t)o * d + o : Sacc + (int64_t)o * d + n0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        pa[u] = Hd[(int64_t)min(mi0 + y, d - 1) * d + o + x];          // A_ip (rows past d: see chol_iter_kernel)
+        pb[u] = src[(int64_t)y * d + x];                               // S_pj, or Linv_pp itself
+    }
+    d4 c[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
+                c[i][j][v] = at_panel ? 0.0 : Sacc[(int64_t)min(gm, d - 1) * d + gn];
+            }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Pi[y * DL + x] = pa[u];
+        Pj[y * DL + x] = pb[u];
+    }
+    __syncthreads();
+    d4 li[2][2], xp[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; xp[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        double ai[2], bs[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) ai[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bs[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (ks > 4 * ct[j] + 3) continue;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) li[i][j] = mfma4(ai[i], gb[ks][j], li[i][j]);
+        }
+        if (!at_panel) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if (ks > 4 * rt[i] + 3) continue;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) xp[i][j] = mfma4(ga[ks][i], bs[j], xp[i][j]);
+            }
+        }
+    }
+    __syncthreads();
+    // Pi := L_ip (row m, panel column k), Pj := Linv_pj (panel row k, column n)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                Pi[(wm * 32 + i * 16 + 4 * v + fq) * DL + ct[j] * 16 + fr] = li[i][j][v];
+                if (!at_panel) {
+                    const int m = rt[i] * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+                    Pj[m * DL + n] = -xp[i][j][v];
+                    if (mi0 == o + NB) Linv[(int64_t)(o + m) * d + n0 + n] = -xp[i][j][v];
+                }
+            }
+    __syncthreads();
+    for (int ks = 0; ks < 16; ++ks) {
+        double a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
+                if (gm < d) Sacc[(int64_t)gm * d + gn] = c[i][j][v];
+            }
+}
+
 // One whole iteration of the blocked Cholesky factorization in a single launch.  The panel is
 // the 64 columns o .. o+63, whose diagonal block has already been factored (Dinv = L11^-1).
 // Workgroup (ti, tj), ti >= tj, owns the 64 x 64 tile (ti, tj) of the trailing matrix:
@@ -282,12 +401,20 @@ __device__ __forceinline__ void tri_decode(int t, int& big, int& small)
 //   3. workgroup 0 owns tile (0, 0), the next diagonal block: it does not write it back but
 //      factors it right away (chol_block) and stores L11, L11^-1 and Dinv_next for the next
 //      launch, overlapped with the other tiles of this launch.
+// Workgroups past the ntrail trailing tiles (when Sacc != null) are tiles of the triangular inverse
+// (chol_inverse_tile): (row block, column block) = (o / 64 + 1 + e / (o / 64 + 1), e % (o / 64 + 1)).
 __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
                                                         const double* __restrict__ Dinv, double* __restrict__ L,
                                                         double* __restrict__ Linv, double* __restrict__ Dinv_next,
-                                                        int* __restrict__ flag)
+                                                        int* __restrict__ flag, int ntrail,
+                                                        double* __restrict__ Sacc)
 {
     __shared__ double lds[2 * NB * DL + NB];  // two tiles: 2 workgroups per compute unit
+    if ((int)blockIdx.x >= ntrail) {
+        const int pcols = o / NB + 1, e = (int)blockIdx.x - ntrail;
+        chol_inverse_tile(lds, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
+        return;
+    }
     double* Pi = lds;
     double* Pj = lds + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -423,7 +550,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
 
 // H_d = L L^T.  One stand-alone launch for the first diagonal block, then one fused launch
 // per 64-column panel.
-hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag)
+hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc)
 {
     hipStream_t s = c->stream;
     double* Dinv[2] = {c->Dblk.as<double>(), c->Dblk.as<double>() + NB * NB};
@@ -432,14 +559,26 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
     int it = 0;
     for (int o = 0; o + NB < d; o += NB, ++it) {
         const int T = (d - o - NB + NB - 1) / NB;
-        hipLaunchKernelGGL(chol_iter_kernel, dim3(T * (T + 1) / 2), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                           Dinv[(it + 1) & 1], flag);
+        const int ntrail = T * (T + 1) / 2;
+        const int ninv = Sacc ? T * (it + 1) : 0;      // tiles of the triangular inverse (row below, column up to the panel)
+        hipLaunchKernelGGL(chol_iter_kernel, dim3(ntrail + ninv), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                           Dinv[(it + 1) & 1], flag, ntrail, Sacc);
+    }
+    if (Sacc && it > 0) {
+        // last block row of L^-1: Linv[last][0 : last] = -Linv[last][last] S[last][0 : last]
+        const int o = it * NB;                          // first row of the last block
+        GemmP q;
+        q.M = d - o; q.N = o; q.K = d - o;
+        q.A = Linv + (int64_t)o * d + o; q.lda = d;
+        q.B = Sacc + (int64_t)o * d; q.ldb = d;
+        q.C = Linv + (int64_t)o * d; q.ldc = d;
+        q.alpha = -1.0;
+        hipError_t e = gemm64(s, q, false, false);
+        if (e != hipSuccess) return e;
     }
     return hipGetLastError();
 }
 
-// Linv holds the inverses of the 64 x 64 diagonal blocks of L and zeros elsewhere.
-// Level s: for every pair of adjacent s-blocks [[A, 0], [C, B]] with A^-1, B^-1 known,
 // the missing block of the inverse is -B^-1 C A^-1.
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T)
 {

@@ -132,7 +132,9 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
 
 // factor.hip
-hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag);  // Hd = L L^T; Linv gets the diagonal-block inverses
+// Sacc != null (d x d scratch): L^-1 is completed alongside the factorization (Linv then holds all of it);
+// Sacc == null: only the diagonal blocks of L^-1 are written (trtri_lower finishes it)
+hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc);  // Hd = L L^T; Linv gets the diagonal-block inverses
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
 hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
 // `rows_ready` (may be null): rows_ready[k] is recorded on the context's stream once the pivot rows of
