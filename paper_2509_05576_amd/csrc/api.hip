@@ -532,10 +532,13 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
         }
         {
             StageScope sc(ctx, FOBQ_STAGE_COLUMNS, side);
-            int k = 0;
+            int k = 0, waited = -1;
             for (int o = 0; o < steps; o += block, ++k) {
                 const int nb = (block < steps - o) ? block : steps - o;
-                FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[k], 0), "stream wait");
+                if (k > waited) {
+                    for (waited = k; !rows_announced(waited, nblocks);) ++waited;
+                    FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[waited], 0), "stream wait");
+                }
                 FOBQ_TRY(launch_chain(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
                                       codesT, DT, Rp, lossrow), "column block");
                 const int r = d - o - nb;

@@ -921,7 +921,8 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 {
     hipStream_t s = c->stream;
     auto ready = [&](int k) {
-        if (rows_ready && k < (int)rows_ready->size()) (void)hipEventRecord((*rows_ready)[k], s);
+        if (rows_ready && k < (int)rows_ready->size() && rows_announced(k, (int)rows_ready->size()))
+            (void)hipEventRecord((*rows_ready)[k], s);
     };
     double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};

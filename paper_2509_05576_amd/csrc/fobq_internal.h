@@ -137,8 +137,14 @@ hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, doubl
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc);  // Hd = L L^T; Linv gets the diagonal-block inverses
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
 hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
+// Whether eliminate_blocked records rows_ready[k] after block k of n.  A record between two dependent
+// launches costs about 4 us on the elimination's critical path, so only every fourth block is
+// announced while the column loop has slack, and every block near the end, where the column loop's
+// lag behind the elimination is what is left on the critical path.  A consumer of block k waits for
+// the first announced block >= k (the last block is always announced).
+inline bool rows_announced(int k, int n) { return (k & 3) == 3 || k >= n - 4; }
 // `rows_ready` (may be null): rows_ready[k] is recorded on the context's stream once the pivot rows of
-// block k (rows k*block .. of U and Un) are complete
+// block k (rows k*block .. of U and Un) are complete, for the blocks k that rows_announced names
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag,
                              const std::vector<hipEvent_t>* rows_ready);
 
