@@ -107,8 +107,10 @@ struct DeviceGuard {
 };
 
 constexpr int64_t MAX_DCOL = 32768;
-// inverse tiles fused into the factorization launches: 0.31 vs 0.37 ms at d = 512, 1.38 vs 1.68 ms at 2304,
-// even at 4608 (5.38 vs 5.29 ms), slower beyond (26.2 vs 22.0 ms at 8192: three products per tile against one)
+// L^-1 and L^-T L^-1 fused into the factorization launches against the separate recursive-doubling
+// inverse and product, damped inverse of a d x d matrix: 0.51 vs 0.69 ms at d = 1024, 1.29 vs 1.69 ms at
+// 2304, 3.81 vs 4.06 ms at 4096, even at 4608 (5.23 vs 5.21 ms), slower beyond (27.9 vs 22.2 ms at 8192:
+// three products per inverse tile against one, and the launches are full without them)
 constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
 
@@ -141,18 +143,20 @@ static int enqueue_inverse(fobq_ctx* ctx, const double* H, int d, double damp, d
     {
         StageScope sc(ctx, FOBQ_STAGE_CHOLESKY);
         FOBQ_TRY(launch_damp(s, H, d, damp, damp_abs, Hd, ctx->scal.as<double>()), "damp");
-        // the triangular inverse rides along with the factorization (tiles in the shadow of its critical
-        // path) while the launches are small; for large d the extra tiles would slow the launches down by
+        // the triangular inverse and L^-T L^-1 ride along with the factorization (tiles in the shadow of
+        // its critical path) while the launches are small; for large d the extra tiles would slow the launches down by
         // more than the separate recursive-doubling inverse costs
         const bool fused_inverse = d <= FUSED_INVERSE_MAX_D;
-        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H, fused_inverse ? ctx->T.as<double>() : nullptr),
-                 "cholesky");
+        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H, fused_inverse ? ctx->T.as<double>() : nullptr,
+                                ctx->Hinv.as<double>()), "cholesky");
         fused = fused_inverse;
     }
     {
         StageScope sc(ctx, FOBQ_STAGE_INVERSE);
-        if (!fused) FOBQ_TRY(trtri_lower(ctx, L, d, Linv, ctx->T.as<double>()), "trtri");
-        FOBQ_TRY(lauum_upper(ctx, Linv, d, ctx->Hinv.as<double>()), "lauum");
+        if (!fused) {
+            FOBQ_TRY(trtri_lower(ctx, L, d, Linv, ctx->T.as<double>()), "trtri");
+            FOBQ_TRY(lauum_upper(ctx, Linv, d, ctx->Hinv.as<double>()), "lauum");
+        }
     }
     return FOBQ_OK;
 }

@@ -391,6 +391,64 @@ __device__ __forceinline__ void chol_inverse_tile(double* lds, const double* __r
             }
 }
 
+// Hinv = Linv^T Linv alongside the factorization: block row k of L^-1 is complete one launch after its
+// panel, and adds Linv_km^T Linv_kn to every tile (m, n), m <= n <= k, of the upper triangle of Hinv
+// (first touched, from zero, when n = k).  One tile per workgroup, again in the shadow of workgroup 0.
+__device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int mt, int nt,
+                                                const double* __restrict__ Linv, double* __restrict__ Hinv)
+{
+    double* Pi = lds;
+    double* Pj = lds + NB * DL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const bool first = nt == kt;
+    const double* __restrict__ rowk = Linv + (int64_t)NB * kt * d;
+    double pa[16], pb[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        pa[u] = rowk[(int64_t)y * d + NB * mt + x];
+        pb[u] = rowk[(int64_t)y * d + NB * nt + x];
+    }
+    d4 c[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = NB * mt + wm * 32 + i * 16 + 4 * v + fq, gn = NB * nt + wn * 32 + j * 16 + fr;
+                c[i][j][v] = first ? 0.0 : Hinv[(int64_t)gm * d + gn];
+            }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int y = wave + 4 * u, x = lane;
+        Pi[y * DL + x] = pa[u];
+        Pj[y * DL + x] = pb[u];
+    }
+    __syncthreads();
+    for (int ks = 0; ks < 16; ++ks) {
+        double a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = Pi[(4 * ks + fq) * DL + wm * 32 + i * 16 + fr];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = NB * mt + wm * 32 + i * 16 + 4 * v + fq, gn = NB * nt + wn * 32 + j * 16 + fr;
+                Hinv[(int64_t)gm * d + gn] = c[i][j][v];
+            }
+}
+
 // One whole iteration of the blocked Cholesky factorization in a single launch.  The panel is
 // the 64 columns o .. o+63, whose diagonal block has already been factored (Dinv = L11^-1).
 // Workgroup (ti, tj), ti >= tj, owns the 64 x 64 tile (ti, tj) of the trailing matrix:
@@ -401,15 +459,22 @@ __device__ __forceinline__ void chol_inverse_tile(double* lds, const double* __r
 //   3. workgroup 0 owns tile (0, 0), the next diagonal block: it does not write it back but
 //      factors it right away (chol_block) and stores L11, L11^-1 and Dinv_next for the next
 //      launch, overlapped with the other tiles of this launch.
-// Workgroups past the ntrail trailing tiles (when Sacc != null) are tiles of the triangular inverse
-// (chol_inverse_tile): (row block, column block) = (o / 64 + 1 + e / (o / 64 + 1), e % (o / 64 + 1)).
+// Workgroups past the ntrail trailing tiles (when Sacc != null) are first the ninv tiles of the triangular
+// inverse (chol_inverse_tile): (row block, column block) = (o / 64 + 1 + e / (o / 64 + 1), e % (o / 64 + 1)),
+// then the tiles of Hinv that block row o / 64 - 1 of L^-1 contributes to (chol_lauum_tile).
 __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
                                                         const double* __restrict__ Dinv, double* __restrict__ L,
                                                         double* __restrict__ Linv, double* __restrict__ Dinv_next,
-                                                        int* __restrict__ flag, int ntrail,
-                                                        double* __restrict__ Sacc)
+                                                        int* __restrict__ flag, int ntrail, int ninv,
+                                                        double* __restrict__ Sacc, double* __restrict__ Hinv)
 {
     __shared__ double lds[2 * NB * DL + NB];  // two tiles: 2 workgroups per compute unit
+    if ((int)blockIdx.x >= ntrail + ninv) {
+        int nt, mt;
+        tri_decode((int)blockIdx.x - ntrail - ninv, nt, mt);          // mt <= nt <= o / 64 - 1
+        chol_lauum_tile(lds, d, o / NB - 1, mt, nt, Linv, Hinv);
+        return;
+    }
     if ((int)blockIdx.x >= ntrail) {
         const int pcols = o / NB + 1, e = (int)blockIdx.x - ntrail;
         chol_inverse_tile(lds, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
@@ -550,7 +615,8 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
 
 // H_d = L L^T.  One stand-alone launch for the first diagonal block, then one fused launch
 // per 64-column panel.
-hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc)
+hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc,
+                          double* Hinv)
 {
     hipStream_t s = c->stream;
     double* Dinv[2] = {c->Dblk.as<double>(), c->Dblk.as<double>() + NB * NB};
@@ -561,8 +627,9 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         const int T = (d - o - NB + NB - 1) / NB;
         const int ntrail = T * (T + 1) / 2;
         const int ninv = Sacc ? T * (it + 1) : 0;      // tiles of the triangular inverse (row below, column up to the panel)
-        hipLaunchKernelGGL(chol_iter_kernel, dim3(ntrail + ninv), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                           Dinv[(it + 1) & 1], flag, ntrail, Sacc);
+        const int nlau = Sacc ? it * (it + 1) / 2 : 0;  // tiles of Hinv that block row it - 1 of L^-1 adds to
+        hipLaunchKernelGGL(chol_iter_kernel, dim3(ntrail + ninv + nlau), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L,
+                           Linv, Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
     }
     if (Sacc && it > 0) {
         // last block row of L^-1: Linv[last][0 : last] = -Linv[last][last] S[last][0 : last]
@@ -574,6 +641,20 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         q.C = Linv + (int64_t)o * d; q.ldc = d;
         q.alpha = -1.0;
         hipError_t e = gemm64(s, q, false, false);
+        if (e != hipSuccess) return e;
+    }
+    if (Sacc) {
+        // what the launches above have not added to Hinv: the last two block rows of L^-1 (all of it if
+        // there are at most two); the tiles right of those rows' first column are touched for the first time
+        const int k0 = max(0, it - 1) * NB;
+        GemmP q;
+        q.M = d; q.N = d; q.K = d;
+        q.A = Linv; q.lda = d;
+        q.B = Linv; q.ldb = d;
+        q.C = Hinv; q.ldc = d;
+        q.cmode = CMODE_UPPER; q.kmode = KMODE_GE_MAX_MN; q.kmin = k0;
+        q.beta = 1.0; q.beta_ncols = k0;
+        hipError_t e = gemm64(s, q, true, false);
         if (e != hipSuccess) return e;
     }
     return hipGetLastError();

@@ -47,6 +47,8 @@ struct GemmP {
     const double* rowscale = nullptr;
     double alpha = 1.0, beta = 0.0;
     int cmode = CMODE_ALL, kmode = KMODE_FULL;
+    int kmin = 0;                      // k starts no lower than this (a multiple of 64)
+    int beta_ncols = -1;               // >= 0: beta applies only to the tiles left of this column (0 elsewhere)
     // batching (blockIdx.z): element strides and per-batch clamps
     int batches = 1;
     int64_t sA = 0, sB = 0, sC = 0;
@@ -132,9 +134,11 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
 
 // factor.hip
-// Sacc != null (d x d scratch): L^-1 is completed alongside the factorization (Linv then holds all of it);
-// Sacc == null: only the diagonal blocks of L^-1 are written (trtri_lower finishes it)
-hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc);  // Hd = L L^T; Linv gets the diagonal-block inverses
+// Sacc != null (d x d scratch): L^-1 and the upper tiles of Hinv = L^-T L^-1 are completed alongside the
+// factorization; Sacc == null: only the diagonal blocks of L^-1 are written and Hinv is not touched
+// (trtri_lower and lauum_upper finish the job)
+hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc,
+                          double* Hinv);  // Hd = L L^T; Linv gets the diagonal-block inverses
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
 hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
 // Whether eliminate_blocked records rows_ready[k] after block k of n.  A record between two dependent

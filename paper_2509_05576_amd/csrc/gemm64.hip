@@ -36,6 +36,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmP p)
     if (p.kmode == KMODE_GE_MAX_MN) k_lo = max(m0, n0);      // multiples of 64
     else if (p.kmode == KMODE_GE_N) k_lo = n0;
     else if (p.kmode == KMODE_LT_M) k_hi = min(K, m0 + TM);
+    k_lo = max(k_lo, p.kmin);
 
     const double* __restrict__ A = p.A + (int64_t)b * p.sA;
     const double* __restrict__ B = p.B + (int64_t)b * p.sB;
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmP p)
 
     if (k_lo < k_hi) gload(k_lo);
     d4 cin[2][2];
-    const bool use_c = p.beta != 0.0;
+    const bool use_c = p.beta != 0.0 && (p.beta_ncols < 0 || n0 < p.beta_ncols);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
