@@ -272,6 +272,77 @@ __device__ __forceinline__ void tri_decode(int t, int& big, int& small)
     small = t - i * (i + 1) / 2;
 }
 
+// A 64 x 64 lower-triangular block T in the fragment layout (frag_source) as an MFMA operand: operand tile
+// t (of 4; 16 rows of T as A-operand, or 16 columns of T^T as B-operand) only needs the k-steps 0 .. 4 t + 3.
+// A wavefront takes the two operand tiles {W, 3 - W}, W = 0 or 1: 20 of 32 (k-step, tile) pairs either way.
+// W is a template parameter so that the k-loops below are straight-line code: with a run-time W
+// every skipped pair is a branch, and the branches keep the LDS reads of one k-step from being
+// issued under the MFMAs of the one before.
+template <int W>
+__device__ __forceinline__ void tri_frag_load(const double* __restrict__ F, int lane, double (&g)[16][2])
+{
+    constexpr int t[2] = {W, 3 - W};
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            g[ks][j] = (ks <= 4 * t[j] + 3) ? F[(((t[j] >> 1) * 16 + ks) * 2 + (t[j] & 1)) * 64 + lane] : 0.0;
+}
+
+// li (+ lj if TWO) += P T^T for the wavefront's 32 rows (from row0) and its two column tiles {W, 3 - W}:
+// A-operand rows out of LDS (Pi / Pj, row-major [row][k]), B-operand = g.
+template <int W, bool TWO>
+__device__ __forceinline__ void tri_right_product(const double* Pi, const double* Pj, const double (&g)[16][2],
+                                                  int row0, int fr, int fq, d4 (&li)[2][2], d4 (&lj)[2][2])
+{
+    constexpr int t[2] = {W, 3 - W};
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        double ai[2], aj[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            ai[i] = Pi[(row0 + i * 16 + fr) * DL + 4 * ks + fq];
+            if (TWO) aj[i] = Pj[(row0 + i * 16 + fr) * DL + 4 * ks + fq];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (ks > 4 * t[j] + 3) continue;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                li[i][j] = mfma4(ai[i], g[ks][j], li[i][j]);
+                if (TWO) lj[i][j] = mfma4(aj[i], g[ks][j], lj[i][j]);
+            }
+        }
+    }
+}
+
+// ui (+ uj if TWO) += T P for the wavefront's two row tiles {W, 3 - W} and its 32 columns (from col0):
+// A-operand = g, B-operand columns out of LDS (Pi / Pj, row-major [k][column]).
+template <int W, bool TWO>
+__device__ __forceinline__ void tri_left_product(const double* Pi, const double* Pj, const double (&g)[16][2],
+                                                 int col0, int fr, int fq, d4 (&ui)[2][2], d4 (&uj)[2][2])
+{
+    constexpr int t[2] = {W, 3 - W};
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        double bi[2], bj[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bi[j] = Pi[(4 * ks + fq) * DL + col0 + j * 16 + fr];
+            if (TWO) bj[j] = Pj[(4 * ks + fq) * DL + col0 + j * 16 + fr];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (ks > 4 * t[i] + 3) continue;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                ui[i][j] = mfma4(g[ks][i], bi[j], ui[i][j]);
+                if (TWO) uj[i][j] = mfma4(g[ks][i], bj[j], uj[i][j]);
+            }
+        }
+    }
+}
+
 // Triangular inverse alongside the factorization (right-looking): with S_ij = sum_{m=j}^{i-1} L_im Linv_mj
 // the blocks of L^-1 below the diagonal are Linv_ij = -Linv_ii S_ij.  In the launch of panel p, once
 // per tile (i, j), i > p >= j:
@@ -483,7 +554,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     double* Pi = lds;
     double* Pj = lds + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int wm = wave >> 1, wn = __builtin_amdgcn_readfirstlane(wave & 1), fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
     tri_decode(blockIdx.x, ti, tj);
@@ -497,21 +568,22 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     // this lane's B-operand elements of L11^-T for those k-steps, straight from global memory
     // (32 KB shared by every workgroup of the launch: cache hits)
     double gb[16][2];
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            gb[ks][j] = (ks <= 4 * ct[j] + 3) ? Dinv[(((ct[j] >> 1) * 16 + ks) * 2 + (ct[j] & 1)) * 64 + lane] : 0.0;
+    if (wn == 0) tri_frag_load<0>(Dinv, lane, gb); else tri_frag_load<1>(Dinv, lane, gb);
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int y = wave + 4 * u, x = lane;
-        const int gi = mi0 + y, gj = mj0 + y;
         // Rows past d are read from row d - 1 (clamped address, no branch per load): they only
         // reach outputs past d, which are never stored or are replaced by the identity padding.
-        pa[u] = Hd[(int64_t)min(gi, d - 1) * d + o + x];
-        pb[u] = Hd[(int64_t)min(diag_tile ? gi : gj, d - 1) * d + o + x];
+        pa[u] = Hd[(int64_t)min(mi0 + y, d - 1) * d + o + x];
+    }
+    if (!diag_tile) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int y = wave + 4 * u, x = lane;
+            pb[u] = Hd[(int64_t)min(mj0 + y, d - 1) * d + o + x];
+        }
     }
     d4 c[2][2];
 #pragma unroll
@@ -536,25 +608,12 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; lj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-        double b[2], ai[2], aj[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = gb[ks][j];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            ai[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
-            aj[i] = diag_tile ? 0.0 : Pj[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (ks > 4 * ct[j] + 3) continue;          // wavefront-uniform: the rest of L11^-T's rows is zero
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                li[i][j] = mfma4(ai[i], b[j], li[i][j]);
-                if (!diag_tile) lj[i][j] = mfma4(aj[i], b[j], lj[i][j]);
-            }
-        }
+    if (wn == 0) {
+        if (diag_tile) tri_right_product<0, false>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
+        else tri_right_product<0, true>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
+    } else {
+        if (diag_tile) tri_right_product<1, false>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
+        else tri_right_product<1, true>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
     }
     __syncthreads();
 #pragma unroll
@@ -570,6 +629,7 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
             }
     __syncthreads();
     const double* Qj = diag_tile ? Pi : Pj;
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         double a[2], b[2];
 #pragma unroll
@@ -861,7 +921,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     double* Pj = lds + NB * DL;
     double* rs = lds + 2 * NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int wm = __builtin_amdgcn_readfirstlane(wave >> 1), wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
     tri_decode(blockIdx.x, tj, ti);          // ti <= tj
@@ -874,11 +934,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     const int rt[2] = {wm, 3 - wm};
     // this lane's A-operand elements of G for those k-steps, straight from global memory
     double ga[16][2];
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            ga[ks][i] = (ks <= 4 * rt[i] + 3) ? G[(((rt[i] >> 1) * 16 + ks) * 2 + (rt[i] & 1)) * 64 + lane] : 0.0;
+    if (wm == 0) tri_frag_load<0>(G, lane, ga); else tri_frag_load<1>(G, lane, ga);
     // one round of loads (all in flight together), then the stores to LDS
     double pa[16], pb[16];
 #pragma unroll
@@ -887,7 +943,13 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
         // Columns past d are read from column d - 1 (clamped address, no branch per load): they
         // only reach outputs past d, which are never stored or are replaced by the identity padding.
         pa[u] = A[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
-        pb[u] = A[(int64_t)(o + y) * d + min((diag_tile ? ci0 : cj0) + x, d - 1)];
+    }
+    if (!diag_tile) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int y = wave + 4 * u, x = lane;
+            pb[u] = A[(int64_t)(o + y) * d + min(cj0 + x, d - 1)];
+        }
     }
     const double rsv = (tid < NB) ? rinv[tid] : 0.0;
     d4 c[2][2];
@@ -914,25 +976,12 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) { ui[i][j] = d4{0.0, 0.0, 0.0, 0.0}; uj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-        double a[2], bi[2], bj[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = ga[ks][i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            bi[j] = Pi[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-            bj[j] = diag_tile ? 0.0 : Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            if (ks > 4 * rt[i] + 3) continue;          // wavefront-uniform: the rest of G's rows is zero
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                ui[i][j] = mfma4(a[i], bi[j], ui[i][j]);
-                if (!diag_tile) uj[i][j] = mfma4(a[i], bj[j], uj[i][j]);
-            }
-        }
+    if (wm == 0) {
+        if (diag_tile) tri_left_product<0, false>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
+        else tri_left_product<0, true>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
+    } else {
+        if (diag_tile) tri_left_product<1, false>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
+        else tri_left_product<1, true>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
     }
     __syncthreads();
     // Pi := Un12_i (rows scaled by 1 / pivot), Pj := U12_j
@@ -953,6 +1002,7 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
                 }
             }
     __syncthreads();
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         double a[2], b[2];
 #pragma unroll
