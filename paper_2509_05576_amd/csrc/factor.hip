@@ -27,6 +27,9 @@ constexpr int NB = 64;
 // 64 x 64 triangular inverse from the tile inverses -- is 16 x 16 x 16 products on
 // the matrix cores (4 MFMAs each), one tile per wavefront.
 typedef double d4 __attribute__((ext_vector_type(4)));
+constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
+// launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
+constexpr int DENSE_LAUNCH_TILES = 1024;
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
@@ -90,7 +93,7 @@ __device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, in
 //   (after each of b = 0..2: trail(b) on all wavefronts)
 //   then          tinv(3)       X_21, X_20
 //   then          X_30          X_31               X_32
-// Called by all 256 threads of the workgroup; ends with a barrier.
+// Called by all NT threads of the workgroup; ends with a barrier.
 template <class SW, class TI, class TR, class TF>
 __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR trail, TF tf)
 {
@@ -123,7 +126,7 @@ __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR
 //        Xm = L^-1 (lower);  rq (64 doubles of LDS) is scratch: 1 / L[k][k]
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1 so that
 //         the arithmetic stays finite; the caller reports ENOTPD).
-// Called by all 256 threads of the workgroup; ends with a barrier.
+// Called by all NT threads of the workgroup; ends with a barrier.
 __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, int* __restrict__ flag)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -193,7 +196,7 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
         int t = 0;
         for (int i = b + 1; i < 4; ++i)
             for (int j = b + 1; j <= i; ++j, ++t) {
-                if ((t & 3) != wave) continue;
+                if ((t & (NT / 64 - 1)) != wave) continue;
                 d4 acc;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
@@ -223,7 +226,7 @@ __device__ __forceinline__ void chol_block_store(const double* Am, const double*
                                                  double* __restrict__ L, double* __restrict__ Linv,
                                                  double* __restrict__ Dinv)
 {
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+    for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
         const double xv = (in && j <= i) ? Xm[i * DL + j] : 0.0;
@@ -243,14 +246,14 @@ __device__ __forceinline__ void chol_block_store(const double* Am, const double*
 //   out: L[o:o+nb, o:o+nb] = L11 (lower, upper part zeroed)
 //        Linv[o:o+nb, o:o+nb] = L11^-1 (lower, upper part zeroed)
 //        Dinv (4096 doubles) = L11^-1 zero padded, in the fragment layout
-__global__ __launch_bounds__(256) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
+__global__ __launch_bounds__(NT) void chol_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ L, double* __restrict__ Linv,
                                                         double* __restrict__ Dinv, int* __restrict__ flag)
 {
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
     __shared__ double rq[NB];
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+    for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
         if (i < nb && j < nb) v = (j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
@@ -289,59 +292,55 @@ __device__ __forceinline__ void tri_frag_load(const double* __restrict__ F, int 
             g[ks][j] = (ks <= 4 * t[j] + 3) ? F[(((t[j] >> 1) * 16 + ks) * 2 + (t[j] & 1)) * 64 + lane] : 0.0;
 }
 
-// li (+ lj if TWO) += P T^T for the wavefront's 32 rows (from row0) and its two column tiles {W, 3 - W}:
+// li (+ lj if TWO) += P T^T for the wavefront's 16 rows (from row0) and its two column tiles {W, 3 - W}:
 // A-operand rows out of LDS (Pi / Pj, row-major [row][k]), B-operand = g.
 template <int W, bool TWO>
 __device__ __forceinline__ void tri_right_product(const double* Pi, const double* Pj, const double (&g)[16][2],
-                                                  int row0, int fr, int fq, d4 (&li)[2][2], d4 (&lj)[2][2])
+                                                  int row0, int fr, int fq, d4 (&li)[2], d4 (&lj)[2])
 {
     constexpr int t[2] = {W, 3 - W};
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double ai[2], aj[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            ai[i] = Pi[(row0 + i * 16 + fr) * DL + 4 * ks + fq];
-            if (TWO) aj[i] = Pj[(row0 + i * 16 + fr) * DL + 4 * ks + fq];
-        }
+        const double ai = Pi[(row0 + fr) * DL + 4 * ks + fq];
+        double aj = 0.0;
+        if (TWO) aj = Pj[(row0 + fr) * DL + 4 * ks + fq];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if (ks > 4 * t[j] + 3) continue;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                li[i][j] = mfma4(ai[i], g[ks][j], li[i][j]);
-                if (TWO) lj[i][j] = mfma4(aj[i], g[ks][j], lj[i][j]);
-            }
+            li[j] = mfma4(ai, g[ks][j], li[j]);
+            if (TWO) lj[j] = mfma4(aj, g[ks][j], lj[j]);
         }
     }
 }
 
-// ui (+ uj if TWO) += T P for the wavefront's two row tiles {W, 3 - W} and its 32 columns (from col0):
+// ui (+ uj if TWO) += T P for the wavefront's two row tiles {W, 3 - W} and its 16 columns (from col0):
 // A-operand = g, B-operand columns out of LDS (Pi / Pj, row-major [k][column]).
 template <int W, bool TWO>
 __device__ __forceinline__ void tri_left_product(const double* Pi, const double* Pj, const double (&g)[16][2],
-                                                 int col0, int fr, int fq, d4 (&ui)[2][2], d4 (&uj)[2][2])
+                                                 int col0, int fr, int fq, d4 (&ui)[2], d4 (&uj)[2])
 {
     constexpr int t[2] = {W, 3 - W};
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double bi[2], bj[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            bi[j] = Pi[(4 * ks + fq) * DL + col0 + j * 16 + fr];
-            if (TWO) bj[j] = Pj[(4 * ks + fq) * DL + col0 + j * 16 + fr];
-        }
+        const double bi = Pi[(4 * ks + fq) * DL + col0 + fr];
+        double bj = 0.0;
+        if (TWO) bj = Pj[(4 * ks + fq) * DL + col0 + fr];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             if (ks > 4 * t[i] + 3) continue;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                ui[i][j] = mfma4(g[ks][i], bi[j], ui[i][j]);
-                if (TWO) uj[i][j] = mfma4(g[ks][i], bj[j], uj[i][j]);
-            }
+            ui[i] = mfma4(g[ks][i], bi, ui[i]);
+            if (TWO) uj[i] = mfma4(g[ks][i], bj, uj[i]);
         }
     }
 }
+
+// Work split of the fused panel kernels below: NT = 512 threads = 8 wavefronts per 64 x 64 tile, two per
+// SIMD.  One wavefront alone issues a v_mfma_f64_16x16x4_f64 only every ~140 cycles (measured: 59 ns per
+// instruction per wavefront whatever the number of independent accumulators); two wavefronts on a SIMD
+// interleave to the pipe's own rate of one per ~64 cycles.  The products of workgroup 0 are on the critical
+// path of the whole factorization, so they are spread over twice the wavefronts a 64 x 64 tile needs.
+// Wavefront w: wr = w / 2 is its 16-row slice of the tile, w2 = w % 2 its 32-column half (and the parity
+// W of its operand tiles in the triangular products).
 
 // Triangular inverse alongside the factorization (right-looking): with S_ij = sum_{m=j}^{i-1} L_im Linv_mj
 // the blocks of L^-1 below the diagonal are Linv_ij = -Linv_ii S_ij.  In the launch of panel p, once
@@ -358,108 +357,75 @@ __device__ __forceinline__ void chol_inverse_tile(double* lds, const double* __r
 {
     double* Pi = lds;
     double* Pj = lds + NB * DL;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int mi0 = NB * it, n0 = NB * jt;
     const bool at_panel = n0 == o;                     // j = p
-    const int ct[2] = {wn, 3 - wn};                     // column tiles of the panel product (see chol_iter_kernel)
-    const int rt[2] = {wm, 3 - wm};                     // row tiles of Linv_pp S_pj
-    double gb[16][2], ga[16][2];
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            gb[ks][j] = (ks <= 4 * ct[j] + 3) ? Dinv[(((ct[j] >> 1) * 16 + ks) * 2 + (ct[j] & 1)) * 64 + lane] : 0.0;
-            ga[ks][j] = (!at_panel && ks <= 4 * rt[j] + 3) ? Dinv[(((rt[j] >> 1) * 16 + ks) * 2 + (rt[j] & 1)) * 64 + lane] : 0.0;
-        }
-    double pa[16], pb[16];
+    // Linv_pp is the B-operand (transposed) of the first product and the A-operand of the second: the
+    // same fragment elements serve both
+    const int t2[2] = {w2, 3 - w2};
+    double g[16][2];
+    if (w2 == 0) tri_frag_load<0>(Dinv, lane, g); else tri_frag_load<1>(Dinv, lane, g);
+    double pa[8], pb[8];
     const double* __restrict__ src = at_panel ? Linv + (int64_t)o * d + o : Sacc + (int64_t)o * d + n0;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         pa[u] = Hd[(int64_t)min(mi0 + y, d - 1) * d + o + x];          // A_ip (rows past d: see chol_iter_kernel)
         pb[u] = src[(int64_t)y * d + x];                               // S_pj, or Linv_pp itself
     }
-    d4 c[2][2];
+    d4 c[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int v = 0; v < 4; ++v) {
+            const int gm = mi0 + wr * 16 + 4 * v + fq, gn = n0 + w2 * 32 + j * 16 + fr;
+            c[j][v] = at_panel ? 0.0 : Sacc[(int64_t)min(gm, d - 1) * d + gn];
+        }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
-                c[i][j][v] = at_panel ? 0.0 : Sacc[(int64_t)min(gm, d - 1) * d + gn];
-            }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         Pi[y * DL + x] = pa[u];
         Pj[y * DL + x] = pb[u];
     }
     __syncthreads();
-    d4 li[2][2], xp[2][2];
+    d4 li[2], xp[2], none[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; xp[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-        double ai[2], bs[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) ai[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) bs[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (ks > 4 * ct[j] + 3) continue;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) li[i][j] = mfma4(ai[i], gb[ks][j], li[i][j]);
-        }
-        if (!at_panel) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                if (ks > 4 * rt[i] + 3) continue;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) xp[i][j] = mfma4(ga[ks][i], bs[j], xp[i][j]);
-            }
-        }
+    for (int j = 0; j < 2; ++j) { li[j] = d4{0.0, 0.0, 0.0, 0.0}; xp[j] = d4{0.0, 0.0, 0.0, 0.0}; }
+    if (w2 == 0) {
+        tri_right_product<0, false>(Pi, Pi, g, wr * 16, fr, fq, li, none);
+        if (!at_panel) tri_left_product<0, false>(Pj, Pj, g, wr * 16, fr, fq, xp, none);
+    } else {
+        tri_right_product<1, false>(Pi, Pi, g, wr * 16, fr, fq, li, none);
+        if (!at_panel) tri_left_product<1, false>(Pj, Pj, g, wr * 16, fr, fq, xp, none);
     }
     __syncthreads();
     // Pi := L_ip (row m, panel column k), Pj := Linv_pj (panel row k, column n)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                Pi[(wm * 32 + i * 16 + 4 * v + fq) * DL + ct[j] * 16 + fr] = li[i][j][v];
-                if (!at_panel) {
-                    const int m = rt[i] * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
-                    Pj[m * DL + n] = -xp[i][j][v];
-                    if (mi0 == o + NB) Linv[(int64_t)(o + m) * d + n0 + n] = -xp[i][j][v];
-                }
+        for (int v = 0; v < 4; ++v) {
+            Pi[(wr * 16 + 4 * v + fq) * DL + t2[j] * 16 + fr] = li[j][v];
+            if (!at_panel) {
+                const int m = t2[j] * 16 + 4 * v + fq, n = wr * 16 + fr;
+                Pj[m * DL + n] = -xp[j][v];
+                if (mi0 == o + NB) Linv[(int64_t)(o + m) * d + n0 + n] = -xp[j][v];
             }
+        }
     __syncthreads();
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double a[2], b[2];
+        const double a = Pi[(wr * 16 + fr) * DL + 4 * ks + fq];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+        for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Pj[(4 * ks + fq) * DL + w2 * 32 + j * 16 + fr], c[j]);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
-                if (gm < d) Sacc[(int64_t)gm * d + gn] = c[i][j][v];
-            }
+        for (int v = 0; v < 4; ++v) {
+            const int gm = mi0 + wr * 16 + 4 * v + fq, gn = n0 + w2 * 32 + j * 16 + fr;
+            if (gm < d) Sacc[(int64_t)gm * d + gn] = c[j][v];
+        }
 }
 
 // Hinv = Linv^T Linv alongside the factorization: block row k of L^-1 is complete one launch after its
@@ -470,54 +436,45 @@ __device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int 
 {
     double* Pi = lds;
     double* Pj = lds + NB * DL;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const bool first = nt == kt;
     const double* __restrict__ rowk = Linv + (int64_t)NB * kt * d;
-    double pa[16], pb[16];
+    double pa[8], pb[8];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         pa[u] = rowk[(int64_t)y * d + NB * mt + x];
         pb[u] = rowk[(int64_t)y * d + NB * nt + x];
     }
-    d4 c[2][2];
+    d4 c[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int v = 0; v < 4; ++v) {
+            const int gm = NB * mt + wr * 16 + 4 * v + fq, gn = NB * nt + w2 * 32 + j * 16 + fr;
+            c[j][v] = first ? 0.0 : Hinv[(int64_t)gm * d + gn];
+        }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = NB * mt + wm * 32 + i * 16 + 4 * v + fq, gn = NB * nt + wn * 32 + j * 16 + fr;
-                c[i][j][v] = first ? 0.0 : Hinv[(int64_t)gm * d + gn];
-            }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         Pi[y * DL + x] = pa[u];
         Pj[y * DL + x] = pb[u];
     }
     __syncthreads();
+#pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double a[2], b[2];
+        const double a = Pi[(4 * ks + fq) * DL + wr * 16 + fr];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = Pi[(4 * ks + fq) * DL + wm * 32 + i * 16 + fr];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+        for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Pj[(4 * ks + fq) * DL + w2 * 32 + j * 16 + fr], c[j]);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = NB * mt + wm * 32 + i * 16 + 4 * v + fq, gn = NB * nt + wn * 32 + j * 16 + fr;
-                Hinv[(int64_t)gm * d + gn] = c[i][j][v];
-            }
+        for (int v = 0; v < 4; ++v) {
+            const int gm = NB * mt + wr * 16 + 4 * v + fq, gn = NB * nt + w2 * 32 + j * 16 + fr;
+            Hinv[(int64_t)gm * d + gn] = c[j][v];
+        }
 }
 
 // One whole iteration of the blocked Cholesky factorization in a single launch.  The panel is
@@ -533,11 +490,15 @@ __device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int 
 // Workgroups past the ntrail trailing tiles (when Sacc != null) are first the ninv tiles of the triangular
 // inverse (chol_inverse_tile): (row block, column block) = (o / 64 + 1 + e / (o / 64 + 1), e % (o / 64 + 1)),
 // then the tiles of Hinv that block row o / 64 - 1 of L^-1 contributes to (chol_lauum_tile).
-__global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
-                                                        const double* __restrict__ Dinv, double* __restrict__ L,
-                                                        double* __restrict__ Linv, double* __restrict__ Dinv_next,
-                                                        int* __restrict__ flag, int ntrail, int ninv,
-                                                        double* __restrict__ Sacc, double* __restrict__ Hinv)
+// WPS = wavefronts per SIMD the register budget allows: 2 (one workgroup per compute unit, workgroup 0 has
+// its matrix pipes to itself: faster while the launch's tiles fit in workgroup 0's shadow anyway) or 4
+// (two workgroups per compute unit: more tile throughput for the large launches).
+template <int WPS>
+__global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
+                                                       const double* __restrict__ Dinv, double* __restrict__ L,
+                                                       double* __restrict__ Linv, double* __restrict__ Dinv_next,
+                                                       int* __restrict__ flag, int ntrail, int ninv,
+                                                       double* __restrict__ Sacc, double* __restrict__ Hinv)
 {
     __shared__ double lds[2 * NB * DL + NB];  // two tiles: 2 workgroups per compute unit
     if ((int)blockIdx.x >= ntrail + ninv) {
@@ -553,8 +514,8 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     }
     double* Pi = lds;
     double* Pj = lds + NB * DL;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = __builtin_amdgcn_readfirstlane(wave & 1), fr = lane & 15, fq = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
     tri_decode(blockIdx.x, ti, tj);
@@ -570,87 +531,74 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     double gb[16][2];
     if (wn == 0) tri_frag_load<0>(Dinv, lane, gb); else tri_frag_load<1>(Dinv, lane, gb);
     // one round of loads (all in flight together), then the stores to LDS
-    double pa[16], pb[16];
+    double pa[8], pb[8];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         // Rows past d are read from row d - 1 (clamped address, no branch per load): they only
         // reach outputs past d, which are never stored or are replaced by the identity padding.
         pa[u] = Hd[(int64_t)min(mi0 + y, d - 1) * d + o + x];
     }
     if (!diag_tile) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int y = wave + 4 * u, x = lane;
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
             pb[u] = Hd[(int64_t)min(mj0 + y, d - 1) * d + o + x];
         }
     }
-    d4 c[2][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
-                c[i][j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
-            }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         Pi[y * DL + x] = pa[u];
         if (!diag_tile) Pj[y * DL + x] = pb[u];
     }
     __syncthreads();
+    // the tile itself: in flight during the panel product
+    d4 c[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int gm = mi0 + wr * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+            c[j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+        }
 
-    d4 li[2][2], lj[2][2];
+    d4 li[2], lj[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { li[i][j] = d4{0.0, 0.0, 0.0, 0.0}; lj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
+    for (int j = 0; j < 2; ++j) { li[j] = d4{0.0, 0.0, 0.0, 0.0}; lj[j] = d4{0.0, 0.0, 0.0, 0.0}; }
     if (wn == 0) {
-        if (diag_tile) tri_right_product<0, false>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
-        else tri_right_product<0, true>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
+        if (diag_tile) tri_right_product<0, false>(Pi, Pj, gb, wr * 16, fr, fq, li, lj);
+        else tri_right_product<0, true>(Pi, Pj, gb, wr * 16, fr, fq, li, lj);
     } else {
-        if (diag_tile) tri_right_product<1, false>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
-        else tri_right_product<1, true>(Pi, Pj, gb, wm * 32, fr, fq, li, lj);
+        if (diag_tile) tri_right_product<1, false>(Pi, Pj, gb, wr * 16, fr, fq, li, lj);
+        else tri_right_product<1, true>(Pi, Pj, gb, wr * 16, fr, fq, li, lj);
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = wm * 32 + i * 16 + 4 * v + fq, n = ct[j] * 16 + fr;
-                Pi[m * DL + n] = li[i][j][v];
-                if (!diag_tile) Pj[m * DL + n] = lj[i][j][v];
-                if (tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[i][j][v];
-            }
+        for (int v = 0; v < 4; ++v) {
+            const int m = wr * 16 + 4 * v + fq, n = ct[j] * 16 + fr;
+            Pi[m * DL + n] = li[j][v];
+            if (!diag_tile) Pj[m * DL + n] = lj[j][v];
+            if (tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[j][v];
+        }
     __syncthreads();
     const double* Qj = diag_tile ? Pi : Pj;
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double a[2], b[2];
+        const double a = -Pi[(wr * 16 + fr) * DL + 4 * ks + fq];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = -Pi[(wm * 32 + i * 16 + fr) * DL + 4 * ks + fq];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Qj[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+        for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Qj[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq], c[j]);
     }
     if (blockIdx.x != 0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int gm = mi0 + wm * 32 + i * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
-                    if (gm < d && gn < d) Hd[(int64_t)gm * d + gn] = c[i][j][v];
-                }
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wr * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+                if (gm < d && gn < d) Hd[(int64_t)gm * d + gn] = c[j][v];
+            }
         return;
     }
     // tile (0, 0): the next diagonal block, of size nbn
@@ -658,16 +606,14 @@ __global__ __launch_bounds__(256, 2) void chol_iter_kernel(double* __restrict__ 
     __syncthreads();
     double* Am = Pi;
     double* Xm = Pj;
-    for (int idx = tid; idx < NB * NB; idx += 256) Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
+    for (int idx = tid; idx < NB * NB; idx += NT) Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
-                Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
-            }
+        for (int v = 0; v < 4; ++v) {
+            const int m = wr * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
+            Am[m * DL + n] = (m < nbn && n < nbn) ? c[j][v] : (m == n ? 1.0 : 0.0);
+        }
     __syncthreads();
     chol_block(Am, Xm, lds + 2 * NB * DL, flag);
     chol_block_store(Am, Xm, d, r0, nbn, L, Linv, Dinv_next);
@@ -680,7 +626,7 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
 {
     hipStream_t s = c->stream;
     double* Dinv[2] = {c->Dblk.as<double>(), c->Dblk.as<double>() + NB * NB};
-    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), 0, s, Hd, (int64_t)d, 0, min(NB, d), L, Linv, Dinv[0],
+    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Hd, (int64_t)d, 0, min(NB, d), L, Linv, Dinv[0],
                        flag);
     int it = 0;
     for (int o = 0; o + NB < d; o += NB, ++it) {
@@ -688,8 +634,13 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         const int ntrail = T * (T + 1) / 2;
         const int ninv = Sacc ? T * (it + 1) : 0;      // tiles of the triangular inverse (row below, column up to the panel)
         const int nlau = Sacc ? it * (it + 1) / 2 : 0;  // tiles of Hinv that block row it - 1 of L^-1 adds to
-        hipLaunchKernelGGL(chol_iter_kernel, dim3(ntrail + ninv + nlau), dim3(256), 0, s, Hd, d, o, Dinv[it & 1], L,
-                           Linv, Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
+        const int tiles = ntrail + ninv + nlau;
+        if (tiles <= DENSE_LAUNCH_TILES)
+            hipLaunchKernelGGL(chol_iter_kernel<2>, dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
+        else
+            hipLaunchKernelGGL(chol_iter_kernel<4>, dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
     }
     if (Sacc && it > 0) {
         // last block row of L^-1: Linv[last][0 : last] = -Linv[last][last] S[last][0 : last]
@@ -770,7 +721,7 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 //   in : Am = the block, full symmetric (identity padding past its size), Xm = 0
 //   out: Am upper triangle = U11 (pivot row j = row j), rv[j] = 1 / pivot_j
 //        (so Un11[i][j] = Am[i][j] * rv[i]),  Xm = G = (Un11^T)^-1 (unit lower)
-// Called by all 256 threads of the workgroup; ends with a barrier.
+// Called by all NT threads of the workgroup; ends with a barrier.
 __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, int* __restrict__ flag)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -837,7 +788,7 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
         int t = 0;
         for (int i = b + 1; i < 4; ++i)
             for (int j = i; j < 4; ++j, ++t) {
-                if ((t & 3) != wave) continue;
+                if ((t & (NT / 64 - 1)) != wave) continue;
                 d4 acc;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[v] = Am[(16 * i + 4 * v + fq) * DL + 16 * j + fr];
@@ -859,7 +810,7 @@ __device__ __forceinline__ void elim_block_store(const double* Am, const double*
                                                  double* __restrict__ Un, double* __restrict__ G,
                                                  double* __restrict__ Gf, double* __restrict__ rinv)
 {
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+    for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         const bool in = i < nb && j < nb;
         if (G) G[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
@@ -882,7 +833,7 @@ __device__ __forceinline__ void elim_block_store(const double* Am, const double*
 //        G (64 x 64, ld 64)  = (Un11^T)^-1: pivot rows right of the block are G * A[o:o+nb, o+nb:];
 //        Gf = the same in the fragment layout (either may be null)
 //        rinv[j] = 1 / pivot_j
-__global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
+__global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict__ A, int64_t ld, int o, int nb,
                                                         double* __restrict__ U, double* __restrict__ Un,
                                                         double* __restrict__ G, double* __restrict__ Gf,
                                                         double* __restrict__ rinv, int* __restrict__ flag)
@@ -890,7 +841,7 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
     __shared__ double rv[NB];
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) {
+    for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         double v = (i == j) ? 1.0 : 0.0;
         if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
@@ -910,18 +861,19 @@ __global__ __launch_bounds__(256) void elim_diag_kernel(const double* __restrict
 //      Un12 = D^-1 U12; the tiles of the first tile row also store them into U and Un;
 //   2. A22(ti, tj) -= Un12_i^T U12_j        (Eq. 12 for the 64 columns of the panel at once);
 //   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
-__global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ A, int d, int o,
-                                                        const double* __restrict__ G, const double* __restrict__ rinv,
-                                                        double* __restrict__ U, double* __restrict__ Un,
-                                                        double* __restrict__ G_next, double* __restrict__ rinv_next,
-                                                        int* __restrict__ flag)
+template <int WPS>
+__global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__ A, int d, int o,
+                                                       const double* __restrict__ G, const double* __restrict__ rinv,
+                                                       double* __restrict__ U, double* __restrict__ Un,
+                                                       double* __restrict__ G_next, double* __restrict__ rinv_next,
+                                                       int* __restrict__ flag)
 {
     __shared__ double lds[2 * NB * DL + NB];   // two tiles: 2 workgroups per compute unit
     double* Pi = lds;
     double* Pj = lds + NB * DL;
     double* rs = lds + 2 * NB * DL;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = __builtin_amdgcn_readfirstlane(wave >> 1), wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
     tri_decode(blockIdx.x, tj, ti);          // ti <= tj
@@ -929,101 +881,88 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
 
     // Pivot rows U12 = G A12: G is lower triangular, so the 16 rows of row tile rt (of 4) only need
-    // the k-steps 0 .. 4 rt + 3.  The wavefronts with wm = 0 take the row tiles 0 and 3, those with
-    // wm = 1 the tiles 1 and 2: 20 of 32 (k-step, tile) pairs each.
-    const int rt[2] = {wm, 3 - wm};
+    // the k-steps 0 .. 4 rt + 3.  The wavefronts with w2 = 0 take the row tiles 0 and 3, those with
+    // w2 = 1 the tiles 1 and 2 (20 of 32 (k-step, tile) pairs each), for the 16 columns of slice wr.
+    const int rt[2] = {w2, 3 - w2};
     // this lane's A-operand elements of G for those k-steps, straight from global memory
     double ga[16][2];
-    if (wm == 0) tri_frag_load<0>(G, lane, ga); else tri_frag_load<1>(G, lane, ga);
+    if (w2 == 0) tri_frag_load<0>(G, lane, ga); else tri_frag_load<1>(G, lane, ga);
     // one round of loads (all in flight together), then the stores to LDS
-    double pa[16], pb[16];
+    double pa[8], pb[8];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         // Columns past d are read from column d - 1 (clamped address, no branch per load): they
         // only reach outputs past d, which are never stored or are replaced by the identity padding.
         pa[u] = A[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
     }
     if (!diag_tile) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int y = wave + 4 * u, x = lane;
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
             pb[u] = A[(int64_t)(o + y) * d + min(cj0 + x, d - 1)];
         }
     }
     const double rsv = (tid < NB) ? rinv[tid] : 0.0;
-    d4 c[2][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
-                c[i][j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
-            }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int y = wave + 4 * u, x = lane;
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
         Pi[y * DL + x] = pa[u];
         if (!diag_tile) Pj[y * DL + x] = pb[u];
     }
     if (tid < NB) rs[tid] = rsv;
     __syncthreads();
+    // the trailing tile itself (rows of slice wr, the 32 columns of half w2): in flight during the product
+    d4 c[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int gm = ci0 + wr * 16 + 4 * v + fq, gn = cj0 + w2 * 32 + j * 16 + fr;
+            c[j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+        }
 
-    d4 ui[2][2], uj[2][2];
+    d4 ui[2], uj[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { ui[i][j] = d4{0.0, 0.0, 0.0, 0.0}; uj[i][j] = d4{0.0, 0.0, 0.0, 0.0}; }
-    if (wm == 0) {
-        if (diag_tile) tri_left_product<0, false>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
-        else tri_left_product<0, true>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
+    for (int i = 0; i < 2; ++i) { ui[i] = d4{0.0, 0.0, 0.0, 0.0}; uj[i] = d4{0.0, 0.0, 0.0, 0.0}; }
+    if (w2 == 0) {
+        if (diag_tile) tri_left_product<0, false>(Pi, Pj, ga, wr * 16, fr, fq, ui, uj);
+        else tri_left_product<0, true>(Pi, Pj, ga, wr * 16, fr, fq, ui, uj);
     } else {
-        if (diag_tile) tri_left_product<1, false>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
-        else tri_left_product<1, true>(Pi, Pj, ga, wn * 32, fr, fq, ui, uj);
+        if (diag_tile) tri_left_product<1, false>(Pi, Pj, ga, wr * 16, fr, fq, ui, uj);
+        else tri_left_product<1, true>(Pi, Pj, ga, wr * 16, fr, fq, ui, uj);
     }
     __syncthreads();
     // Pi := Un12_i (rows scaled by 1 / pivot), Pj := U12_j
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = rt[i] * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
-                const double uiv = ui[i][j][v];
-                const double ujv = diag_tile ? uiv : uj[i][j][v];
-                Pi[m * DL + n] = uiv * rs[m];
-                Pj[m * DL + n] = ujv;
-                if (ti == 0 && cj0 + n < d) {
-                    U[(int64_t)(o + m) * d + cj0 + n] = ujv;
-                    Un[(int64_t)(o + m) * d + cj0 + n] = ujv * rs[m];
-                }
+        for (int v = 0; v < 4; ++v) {
+            const int m = rt[i] * 16 + 4 * v + fq, n = wr * 16 + fr;
+            const double uiv = ui[i][v];
+            const double ujv = diag_tile ? uiv : uj[i][v];
+            Pi[m * DL + n] = uiv * rs[m];
+            Pj[m * DL + n] = ujv;
+            if (ti == 0 && cj0 + n < d) {
+                U[(int64_t)(o + m) * d + cj0 + n] = ujv;
+                Un[(int64_t)(o + m) * d + cj0 + n] = ujv * rs[m];
             }
+        }
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        double a[2], b[2];
+        const double a = -Pi[(4 * ks + fq) * DL + wr * 16 + fr];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = -Pi[(4 * ks + fq) * DL + wm * 32 + i * 16 + fr];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Pj[(4 * ks + fq) * DL + wn * 32 + j * 16 + fr];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) c[i][j] = mfma4(a[i], b[j], c[i][j]);
+        for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Pj[(4 * ks + fq) * DL + w2 * 32 + j * 16 + fr], c[j]);
     }
     if (blockIdx.x != 0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int gm = ci0 + wm * 32 + i * 16 + 4 * v + fq, gn = cj0 + wn * 32 + j * 16 + fr;
-                    if (gm < d && gn < d) A[(int64_t)gm * d + gn] = c[i][j][v];
-                }
+            for (int v = 0; v < 4; ++v) {
+                const int gm = ci0 + wr * 16 + 4 * v + fq, gn = cj0 + w2 * 32 + j * 16 + fr;
+                if (gm < d && gn < d) A[(int64_t)gm * d + gn] = c[j][v];
+            }
         return;
     }
     // tile (0, 0): the next diagonal block, of size nbn
@@ -1032,15 +971,13 @@ __global__ __launch_bounds__(256, 2) void elim_iter_kernel(double* __restrict__ 
     double* Am = Pi;
     double* Xm = Pj;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = wm * 32 + i * 16 + 4 * v + fq, n = wn * 32 + j * 16 + fr;
-                Am[m * DL + n] = (m < nbn && n < nbn) ? c[i][j][v] : (m == n ? 1.0 : 0.0);
-                Xm[m * DL + n] = 0.0;
-            }
+        for (int v = 0; v < 4; ++v) {
+            const int m = wr * 16 + 4 * v + fq, n = w2 * 32 + j * 16 + fr;
+            Am[m * DL + n] = (m < nbn && n < nbn) ? c[j][v] : (m == n ? 1.0 : 0.0);
+            Xm[m * DL + n] = 0.0;
+        }
     __syncthreads();
     elim_block(Am, Xm, rs, flag);
     elim_block_store(Am, Xm, rs, d, r0, nbn, U, Un, nullptr, G_next, rinv_next);
@@ -1059,13 +996,17 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
     if (block == NB && steps == d) {
         // one stand-alone launch for the first diagonal block, then one fused launch per panel
-        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un,
+        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(NT), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un,
                            (double*)nullptr, Gb[0], rb[0], flag);
         int it = 0;
         for (int o = 0; o + NB < d; o += NB, ++it) {
             const int T = (d - o - NB + NB - 1) / NB;
-            hipLaunchKernelGGL(elim_iter_kernel, dim3(T * (T + 1) / 2), dim3(256), 0, s, A, d, o, Gb[it & 1],
-                               rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
+            if (T * (T + 1) / 2 <= DENSE_LAUNCH_TILES)
+                hipLaunchKernelGGL(elim_iter_kernel<2>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, A, d, o, Gb[it & 1],
+                                   rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
+            else
+                hipLaunchKernelGGL(elim_iter_kernel<4>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, A, d, o, Gb[it & 1],
+                                   rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
             ready(it);          // rows of block `it` complete (its diagonal part came from the previous launch)
         }
         ready(it);              // last block: only a diagonal part
@@ -1077,7 +1018,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     int it = 0;
     for (int o = 0; o < steps; o += block, ++it) {
         const int nb = min(block, steps - o);
-        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(256), 0, s, A, (int64_t)d, o, nb, U, Un, G,
+        hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(NT), 0, s, A, (int64_t)d, o, nb, U, Un, G,
                            (double*)nullptr, rinv, flag);
         const int r = d - o - nb;
         if (r <= 0) { ready(it); break; }
