@@ -241,7 +241,9 @@ __global__ __launch_bounds__(256) void gather_h_kernel(const double* __restrict_
 {
     const int b = blockIdx.x * 256 + threadIdx.x;
     const int a = blockIdx.y;
-    if (b >= d) return;
+    // the elimination maintains (and reads) the upper triangle only, plus the whole 64 x 64 tiles on the
+    // diagonal that its tile updates load and store
+    if (b >= d || b < (a & ~63)) return;
     int pa = perm[a], pb = perm[b];
     pa = min(max(pa, 0), d - 1);
     pb = min(max(pb, 0), d - 1);
