@@ -67,15 +67,21 @@ __device__ __forceinline__ d4 mfma4(double a, double b, d4 c)
 // One off-diagonal 16 x 16 tile of the inverse X of a 64 x 64 lower triangular matrix T:
 //   X_ij = -X_ii sum_{m=j}^{i-1} T_im X_mj        (X_ii and the X_mj already in Xm).
 // tfetch(i, m, ks) returns this lane's A-operand element of tile T_im for k-step ks, i.e.
-// T_im[fr][4 ks + fq].  One wavefront.
+// T_im[fr][4 ks + fq].  One wavefront.  inv_tile_sum adds the terms m0 <= m < m1 to t,
+// inv_tile_finish multiplies by -X_ii and stores the tile.
 template <class TF>
-__device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, int fr, int fq)
+__device__ __forceinline__ d4 inv_tile_sum(const double* Xm, TF tfetch, int i, int j, int m0, int m1, d4 t, int fr,
+                                           int fq)
 {
-    d4 t = {0.0, 0.0, 0.0, 0.0};
-    for (int m = j; m < i; ++m)
+    for (int m = m0; m < m1; ++m)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             t = mfma4(tfetch(i, m, ks), Xm[(16 * m + 4 * ks + fq) * DL + 16 * j + fr], t);
+    return t;
+}
+
+__device__ __forceinline__ void inv_tile_finish(double* Xm, int i, int j, d4 t, int fr, int fq)
+{
     // the accumulator layout (row 4 v + fq, column fr) is the B-operand layout of k-step v
     d4 r = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -85,15 +91,22 @@ __device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, in
     __builtin_amdgcn_wave_barrier();
 }
 
+template <class TF>
+__device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, int fr, int fq)
+{
+    inv_tile_finish(Xm, i, j, inv_tile_sum(Xm, tfetch, i, j, j, i, d4{0.0, 0.0, 0.0, 0.0}, fr, fq), fr, fq);
+}
+
 // Schedule shared by chol_block and elim_block.  sweep(b): pivots of diagonal tile b and the
 // tiles below / right of it; tinv(b): triangular inverse of diagonal tile b into Xm;
 // trail(b): update of the tiles behind tile row/column b; tf: tile fetch for inv_tile.
-//   interval      wavefront 0   wavefront 1        wavefront 2
-//   b = 0..3      sweep(b)      tinv(b-1)          X_10 (b = 3)
+//   interval      wavefront 0   wavefront 1   wavefront 2   wavefronts 3, 4, 5
+//   b = 0..3      sweep(b)      tinv(b-1)     X_10 (b = 3)
 //   (after each of b = 0..2: trail(b) on all wavefronts)
-//   then          tinv(3)       X_21, X_20
-//   then          X_30          X_31               X_32
-// Called by all NT threads of the workgroup; ends with a barrier.
+//   then          tinv(3)       X_21          X_20          the sums of X_30, X_31, X_32 as far as they
+//                                                           do not need this interval's tiles
+//   then                                                    rest of the sums, times -X_33
+// Called by all NT threads of the workgroup (at least 6 wavefronts); ends with a barrier.
 template <class SW, class TI, class TR, class TF>
 __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR trail, TF tf)
 {
@@ -110,13 +123,17 @@ __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR
             __syncthreads();
         }
     }
+    d4 t = {0.0, 0.0, 0.0, 0.0};
+    const int j3 = wave - 3;                       // wavefronts 3, 4, 5: column tile of X_3j
     if (wave == 0) tinv(3);
-    else if (wave == 1) {
-        inv_tile(Xm, tf, 2, 1, fr, fq);
-        inv_tile(Xm, tf, 2, 0, fr, fq);
-    }
+    else if (wave == 1) inv_tile(Xm, tf, 2, 1, fr, fq);
+    else if (wave == 2) inv_tile(Xm, tf, 2, 0, fr, fq);
+    else if (wave <= 5) t = inv_tile_sum(Xm, tf, 3, j3, j3, j3 == 2 ? 3 : 2, t, fr, fq);   // X_2j is not there yet
     __syncthreads();
-    if (wave < 3) inv_tile(Xm, tf, 3, wave, fr, fq);
+    if (wave >= 3 && wave <= 5) {
+        if (j3 < 2) t = inv_tile_sum(Xm, tf, 3, j3, 2, 3, t, fr, fq);
+        inv_tile_finish(Xm, 3, j3, t, fr, fq);
+    }
     __syncthreads();
 }
 
