@@ -98,38 +98,40 @@ __device__ __forceinline__ void inv_tile(double* Xm, TF tfetch, int i, int j, in
 }
 
 // Schedule shared by chol_block and elim_block.  sweep(b): pivots of diagonal tile b and the
-// tiles below / right of it; tinv(b): triangular inverse of diagonal tile b into Xm;
+// tiles below / right of it -- and, for b >= 1, the inverse X_bb of the diagonal tile, carried along in
+// 16 lanes that the sweep leaves idle; tinv(0): triangular inverse of diagonal tile 0 into Xm;
 // trail(b): update of the tiles behind tile row/column b; tf: tile fetch for inv_tile.
-//   interval      wavefront 0   wavefront 1   wavefront 2   wavefronts 3, 4, 5
-//   b = 0..3      sweep(b)      tinv(b-1)     X_10 (b = 3)
+//   interval   wavefront 0        wavefront 1   wavefront 2   wavefronts 3, 4, 5
+//   b = 0      sweep(0)
+//   b = 1      sweep(1) + X_11    tinv(0)
+//   b = 2      sweep(2) + X_22                  X_10
+//   b = 3      sweep(3) + X_33    X_21          X_20          the sums of X_30, X_31, X_32 as far as they
+//                                                             do not need this interval's tiles
+//   then                                                      rest of the sums, times -X_33
 //   (after each of b = 0..2: trail(b) on all wavefronts)
-//   then          tinv(3)       X_21          X_20          the sums of X_30, X_31, X_32 as far as they
-//                                                           do not need this interval's tiles
-//   then                                                    rest of the sums, times -X_33
 // Called by all NT threads of the workgroup (at least 6 wavefronts); ends with a barrier.
 template <class SW, class TI, class TR, class TF>
 __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR trail, TF tf)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fr = lane & 15, fq = lane >> 4;
+    d4 t = {0.0, 0.0, 0.0, 0.0};
+    const int j3 = wave - 3;                       // wavefronts 3, 4, 5: column tile of X_3j
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         if (wave == 0) sweep(b);
-        else if (wave == 1 && b > 0) tinv(b - 1);
-        else if (wave == 2 && b == 3) inv_tile(Xm, tf, 1, 0, fr, fq);
+        else if (wave == 1 && b == 1) tinv(0);
+        else if (wave == 2 && b == 2) inv_tile(Xm, tf, 1, 0, fr, fq);
+        else if (wave == 1 && b == 3) inv_tile(Xm, tf, 2, 1, fr, fq);
+        else if (wave == 2 && b == 3) inv_tile(Xm, tf, 2, 0, fr, fq);
+        else if (wave >= 3 && wave <= 5 && b == 3)
+            t = inv_tile_sum(Xm, tf, 3, j3, j3, j3 == 2 ? 3 : 2, t, fr, fq);   // X_2j is not there yet
         __syncthreads();
         if (b < 3) {
             trail(b);
             __syncthreads();
         }
     }
-    d4 t = {0.0, 0.0, 0.0, 0.0};
-    const int j3 = wave - 3;                       // wavefronts 3, 4, 5: column tile of X_3j
-    if (wave == 0) tinv(3);
-    else if (wave == 1) inv_tile(Xm, tf, 2, 1, fr, fq);
-    else if (wave == 2) inv_tile(Xm, tf, 2, 0, fr, fq);
-    else if (wave <= 5) t = inv_tile_sum(Xm, tf, 3, j3, j3, j3 == 2 ? 3 : 2, t, fr, fq);   // X_2j is not there yet
-    __syncthreads();
     if (wave >= 3 && wave <= 5) {
         if (j3 < 2) t = inv_tile_sum(Xm, tf, 3, j3, 2, 3, t, fr, fq);
         inv_tile_finish(Xm, 3, j3, t, fr, fq);
@@ -155,9 +157,17 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
     // (l_rho,k = (a_rho,k - sum l l) / l_kk); rows above (r < 0) idle on harmless values.
     auto sweep = [&](int b) {
         const int base = 16 * b, rho = lane, r = rho - base;
+        // For b >= 1 the lanes 0..15 (rows above the tile, otherwise idle) carry the rows of the identity
+        // as if they were rows below the tile: those become I L_bb^-T, i.e. lane c ends with column c of
+        // X_bb = L_bb^-1, for the price of no extra instruction.
+        const bool idl = b > 0 && lane < 16;
+        const int rr = idl ? 64 : r;      // row position as far as "below pivot k" (rr > k) goes
         double a[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) a[j] = (j <= r) ? Am[rho * DL + base + j] : Am[(base + j) * DL + rho];
+        for (int j = 0; j < 16; ++j) {
+            a[j] = (j <= r) ? Am[rho * DL + base + j] : Am[(base + j) * DL + rho];
+            if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
+        }
         // Each lane of the tile also keeps its own diagonal entry in `dg` and updates it locally
         // (dg -= l_rk^2), so the pivot of step k+1 is available one fma after l_rk: the
         // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
@@ -174,7 +184,7 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
             const double rs = pivot_rsqrt(piv);                    // 1 / L[k][k]
             own = (r == k) ? rs : own;
             const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
-            const double lm = (r > k) ? t : 0.0;
+            const double lm = (rr > k) ? t : 0.0;
             dg -= lm * lm;
             a[k] = t;
 #pragma unroll
@@ -185,6 +195,10 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
 #pragma unroll
             for (int j = 0; j < 16; ++j) Am[rho * DL + base + j] = (j <= r) ? a[j] : 0.0;
             if (r < 16) rq[rho] = own;
+        }
+        if (idl) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) Xm[(base + k) * DL + base + lane] = a[k];
         }
     };
     // the diagonal tile's inverse by forward substitution: lane c (mod 16) solves L x = e_c;
@@ -750,9 +764,17 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
     // in the same sweep; columns left of it (r < 0) idle on harmless values.
     auto sweep = [&](int b) {
         const int base = 16 * b, c = lane, r = c - base;
+        // For b >= 1 the lanes 0..15 (columns left of the tile, otherwise idle) carry the columns of the
+        // identity as if they were columns right of the tile: those become G_bb I, i.e. lane c ends with
+        // column c of G_bb = (Un_bb^T)^-1.
+        const bool idl = b > 0 && lane < 16;
+        const int rr = idl ? 64 : r;      // column position as far as "right of pivot k" (rr > k) goes
         double a[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+        for (int j = 0; j < 16; ++j) {
+            a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+            if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
+        }
         // as in chol_block: every lane of the tile keeps its own diagonal entry in `dg`
         double dg = Am[c * DL + c];
         double own = 0.0;
@@ -766,7 +788,7 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
             const double pi = pivot_rcp(piv);
             own = (r == k) ? pi : own;
             const double cr = (r == k) ? piv : a[k];          // A[k][c] = U[k][c] for c >= k
-            const double fm = (r > k) ? cr * pi : 0.0;        // Un[k][c]
+            const double fm = (rr > k) ? cr * pi : 0.0;       // Un[k][c]
             dg -= fm * cr;
             a[k] = cr;
 #pragma unroll
@@ -778,6 +800,10 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
             for (int k = 0; k < 16; ++k)
                 if (k <= r) Am[(base + k) * DL + c] = a[k];   // U[k][c] for k <= c
             if (r < 16) rv[c] = own;
+        }
+        if (idl) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) Xm[(base + k) * DL + base + lane] = a[k];
         }
     };
     // G_bb = (Un_bb^T)^-1 (unit lower) by forward substitution: lane c (mod 16) solves
