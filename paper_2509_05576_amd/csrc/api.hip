@@ -108,8 +108,8 @@ struct DeviceGuard {
 
 constexpr int64_t MAX_DCOL = 32768;
 // L^-1 and L^-T L^-1 fused into the factorization launches against the separate recursive-doubling
-// inverse and product, damped inverse of a d x d matrix: 0.51 vs 0.69 ms at d = 1024, 1.29 vs 1.69 ms at
-// 2304, 3.81 vs 4.06 ms at 4096, even at 4608 (5.23 vs 5.21 ms), slower beyond (27.9 vs 22.2 ms at 8192:
+// inverse and product, damped inverse of a d x d matrix: 1.1 vs 1.5 ms at d = 2304, even from 4096 to
+// 5120 (3.77 vs 3.80, 6.30 vs 6.29 ms), slower beyond (10.5 vs 9.8 ms at 6144, 25.9 vs 21.2 ms at 8192:
 // three products per inverse tile against one, and the launches are full without them)
 constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
