@@ -186,28 +186,41 @@ static int check_shape(fobq_ctx* ctx, int64_t d_row, int64_t d_col)
 }
 
 // grid, scores, order.  Needs ctx->hdiag filled.  Enqueue only.
-static int enqueue_order(fobq_ctx* ctx, const float* W, int R, int d, const fobq_opts* o,
-                         float* scales_out, float* zeros_out)
+// sort key: 0 "sensi", 1 "err", 2 "w" (Section 4.1, Table 3)
+static int order_kind(const fobq_opts* o)
 {
-    hipStream_t s = ctx->stream;
+    return (o->order == FOBQ_ORDER_ERR_DESC || o->order == FOBQ_ORDER_ERR_ASC) ? 1
+         : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
+}
+
+// The part of the ordering that needs W only (grid, per-chunk column sums), on stream `st`: in the
+// whole-layer path it runs beside the factorization.
+static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, int R, int d, const fobq_opts* o,
+                               float* scales_out, float* zeros_out)
+{
     const int G = o->group > 0 ? d / o->group : 1;
     FOBQ_TRY(ctx->scale.ensure((size_t)R * G * sizeof(double)), "workspace scale");
     FOBQ_TRY(ctx->zero.ensure((size_t)R * G * sizeof(double)), "workspace zero");
-    FOBQ_TRY(ctx->S.ensure((size_t)d * sizeof(double)), "workspace S");
     const int chunks = sens_chunks(R);
     FOBQ_TRY(ctx->Spart.ensure((size_t)chunks * d * sizeof(double)), "workspace Spart");
+    FOBQ_TRY(launch_grid(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
+                         scales_out, zeros_out), "grid");
+    FOBQ_TRY(launch_sens_partial(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
+                                 ctx->Spart.as<double>(), chunks, order_kind(o)), "sensitivity");
+    return FOBQ_OK;
+}
+
+// The rest, on the context's stream: scores (needs diag Hinv in ctx->hdiag) and the order.
+static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o)
+{
+    hipStream_t s = ctx->stream;
+    FOBQ_TRY(ctx->S.ensure((size_t)d * sizeof(double)), "workspace S");
     FOBQ_TRY(ctx->perm.ensure((size_t)d * sizeof(int)), "workspace perm");
     FOBQ_TRY(ctx->invperm.ensure((size_t)d * sizeof(int)), "workspace invperm");
     StageScope sc(ctx, FOBQ_STAGE_ORDER);
-    FOBQ_TRY(launch_grid(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                         scales_out, zeros_out), "grid");
-    // sort key: 0 "sensi", 1 "err", 2 "w" (Section 4.1, Table 3)
-    const int kind = (o->order == FOBQ_ORDER_ERR_DESC || o->order == FOBQ_ORDER_ERR_ASC) ? 1
-                   : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
     const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC && o->order <= FOBQ_ORDER_W_ASC;
-    FOBQ_TRY(launch_sensitivity(s, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                                ctx->hdiag.as<double>(), ctx->Spart.as<double>(), chunks, ctx->S.as<double>(), kind),
-             "sensitivity");
+    FOBQ_TRY(launch_sens_reduce(s, ctx->Spart.as<double>(), sens_chunks(R), d, ctx->hdiag.as<double>(),
+                                ctx->S.as<double>(), order_kind(o)), "sensitivity");
     // the dynamic order starts from the identity and exchanges columns step by step
     if (o->order == FOBQ_ORDER_NATURAL || o->order == FOBQ_ORDER_SENSI_DYNAMIC)
         FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
@@ -433,7 +446,9 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
     FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
     FOBQ_TRY(launch_take_diag(ctx->stream, Hinv, d, ctx->hdiag.as<double>()), "diag");
-    rc = enqueue_order(ctx, W, R, d, opts, nullptr, nullptr);
+    rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, nullptr, nullptr);
+    if (rc) return rc;
+    rc = enqueue_order(ctx, R, d, opts);
     if (rc) return rc;
     if (S) FOBQ_TRY(hipMemcpyAsync(S, ctx->S.p, (size_t)d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy S");
     if (perm) FOBQ_TRY(hipMemcpyAsync(perm, ctx->perm.p, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, ctx->stream), "copy perm");
@@ -483,12 +498,21 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), s), "clear flags");
     FOBQ_TRY(hipMemsetAsync(ctx->lossrow.p, 0, (size_t)R * sizeof(double), s), "clear loss");
 
+    // grid and the W-only part of the column scores: on the side stream, beside the factorization
+    rc = ensure_sync_events(ctx, 2);
+    if (rc) return rc;
+    FOBQ_TRY(hipEventRecord(ctx->sync_ev[0], s), "event");
+    FOBQ_TRY(hipStreamWaitEvent(ctx->side, ctx->sync_ev[0], 0), "stream wait");
+    rc = enqueue_grid_scores(ctx, ctx->side, W, R, d, opts, out->scales, out->zeros);
+    if (rc) return rc;
+    FOBQ_TRY(hipEventRecord(ctx->sync_ev[1], ctx->side), "event");
     // damp, Cholesky, inverse
     rc = enqueue_inverse(ctx, H, d, opts->damp, opts->damp_abs);
     if (rc) return rc;
     FOBQ_TRY(launch_take_diag(s, ctx->Hinv.as<double>(), d, ctx->hdiag.as<double>()), "diag");
-    // grid, column scores, order
-    rc = enqueue_order(ctx, W, R, d, opts, out->scales, out->zeros);
+    FOBQ_TRY(hipStreamWaitEvent(s, ctx->sync_ev[1], 0), "stream wait");
+    // column scores, order
+    rc = enqueue_order(ctx, R, d, opts);
     if (rc) return rc;
     {
         StageScope sc(ctx, FOBQ_STAGE_PERMUTE);

@@ -156,9 +156,10 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
                        double* scale, double* zero, float* scales_out, float* zeros_out);
 hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag);
-hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
-                              const double* scale, const double* zero, const double* hdiag,
-                              double* Spart, int chunks, double* S, int kind);
+hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                               const double* scale, const double* zero, double* Spart, int chunks, int kind);
+hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* hdiag, double* S,
+                              int kind);
 int sens_chunks(int R);
 hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm, int ascending);
 hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm);

@@ -115,15 +115,22 @@ __global__ __launch_bounds__(256) void sens_reduce_kernel(const double* __restri
 
 int sens_chunks(int R) { return (R + SENS_RC - 1) / SENS_RC; }
 
-hipError_t launch_sensitivity(hipStream_t s, const float* W, int R, int d, int bits, int group,
-                              const double* scale, const double* zero, const double* hdiag,
-                              double* Spart, int chunks, double* S, int kind)
+// pass 1: per-chunk sums over the rows (needs W and the grid only)
+hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int bits, int group,
+                               const double* scale, const double* zero, double* Spart, int chunks, int kind)
 {
     const int gs = group > 0 ? group : d;
     const int G = group > 0 ? d / group : 1;
     const double maxq = (double)((1 << bits) - 1);
     hipLaunchKernelGGL(sens_partial_kernel, dim3((d + 255) / 256, chunks), dim3(256), 0, s, W, R, d, gs, G, maxq,
                        scale, zero, Spart, kind);
+    return hipGetLastError();
+}
+
+// pass 2: sum of the chunks, and for "sensi" the division by 2 [Hinv]_jj
+hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* hdiag, double* S,
+                              int kind)
+{
     hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, hdiag, S, kind);
     return hipGetLastError();
 }
@@ -138,42 +145,48 @@ __device__ __forceinline__ double sort_key(double v)
     return (!(v == v) || v > 1.0e300 || v < -1.0e300) ? -1.0e308 : v;
 }
 
-// blockIdx.x: 256 columns j; blockIdx.y: a slice of 256 comparison columns k.  Partial ranks are
-// integers, so adding them with atomics gives the same result in any order.
-__global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ S, int d, int* __restrict__ rank,
-                                                         double sign)
+// One workgroup ranks 32 columns j against all d columns k (staged through LDS 256 at a time), eight
+// threads per column each taking every eighth k, and writes both directions of the order: no zero-filled
+// counters, no atomics, no second pass.
+__global__ __launch_bounds__(256) void rank_sort_kernel(const double* __restrict__ S, int d, int* __restrict__ perm,
+                                                        int* __restrict__ invperm, double sign)
 {
     __shared__ double tile[256];
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    const int base = blockIdx.y * 256;
-    const int k = base + threadIdx.x;
-    tile[threadIdx.x] = (k < d) ? sort_key(sign * S[k]) : 0.0;
-    __syncthreads();
-    if (j >= d) return;
-    const double sj = sort_key(sign * S[j]);
-    const int lim = min(256, d - base);
+    __shared__ int part_cnt[8][32];
+    const int jl = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int j = blockIdx.x * 32 + jl;
+    const double sj = (j < d) ? sort_key(sign * S[j]) : 0.0;
     int cnt = 0;
-    for (int u = 0; u < lim; ++u) {
-        const double v = tile[u];
-        cnt += (v > sj || (v == sj && base + u < j)) ? 1 : 0;
+    for (int base = 0; base < d; base += 256) {
+        const int k = base + threadIdx.x;
+        __syncthreads();
+        tile[threadIdx.x] = (k < d) ? sort_key(sign * S[k]) : 0.0;
+        __syncthreads();
+        const int lim = min(256, d - base);
+        // columns before j win ties: up to j - base of the tile's entries count when equal
+        const int before = min(max(j - base, 0), lim);
+#pragma unroll 4
+        for (int u = part; u < lim; u += 8) {
+            const double v = tile[u];
+            cnt += (v > sj || (v == sj && u < before)) ? 1 : 0;
+        }
     }
-    if (cnt) atomicAdd(&rank[j], cnt);
-}
-
-__global__ __launch_bounds__(256) void rank_scatter_kernel(const int* __restrict__ rank, int d, int* __restrict__ perm)
-{
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j < d) perm[min(max(rank[j], 0), d - 1)] = j;
+    part_cnt[part][jl] = cnt;
+    __syncthreads();
+    if (part == 0 && j < d) {
+        int r = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r += part_cnt[q][jl];
+        r = min(max(r, 0), d - 1);
+        perm[r] = j;
+        invperm[j] = r;
+    }
 }
 
 hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm, int ascending)
 {
-    // invperm doubles as the rank array: invperm[j] = rank of column j = its step
-    hipError_t e = launch_fill_i32(s, invperm, d, 0);
-    if (e != hipSuccess) return e;
-    const int nb = (d + 255) / 256;
-    hipLaunchKernelGGL(rank_count_kernel, dim3(nb, nb), dim3(256), 0, s, S, d, invperm, ascending ? -1.0 : 1.0);
-    hipLaunchKernelGGL(rank_scatter_kernel, dim3(nb), dim3(256), 0, s, invperm, d, perm);
+    hipLaunchKernelGGL(rank_sort_kernel, dim3((d + 31) / 32), dim3(256), 0, s, S, d, perm, invperm,
+                       ascending ? -1.0 : 1.0);
     return hipGetLastError();
 }
 
