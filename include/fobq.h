@@ -196,7 +196,10 @@ typedef enum {
     FOBQ_STAGE_COUNT = 9
 } fobq_stage;
 
-/* Turn hipEvent timing of the stages on or off (off by default). */
+/* Turn hipEvent timing of the stages on or off (off by default): on = 0 none, 1 every stage,
+ * or a sum of FOBQ_PROFILE_STAGE(s) for the stages s to time (each timed interval costs two
+ * event records on the stream, a few microseconds of launch gap each). */
+#define FOBQ_PROFILE_STAGE(s) (2 << (s))
 int fobq_profile_enable(fobq_ctx* ctx, int on);
 /* Synchronises, folds pending events, returns accumulated milliseconds and the
  * number of timed intervals of `stage` since the last reset. */

@@ -219,7 +219,12 @@ def fobq_sensitivity(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int
     return S, perm
 
 
-def fobq_profile_enable(ctx: int, on: bool) -> None:
+def FOBQ_PROFILE_STAGE(stage: int) -> int:
+    return 2 << stage
+
+
+def fobq_profile_enable(ctx: int, on) -> None:
+    """on: False / True (every stage), or a sum of FOBQ_PROFILE_STAGE(s)."""
     _check(ctx, load_library().fobq_profile_enable(ctypes.c_void_p(ctx), int(on)))
 
 

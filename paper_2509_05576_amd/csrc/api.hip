@@ -44,7 +44,7 @@ static hipEvent_t take_event(fobq_ctx* c)
 
 StageScope::StageScope(fobq_ctx* c_, int stage_, hipStream_t on) : c(c_), stage(stage_), st(on ? on : c_->stream)
 {
-    if (!c->profiling) return;
+    if (!(c->profiling >> stage & 1u)) return;
     e0 = take_event(c);
     e1 = take_event(c);
     if (e0) (void)hipEventRecord(e0, st);
@@ -52,7 +52,7 @@ StageScope::StageScope(fobq_ctx* c_, int stage_, hipStream_t on) : c(c_), stage(
 
 StageScope::~StageScope()
 {
-    if (!c->profiling || !e0 || !e1) return;
+    if (!e0 || !e1) return;
     (void)hipEventRecord(e1, st);
     c->timer.pending[stage].push_back({e0, e1});
 }
@@ -633,7 +633,7 @@ int fobq_finish(fobq_ctx* ctx)
 int fobq_profile_enable(fobq_ctx* ctx, int on)
 {
     if (!ctx) return FOBQ_EINVAL;
-    ctx->profiling = on != 0;
+    ctx->profiling = on == 1 ? ~0u : (unsigned)on >> 1;
     return FOBQ_OK;
 }
 

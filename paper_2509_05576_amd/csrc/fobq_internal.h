@@ -107,7 +107,7 @@ struct fobq_ctx {
     std::vector<hipEvent_t> sync_ev;
 
     bool pending = false;   // a layer was enqueued without the final status read (fobq_finish outstanding)
-    bool profiling = false;
+    unsigned profiling = 0;     // bit s: stage s is timed
     fobq::StageTimer timer;
 };
 
