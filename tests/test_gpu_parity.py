@@ -376,6 +376,37 @@ def test_loss_equals_layer_output_error_plus_damping_term(fobq, ctx):
     assert abs(float(out.loss.cpu()[0]) - expect) <= 1e-6 * expect
 
 
+def test_stage_timing_of_chosen_stages(fobq, ctx):
+    # FOBQ_PROFILE_STAGE masks: only the chosen stages record events; True times every stage
+    W, X = _problem(24, 200, 300, 77, w_std=0.05)
+    Wd_, Xd = _dev(W), _dev(X)
+    chol, xxt = fobq.STAGES.index("cholesky"), fobq.STAGES.index("xxt")
+    fobq.fobq_profile_enable(ctx.handle, fobq.FOBQ_PROFILE_STAGE(xxt))
+    fobq.fobq_profile_reset(ctx.handle)
+    ctx.hessian(Xd)
+    ctx.quantize_layer(Wd_, bits=4)
+    st = ctx.stage_ms()
+    assert st["xxt"][1] == 1 and st["xxt"][0] > 0.0
+    assert all(st[name][1] == 0 for name in fobq.STAGES if name != "xxt")
+    fobq.fobq_profile_enable(ctx.handle, fobq.FOBQ_PROFILE_STAGE(xxt) + fobq.FOBQ_PROFILE_STAGE(chol))
+    fobq.fobq_profile_reset(ctx.handle)
+    ctx.hessian(Xd)
+    ctx.quantize_layer(Wd_, bits=4)
+    st = ctx.stage_ms()
+    assert st["xxt"][1] == 1 and st["cholesky"][1] == 1 and st["columns"][1] == 0
+    fobq.fobq_profile_enable(ctx.handle, True)
+    fobq.fobq_profile_reset(ctx.handle)
+    ctx.hessian(Xd)
+    ctx.quantize_layer(Wd_, bits=4)
+    st = ctx.stage_ms()
+    assert all(st[name][1] >= 1 for name in ("xxt", "finalize", "cholesky", "order", "permute", "columns", "emit"))
+    fobq.fobq_profile_enable(ctx.handle, False)
+    fobq.fobq_profile_reset(ctx.handle)
+    ctx.hessian(Xd)
+    ctx.quantize_layer(Wd_, bits=4)
+    assert all(v[1] == 0 for v in ctx.stage_ms().values())
+
+
 def test_enqueue_and_finish_on_several_contexts(fobq, ctx):
     # independent layers in flight on three contexts / streams at once give the results of the blocking call
     probs = [_problem(40 + 10 * i, 150 + 40 * i, 500, 40 + i, w_std=0.05) for i in range(3)]
