@@ -328,22 +328,36 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
     const int* __restrict__ perm, double maxq, uint8_t* __restrict__ codesT, double* __restrict__ DT, int Rp,
     double* __restrict__ lossrow)
 {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * CHAIN_WAVES + (threadIdx.x >> 6);
-    if (row >= R) return;                    // whole wavefront leaves; no barriers in this kernel
+    // the block's pivot rows, fetched once per workgroup (every row of W needs all of them)
+    __shared__ double Us[CB][CB + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool col_ok = lane < nb;
     const int cl = col_ok ? lane : 0;        // safe column for address arithmetic
-    double* __restrict__ wptr = Wp + (int64_t)row * d + o + cl;
+    {
+        double t[CB / CHAIN_WAVES];
+#pragma unroll
+        for (int i = 0; i < CB / CHAIN_WAVES; ++i) {
+            const int j = wave + CHAIN_WAVES * i;
+            t[i] = Un[(int64_t)(o + min(j, nb - 1)) * d + o + cl];
+        }
+#pragma unroll
+        for (int i = 0; i < CB / CHAIN_WAVES; ++i) Us[wave + CHAIN_WAVES * i][lane] = t[i];
+    }
+    const int row = blockIdx.x * CHAIN_WAVES + wave;
+    const int rw = min(row, R - 1);
+    double* __restrict__ wptr = Wp + (int64_t)rw * d + o + cl;
     const double w0 = *wptr;
     int pj = perm[o + cl];
     pj = min(max(pj, 0), d - 1);
-    const int64_t gi = (int64_t)row * G + pj / gs;
+    const int64_t gi = (int64_t)rw * G + pj / gs;
     const double s = scale[gi], z = zero[gi];
     const double hp = 0.5 / U[(int64_t)(o + cl) * d + o + cl];
+    __syncthreads();
+    if (row >= R) return;                    // whole wavefront leaves; no barrier after this point
     double u[CB];
 #pragma unroll
     for (int j = 0; j < CB; ++j)
-        u[j] = (j < nb && lane > j && col_ok) ? Un[(int64_t)(o + j) * d + o + lane] : 0.0;
+        u[j] = (j < nb && lane > j && col_ok) ? Us[j][lane] : 0.0;
 
     double w = w0, mycode = 0.0, mydiff = 0.0;
     bool suspect = false;
