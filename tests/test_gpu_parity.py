@@ -164,7 +164,7 @@ def test_hessian_conv_argument_and_state_errors(fobq, ctx):
     fobq.fobq_hessian_finalize(ctx.handle)
 
 
-@pytest.mark.parametrize("d", [1, 7, 64, 65, 100, 128, 300, 1000])
+@pytest.mark.parametrize("d", [1, 7, 64, 65, 100, 128, 129, 192, 257, 300, 1000])
 def test_spd_inverse_matches_oracle(fobq, ctx, d):
     _say(f"spd_inverse d={d}")
     _, X = _problem(1, d, max(2 * d, 8), 200 + d)
