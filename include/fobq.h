@@ -186,9 +186,9 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
 typedef enum {
     FOBQ_STAGE_XXT = 0,      /* the X X^T kernel launches only                              */
     FOBQ_STAGE_FINALIZE = 1, /* split reduction, 2/N, mirror                                */
-    FOBQ_STAGE_CHOLESKY = 2, /* damping + H = L L^T                                         */
-    FOBQ_STAGE_INVERSE = 3,  /* L^-1 and L^-T L^-1                                          */
-    FOBQ_STAGE_ORDER = 4,    /* grid, sensitivity, sort                                     */
+    FOBQ_STAGE_CHOLESKY = 2, /* damping + H = L L^T (d_col <= 4096: also L^-1, L^-T L^-1)   */
+    FOBQ_STAGE_INVERSE = 3,  /* L^-1 and L^-T L^-1 where they are separate launches         */
+    FOBQ_STAGE_ORDER = 4,    /* column scores and sort (the grid runs beside the Cholesky)  */
     FOBQ_STAGE_PERMUTE = 5,  /* gather W and Hinv into processing order                     */
     FOBQ_STAGE_ELIMINATE = 6,/* shared-Hinv elimination (blocked form only)                 */
     FOBQ_STAGE_COLUMNS = 7,  /* column loop: quantize + compensate (+ Eq. 12 when unblocked)*/

@@ -1,5 +1,7 @@
 // Dense factorizations of the path, all fp64, all blocked with 64-wide panels:
-//   cholesky_lower   H_d = L L^T                       (Section 5, item 1)
+//   cholesky_lower   H_d = L L^T                       (Section 5, item 1); for d up to a limit its panel
+//                    launches also carry L^-1 and Hinv = L^-T L^-1 (tiles in the shadow of the
+//                    critical path), otherwise:
 //   trtri_lower      L^-1 by recursive doubling of the block size
 //   lauum_upper      Hinv = L^-T L^-1
 //   eliminate_blocked the shared-Hinv elimination of Eq. 12, B columns at a time:
@@ -8,7 +10,8 @@
 //                    Un[t, :] = U[t, :] / U[t, t]; the weight compensation of Eq. 9 / 11
 //                    for step t is  W[:, k] -= (w_t - q_t) * Un[t, k].
 // The 64 x 64 diagonal blocks are handled by one workgroup in LDS; everything
-// else is a rank-64 update on the matrix cores (gemm64).
+// else is a rank-64 update on the matrix cores, fused into the panel launches
+// (chol_iter_kernel, elim_iter_kernel) or through gemm64.
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -21,11 +24,12 @@ constexpr int NB = 64;
 // the unblocked sweep over the 16 pivots of a diagonal tile: one wavefront, one
 // row (Cholesky) or column (elimination) of the whole block per lane, so the same
 // sweep also produces the tiles below (right of) the diagonal tile; pivot rows are
-// broadcast with v_readlane.  The triangular inverse of a diagonal tile is a
-// forward substitution done by a second wavefront while the first one already
-// sweeps the next tile.  Everything else -- trailing update, assembly of the
-// 64 x 64 triangular inverse from the tile inverses -- is 16 x 16 x 16 products on
-// the matrix cores (4 MFMAs each), one tile per wavefront.
+// broadcast with v_readlane.  The triangular inverse of a diagonal tile comes out
+// of the same sweep, in lanes it would leave idle (the first tile's: a forward
+// substitution on a second wavefront during the next sweep).  Everything else --
+// trailing update, assembly of the 64 x 64 triangular inverse from the tile
+// inverses -- is 16 x 16 x 16 products on the matrix cores (4 MFMAs each), one tile
+// per wavefront, one interval behind the sweeps.
 typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
 // launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
