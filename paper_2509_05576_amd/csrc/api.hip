@@ -127,7 +127,6 @@ static int ensure_factor_ws(fobq_ctx* ctx, int64_t d)
     FOBQ_TRY(ctx->Dblk.ensure((4 * 64 * 64 + 128) * sizeof(double)), "workspace Dblk");
     FOBQ_TRY(ctx->scal.ensure(16 * sizeof(double)), "workspace scal");
     FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
-    FOBQ_TRY(ctx->hdiag.ensure((size_t)d * sizeof(double)), "workspace hdiag");
     return FOBQ_OK;
 }
 
@@ -185,7 +184,6 @@ static int check_shape(fobq_ctx* ctx, int64_t d_row, int64_t d_col)
     return FOBQ_OK;
 }
 
-// grid, scores, order.  Needs ctx->hdiag filled.  Enqueue only.
 // sort key: 0 "sensi", 1 "err", 2 "w" (Section 4.1, Table 3)
 static int order_kind(const fobq_opts* o)
 {
@@ -210,8 +208,8 @@ static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, in
     return FOBQ_OK;
 }
 
-// The rest, on the context's stream: scores (needs diag Hinv in ctx->hdiag) and the order.
-static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o)
+// The rest, on the context's stream: scores (with the diagonal of Hinv, d x d) and the order.
+static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o, const double* Hinv)
 {
     hipStream_t s = ctx->stream;
     FOBQ_TRY(ctx->S.ensure((size_t)d * sizeof(double)), "workspace S");
@@ -219,8 +217,8 @@ static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o)
     FOBQ_TRY(ctx->invperm.ensure((size_t)d * sizeof(int)), "workspace invperm");
     StageScope sc(ctx, FOBQ_STAGE_ORDER);
     const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC && o->order <= FOBQ_ORDER_W_ASC;
-    FOBQ_TRY(launch_sens_reduce(s, ctx->Spart.as<double>(), sens_chunks(R), d, ctx->hdiag.as<double>(),
-                                ctx->S.as<double>(), order_kind(o)), "sensitivity");
+    FOBQ_TRY(launch_sens_reduce(s, ctx->Spart.as<double>(), sens_chunks(R), d, Hinv, ctx->S.as<double>(),
+                                order_kind(o)), "sensitivity");
     // the dynamic order starts from the identity and exchanges columns step by step
     if (o->order == FOBQ_ORDER_NATURAL || o->order == FOBQ_ORDER_SENSI_DYNAMIC)
         FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
@@ -278,7 +276,7 @@ int fobq_destroy(fobq_ctx* ctx)
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
                       &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
-                      &ctx->S, &ctx->Spart, &ctx->hdiag, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
+                      &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
     for (DevBuf* b : bufs) b->release();
     delete ctx;
     return FOBQ_OK;
@@ -442,13 +440,11 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int R = (int)d_row, d = (int)d_col;
-    FOBQ_TRY(ctx->hdiag.ensure((size_t)d * sizeof(double)), "workspace hdiag");
     FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
     FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
-    FOBQ_TRY(launch_take_diag(ctx->stream, Hinv, d, ctx->hdiag.as<double>()), "diag");
     rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, nullptr, nullptr);
     if (rc) return rc;
-    rc = enqueue_order(ctx, R, d, opts);
+    rc = enqueue_order(ctx, R, d, opts, Hinv);
     if (rc) return rc;
     if (S) FOBQ_TRY(hipMemcpyAsync(S, ctx->S.p, (size_t)d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy S");
     if (perm) FOBQ_TRY(hipMemcpyAsync(perm, ctx->perm.p, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, ctx->stream), "copy perm");
@@ -509,10 +505,9 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     // damp, Cholesky, inverse
     rc = enqueue_inverse(ctx, H, d, opts->damp, opts->damp_abs);
     if (rc) return rc;
-    FOBQ_TRY(launch_take_diag(s, ctx->Hinv.as<double>(), d, ctx->hdiag.as<double>()), "diag");
     FOBQ_TRY(hipStreamWaitEvent(s, ctx->sync_ev[1], 0), "stream wait");
     // column scores, order
-    rc = enqueue_order(ctx, R, d, opts);
+    rc = enqueue_order(ctx, R, d, opts, ctx->Hinv.as<double>());
     if (rc) return rc;
     {
         StageScope sc(ctx, FOBQ_STAGE_PERMUTE);
@@ -589,8 +584,8 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
         StageScope sc(ctx, FOBQ_STAGE_EMIT);
         if (out->codes || out->Q)
             FOBQ_TRY(launch_emit(s, codesT, Rp, R, d, steps, ctx->invperm.as<int>(), scale, zero, G, opts->group,
-                                 out->codes, out->Q), "emit");
-        if (out->loss) FOBQ_TRY(launch_loss(s, lossrow, R, out->loss), "loss");
+                                 out->codes, out->Q, lossrow, out->loss), "emit");
+        else if (out->loss) FOBQ_TRY(launch_loss(s, lossrow, R, out->loss), "loss");
         if (out->perm)
             FOBQ_TRY(hipMemcpyAsync(out->perm, perm, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, s), "copy perm");
         if (out->W_work)

@@ -97,7 +97,6 @@ struct fobq_ctx {
     fobq::DevBuf codesT;    // d x Rp u8
     fobq::DevBuf scale, zero;   // d_row x G fp64
     fobq::DevBuf S, Spart;  // d fp64, chunks x d fp64
-    fobq::DevBuf hdiag;     // d fp64
     fobq::DevBuf perm, invperm; // d int32
     fobq::DevBuf lossrow;   // d_row fp64
 
@@ -157,10 +156,9 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 // quant.hip
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
                        double* scale, double* zero, float* scales_out, float* zeros_out);
-hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag);
 hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int bits, int group,
                                const double* scale, const double* zero, double* Spart, int chunks, int kind);
-hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* hdiag, double* S,
+hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* Hinv, double* S,
                               int kind);
 int sens_chunks(int R);
 hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, int* invperm, int ascending);
@@ -180,7 +178,7 @@ hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A
                        uint8_t* codesT, int Rp, double* lossrow);
 hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int d, int steps,
                        const int* invperm, const double* scale, const double* zero, int G, int group,
-                       uint8_t* codes, float* Q);
+                       uint8_t* codes, float* Q, const double* lossrow, double* loss);   // loss may be null
 hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss);
 hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);

@@ -507,9 +507,12 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
     return hipGetLastError();
 }
 
-// lambda = damp * mean(diag H) + damp_abs   (Section 6.1: damping added to the diagonal)
-__global__ __launch_bounds__(256) void damp_lambda_kernel(const double* __restrict__ H, int d, double damp,
-                                                          double damp_abs, double* __restrict__ lam)
+// Hd = H + lambda I on the tiles on and below the diagonal (all the factorization reads), with
+// lambda = damp * mean(diag H) + damp_abs   (Section 6.1: damping added to the diagonal).
+// One workgroup per 64 x 64 tile; every workgroup sums the diagonal itself, in the same order, so all of
+// them add the same lambda without a launch of its own for it (d reads from cache against 4096 copied).
+__global__ __launch_bounds__(256) void damp_kernel(const double* __restrict__ H, int d, double damp, double damp_abs,
+                                                   double* __restrict__ Hd, double* __restrict__ lam_out)
 {
     __shared__ double part[256];
     double s = 0.0;
@@ -520,26 +523,29 @@ __global__ __launch_bounds__(256) void damp_lambda_kernel(const double* __restri
         if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *lam = damp * (part[0] / (double)d) + damp_abs;
-}
-
-__global__ __launch_bounds__(256) void damp_copy_kernel(const double* __restrict__ H, int d,
-                                                        const double* __restrict__ lam, double* __restrict__ Hd)
-{
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t total = (int64_t)d * d;
-    if (idx >= total) return;
-    const int a = (int)(idx / d), b = (int)(idx % d);
-    double v = H[idx];
-    if (a == b) v += *lam;
-    Hd[idx] = v;
+    const double lam = damp * (part[0] / (double)d) + damp_abs;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *lam_out = lam;
+    // tile (ti, tj), ti >= tj, of index blockIdx.x = ti (ti + 1) / 2 + tj
+    int ti = (int)((sqrtf(8.0f * (float)blockIdx.x + 1.0f) - 1.0f) * 0.5f);
+    while ((ti + 1) * (ti + 2) / 2 <= (int)blockIdx.x) ++ti;
+    while (ti * (ti + 1) / 2 > (int)blockIdx.x) --ti;
+    const int tj = (int)blockIdx.x - ti * (ti + 1) / 2;
+#pragma unroll 4
+    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+        const int a = ti * 64 + (e >> 6), b = tj * 64 + (e & 63);
+        if (a < d && b < d) {
+            double v = H[(int64_t)a * d + b];
+            if (a == b) v += lam;
+            Hd[(int64_t)a * d + b] = v;
+        }
+    }
 }
 
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out)
 {
-    hipLaunchKernelGGL(damp_lambda_kernel, dim3(1), dim3(256), 0, s, H, d, damp, damp_abs, lam_out);
-    const int64_t total = (int64_t)d * d;
-    hipLaunchKernelGGL(damp_copy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, H, d, lam_out, Hd);
+    const int nt = (d + 63) / 64;
+    hipLaunchKernelGGL(damp_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, s, H, d, damp, damp_abs, Hd,
+                       lam_out);
     return hipGetLastError();
 }
 

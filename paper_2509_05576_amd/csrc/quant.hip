@@ -62,18 +62,6 @@ hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, in
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void take_diag_kernel(const double* __restrict__ M, int d, double* __restrict__ diag)
-{
-    const int a = blockIdx.x * 256 + threadIdx.x;
-    if (a < d) diag[a] = M[(int64_t)a * d + a];
-}
-
-hipError_t launch_take_diag(hipStream_t s, const double* M, int d, double* diag)
-{
-    hipLaunchKernelGGL(take_diag_kernel, dim3((d + 255) / 256), dim3(256), 0, s, M, d, diag);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------
 // Column scores (Eq. 10 summed over rows, Section 4.2 steps 1-2):
 //   S_j = sum_i (quant(w_ij) - w_ij)^2 / (2 [Hinv]_jj)
@@ -103,14 +91,14 @@ __global__ __launch_bounds__(256) void sens_partial_kernel(const float* __restri
 }
 
 __global__ __launch_bounds__(256) void sens_reduce_kernel(const double* __restrict__ Spart, int chunks, int d,
-                                                          const double* __restrict__ hdiag, double* __restrict__ S,
+                                                          const double* __restrict__ Hinv, double* __restrict__ S,
                                                           int kind)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= d) return;
     double acc = 0.0;
     for (int c = 0; c < chunks; ++c) acc += Spart[(int64_t)c * d + j];
-    S[j] = (kind == 0) ? acc / (2.0 * hdiag[j]) : acc;
+    S[j] = (kind == 0) ? acc / (2.0 * Hinv[(int64_t)j * d + j]) : acc;
 }
 
 int sens_chunks(int R) { return (R + SENS_RC - 1) / SENS_RC; }
@@ -127,11 +115,11 @@ hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int 
     return hipGetLastError();
 }
 
-// pass 2: sum of the chunks, and for "sensi" the division by 2 [Hinv]_jj
-hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* hdiag, double* S,
+// pass 2: sum of the chunks, and for "sensi" the division by 2 [Hinv]_jj (Hinv: d x d, its diagonal is read)
+hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* Hinv, double* S,
                               int kind)
 {
-    hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, hdiag, S, kind);
+    hipLaunchKernelGGL(sens_reduce_kernel, dim3((d + 255) / 256), dim3(256), 0, s, Spart, chunks, d, Hinv, S, kind);
     return hipGetLastError();
 }
 
@@ -237,38 +225,35 @@ hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm
 // ---------------------------------------------------------------------------
 // Put W and Hinv into processing order (Section 4.2 step 3):
 //   Wp[i][t] = W[i][perm[t]] (widened),  A[a][b] = Hinv[perm[a]][perm[b]]
-// Hinv is read from its upper triangle.
-__global__ __launch_bounds__(256) void gather_w_kernel(const float* __restrict__ W, int R, int d,
-                                                       const int* __restrict__ perm, double* __restrict__ Wp)
+// Hinv is read from its upper triangle.  Both gathers in one launch: blockIdx.x < R walks the
+// rows of W, the rest the rows of Hinv (blockIdx.y: 256 columns).
+__global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ W, int R, int d,
+                                                     const int* __restrict__ perm, const double* __restrict__ Hu,
+                                                     double* __restrict__ Wp, double* __restrict__ A)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    const int i = blockIdx.y;
+    const int t = blockIdx.y * 256 + threadIdx.x;
     if (t >= d) return;
-    int j = perm[t];
-    j = min(max(j, 0), d - 1);
-    Wp[(int64_t)i * d + t] = (double)W[(int64_t)i * d + j];
-}
-
-__global__ __launch_bounds__(256) void gather_h_kernel(const double* __restrict__ Hu, int d, const int* __restrict__ perm,
-                                                       double* __restrict__ A)
-{
-    const int b = blockIdx.x * 256 + threadIdx.x;
-    const int a = blockIdx.y;
+    int pt = perm[t];
+    pt = min(max(pt, 0), d - 1);
+    if ((int)blockIdx.x < R) {
+        const int i = blockIdx.x;
+        Wp[(int64_t)i * d + t] = (double)W[(int64_t)i * d + pt];
+        return;
+    }
     // the elimination maintains (and reads) the upper triangle only, plus the whole 64 x 64 tiles on the
     // diagonal that its tile updates load and store
-    if (b >= d || b < (a & ~63)) return;
-    int pa = perm[a], pb = perm[b];
+    const int a = (int)blockIdx.x - R;
+    if (t < (a & ~63)) return;
+    int pa = perm[a];
     pa = min(max(pa, 0), d - 1);
-    pb = min(max(pb, 0), d - 1);
-    const int lo = min(pa, pb), hi = max(pa, pb);
-    A[(int64_t)a * d + b] = Hu[(int64_t)lo * d + hi];
+    const int lo = min(pa, pt), hi = max(pa, pt);
+    A[(int64_t)a * d + t] = Hu[(int64_t)lo * d + hi];
 }
 
 hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
                          const double* Hinv_upper, double* Wp, double* A)
 {
-    hipLaunchKernelGGL(gather_w_kernel, dim3((d + 255) / 256, R), dim3(256), 0, s, W, R, d, perm, Wp);
-    hipLaunchKernelGGL(gather_h_kernel, dim3((d + 255) / 256, d), dim3(256), 0, s, Hinv_upper, d, perm, A);
+    hipLaunchKernelGGL(gather_kernel, dim3(R + d, (d + 255) / 256), dim3(256), 0, s, W, R, d, perm, Hinv_upper, Wp, A);
     return hipGetLastError();
 }
 
@@ -616,11 +601,25 @@ hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A
 // ---------------------------------------------------------------------------
 // Outputs in original column order: codes[i][c] and Q[i][c] = scale * (code - zero)
 // for the column c processed at step invperm[c] < steps; others get code 0, Q 0.
+// Workgroup (0, 0) also adds up the per-row loss terms (loss != null).
 __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ codesT, int Rp, int R, int d, int steps,
                                                    const int* __restrict__ invperm, const double* __restrict__ scale,
                                                    const double* __restrict__ zero, int G, int gs,
-                                                   uint8_t* __restrict__ codes, float* __restrict__ Q)
+                                                   uint8_t* __restrict__ codes, float* __restrict__ Q,
+                                                   const double* __restrict__ lossrow, double* __restrict__ loss)
 {
+    if (loss && blockIdx.x == 0 && blockIdx.y == 0) {       // uniform over the workgroup
+        __shared__ double part[256];
+        double s = 0.0;
+        for (int i = threadIdx.x; i < R; i += 256) s += lossrow[i];
+        part[threadIdx.x] = s;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *loss = part[0];
+    }
     const int c = blockIdx.x * 256 + threadIdx.x;
     const int i = blockIdx.y;
     if (c >= d) return;
@@ -638,11 +637,11 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 
 hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int d, int steps,
                        const int* invperm, const double* scale, const double* zero, int G, int group,
-                       uint8_t* codes, float* Q)
+                       uint8_t* codes, float* Q, const double* lossrow, double* loss)
 {
     const int gs = group > 0 ? group : d;
     hipLaunchKernelGGL(emit_kernel, dim3((d + 255) / 256, R), dim3(256), 0, s, codesT, Rp, R, d, steps, invperm,
-                       scale, zero, G, gs, codes, Q);
+                       scale, zero, G, gs, codes, Q, lossrow, loss);
     return hipGetLastError();
 }
 
