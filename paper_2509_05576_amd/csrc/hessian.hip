@@ -509,12 +509,12 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
 
 // Hd = H + lambda I on the tiles on and below the diagonal (all the factorization reads), with
 // lambda = damp * mean(diag H) + damp_abs   (Section 6.1: damping added to the diagonal).
-// One workgroup per 64 x 64 tile; every workgroup sums the diagonal itself, in the same order, so all of
-// them add the same lambda without a launch of its own for it (d reads from cache against 4096 copied).
-__global__ __launch_bounds__(256) void damp_kernel(const double* __restrict__ H, int d, double damp, double damp_abs,
-                                                   double* __restrict__ Hd, double* __restrict__ lam_out)
+// Four workgroups per 64 x 64 tile.  OWN_SUM: every workgroup sums the diagonal itself, in the same order,
+// so all of them add the same lambda without a launch of its own for it -- d cache lines read per
+// workgroup against 4096 elements copied, which pays for small d only; otherwise workgroup-uniform
+// lambda comes from lam_io, written by damp_lambda_kernel.
+__device__ __forceinline__ double diag_sum(const double* __restrict__ H, int d, double* part)
 {
-    __shared__ double part[256];
     double s = 0.0;
     for (int a = threadIdx.x; a < d; a += 256) s += H[(int64_t)a * d + a];
     part[threadIdx.x] = s;
@@ -523,29 +523,60 @@ __global__ __launch_bounds__(256) void damp_kernel(const double* __restrict__ H,
         if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    const double lam = damp * (part[0] / (double)d) + damp_abs;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *lam_out = lam;
+    return part[0];
+}
+
+__global__ __launch_bounds__(256) void damp_lambda_kernel(const double* __restrict__ H, int d, double damp,
+                                                          double damp_abs, double* __restrict__ lam)
+{
+    __shared__ double part[256];
+    const double tr = diag_sum(H, d, part);
+    if (threadIdx.x == 0) *lam = damp * (tr / (double)d) + damp_abs;
+}
+
+template <bool OWN_SUM>
+__global__ __launch_bounds__(256) void damp_kernel(const double* __restrict__ H, int d, double damp, double damp_abs,
+                                                   double* __restrict__ Hd, double* __restrict__ lam_io)
+{
+    __shared__ double part[256];
+    double lam;
+    if (OWN_SUM) {
+        lam = damp * (diag_sum(H, d, part) / (double)d) + damp_abs;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *lam_io = lam;
+    } else {
+        lam = *lam_io;
+    }
     // tile (ti, tj), ti >= tj, of index blockIdx.x = ti (ti + 1) / 2 + tj
     int ti = (int)((sqrtf(8.0f * (float)blockIdx.x + 1.0f) - 1.0f) * 0.5f);
     while ((ti + 1) * (ti + 2) / 2 <= (int)blockIdx.x) ++ti;
     while (ti * (ti + 1) / 2 > (int)blockIdx.x) --ti;
     const int tj = (int)blockIdx.x - ti * (ti + 1) / 2;
-#pragma unroll 4
-    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    // blockIdx.y: which 16 rows of the tile; 4 elements per thread, all loads before the stores
+    double v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (int)blockIdx.y * 1024 + threadIdx.x + 256 * i;
+        const int a = min(ti * 64 + (e >> 6), d - 1), b = min(tj * 64 + (e & 63), d - 1);
+        v[i] = H[(int64_t)a * d + b];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (int)blockIdx.y * 1024 + threadIdx.x + 256 * i;
         const int a = ti * 64 + (e >> 6), b = tj * 64 + (e & 63);
-        if (a < d && b < d) {
-            double v = H[(int64_t)a * d + b];
-            if (a == b) v += lam;
-            Hd[(int64_t)a * d + b] = v;
-        }
+        if (a < d && b < d) Hd[(int64_t)a * d + b] = (a == b) ? v[i] + lam : v[i];
     }
 }
 
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out)
 {
     const int nt = (d + 63) / 64;
-    hipLaunchKernelGGL(damp_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, s, H, d, damp, damp_abs, Hd,
-                       lam_out);
+    const dim3 grid((unsigned)(nt * (nt + 1) / 2), 4);
+    if (d <= 512) {
+        hipLaunchKernelGGL(damp_kernel<true>, grid, dim3(256), 0, s, H, d, damp, damp_abs, Hd, lam_out);
+    } else {
+        hipLaunchKernelGGL(damp_lambda_kernel, dim3(1), dim3(256), 0, s, H, d, damp, damp_abs, lam_out);
+        hipLaunchKernelGGL(damp_kernel<false>, grid, dim3(256), 0, s, H, d, damp, damp_abs, Hd, lam_out);
+    }
     return hipGetLastError();
 }
 
