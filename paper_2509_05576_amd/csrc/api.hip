@@ -310,8 +310,8 @@ static int clear_slabs(fobq_ctx* ctx, int64_t n)
 {
     const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
     if (need > ctx->h_zeroed) {
-        const size_t dd = (size_t)ctx->h_d * ctx->h_d * sizeof(double);
-        FOBQ_TRY(hipMemsetAsync(ctx->Hpart.as<char>() + dd * ctx->h_zeroed, 0, dd * (need - ctx->h_zeroed), ctx->stream),
+        const int64_t dd = (int64_t)ctx->h_d * ctx->h_d;
+        FOBQ_TRY(launch_clear_f64(ctx->stream, ctx->Hpart.as<double>() + dd * ctx->h_zeroed, dd * (need - ctx->h_zeroed)),
                  "clear Hessian accumulator");
         ctx->h_zeroed = need;
     }
@@ -417,7 +417,7 @@ int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d64, double* Hinv)
     const int d = (int)d64;
     int rc = ensure_factor_ws(ctx, d);
     if (rc) return rc;
-    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
+    FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
     rc = enqueue_inverse(ctx, H, d, 0.0, 0.0);
     if (rc) return rc;
     // full symmetric copy out of the upper tiles
@@ -441,7 +441,7 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int R = (int)d_row, d = (int)d_col;
     FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
-    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), ctx->stream), "clear flags");
+    FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
     rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, nullptr, nullptr);
     if (rc) return rc;
     rc = enqueue_order(ctx, R, d, opts, Hinv);
@@ -491,8 +491,7 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     FOBQ_TRY(ctx->DT.ensure((size_t)d * Rp * sizeof(double)), "workspace DT");
     FOBQ_TRY(ctx->codesT.ensure((size_t)d * Rp), "workspace codesT");
     FOBQ_TRY(ctx->lossrow.ensure((size_t)R * sizeof(double)), "workspace lossrow");
-    FOBQ_TRY(hipMemsetAsync(ctx->flags.p, 0, FLAG_COUNT * sizeof(int), s), "clear flags");
-    FOBQ_TRY(hipMemsetAsync(ctx->lossrow.p, 0, (size_t)R * sizeof(double), s), "clear loss");
+    FOBQ_TRY(launch_clear_words(s, ctx->flags.p, FLAG_COUNT, ctx->lossrow.p, 2 * (int64_t)R), "clear flags and loss");
 
     // grid and the W-only part of the column scores: on the side stream, beside the factorization
     rc = ensure_sync_events(ctx, 2);

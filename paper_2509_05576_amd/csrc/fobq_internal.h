@@ -182,5 +182,7 @@ hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int 
 hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss);
 hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);
+hipError_t launch_clear_f64(hipStream_t s, double* p, int64_t n);
+hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2);   // 4-byte words
 
 }  // namespace fobq
