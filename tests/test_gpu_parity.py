@@ -239,6 +239,28 @@ def test_quantize_layer_matches_oracle(fobq, ctx, r, d, n, bits, group, order, b
     _compare_layer(out, ref, W, bits)
 
 
+def test_random_small_layers_match_oracle(fobq, ctx):
+    # seeded draw of shapes and options: block counts from 1 to 10 with ragged tails, every bit width,
+    # groups, the blocked, narrow-block and unblocked column loops
+    rng = np.random.default_rng(20250905)
+    for case in range(24):
+        d = int(rng.integers(1, 640))
+        r = int(rng.integers(1, 260))
+        n = int(rng.integers(max(4, d // 2), 3 * d + 8))
+        bits = int(rng.integers(2, 9))
+        divisors = [g for g in (8, 16, 32, 64, 128) if d % g == 0]
+        group = int(rng.choice(divisors)) if divisors and rng.random() < 0.4 else 0
+        order = int(rng.choice([0, 1, 1, 5]))
+        block = int(rng.choice([0, 0, 0, 64, 32, 1]))
+        _say(f"random layer {case}: r={r} d={d} n={n} bits={bits} group={group} order={order} block={block}")
+        W, X = _problem(r, d, n, 9000 + case, w_std=0.05)
+        ctx.hessian(_dev(X))
+        out = ctx.quantize_layer(_dev(W), bits=bits, group=group, order=order, block=block, damp=0.01)
+        ref = oracle.quantize_layer(W, X=X, bits=bits, group=group, order_mode=order)
+        ref = _oracle_with_gpu_perm(W, ref.H, out.perm.cpu().numpy(), ref, bits=bits, group=group)
+        _compare_layer(out, ref, W, bits)
+
+
 @pytest.mark.parametrize("order", [3, 4, 5, 6, 7])
 def test_ablation_orders_match_oracle(fobq, ctx, order):
     # the sort keys and directions of the ordering ablation (Section 4.1, Table 3)
