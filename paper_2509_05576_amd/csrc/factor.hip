@@ -12,6 +12,8 @@
 // The 64 x 64 diagonal blocks are handled by one workgroup in LDS; everything
 // else is a rank-64 update on the matrix cores, fused into the panel launches
 // (chol_iter_kernel, elim_iter_kernel) or through gemm64.
+#include <hip/hip_ext.h>
+
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -1048,13 +1050,19 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
         int it = 0;
         for (int o = 0; o + NB < d; o += NB, ++it) {
             const int T = (d - o - NB + NB - 1) / NB;
+            // rows of block `it` are complete when this launch is (its diagonal part came from the previous
+            // one): an announced block's event rides on the launch itself as its stop event -- a separate
+            // hipEventRecord between two dependent launches costs about 4 us of bubble
+            hipEvent_t done = (rows_ready && it < (int)rows_ready->size() && rows_announced(it, (int)rows_ready->size()))
+                                  ? (*rows_ready)[it] : nullptr;
             if (T * (T + 1) / 2 <= DENSE_LAUNCH_TILES)
-                hipLaunchKernelGGL(elim_iter_kernel<2>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, A, d, o, Gb[it & 1],
-                                   rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
+                hipExtLaunchKernelGGL(elim_iter_kernel<2>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
+                                      (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                      rb[(it + 1) & 1], flag);
             else
-                hipLaunchKernelGGL(elim_iter_kernel<4>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, A, d, o, Gb[it & 1],
-                                   rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag);
-            ready(it);          // rows of block `it` complete (its diagonal part came from the previous launch)
+                hipExtLaunchKernelGGL(elim_iter_kernel<4>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
+                                      (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                      rb[(it + 1) & 1], flag);
         }
         ready(it);              // last block: only a diagonal part
         return hipGetLastError();
