@@ -194,7 +194,7 @@ static int order_kind(const fobq_opts* o)
 // The part of the ordering that needs W only (grid, per-chunk column sums), on stream `st`: in the
 // whole-layer path it runs beside the factorization.
 static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, int R, int d, const fobq_opts* o,
-                               float* scales_out, float* zeros_out)
+                               float* scales_out, float* zeros_out, hipEvent_t done = nullptr)
 {
     const int G = o->group > 0 ? d / o->group : 1;
     FOBQ_TRY(ctx->scale.ensure((size_t)R * G * sizeof(double)), "workspace scale");
@@ -204,7 +204,7 @@ static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, in
     FOBQ_TRY(launch_grid(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
                          scales_out, zeros_out), "grid");
     FOBQ_TRY(launch_sens_partial(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                                 ctx->Spart.as<double>(), chunks, order_kind(o)), "sensitivity");
+                                 ctx->Spart.as<double>(), chunks, order_kind(o), done), "sensitivity");
     return FOBQ_OK;
 }
 
@@ -491,16 +491,15 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     FOBQ_TRY(ctx->DT.ensure((size_t)d * Rp * sizeof(double)), "workspace DT");
     FOBQ_TRY(ctx->codesT.ensure((size_t)d * Rp), "workspace codesT");
     FOBQ_TRY(ctx->lossrow.ensure((size_t)R * sizeof(double)), "workspace lossrow");
-    FOBQ_TRY(launch_clear_words(s, ctx->flags.p, FLAG_COUNT, ctx->lossrow.p, 2 * (int64_t)R), "clear flags and loss");
-
-    // grid and the W-only part of the column scores: on the side stream, beside the factorization
+    // grid and the W-only part of the column scores: on the side stream, beside the factorization.  The
+    // events that order the streams ride on launches (see gemm64's `done`), here on the clearing kernel.
     rc = ensure_sync_events(ctx, 2);
     if (rc) return rc;
-    FOBQ_TRY(hipEventRecord(ctx->sync_ev[0], s), "event");
+    FOBQ_TRY(launch_clear_words(s, ctx->flags.p, FLAG_COUNT, ctx->lossrow.p, 2 * (int64_t)R, ctx->sync_ev[0]),
+             "clear flags and loss");
     FOBQ_TRY(hipStreamWaitEvent(ctx->side, ctx->sync_ev[0], 0), "stream wait");
-    rc = enqueue_grid_scores(ctx, ctx->side, W, R, d, opts, out->scales, out->zeros);
+    rc = enqueue_grid_scores(ctx, ctx->side, W, R, d, opts, out->scales, out->zeros, ctx->sync_ev[1]);
     if (rc) return rc;
-    FOBQ_TRY(hipEventRecord(ctx->sync_ev[1], ctx->side), "event");
     // damp, Cholesky, inverse
     rc = enqueue_inverse(ctx, H, d, opts->damp, opts->damp_abs);
     if (rc) return rc;
@@ -508,10 +507,16 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     // column scores, order
     rc = enqueue_order(ctx, R, d, opts, ctx->Hinv.as<double>());
     if (rc) return rc;
+    // blocked path: the event that lets the column loop's stream start rides on the gather launch
+    const int nblocks = block == 1 ? 0 : (steps + block - 1) / block;
+    if (nblocks > 0) {
+        rc = ensure_sync_events(ctx, (size_t)nblocks + 2);
+        if (rc) return rc;
+    }
     {
         StageScope sc(ctx, FOBQ_STAGE_PERMUTE);
         FOBQ_TRY(launch_gather(s, W, R, d, ctx->perm.as<int>(), ctx->Hinv.as<double>(), ctx->Wp.as<double>(),
-                               ctx->A.as<double>()), "permute");
+                               ctx->A.as<double>(), nblocks > 0 ? ctx->sync_ev[nblocks] : nullptr), "permute");
     }
     double* A = ctx->A.as<double>();
     double* Wp = ctx->Wp.as<double>();
@@ -539,13 +544,9 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
         // Eq. 12 does not involve W: the elimination runs ahead on the context's stream and the
         // column loop follows on the side stream, block k as soon as the pivot rows of block k exist
         // (both are chains of short dependent launches that leave most of the GPU idle).
-        const int nblocks = (steps + block - 1) / block;
-        rc = ensure_sync_events(ctx, (size_t)nblocks + 2);
-        if (rc) return rc;
         hipStream_t side = ctx->side;
         std::vector<hipEvent_t> rows_ready(ctx->sync_ev.begin(), ctx->sync_ev.begin() + nblocks);
         hipEvent_t ev_start = ctx->sync_ev[nblocks], ev_done = ctx->sync_ev[nblocks + 1];
-        FOBQ_TRY(hipEventRecord(ev_start, s), "event");
         FOBQ_TRY(hipStreamWaitEvent(side, ev_start, 0), "stream wait");
         {
             StageScope sc(ctx, FOBQ_STAGE_ELIMINATE);
@@ -561,9 +562,10 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
                     for (waited = k; !rows_announced(waited, nblocks);) ++waited;
                     FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[waited], 0), "stream wait");
                 }
-                FOBQ_TRY(launch_chain(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
-                                      codesT, DT, Rp, lossrow), "column block");
                 const int r = d - o - nb;
+                const bool last = o + block >= steps;
+                FOBQ_TRY(launch_chain(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
+                                      codesT, DT, Rp, lossrow, (last && r <= 0) ? ev_done : nullptr), "column block");
                 if (r <= 0) break;
                 // deferred compensation of the columns right of the block:
                 // W[:, o+nb:] -= D[:, block] * Un[block, o+nb:]
@@ -573,10 +575,9 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
                 p.B = Un + (int64_t)o * d + (o + nb); p.ldb = d;
                 p.C = Wp + (o + nb); p.ldc = d;
                 p.alpha = -1.0; p.beta = 1.0;
-                FOBQ_TRY(gemm64(side, p, true, false), "column block update");
+                FOBQ_TRY(gemm64(side, p, true, false, last ? ev_done : nullptr), "column block update");
             }
         }
-        FOBQ_TRY(hipEventRecord(ev_done, side), "event");
         FOBQ_TRY(hipStreamWaitEvent(s, ev_done, 0), "stream wait");
     }
     {

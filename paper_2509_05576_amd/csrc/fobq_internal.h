@@ -55,7 +55,10 @@ struct GemmP {
     int Mtot = -1, mstep = 0;          // M_eff = min(M, Mtot - b*mstep) when Mtot >= 0
     int Ktot = -1, kstep = 0;          // K_eff likewise
 };
-hipError_t gemm64(hipStream_t s, const GemmP& p, bool TA, bool TB);
+// `done` (here and in the launchers below that take one; may be null): an event that is recorded when the launch
+// completes.  It rides on the launch as its stop event (hipExtLaunchKernelGGL): a separate hipEventRecord
+// between two dependent launches is a bubble of about 4 us on the stream.
+hipError_t gemm64(hipStream_t s, const GemmP& p, bool TA, bool TB, hipEvent_t done = nullptr);
 
 // ---------------------------------------------------------------------------
 // Stage timing (hipEvents on the context's stream), off by default.
@@ -157,7 +160,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,
                        double* scale, double* zero, float* scales_out, float* zeros_out);
 hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int bits, int group,
-                               const double* scale, const double* zero, double* Spart, int chunks, int kind);
+                               const double* scale, const double* zero, double* Spart, int chunks, int kind, hipEvent_t done = nullptr);
 hipError_t launch_sens_reduce(hipStream_t s, const double* Spart, int chunks, int d, const double* Hinv, double* S,
                               int kind);
 int sens_chunks(int R);
@@ -165,11 +168,11 @@ hipError_t launch_rank_sort(hipStream_t s, const double* S, int d, int* perm, in
 hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm);
 hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm, int* invperm, int* flag);
 hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
-                         const double* Hinv_upper, double* Wp, double* A);
+                         const double* Hinv_upper, double* Wp, double* A, hipEvent_t done = nullptr);
 hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         const double* Un, const double* U, const double* scale, const double* zero,
                         int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow);
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow, hipEvent_t done = nullptr);
 hipError_t launch_invert_perm(hipStream_t s, const int* perm, int d, int* invperm);
 hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, double* A, const double* scale,
                              const double* zero, int G, int group, int* perm, int bits, double* Spart, int chunks);
@@ -183,6 +186,7 @@ hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss
 hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);
 hipError_t launch_clear_f64(hipStream_t s, double* p, int64_t n);
-hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2);   // 4-byte words
+hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2,
+                              hipEvent_t done = nullptr);   // 4-byte words
 
 }  // namespace fobq

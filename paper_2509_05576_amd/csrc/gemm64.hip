@@ -13,6 +13,8 @@
 // then stored to LDS.  The C tile is prefetched with the first chunk.  The rank-64
 // updates (K = 64) are latency bound -- a few tiles per launch -- so a single
 // exposed memory round trip is what matters there.
+#include <hip/hip_ext.h>
+
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -120,14 +122,18 @@ __global__ __launch_bounds__(GT) void gemm64_kernel(GemmP p)
         }
 }
 
-hipError_t gemm64(hipStream_t s, const GemmP& p, bool TA, bool TB)
+hipError_t gemm64(hipStream_t s, const GemmP& p, bool TA, bool TB, hipEvent_t done)
 {
-    if (p.M <= 0 || p.N <= 0 || p.batches <= 0) return hipSuccess;
+    if (p.M <= 0 || p.N <= 0 || p.batches <= 0) {
+        if (done) return hipEventRecord(done, s);
+        return hipSuccess;
+    }
     dim3 grid((p.N + TN - 1) / TN, (p.M + TM - 1) / TM, p.batches), block(GT);
-    if (!TA && !TB) hipLaunchKernelGGL((gemm64_kernel<false, false>), grid, block, 0, s, p);
-    else if (!TA && TB) hipLaunchKernelGGL((gemm64_kernel<false, true>), grid, block, 0, s, p);
-    else if (TA && !TB) hipLaunchKernelGGL((gemm64_kernel<true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((gemm64_kernel<true, true>), grid, block, 0, s, p);
+    // `done` rides on the launch as its stop event (see fobq_internal.h)
+    if (!TA && !TB) hipExtLaunchKernelGGL((gemm64_kernel<false, false>), grid, block, 0, s, nullptr, done, 0, p);
+    else if (!TA && TB) hipExtLaunchKernelGGL((gemm64_kernel<false, true>), grid, block, 0, s, nullptr, done, 0, p);
+    else if (TA && !TB) hipExtLaunchKernelGGL((gemm64_kernel<true, false>), grid, block, 0, s, nullptr, done, 0, p);
+    else hipExtLaunchKernelGGL((gemm64_kernel<true, true>), grid, block, 0, s, nullptr, done, 0, p);
     return hipGetLastError();
 }
 

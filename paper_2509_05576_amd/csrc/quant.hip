@@ -1,4 +1,6 @@
 // Grid, sensitivity, ordering, permutation and the column loop (Section 4.2).
+#include <hip/hip_ext.h>
+
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -105,13 +107,14 @@ int sens_chunks(int R) { return (R + SENS_RC - 1) / SENS_RC; }
 
 // pass 1: per-chunk sums over the rows (needs W and the grid only)
 hipError_t launch_sens_partial(hipStream_t s, const float* W, int R, int d, int bits, int group,
-                               const double* scale, const double* zero, double* Spart, int chunks, int kind)
+                               const double* scale, const double* zero, double* Spart, int chunks, int kind,
+                               hipEvent_t done)
 {
     const int gs = group > 0 ? group : d;
     const int G = group > 0 ? d / group : 1;
     const double maxq = (double)((1 << bits) - 1);
-    hipLaunchKernelGGL(sens_partial_kernel, dim3((d + 255) / 256, chunks), dim3(256), 0, s, W, R, d, gs, G, maxq,
-                       scale, zero, Spart, kind);
+    hipExtLaunchKernelGGL(sens_partial_kernel, dim3((d + 255) / 256, chunks), dim3(256), 0, s, nullptr, done, 0, W, R, d,
+                          gs, G, maxq, scale, zero, Spart, kind);
     return hipGetLastError();
 }
 
@@ -251,9 +254,10 @@ __global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ W
 }
 
 hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
-                         const double* Hinv_upper, double* Wp, double* A)
+                         const double* Hinv_upper, double* Wp, double* A, hipEvent_t done)
 {
-    hipLaunchKernelGGL(gather_kernel, dim3(R + d, (d + 255) / 256), dim3(256), 0, s, W, R, d, perm, Hinv_upper, Wp, A);
+    hipExtLaunchKernelGGL(gather_kernel, dim3(R + d, (d + 255) / 256), dim3(256), 0, s, nullptr, done, 0, W, R, d, perm,
+                          Hinv_upper, Wp, A);
     return hipGetLastError();
 }
 
@@ -365,13 +369,13 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
 hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
                         const double* Un, const double* U, const double* scale, const double* zero,
                         int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow)
+                        uint8_t* codesT, double* DT, int Rp, double* lossrow, hipEvent_t done)
 {
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
     dim3 grid((R + CHAIN_WAVES - 1) / CHAIN_WAVES), block(64 * CHAIN_WAVES);
-    hipLaunchKernelGGL(chain_kernel, grid, block, 0, s, Wp, R, d, o, nb, Un, U, scale, zero, G, gs, perm, maxq,
-                       codesT, DT, Rp, lossrow);
+    hipExtLaunchKernelGGL(chain_kernel, grid, block, 0, s, nullptr, done, 0, Wp, R, d, o, nb, Un, U, scale, zero, G, gs,
+                          perm, maxq, codesT, DT, Rp, lossrow);
     return hipGetLastError();
 }
 
@@ -695,13 +699,13 @@ __global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* __restrict__
         if (i < n1) p1[i] = 0u; else p2[i - n1] = 0u;
     }
 }
-hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2)
+hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2, hipEvent_t done)
 {
     const int64_t n = n1 + n2;
-    if (n <= 0) return hipSuccess;
+    if (n <= 0) return done ? hipEventRecord(done, s) : hipSuccess;
     const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s,
-                       (uint32_t*)p1, n1, (uint32_t*)p2, n2);
+    hipExtLaunchKernelGGL(clear_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, nullptr,
+                          done, 0, (uint32_t*)p1, n1, (uint32_t*)p2, n2);
     return hipGetLastError();
 }
 
