@@ -57,6 +57,17 @@ StageScope::~StageScope()
     c->timer.pending[stage].push_back({e0, e1});
 }
 
+LaunchEvents stage_launch_events(fobq_ctx* c, int stage)
+{
+    LaunchEvents ev;
+    if (!(c->profiling >> stage & 1u)) return ev;
+    ev.start = take_event(c);
+    ev.stop = take_event(c);
+    if (ev.start && ev.stop) c->timer.pending[stage].push_back({ev.start, ev.stop});
+    else ev = LaunchEvents();
+    return ev;
+}
+
 // events (no timing) that order the side stream behind the context's stream and back
 static int ensure_sync_events(fobq_ctx* c, size_t n)
 {
@@ -332,10 +343,8 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     int rc = clear_slabs(ctx, n);
     if (rc) return rc;
     ctx->h_conv_c = -1;
-    {
-        StageScope sc(ctx, FOBQ_STAGE_XXT);
-        FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits), "xxt");
-    }
+    FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits,
+                        stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt");
     ctx->h_n += n;
     return FOBQ_OK;
 }
@@ -377,9 +386,9 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
         // the padded copy is stream-ordered: a later call reuses the buffer only after this launch
         FOBQ_TRY(launch_pad_maps(ctx->stream, maps, (int)n_img, (int)h, (int)w, (int)c, pad, ctx->maps_pad.as<float>()),
                  "pad maps");
-        StageScope sc(ctx, FOBQ_STAGE_XXT);
         FOBQ_TRY(launch_xxt_conv(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, k, stride,
-                                 (int)ho, (int)wo, npix, ctx->Hpart.as<double>(), ctx->h_splits), "xxt (convolution)");
+                                 (int)ho, (int)wo, npix, ctx->Hpart.as<double>(), ctx->h_splits,
+                                 stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (convolution)");
     }
     ctx->h_n += npix;
     return FOBQ_OK;

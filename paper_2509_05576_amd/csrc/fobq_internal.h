@@ -118,6 +118,12 @@ namespace fobq {
 int set_err(fobq_ctx* c, int code, const char* fmt, ...);
 int hip_err(fobq_ctx* c, hipError_t e, const char* what);
 
+// Timing of a stage that is exactly one launch: the two events ride on the launch as its start and stop
+// events (no bubble on the stream; StageScope's records cost about 4 us each).  Both null when the stage is
+// not being timed.
+struct LaunchEvents { hipEvent_t start = nullptr, stop = nullptr; };
+LaunchEvents stage_launch_events(fobq_ctx* c, int stage);
+
 struct StageScope {
     fobq_ctx* c; int stage; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr;
     StageScope(fobq_ctx* c_, int stage_, hipStream_t on = nullptr);   // on == nullptr: the context's stream
@@ -125,12 +131,14 @@ struct StageScope {
 };
 
 // hessian.hip
-hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits);
+hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits,
+                      LaunchEvents ev = LaunchEvents());
 int xxt_pick_splits(int d);
 int xxt_slabs_touched(int d, int64_t n, int splits);
 hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, int w, int c, int pad, float* out);
 hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
-                           int ho, int wo, int64_t npix, double* Hpart, int splits);
+                           int ho, int wo, int64_t npix, double* Hpart, int splits,
+                           LaunchEvents ev = LaunchEvents());
 hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
                                    int conv_c, int conv_kk);
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);

@@ -23,6 +23,8 @@
 // kernel the rows are taken tap-major (row' = (ky*k + kx)*C + c) so that consecutive rows are
 // consecutive channels, which NHWC stores contiguously; the finalize kernel of this mode puts
 // H back into the (c, ky, kx) order.
+#include <hip/hip_ext.h>
+
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -411,20 +413,21 @@ int xxt_slabs_touched(int d, int64_t n, int splits)
 
 template <int MODE>
 static void xxt_launch(hipStream_t s, int xt, int wgs, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
-                       int chunks, int64_t per_wg, int64_t total, const ConvP& cp)
+                       int chunks, int64_t per_wg, int64_t total, const ConvP& cp, LaunchEvents ev)
 {
     // pieces per tile, rounded: the number of classes of ranges (see the kernel)
     int classes = (int)((chunks + per_wg / 2) / per_wg);
     classes = classes < 1 ? 1 : (classes > wgs ? wgs : classes);
     if (xt == 128)
-        hipLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total,
-                           classes, cp);
+        hipExtLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n, Hpart,
+                              chunks, per_wg, total, classes, cp);
     else
-        hipLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, X, ld, d, n, Hpart, chunks, per_wg, total,
-                           classes, cp);
+        hipExtLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n, Hpart,
+                              chunks, per_wg, total, classes, cp);
 }
 
-hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits)
+hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits,
+                      LaunchEvents ev)
 {
     const int xt = xxt_tile(d);
     const int nt = (d + xt - 1) / xt;
@@ -435,15 +438,16 @@ hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t 
     const int wgs = (int)((total + per_wg - 1) / per_wg);
     const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     ConvP none{};
-    if (fast) xxt_launch<0>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none);
-    else      xxt_launch<1>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none);
+    if (fast) xxt_launch<0>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none, ev);
+    else      xxt_launch<1>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none, ev);
     return hipGetLastError();
 }
 
 // Convolution mode: padded = the copy written by launch_pad_maps ((n_img + 1) x hp x wp x c),
 // d = c k^2, one calibration column per output pixel; npix = n_img * ho * wo < 2^31 - 64.
 hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
-                           int ho, int wo, int64_t npix, double* Hpart, int splits)
+                           int ho, int wo, int64_t npix, double* Hpart, int splits,
+                           LaunchEvents ev)
 {
     const int d = c * k * k;
     const int xt = xxt_tile(d);
@@ -460,7 +464,7 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
     cp.div_row = fastdiv_make((uint32_t)wo);
     cp.div_c = fastdiv_make((uint32_t)c);
     cp.div_k = fastdiv_make((uint32_t)k);
-    xxt_launch<2>(s, xt, wgs, padded, 0, d, npix, Hpart, chunks, per_wg, total, cp);
+    xxt_launch<2>(s, xt, wgs, padded, 0, d, npix, Hpart, chunks, per_wg, total, cp, ev);
     return hipGetLastError();
 }
 
