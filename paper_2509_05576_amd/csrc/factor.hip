@@ -146,7 +146,8 @@ __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR
 }
 
 // Cholesky of the 64 x 64 block held in LDS.
-//   in : Am lower triangle = the block (identity padding past its size), Xm = 0
+//   in : Am lower triangle = the block (identity padding past its size); Xm need not be initialised (every
+//        entry of its lower triangle, whole diagonal 16 x 16 tiles included, is written before it is read)
 //   out: Am = L (lower; the strictly upper parts of the diagonal 16 x 16 tiles are zeroed),
 //        Xm = L^-1 (lower);  rq (64 doubles of LDS) is scratch: 1 / L[k][k]
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1 so that
@@ -295,7 +296,6 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const double* __restrict_
         double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
         if (i < nb && j < nb) v = (j <= i) ? A[(int64_t)(o + i) * ld + o + j] : 0.0;
         Am[i * DL + j] = v;
-        Xm[i * DL + j] = 0.0;
     }
     __syncthreads();
     chol_block(Am, Xm, rq, flag);
@@ -643,7 +643,6 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     __syncthreads();
     double* Am = Pi;
     double* Xm = Pj;
-    for (int idx = tid; idx < NB * NB; idx += NT) Xm[(idx >> 6) * DL + (idx & 63)] = 0.0;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -755,7 +754,7 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 // ---------------------------------------------------------------------------
 // Shared-Hinv elimination (Eq. 12) of the 64 x 64 block held in LDS.  With A11 the block,
 // U11 its pivot rows, D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
-//   in : Am = the block, full symmetric (identity padding past its size), Xm = 0
+//   in : Am = the block, full symmetric (identity padding past its size); Xm need not be initialised
 //   out: Am upper triangle = U11 (pivot row j = row j), rv[j] = 1 / pivot_j
 //        (so Un11[i][j] = Am[i][j] * rv[i]),  Xm = G = (Un11^T)^-1 (unit lower)
 // Called by all NT threads of the workgroup; ends with a barrier.
@@ -895,7 +894,6 @@ __global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict_
         double v = (i == j) ? 1.0 : 0.0;
         if (i < nb && j < nb) v = A[(int64_t)(o + min(i, j)) * ld + o + max(i, j)];   // upper triangle is the maintained one
         Am[i * DL + j] = v;
-        Xm[i * DL + j] = 0.0;
     }
     __syncthreads();
     elim_block(Am, Xm, rv, flag);
@@ -1025,7 +1023,6 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
         for (int v = 0; v < 4; ++v) {
             const int m = wr * 16 + 4 * v + fq, n = w2 * 32 + j * 16 + fr;
             Am[m * DL + n] = (m < nbn && n < nbn) ? c[j][v] : (m == n ? 1.0 : 0.0);
-            Xm[m * DL + n] = 0.0;
         }
     __syncthreads();
     elim_block(Am, Xm, rs, flag);
