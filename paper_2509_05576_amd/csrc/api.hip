@@ -286,7 +286,7 @@ int fobq_destroy(fobq_ctx* ctx)
     }
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
-                      &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->codesT, &ctx->scale, &ctx->zero,
+                      &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
                       &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
     for (DevBuf* b : bufs) b->release();
     delete ctx;
@@ -498,6 +498,7 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     FOBQ_TRY(ctx->Un.ensure(dd), "workspace Un");
     FOBQ_TRY(ctx->Wp.ensure((size_t)R * d * sizeof(double)), "workspace Wp");
     FOBQ_TRY(ctx->DT.ensure((size_t)d * Rp * sizeof(double)), "workspace DT");
+    FOBQ_TRY(ctx->corr.ensure(2 * (size_t)R * 64 * sizeof(double)), "workspace corr");
     FOBQ_TRY(ctx->codesT.ensure((size_t)d * Rp), "workspace codesT");
     FOBQ_TRY(ctx->lossrow.ensure((size_t)R * sizeof(double)), "workspace lossrow");
     // grid and the W-only part of the column scores: on the side stream, beside the factorization.  The
@@ -563,29 +564,34 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
                                        &rows_ready), "eliminate");
         }
         {
+            // One launch per block: its chain, and beside it the deferred compensation of the block before
+            // for the columns from the next block on (see col_block_kernel); the event that hands the
+            // result back to the context's stream rides on the last launch.
             StageScope sc(ctx, FOBQ_STAGE_COLUMNS, side);
+            double* corr[2] = {ctx->corr.as<double>(), ctx->corr.as<double>() + (size_t)R * 64};
             int k = 0, waited = -1;
+            int po = 0, pnb = 0;                 // the block before
             for (int o = 0; o < steps; o += block, ++k) {
                 const int nb = (block < steps - o) ? block : steps - o;
+                const bool has_next = o + nb < steps;
+                const int nb_next = has_next ? ((block < steps - o - nb) ? block : steps - o - nb) : 0;
                 if (k > waited) {
                     for (waited = k; !rows_announced(waited, nblocks);) ++waited;
                     FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[waited], 0), "stream wait");
                 }
-                const int r = d - o - nb;
-                const bool last = o + block >= steps;
-                FOBQ_TRY(launch_chain(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
-                                      codesT, DT, Rp, lossrow, (last && r <= 0) ? ev_done : nullptr), "column block");
-                if (r <= 0) break;
-                // deferred compensation of the columns right of the block:
-                // W[:, o+nb:] -= D[:, block] * Un[block, o+nb:]
-                GemmP p;
-                p.M = R; p.N = r; p.K = nb;
-                p.A = DT + (int64_t)o * Rp; p.lda = Rp;
-                p.B = Un + (int64_t)o * d + (o + nb); p.ldb = d;
-                p.C = Wp + (o + nb); p.ldc = d;
-                p.alpha = -1.0; p.beta = 1.0;
-                FOBQ_TRY(gemm64(side, p, true, false, last ? ev_done : nullptr), "column block update");
+                // the last launch of the loop: this one, unless columns are left over right of the last block
+                const bool last = !has_next && o + nb >= d;
+                FOBQ_TRY(launch_col_block(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,
+                                          codesT, DT, Rp, lossrow, k > 0 ? corr[(k - 1) & 1] : nullptr,
+                                          has_next ? corr[k & 1] : nullptr, nb_next, po, pnb, o + nb,
+                                          last ? ev_done : nullptr), "column block");
+                po = o; pnb = nb;
             }
+            // stop_after: the last processed block's compensation of all the columns that stay unprocessed
+            if (k == 0 || po + pnb < d)
+                FOBQ_TRY(launch_col_block(side, Wp, R, d, 0, 0, Un, U, scale, zero, G, opts->group, perm, opts->bits,
+                                          codesT, DT, Rp, lossrow, nullptr, nullptr, 0, po, pnb, po + pnb, ev_done),
+                         "column block update");
         }
         FOBQ_TRY(hipStreamWaitEvent(s, ev_done, 0), "stream wait");
     }

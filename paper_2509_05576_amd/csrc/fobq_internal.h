@@ -97,6 +97,7 @@ struct fobq_ctx {
     // quantization workspace
     fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
     fobq::DevBuf DT;        // d x Rp fp64: (w - q) per processed column
+    fobq::DevBuf corr;      // 2 x d_row x 64 fp64: compensation handed from one column block to the next
     fobq::DevBuf codesT;    // d x Rp u8
     fobq::DevBuf scale, zero;   // d_row x G fp64
     fobq::DevBuf S, Spart;  // d fp64, chunks x d fp64
@@ -177,10 +178,12 @@ hipError_t launch_iota(hipStream_t s, int d, int* perm, int* invperm);
 hipError_t launch_check_perm(hipStream_t s, const int* perm_in, int d, int* perm, int* invperm, int* flag);
 hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int* perm,
                          const double* Hinv_upper, double* Wp, double* A, hipEvent_t done = nullptr);
-hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
-                        const double* Un, const double* U, const double* scale, const double* zero,
-                        int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow, hipEvent_t done = nullptr);
+hipError_t launch_col_block(hipStream_t s, double* Wp, int R, int d, int o, int nb,
+                            const double* Un, const double* U, const double* scale, const double* zero,
+                            int G, int group, const int* perm, int bits,
+                            uint8_t* codesT, double* DT, int Rp, double* lossrow,
+                            const double* corr_in, double* corr_out, int nb_next,
+                            int uo, int unb, int c0, hipEvent_t done = nullptr);
 hipError_t launch_invert_perm(hipStream_t s, const int* perm, int d, int* invperm);
 hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, double* A, const double* scale,
                              const double* zero, int G, int group, int* perm, int bits, double* Spart, int chunks);

@@ -276,7 +276,7 @@ hipError_t launch_gather(hipStream_t s, const float* W, int R, int d, const int*
 // unrolled, so there is no memory access on the sequential chain.  diff is stored
 // (DT) for the deferred rank-nb update of the columns right of the block.
 constexpr int CB = 64;
-constexpr int CHAIN_WAVES = 4;
+constexpr int CHAIN_WAVES = 8;
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
 {
@@ -311,38 +311,63 @@ __device__ __forceinline__ void chain_steps(double& w, const double (&u)[64], do
     }
 }
 
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
-    double* __restrict__ Wp, int R, int d, int o, int nb, const double* __restrict__ Un,
-    const double* __restrict__ U, const double* __restrict__ scale, const double* __restrict__ zero, int G, int gs,
-    const int* __restrict__ perm, double maxq, uint8_t* __restrict__ codesT, double* __restrict__ DT, int Rp,
-    double* __restrict__ lossrow)
+// One launch per column block k does two things that do not depend on each other:
+//   (chain role, workgroups 0 .. n_chain-1)   the 64 sequential steps of block k, one row of W per wavefront;
+//   (update role, the remaining workgroups)   the deferred compensation of block k-1 for the columns from
+//                                             block k+1 on:  W[:, c0:] -= D_{k-1} Un[block k-1, c0:]
+// Block k's own columns get block k-1's compensation without waiting for that product: a row's share of it,
+// sum_j diff_j Un[o'+j][o+c], is row-local, so the wavefront that has produced the diff_j of its row in launch
+// k-1 computes it there (64 fmas per lane, `corr_out`) and this launch subtracts it when it loads its
+// columns (`corr_in`).  The sequential loop is therefore one launch per block instead of chain, product,
+// chain, ... with the product on the critical path.
+struct ColChainP {
+    double* Wp; int R, d, o, nb;
+    const double* Un; const double* U; const double* scale; const double* zero; int G, gs;
+    const int* perm; double maxq; uint8_t* codesT; double* DT; int Rp; double* lossrow;
+    const double* corr_in; double* corr_out; int nb_next;
+};
+struct ColUpdateP {
+    int tiles_n;                 // column tiles of the update (0: no update in this launch)
+    int o, nb, c0;               // block whose compensation is applied, first column it is applied to
+};
+
+__device__ __forceinline__ void col_chain_role(const ColChainP& c, double* lds, int wg)
 {
-    // the block's pivot rows, fetched once per workgroup (every row of W needs all of them)
-    __shared__ double Us[CB][CB + 1];
+    // the block's pivot rows, fetched once per workgroup (every row of W needs all of them): the part
+    // inside the block, and (corr_out != null) the part above the next block's columns
+    double (*Us)[CB + 1] = reinterpret_cast<double (*)[CB + 1]>(lds);
+    double (*Vs)[CB + 1] = reinterpret_cast<double (*)[CB + 1]>(lds + CB * (CB + 1));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int o = c.o, nb = c.nb, d = c.d;
     const bool col_ok = lane < nb;
     const int cl = col_ok ? lane : 0;        // safe column for address arithmetic
     {
-        double t[CB / CHAIN_WAVES];
+        double t[CB / CHAIN_WAVES], v[CB / CHAIN_WAVES];
+        const int cn = min(lane, max(c.nb_next, 1) - 1);
 #pragma unroll
         for (int i = 0; i < CB / CHAIN_WAVES; ++i) {
             const int j = wave + CHAIN_WAVES * i;
-            t[i] = Un[(int64_t)(o + min(j, nb - 1)) * d + o + cl];
+            t[i] = c.Un[(int64_t)(o + min(j, nb - 1)) * d + o + cl];
+            v[i] = c.corr_out ? c.Un[(int64_t)(o + min(j, nb - 1)) * d + o + nb + cn] : 0.0;
         }
 #pragma unroll
-        for (int i = 0; i < CB / CHAIN_WAVES; ++i) Us[wave + CHAIN_WAVES * i][lane] = t[i];
+        for (int i = 0; i < CB / CHAIN_WAVES; ++i) {
+            Us[wave + CHAIN_WAVES * i][lane] = t[i];
+            Vs[wave + CHAIN_WAVES * i][lane] = v[i];
+        }
     }
-    const int row = blockIdx.x * CHAIN_WAVES + wave;
-    const int rw = min(row, R - 1);
-    double* __restrict__ wptr = Wp + (int64_t)rw * d + o + cl;
-    const double w0 = *wptr;
-    int pj = perm[o + cl];
+    const int row = wg * CHAIN_WAVES + wave;
+    const int rw = min(row, c.R - 1);
+    double* __restrict__ wptr = c.Wp + (int64_t)rw * d + o + cl;
+    double w0 = *wptr;
+    if (c.corr_in) w0 -= c.corr_in[(int64_t)rw * CB + cl];
+    int pj = c.perm[o + cl];
     pj = min(max(pj, 0), d - 1);
-    const int64_t gi = (int64_t)rw * G + pj / gs;
-    const double s = scale[gi], z = zero[gi];
-    const double hp = 0.5 / U[(int64_t)(o + cl) * d + o + cl];
+    const int64_t gi = (int64_t)rw * c.G + pj / c.gs;
+    const double s = c.scale[gi], z = c.zero[gi];
+    const double hp = 0.5 / c.U[(int64_t)(o + cl) * d + o + cl];
     __syncthreads();
-    if (row >= R) return;                    // whole wavefront leaves; no barrier after this point
+    if (row >= c.R) return;                  // whole wavefront leaves; no barrier after this point
     double u[CB];
 #pragma unroll
     for (int j = 0; j < CB; ++j)
@@ -350,32 +375,110 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(
 
     double w = w0, mycode = 0.0, mydiff = 0.0;
     bool suspect = false;
-    chain_steps<false>(w, u, s, z, maxq, nb, lane, mycode, mydiff, suspect);
+    chain_steps<false>(w, u, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
     if (__any(suspect)) {                    // wavefront-uniform; practically never taken
         w = w0;
-        chain_steps<true>(w, u, s, z, maxq, nb, lane, mycode, mydiff, suspect);
+        chain_steps<true>(w, u, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
     }
     if (col_ok) {
-        codesT[(int64_t)(o + lane) * Rp + row] = (uint8_t)mycode;
-        DT[(int64_t)(o + lane) * Rp + row] = mydiff;
+        c.codesT[(int64_t)(o + lane) * c.Rp + row] = (uint8_t)mycode;
+        c.DT[(int64_t)(o + lane) * c.Rp + row] = mydiff;
         *wptr = w;
+    }
+    if (c.corr_out) {
+        // lane n: sum over the block's columns j of diff_j Un[o+j][o+nb+n]   (lanes >= nb hold diff 0)
+        const double dk = col_ok ? mydiff : 0.0;
+        double acc = 0.0;
+#pragma unroll
+        for (int k = 0; k < CB; ++k) acc = fma(readlane_f64(dk, k), Vs[k][lane], acc);
+        if (lane < c.nb_next) c.corr_out[(int64_t)row * CB + lane] = acc;
     }
     double loss = col_ok ? mydiff * mydiff * hp : 0.0;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
-    if (lane == 0) lossrow[row] += loss;
+    if (lane == 0) c.lossrow[row] += loss;
 }
 
-hipError_t launch_chain(hipStream_t s, double* Wp, int R, int d, int o, int nb,
-                        const double* Un, const double* U, const double* scale, const double* zero,
-                        int G, int group, const int* perm, int bits,
-                        uint8_t* codesT, double* DT, int Rp, double* lossrow, hipEvent_t done)
+// 64 x 64 tile (ty, tx) of W[:, c0:] -= D^T Un[o : o+nb, c0:], D = DT[o : o+nb, :] (nb x Rp): one chunk of K.
+__device__ __forceinline__ void col_update_role(const ColChainP& c, const ColUpdateP& u, double* lds, int t)
 {
-    const int gs = group > 0 ? group : d;
-    const double maxq = (double)((1 << bits) - 1);
-    dim3 grid((R + CHAIN_WAVES - 1) / CHAIN_WAVES), block(64 * CHAIN_WAVES);
-    hipExtLaunchKernelGGL(chain_kernel, grid, block, 0, s, nullptr, done, 0, Wp, R, d, o, nb, Un, U, scale, zero, G, gs,
-                          perm, maxq, codesT, DT, Rp, lossrow);
+    typedef double d4 __attribute__((ext_vector_type(4)));
+    constexpr int LD = CB + 2;
+    double (*As)[LD] = reinterpret_cast<double (*)[LD]>(lds);            // As[m][k] = D[k][m0 + m]
+    double (*Bs)[LD] = reinterpret_cast<double (*)[LD]>(lds + CB * LD);   // Bs[n][k] = Un[o + k][n0 + n]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ty = t / u.tiles_n, tx = t - ty * u.tiles_n;
+    const int m0 = ty * 64, n0 = u.c0 + tx * 64;
+    const int d = c.d;
+    double ra[8], rb[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int k = wave + 8 * i;
+        const bool kv = k < u.nb;
+        const int kk = u.o + min(k, u.nb - 1);
+        ra[i] = (kv && m0 + lane < c.R) ? c.DT[(int64_t)kk * c.Rp + m0 + lane] : 0.0;
+        rb[i] = (kv && n0 + lane < d) ? c.Un[(int64_t)kk * d + min(n0 + lane, d - 1)] : 0.0;
+    }
+    const int wr = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
+    d4 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int gm = m0 + wr * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
+            acc[j][v] = (gm < c.R && gn < d) ? c.Wp[(int64_t)gm * d + gn] : 0.0;
+        }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        As[lane][wave + 8 * i] = -ra[i];
+        Bs[lane][wave + 8 * i] = rb[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        const double a = As[wr * 16 + fr][4 * ks + fq];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Bs[wn * 32 + j * 16 + fr][4 * ks + fq], acc[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int gm = m0 + wr * 16 + 4 * v + fq, gn = n0 + wn * 32 + j * 16 + fr;
+            if (gm < c.R && gn < d) c.Wp[(int64_t)gm * d + gn] = acc[j][v];
+        }
+}
+
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void col_block_kernel(ColChainP c, ColUpdateP u, int n_chain)
+{
+    __shared__ double lds[2 * CB * (CB + 2)];
+    if ((int)blockIdx.x < n_chain) col_chain_role(c, lds, (int)blockIdx.x);
+    else col_update_role(c, u, lds, (int)blockIdx.x - n_chain);
+}
+
+// chain: block [o, o+nb) (nb = 0: no chain in this launch); update: the compensation of block [uo, uo+unb) for
+// the columns from c0 on (unb = 0 or c0 >= d: no update in this launch)
+hipError_t launch_col_block(hipStream_t s, double* Wp, int R, int d, int o, int nb,
+                            const double* Un, const double* U, const double* scale, const double* zero,
+                            int G, int group, const int* perm, int bits,
+                            uint8_t* codesT, double* DT, int Rp, double* lossrow,
+                            const double* corr_in, double* corr_out, int nb_next,
+                            int uo, int unb, int c0, hipEvent_t done)
+{
+    ColChainP c;
+    c.Wp = Wp; c.R = R; c.d = d; c.o = o; c.nb = nb; c.Un = Un; c.U = U; c.scale = scale; c.zero = zero;
+    c.G = G; c.gs = group > 0 ? group : d; c.perm = perm; c.maxq = (double)((1 << bits) - 1);
+    c.codesT = codesT; c.DT = DT; c.Rp = Rp; c.lossrow = lossrow;
+    c.corr_in = corr_in; c.corr_out = corr_out; c.nb_next = nb_next;
+    ColUpdateP u;
+    u.o = uo; u.nb = unb; u.c0 = c0;
+    u.tiles_n = (unb > 0 && c0 < d) ? (d - c0 + 63) / 64 : 0;
+    const int n_chain = nb > 0 ? (R + CHAIN_WAVES - 1) / CHAIN_WAVES : 0;
+    const int n_upd = u.tiles_n * ((R + 63) / 64);
+    if (n_chain + n_upd == 0) return done ? hipEventRecord(done, s) : hipSuccess;
+    hipExtLaunchKernelGGL(col_block_kernel, dim3(n_chain + n_upd), dim3(64 * CHAIN_WAVES), 0, s, nullptr, done, 0, c, u,
+                          n_chain);
     return hipGetLastError();
 }
 
