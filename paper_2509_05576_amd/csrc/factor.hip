@@ -36,12 +36,26 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
 // launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
 constexpr int DENSE_LAUNCH_TILES = 1024;
+constexpr int SWEEP_LDS = NB + 16 * NB;   // doubles of LDS that chol_block / elim_block need besides the two tiles
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
 {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Pivot of step k of a sweep: the diagonal entry that lane `lane` keeps in dg, as a wavefront-uniform
+// value.  A pivot that is not a positive normal number below 2^996 sets `bad`; it is used as it is
+// (the results are then not defined, possibly not finite: the caller reports ENOTPD, and nothing
+// downstream derives an address or a trip count from them).  The test is on the high word of the
+// uniform value, on the scalar unit, and nothing waits for it: it is not on the sequential path.
+__device__ __forceinline__ double pivot_fetch(double dg, int lane, bool& bad)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(dg), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(dg), lane);
+    bad = bad || (unsigned)(hi - 0x00100000) >= (unsigned)(0x7E300000 - 0x00100000);
     return __hiloint2double(hi, lo);
 }
 
@@ -148,8 +162,8 @@ __device__ __forceinline__ void block_schedule(double* Xm, SW sweep, TI tinv, TR
 // Cholesky of the 64 x 64 block held in LDS.
 //   in : Am lower triangle = the block (identity padding past its size); Xm need not be initialised (every
 //        entry of its lower triangle, whole diagonal 16 x 16 tiles included, is written before it is read)
-//   out: Am = L (lower; the strictly upper parts of the diagonal 16 x 16 tiles are zeroed),
-//        Xm = L^-1 (lower);  rq (64 doubles of LDS) is scratch: 1 / L[k][k]
+//   out: Am = L (lower; what is above the diagonal is not defined),
+//        Xm = L^-1 (lower);  rq (SWEEP_LDS doubles of LDS) is scratch: 1 / L[k][k], then the sweep columns
 //   flag: set to 1 when a pivot is <= 0 or not finite (the pivot is replaced by 1 so that
 //         the arithmetic stays finite; the caller reports ENOTPD).
 // Called by all NT threads of the workgroup; ends with a barrier.
@@ -157,6 +171,7 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
+    double* cb = rq + NB;      // 16 x 64: the columns of the running sweep
 
     // Right-looking Cholesky of the 16 columns base .. base+15 of the block over all rows
     // >= base: lane rho holds row rho.  Rows inside the diagonal tile (0 <= r < 16) hold the
@@ -168,11 +183,10 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
         // as if they were rows below the tile: those become I L_bb^-T, i.e. lane c ends with column c of
         // X_bb = L_bb^-1, for the price of no extra instruction.
         const bool idl = b > 0 && lane < 16;
-        const int rr = idl ? 64 : r;      // row position as far as "below pivot k" (rr > k) goes
         double a[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            a[j] = (j <= r) ? Am[rho * DL + base + j] : Am[(base + j) * DL + rho];
+            a[j] = Am[rho * DL + base + j];       // columns j > r of a tile row: never used
             if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
         }
         // Each lane of the tile also keeps its own diagonal entry in `dg` and updates it locally
@@ -180,27 +194,35 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
         // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
         // rank-1 update of the rest fills the latency.
         double dg = Am[rho * DL + rho];
-        double own = 0.0;
+        double own = 0.0, tp = 0.0, lb[16];
         bool bad = false;
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            double piv = readlane_f64(dg, base + k);
-            const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-            bad = bad || b2;
-            piv = b2 ? 1.0 : piv;
+            const double piv = pivot_fetch(dg, base + k, bad);
             const double rs = pivot_rsqrt(piv);                    // 1 / L[k][k]
             own = (r == k) ? rs : own;
-            const double t = (r == k) ? piv * rs : a[k] * rs;      // l_rk for r >= k
-            const double lm = (rr > k) ? t : 0.0;
-            dg -= lm * lm;
+            // l_rk for r >= k (lane k's a[k] has had the same updates as its dg: it is the pivot).  Lanes
+            // of rows above the pivot go through the same arithmetic on entries that are never stored.
+            const double t = a[k] * rs;
+            dg -= t * t;
             a[k] = t;
+            // Rank-1 update of the columns behind: the next column takes l_jk by readlane (it is on the
+            // sequential path), the others take it one step late as a broadcast read of the column that
+            // every lane leaves in LDS: half an instruction per column instead of two readlanes.
+            cb[k * NB + lane] = t;
+            if (k > 0) {
 #pragma unroll
-            for (int j = k + 1; j < 16; ++j) a[j] -= lm * readlane_f64(t, base + j);
+                for (int j = k + 1; j < 16; ++j) a[j] -= tp * lb[j];
+            }
+            if (k < 15) a[k + 1] -= t * readlane_f64(t, base + k + 1);
+#pragma unroll
+            for (int j = k + 2; j < 16; ++j) lb[j] = cb[k * NB + base + j];   // in flight during the next pivot
+            tp = t;
         }
         if (bad && lane == 0) *flag = 1;
         if (r >= 0) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) Am[rho * DL + base + j] = (j <= r) ? a[j] : 0.0;
+            for (int j = 0; j < 16; ++j) Am[rho * DL + base + j] = a[j];
             if (r < 16) rq[rho] = own;
         }
         if (idl) {
@@ -290,7 +312,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const double* __restrict_
 {
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
-    __shared__ double rq[NB];
+    __shared__ double rq[SWEEP_LDS];
     for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
@@ -537,20 +559,23 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
                                                        int* __restrict__ flag, int ntrail, int ninv,
                                                        double* __restrict__ Sacc, double* __restrict__ Hinv)
 {
-    __shared__ double lds[2 * NB * DL + NB];  // two tiles: 2 workgroups per compute unit
+    // sweep scratch first (its broadcast reads then have constant addresses below 64 KB, i.e. no address
+    // register), then two tiles: 2 workgroups per compute unit
+    __shared__ double lds[SWEEP_LDS + 2 * NB * DL];
+    double* tiles = lds + SWEEP_LDS;
     if ((int)blockIdx.x >= ntrail + ninv) {
         int nt, mt;
         tri_decode((int)blockIdx.x - ntrail - ninv, nt, mt);          // mt <= nt <= o / 64 - 1
-        chol_lauum_tile(lds, d, o / NB - 1, mt, nt, Linv, Hinv);
+        chol_lauum_tile(tiles, d, o / NB - 1, mt, nt, Linv, Hinv);
         return;
     }
     if ((int)blockIdx.x >= ntrail) {
         const int pcols = o / NB + 1, e = (int)blockIdx.x - ntrail;
-        chol_inverse_tile(lds, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
+        chol_inverse_tile(tiles, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
         return;
     }
-    double* Pi = lds;
-    double* Pj = lds + NB * DL;
+    double* Pi = tiles;
+    double* Pj = tiles + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
@@ -651,7 +676,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
             Am[m * DL + n] = (m < nbn && n < nbn) ? c[j][v] : (m == n ? 1.0 : 0.0);
         }
     __syncthreads();
-    chol_block(Am, Xm, lds + 2 * NB * DL, flag);
+    chol_block(Am, Xm, lds, flag);
     chol_block_store(Am, Xm, d, r0, nbn, L, Linv, Dinv_next);
 }
 
@@ -762,6 +787,7 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
+    double* cb = rv + NB;      // 16 x 64: the pivot rows of the running sweep
 
     // Elimination of the 16 pivots base .. base+15 over all columns >= base: lane c holds
     // column c of the 16 pivot rows.  Columns inside the diagonal tile (0 <= r < 16) hold the
@@ -773,37 +799,42 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
         // identity as if they were columns right of the tile: those become G_bb I, i.e. lane c ends with
         // column c of G_bb = (Un_bb^T)^-1.
         const bool idl = b > 0 && lane < 16;
-        const int rr = idl ? 64 : r;      // column position as far as "right of pivot k" (rr > k) goes
         double a[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            a[j] = Am[(base + min(r, j)) * DL + base + max(r, j)];
+            a[j] = Am[(base + j) * DL + c];       // rows j > r of a tile column: never used
             if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
         }
         // as in chol_block: every lane of the tile keeps its own diagonal entry in `dg`
         double dg = Am[c * DL + c];
-        double own = 0.0;
+        double own = 0.0, fp = 0.0, lb[16];
         bool bad = false;
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            double piv = readlane_f64(dg, base + k);
-            const bool b2 = !(piv > 0.0) || !(piv < 1.0e300);
-            bad = bad || b2;
-            piv = b2 ? 1.0 : piv;
+            const double piv = pivot_fetch(dg, base + k, bad);
             const double pi = pivot_rcp(piv);
             own = (r == k) ? pi : own;
-            const double cr = (r == k) ? piv : a[k];          // A[k][c] = U[k][c] for c >= k
-            const double fm = (rr > k) ? cr * pi : 0.0;       // Un[k][c]
+            // A[k][c] = U[k][c] for c >= k (lane k's a[k] has had the same updates as its dg: it is the
+            // pivot).  Lanes of columns left of the pivot go through the same arithmetic on entries that
+            // are never stored.
+            const double cr = a[k];
+            const double fm = cr * pi;                        // Un[k][c]
             dg -= fm * cr;
-            a[k] = cr;
+            // as in chol_block: the next row by readlane, the others one step late from LDS
+            cb[k * NB + lane] = cr;
+            if (k > 0) {
 #pragma unroll
-            for (int j = k + 1; j < 16; ++j) a[j] -= fm * readlane_f64(cr, base + j);
+                for (int j = k + 1; j < 16; ++j) a[j] -= fp * lb[j];
+            }
+            if (k < 15) a[k + 1] -= fm * readlane_f64(cr, base + k + 1);
+#pragma unroll
+            for (int j = k + 2; j < 16; ++j) lb[j] = cb[k * NB + base + j];   // in flight during the next pivot
+            fp = fm;
         }
         if (bad && lane == 0) *flag = 1;
         if (r >= 0) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
-                if (k <= r) Am[(base + k) * DL + c] = a[k];   // U[k][c] for k <= c
+            for (int k = 0; k < 16; ++k) Am[(base + k) * DL + c] = a[k];   // U[k][c] for k <= c
             if (r < 16) rv[c] = own;
         }
         if (idl) {
@@ -888,7 +919,7 @@ __global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict_
 {
     __shared__ double Am[NB * DL];
     __shared__ double Xm[NB * DL];
-    __shared__ double rv[NB];
+    __shared__ double rv[SWEEP_LDS];
     for (int idx = threadIdx.x; idx < NB * NB; idx += NT) {
         const int i = idx >> 6, j = idx & 63;
         double v = (i == j) ? 1.0 : 0.0;
@@ -915,10 +946,10 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
                                                        double* __restrict__ G_next, double* __restrict__ rinv_next,
                                                        int* __restrict__ flag)
 {
-    __shared__ double lds[2 * NB * DL + NB];   // two tiles: 2 workgroups per compute unit
-    double* Pi = lds;
-    double* Pj = lds + NB * DL;
-    double* rs = lds + 2 * NB * DL;
+    __shared__ double lds[SWEEP_LDS + 2 * NB * DL];   // sweep scratch, two tiles: 2 workgroups per compute unit
+    double* Pi = lds + SWEEP_LDS;
+    double* Pj = Pi + NB * DL;
+    double* rs = lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
