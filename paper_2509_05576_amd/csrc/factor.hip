@@ -35,27 +35,15 @@ constexpr int NB = 64;
 typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
 // launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
-constexpr int DENSE_LAUNCH_TILES = 1024;
-constexpr int SWEEP_LDS = NB + 16 * NB;   // doubles of LDS that chol_block / elim_block need besides the two tiles
+constexpr int DENSE_LAUNCH_TILES = 600;
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
+constexpr int CB0 = 48, CB_LEN = CB0 + 16 * 16 + 48;   // sweep column buffer: see chol_block
+constexpr int SWEEP_LDS = NB + CB_LEN + 16 * DL;   // doubles of LDS that chol_block / elim_block need besides the two tiles
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
 {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
-    return __hiloint2double(hi, lo);
-}
-
-// Pivot of step k of a sweep: the diagonal entry that lane `lane` keeps in dg, as a wavefront-uniform
-// value.  A pivot that is not a positive normal number below 2^996 sets `bad`; it is used as it is
-// (the results are then not defined, possibly not finite: the caller reports ENOTPD, and nothing
-// downstream derives an address or a trip count from them).  The test is on the high word of the
-// uniform value, on the scalar unit, and nothing waits for it: it is not on the sequential path.
-__device__ __forceinline__ double pivot_fetch(double dg, int lane, bool& bad)
-{
-    const int lo = __builtin_amdgcn_readlane(__double2loint(dg), lane);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(dg), lane);
-    bad = bad || (unsigned)(hi - 0x00100000) >= (unsigned)(0x7E300000 - 0x00100000);
     return __hiloint2double(hi, lo);
 }
 
@@ -171,7 +159,12 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    double* cb = rq + NB;      // 16 x 64: the columns of the running sweep
+    // The columns of the running sweep: column k at cb[CB0 + 16 k + r], r = row - tile base.  Only the
+    // 16 tile rows are read; what the other lanes write falls into the slots of neighbouring columns,
+    // which is harmless: a column is read right after it is written, before the next one is written.
+    double* cb = rq + NB;
+    double* idt = cb + CB_LEN; // 16 rows of the identity, row stride DL (read from the second sweep on)
+    if (tid < 256) idt[(tid >> 4) * DL + (tid & 15)] = (tid >> 4) == (tid & 15) ? 1.0 : 0.0;
 
     // Right-looking Cholesky of the 16 columns base .. base+15 of the block over all rows
     // >= base: lane rho holds row rho.  Rows inside the diagonal tile (0 <= r < 16) hold the
@@ -183,24 +176,21 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
         // as if they were rows below the tile: those become I L_bb^-T, i.e. lane c ends with column c of
         // X_bb = L_bb^-1, for the price of no extra instruction.
         const bool idl = b > 0 && lane < 16;
+        // one row of 16 per lane: its own (columns j > r of a tile row are never used), or a row of the identity
+        const double* src = idl ? idt + lane * DL : Am + rho * DL + base;
         double a[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            a[j] = Am[rho * DL + base + j];       // columns j > r of a tile row: never used
-            if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
-        }
+        for (int j = 0; j < 16; ++j) a[j] = src[j];
         // Each lane of the tile also keeps its own diagonal entry in `dg` and updates it locally
         // (dg -= l_rk^2), so the pivot of step k+1 is available one fma after l_rk: the
-        // sequential chain per step is readlane, reciprocal square root, multiply, fma; the
-        // rank-1 update of the rest fills the latency.
+        // sequential chain per step is readlane, reciprocal square root, multiply, fma.  A wavefront on
+        // its own issues an instruction of any kind every 5 to 8 cycles, so the sweep costs its
+        // instruction count: nothing sits in the loop that can be done once after it.
         double dg = Am[rho * DL + rho];
-        double own = 0.0, tp = 0.0, lb[16];
-        bool bad = false;
+        double tp = 0.0, lb[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const double piv = pivot_fetch(dg, base + k, bad);
-            const double rs = pivot_rsqrt(piv);                    // 1 / L[k][k]
-            own = (r == k) ? rs : own;
+            const double rs = pivot_rsqrt(readlane_f64(dg, base + k));     // 1 / L[k][k]
             // l_rk for r >= k (lane k's a[k] has had the same updates as its dg: it is the pivot).  Lanes
             // of rows above the pivot go through the same arithmetic on entries that are never stored.
             const double t = a[k] * rs;
@@ -209,21 +199,26 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
             // Rank-1 update of the columns behind: the next column takes l_jk by readlane (it is on the
             // sequential path), the others take it one step late as a broadcast read of the column that
             // every lane leaves in LDS: half an instruction per column instead of two readlanes.
-            cb[k * NB + lane] = t;
+            cb[CB0 + 16 * k + r] = t;
             if (k > 0) {
 #pragma unroll
                 for (int j = k + 1; j < 16; ++j) a[j] -= tp * lb[j];
             }
             if (k < 15) a[k + 1] -= t * readlane_f64(t, base + k + 1);
 #pragma unroll
-            for (int j = k + 2; j < 16; ++j) lb[j] = cb[k * NB + base + j];   // in flight during the next pivot
+            for (int j = k + 2; j < 16; ++j) lb[j] = cb[CB0 + 16 * k + j];   // in flight during the next pivot
             tp = t;
         }
-        if (bad && lane == 0) *flag = 1;
         if (r >= 0) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) Am[rho * DL + base + j] = a[j];
-            if (r < 16) rq[rho] = own;
+            if (r < 16) {
+                // A pivot that is not a positive normal number (nor anything after it) leaves no positive
+                // finite L[r][r] behind: one test per tile row after the sweep instead of one per pivot.
+                const double lrr = Am[rho * DL + rho];
+                if (!(lrr > 0.0) || !(lrr < 1.0e300)) *flag = 1;
+                rq[rho] = pivot_rcp(lrr);
+            }
         }
         if (idl) {
 #pragma unroll
@@ -787,7 +782,9 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, fq = lane >> 4;
-    double* cb = rv + NB;      // 16 x 64: the pivot rows of the running sweep
+    double* cb = rv + NB;      // the pivot rows of the running sweep, laid out as in chol_block
+    double* idt = cb + CB_LEN; // 16 rows of the identity, row stride DL (read from the second sweep on)
+    if (tid < 256) idt[(tid >> 4) * DL + (tid & 15)] = (tid >> 4) == (tid & 15) ? 1.0 : 0.0;
 
     // Elimination of the 16 pivots base .. base+15 over all columns >= base: lane c holds
     // column c of the 16 pivot rows.  Columns inside the diagonal tile (0 <= r < 16) hold the
@@ -799,21 +796,17 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
         // identity as if they were columns right of the tile: those become G_bb I, i.e. lane c ends with
         // column c of G_bb = (Un_bb^T)^-1.
         const bool idl = b > 0 && lane < 16;
+        // one column of 16 per lane: its own (rows j > r of a tile column are never used), or one of the identity
+        const double* src = idl ? idt + lane : Am + base * DL + c;
         double a[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            a[j] = Am[(base + j) * DL + c];       // rows j > r of a tile column: never used
-            if (idl) a[j] = (j == lane) ? 1.0 : 0.0;
-        }
+        for (int j = 0; j < 16; ++j) a[j] = src[j * DL];
         // as in chol_block: every lane of the tile keeps its own diagonal entry in `dg`
         double dg = Am[c * DL + c];
-        double own = 0.0, fp = 0.0, lb[16];
-        bool bad = false;
+        double fp = 0.0, lb[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const double piv = pivot_fetch(dg, base + k, bad);
-            const double pi = pivot_rcp(piv);
-            own = (r == k) ? pi : own;
+            const double pi = pivot_rcp(readlane_f64(dg, base + k));
             // A[k][c] = U[k][c] for c >= k (lane k's a[k] has had the same updates as its dg: it is the
             // pivot).  Lanes of columns left of the pivot go through the same arithmetic on entries that
             // are never stored.
@@ -821,21 +814,25 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
             const double fm = cr * pi;                        // Un[k][c]
             dg -= fm * cr;
             // as in chol_block: the next row by readlane, the others one step late from LDS
-            cb[k * NB + lane] = cr;
+            cb[CB0 + 16 * k + r] = cr;
             if (k > 0) {
 #pragma unroll
                 for (int j = k + 1; j < 16; ++j) a[j] -= fp * lb[j];
             }
             if (k < 15) a[k + 1] -= fm * readlane_f64(cr, base + k + 1);
 #pragma unroll
-            for (int j = k + 2; j < 16; ++j) lb[j] = cb[k * NB + base + j];   // in flight during the next pivot
+            for (int j = k + 2; j < 16; ++j) lb[j] = cb[CB0 + 16 * k + j];   // in flight during the next pivot
             fp = fm;
         }
-        if (bad && lane == 0) *flag = 1;
         if (r >= 0) {
 #pragma unroll
             for (int k = 0; k < 16; ++k) Am[(base + k) * DL + c] = a[k];   // U[k][c] for k <= c
-            if (r < 16) rv[c] = own;
+            if (r < 16) {
+                // a pivot that is not a positive normal number leaves such a value, or a NaN, on the diagonal
+                const double piv = Am[c * DL + c];
+                if (!(piv > 0.0) || !(piv < 1.0e300)) *flag = 1;
+                rv[c] = pivot_rcp(piv);
+            }
         }
         if (idl) {
 #pragma unroll
