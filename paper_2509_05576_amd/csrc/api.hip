@@ -157,7 +157,8 @@ static int enqueue_inverse(fobq_ctx* ctx, const double* H, int d, double damp, d
         // its critical path) while the launches are small; for large d the extra tiles would slow the launches down by
         // more than the separate recursive-doubling inverse costs
         const bool fused_inverse = d <= FUSED_INVERSE_MAX_D;
-        FOBQ_TRY(cholesky_lower(ctx, Hd, L, d, Linv, flags + FLAG_NOTPD_H, fused_inverse ? ctx->T.as<double>() : nullptr,
+        // nothing reads L itself when the inverse rides along: it is not stored then
+        FOBQ_TRY(cholesky_lower(ctx, Hd, fused_inverse ? nullptr : L, d, Linv, flags + FLAG_NOTPD_H, fused_inverse ? ctx->T.as<double>() : nullptr,
                                 ctx->Hinv.as<double>()), "cholesky");
         fused = fused_inverse;
     }
@@ -321,8 +322,7 @@ static int clear_slabs(fobq_ctx* ctx, int64_t n)
 {
     const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
     if (need > ctx->h_zeroed) {
-        const int64_t dd = (int64_t)ctx->h_d * ctx->h_d;
-        FOBQ_TRY(launch_clear_f64(ctx->stream, ctx->Hpart.as<double>() + dd * ctx->h_zeroed, dd * (need - ctx->h_zeroed)),
+        FOBQ_TRY(launch_clear_slabs(ctx->stream, ctx->Hpart.as<double>(), (int)ctx->h_d, ctx->h_zeroed, need - ctx->h_zeroed),
                  "clear Hessian accumulator");
         ctx->h_zeroed = need;
     }

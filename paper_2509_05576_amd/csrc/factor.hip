@@ -289,7 +289,7 @@ __device__ __forceinline__ void chol_block_store(const double* Am, const double*
         frag_source(idx, fi, fj);
         Dinv[idx] = (fi < nb && fj <= fi) ? Xm[fi * DL + fj] : 0.0;     // fj <= fi < nb
         if (in) {
-            L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? Am[i * DL + j] : 0.0;
+            if (L) L[(int64_t)(o + i) * ld + o + j] = (j <= i) ? Am[i * DL + j] : 0.0;
             Linv[(int64_t)(o + i) * ld + o + j] = xv;
         }
     }
@@ -638,7 +638,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
             const int m = wr * 16 + 4 * v + fq, n = ct[j] * 16 + fr;
             Pi[m * DL + n] = li[j][v];
             if (!diag_tile) Pj[m * DL + n] = lj[j][v];
-            if (tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[j][v];
+            if (L && tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[j][v];
         }
     __syncthreads();
     const double* Qj = diag_tile ? Pi : Pj;
@@ -676,7 +676,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
 }
 
 // H_d = L L^T.  One stand-alone launch for the first diagonal block, then one fused launch
-// per 64-column panel.
+// per 64-column panel.  L may be null when only the inverse is wanted (Sacc != null): it is not stored then.
 hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Linv, int* flag, double* Sacc,
                           double* Hinv)
 {

@@ -136,6 +136,7 @@ hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t 
                       LaunchEvents ev = LaunchEvents());
 int xxt_pick_splits(int d);
 int xxt_slabs_touched(int d, int64_t n, int splits);
+hipError_t launch_clear_slabs(hipStream_t s, double* Hpart, int d, int first, int count);
 hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, int w, int c, int pad, float* out);
 hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
                            int ho, int wo, int64_t npix, double* Hpart, int splits,
@@ -196,7 +197,6 @@ hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int 
 hipError_t launch_loss(hipStream_t s, const double* lossrow, int R, double* loss);
 hipError_t launch_hinv_work(hipStream_t s, const double* A, int d, int steps, double* out);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v);
-hipError_t launch_clear_f64(hipStream_t s, double* p, int64_t n);
 hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int64_t n2,
                               hipEvent_t done = nullptr);   // 4-byte words
 

@@ -411,6 +411,23 @@ int xxt_slabs_touched(int d, int64_t n, int splits)
     return (int)(p < splits ? p : splits);
 }
 
+// Zero the part of the slabs [first, first + count) that xxt_kernel adds into and the finalize kernels read:
+// the tiles on and below the diagonal, i.e. in row a the columns up to the end of its diagonal tile.
+__global__ __launch_bounds__(256) void clear_slabs_kernel(double* __restrict__ Hpart, int d, int xt, int first)
+{
+    const int a = blockIdx.x;
+    const int lim = min(d, (a / xt + 1) * xt);
+    double* __restrict__ row = Hpart + ((int64_t)(first + blockIdx.y) * d + a) * d;
+    for (int c = threadIdx.x; c < lim; c += 256) row[c] = 0.0;
+}
+
+hipError_t launch_clear_slabs(hipStream_t s, double* Hpart, int d, int first, int count)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(clear_slabs_kernel, dim3(d, count), dim3(256), 0, s, Hpart, d, xxt_tile(d), first);
+    return hipGetLastError();
+}
+
 template <int MODE>
 static void xxt_launch(hipStream_t s, int xt, int wgs, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
                        int chunks, int64_t per_wg, int64_t total, const ConvP& cp, LaunchEvents ev)

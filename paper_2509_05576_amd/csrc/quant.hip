@@ -812,27 +812,6 @@ hipError_t launch_clear_words(hipStream_t s, void* p1, int64_t n1, void* p2, int
     return hipGetLastError();
 }
 
-// Zero n doubles (large buffers: the slabs of partial Hessian sums): 16-byte stores on the aligned body.
-__global__ __launch_bounds__(256) void clear_f64_kernel(double* __restrict__ p, int64_t n)
-{
-    const int64_t head = (reinterpret_cast<uintptr_t>(p) & 8) ? 1 : 0;     // doubles before the 16-byte boundary
-    const int64_t pairs = (n - head) / 2;
-    double2* __restrict__ q = reinterpret_cast<double2*>(p + head);
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pairs; i += stride) q[i] = make_double2(0.0, 0.0);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (head && n > 0) p[0] = 0.0;
-        if (head + 2 * pairs < n) p[n - 1] = 0.0;
-    }
-}
-hipError_t launch_clear_f64(hipStream_t s, double* p, int64_t n)
-{
-    if (n <= 0) return hipSuccess;
-    const int64_t blocks = (n + 511) / 512;
-    hipLaunchKernelGGL(clear_f64_kernel, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s, p, n);
-    return hipGetLastError();
-}
-
 __global__ __launch_bounds__(256) void fill_i32_kernel(int* __restrict__ p, int64_t n, int v)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
