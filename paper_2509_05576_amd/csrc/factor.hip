@@ -26,7 +26,9 @@ constexpr int NB = 64;
 // the unblocked sweep over the 16 pivots of a diagonal tile: one wavefront, one
 // row (Cholesky) or column (elimination) of the whole block per lane, so the same
 // sweep also produces the tiles below (right of) the diagonal tile; pivot rows are
-// broadcast with v_readlane.  The triangular inverse of a diagonal tile comes out
+// broadcast with v_readlane (next column) and LDS reads (the columns after it).  A
+// wavefront on its own issues one instruction of any kind per 5 to 8 cycles, so the
+// sweep costs its instruction count.  The triangular inverse of a diagonal tile comes out
 // of the same sweep, in lanes it would leave idle (the first tile's: a forward
 // substitution on a second wavefront during the next sweep).  Everything else --
 // trailing update, assembly of the 64 x 64 triangular inverse from the tile
@@ -168,8 +170,9 @@ __device__ __forceinline__ void chol_block(double* Am, double* Xm, double* rq, i
 
     // Right-looking Cholesky of the 16 columns base .. base+15 of the block over all rows
     // >= base: lane rho holds row rho.  Rows inside the diagonal tile (0 <= r < 16) hold the
-    // symmetric tile row; rows below it (r >= 16) get their part of L in the same sweep
-    // (l_rho,k = (a_rho,k - sum l l) / l_kk); rows above (r < 0) idle on harmless values.
+    // tile row (what lies right of its diagonal is carried along and never used); rows below it
+    // (r >= 16) get their part of L in the same sweep (l_rho,k = (a_rho,k - sum l l) / l_kk);
+    // rows above (r < 0) idle on harmless values.
     auto sweep = [&](int b) {
         const int base = 16 * b, rho = lane, r = rho - base;
         // For b >= 1 the lanes 0..15 (rows above the tile, otherwise idle) carry the rows of the identity
@@ -774,8 +777,9 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv)
 // ---------------------------------------------------------------------------
 // Shared-Hinv elimination (Eq. 12) of the 64 x 64 block held in LDS.  With A11 the block,
 // U11 its pivot rows, D = diag(U11) and Un11 = D^-1 U11 (unit upper):  A11 = Un11^T D Un11.
-//   in : Am = the block, full symmetric (identity padding past its size); Xm need not be initialised
-//   out: Am upper triangle = U11 (pivot row j = row j), rv[j] = 1 / pivot_j
+//   in : Am upper triangle = the block (identity padding past its size; what is below the diagonal is
+//        not used); Xm need not be initialised
+//   out: Am upper triangle = U11 (pivot row j = row j; below the diagonal: not defined), rv[j] = 1 / pivot_j
 //        (so Un11[i][j] = Am[i][j] * rv[i]),  Xm = G = (Un11^T)^-1 (unit lower)
 // Called by all NT threads of the workgroup; ends with a barrier.
 __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, int* __restrict__ flag)
@@ -788,7 +792,8 @@ __device__ __forceinline__ void elim_block(double* Am, double* Xm, double* rv, i
 
     // Elimination of the 16 pivots base .. base+15 over all columns >= base: lane c holds
     // column c of the 16 pivot rows.  Columns inside the diagonal tile (0 <= r < 16) hold the
-    // symmetric tile column; columns right of it (r >= 16) get their part of the pivot rows
+    // tile column (what lies below its diagonal is carried along and never used); columns right
+    // of it (r >= 16) get their part of the pivot rows
     // in the same sweep; columns left of it (r < 0) idle on harmless values.
     auto sweep = [&](int b) {
         const int base = 16 * b, c = lane, r = c - base;
