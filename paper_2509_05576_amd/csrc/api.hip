@@ -569,16 +569,13 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
             // result back to the context's stream rides on the last launch.
             StageScope sc(ctx, FOBQ_STAGE_COLUMNS, side);
             double* corr[2] = {ctx->corr.as<double>(), ctx->corr.as<double>() + (size_t)R * 64};
-            int k = 0, waited = -1;
+            int k = 0;
             int po = 0, pnb = 0;                 // the block before
             for (int o = 0; o < steps; o += block, ++k) {
                 const int nb = (block < steps - o) ? block : steps - o;
                 const bool has_next = o + nb < steps;
                 const int nb_next = has_next ? ((block < steps - o - nb) ? block : steps - o - nb) : 0;
-                if (k > waited) {
-                    for (waited = k; !rows_announced(waited, nblocks);) ++waited;
-                    FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[waited], 0), "stream wait");
-                }
+                FOBQ_TRY(hipStreamWaitEvent(side, rows_ready[k], 0), "stream wait");
                 // the last launch of the loop: this one, unless columns are left over right of the last block
                 const bool last = !has_next && o + nb >= d;
                 FOBQ_TRY(launch_col_block(side, Wp, R, d, o, nb, Un, U, scale, zero, G, opts->group, perm, opts->bits,

@@ -1068,7 +1068,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 {
     hipStream_t s = c->stream;
     auto ready = [&](int k) {
-        if (rows_ready && k < (int)rows_ready->size() && rows_announced(k, (int)rows_ready->size()))
+        if (rows_ready && k < (int)rows_ready->size())
             (void)hipEventRecord((*rows_ready)[k], s);
     };
     double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
@@ -1081,10 +1081,9 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
         for (int o = 0; o + NB < d; o += NB, ++it) {
             const int T = (d - o - NB + NB - 1) / NB;
             // rows of block `it` are complete when this launch is (its diagonal part came from the previous
-            // one): an announced block's event rides on the launch itself as its stop event -- a separate
+            // one): the block's event rides on the launch itself as its stop event -- a separate
             // hipEventRecord between two dependent launches costs about 4 us of bubble
-            hipEvent_t done = (rows_ready && it < (int)rows_ready->size() && rows_announced(it, (int)rows_ready->size()))
-                                  ? (*rows_ready)[it] : nullptr;
+            hipEvent_t done = (rows_ready && it < (int)rows_ready->size()) ? (*rows_ready)[it] : nullptr;
             if (T * (T + 1) / 2 <= DENSE_LAUNCH_TILES)
                 hipExtLaunchKernelGGL(elim_iter_kernel<2>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
                                       (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],

@@ -153,16 +153,9 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
                           double* Hinv);  // Hd = L L^T; Linv gets the diagonal-block inverses
 hipError_t trtri_lower(fobq_ctx* c, const double* L, int d, double* Linv, double* T);      // completes Linv
 hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);              // upper tiles of Linv^T Linv
-// Whether eliminate_blocked announces block k of n (rows_ready[k]).  On the elimination's side an
-// announcement is free: the event rides on the panel launch as its stop event (a separate hipEventRecord
-// between two dependent launches would be a bubble of about 4 us).  On the column loop's side every
-// hipStreamWaitEvent is a barrier packet between two of its own dependent launches, so in the long middle
-// stretch only every second block is announced; the first and last four are announced one by one (a prompt
-// start, and no lag at the end).  A consumer of block k waits for the first announced block >= k (the last
-// block is always announced).  C2: column loop done at 1.006 ms, against 1.020 with every block announced.
-inline bool rows_announced(int k, int n) { return (k & 1) == 1 || k < 4 || k >= n - 4; }
 // `rows_ready` (may be null): rows_ready[k] is recorded on the context's stream once the pivot rows of
-// block k (rows k*block .. of U and Un) are complete, for the blocks k that rows_announced names
+// block k (rows k*block .. of U and Un) are complete.  In the fused form the event rides on the panel launch
+// as its stop event: a separate hipEventRecord between two dependent launches would be a bubble of about 4 us.
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag,
                              const std::vector<hipEvent_t>* rows_ready);
 
