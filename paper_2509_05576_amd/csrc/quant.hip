@@ -291,23 +291,38 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
 // whether any lane came that close; EXACT = true uses the true division.  The dependent chain
 // per step is: multiply, rint, max, min, fma, readlane, fma.
 template <bool EXACT>
-__device__ __forceinline__ void chain_steps(double& w, const double (&u)[64], double s, double z, double maxq, int nb,
-                                            int lane, double& mycode, double& mydiff, bool& suspect)
+__device__ __forceinline__ void chain_steps(double& w, const double (*Us)[CB + 1], double s, double z, double maxq,
+                                            int nb, int lane, double& mycode, double& mydiff, bool& suspect)
 {
     const double rcp_s = 1.0 / s;
     const double lo = -z, hi = maxq - z;          // clamp(c + z, 0, maxq) - z = clamp(c, -z, maxq - z)
+    // This lane's pivot-row entries u_j = Us[j][lane] (0 for lanes <= j: they keep the value they were
+    // quantized at) come from LDS 16 steps ahead of their use, so that no memory access sits on the
+    // sequential chain and only 32 of the 64 are in registers at a time.
+    double ub[2][16];
 #pragma unroll
-    for (int j = 0; j < 64; ++j) {
-        if (j < nb) {                             // uniform
-            const double tq = EXACT ? w / s : w * rcp_s;
-            const double c0 = rint(tq);
-            if (!EXACT) suspect = suspect || (fabs(fabs(tq - c0) - 0.5) < 1.0e-9 * fmax(1.0, fabs(tq)));
-            const double cz = fmin(fmax(c0, lo), hi);        // code - zero
-            const double df = w - s * cz;
-            const double dj = readlane_f64(df, j);
-            if (lane == j) { mycode = cz + z; mydiff = df; }
-            w -= dj * u[j];                       // u[j] is 0 for lanes <= j: they keep the value they were quantized at
+    for (int jj = 0; jj < 16; ++jj) ub[0][jj] = Us[jj][lane];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if (g < 3) {
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) ub[(g + 1) & 1][jj] = Us[16 * (g + 1) + jj][lane];
         }
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int j = 16 * g + jj;
+            if (j < nb) {                             // uniform
+                const double tq = EXACT ? w / s : w * rcp_s;
+                const double c0 = rint(tq);
+                if (!EXACT) suspect = suspect || (fabs(fabs(tq - c0) - 0.5) < 1.0e-9 * fmax(1.0, fabs(tq)));
+                const double cz = fmin(fmax(c0, lo), hi);        // code - zero
+                const double df = w - s * cz;
+                const double dj = readlane_f64(df, j);
+                if (lane == j) { mycode = cz + z; mydiff = df; }
+                w -= dj * ub[g & 1][jj];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);            // keeps the loads of the group after the next from moving up here
     }
 }
 
@@ -352,8 +367,9 @@ __device__ __forceinline__ void col_chain_role(const ColChainP& c, double* lds, 
         }
 #pragma unroll
         for (int i = 0; i < CB / CHAIN_WAVES; ++i) {
-            Us[wave + CHAIN_WAVES * i][lane] = t[i];
-            Vs[wave + CHAIN_WAVES * i][lane] = v[i];
+            const int j = wave + CHAIN_WAVES * i;
+            Us[j][lane] = (j < nb && lane > j && col_ok) ? t[i] : 0.0;    // as the chain uses it: see chain_steps
+            Vs[j][lane] = v[i];
         }
     }
     const int row = wg * CHAIN_WAVES + wave;
@@ -368,17 +384,12 @@ __device__ __forceinline__ void col_chain_role(const ColChainP& c, double* lds, 
     const double hp = 0.5 / c.U[(int64_t)(o + cl) * d + o + cl];
     __syncthreads();
     if (row >= c.R) return;                  // whole wavefront leaves; no barrier after this point
-    double u[CB];
-#pragma unroll
-    for (int j = 0; j < CB; ++j)
-        u[j] = (j < nb && lane > j && col_ok) ? Us[j][lane] : 0.0;
-
     double w = w0, mycode = 0.0, mydiff = 0.0;
     bool suspect = false;
-    chain_steps<false>(w, u, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
+    chain_steps<false>(w, Us, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
     if (__any(suspect)) {                    // wavefront-uniform; practically never taken
         w = w0;
-        chain_steps<true>(w, u, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
+        chain_steps<true>(w, Us, s, z, c.maxq, nb, lane, mycode, mydiff, suspect);
     }
     if (col_ok) {
         c.codesT[(int64_t)(o + lane) * c.Rp + row] = (uint8_t)mycode;
@@ -450,7 +461,7 @@ __device__ __forceinline__ void col_update_role(const ColChainP& c, const ColUpd
         }
 }
 
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void col_block_kernel(ColChainP c, ColUpdateP u, int n_chain)
+__global__ __launch_bounds__(64 * CHAIN_WAVES, 4) void col_block_kernel(ColChainP c, ColUpdateP u, int n_chain)
 {
     __shared__ double lds[2 * CB * (CB + 2)];
     if ((int)blockIdx.x < n_chain) col_chain_role(c, lds, (int)blockIdx.x);
