@@ -142,8 +142,8 @@ def main() -> int:
                     help="run one plain device copy of X first (known bytes; calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the method shards by layers / rows, "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (across GPUs the method would shard by whole layers, "
+              "and inside a layer by calibration columns and by rows of W); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
