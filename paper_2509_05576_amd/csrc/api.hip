@@ -318,9 +318,9 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
 }
 
 // clears the slabs of Hpart that a launch over n calibration columns can touch for the first time
-static int clear_slabs(fobq_ctx* ctx, int64_t n)
+static int clear_slabs(fobq_ctx* ctx, int64_t n, bool conv)
 {
-    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits);
+    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits, conv);
     if (need > ctx->h_zeroed) {
         FOBQ_TRY(launch_clear_slabs(ctx->stream, ctx->Hpart.as<double>(), (int)ctx->h_d, ctx->h_zeroed, need - ctx->h_zeroed),
                  "clear Hessian accumulator");
@@ -340,7 +340,7 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     if (n == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    int rc = clear_slabs(ctx, n);
+    int rc = clear_slabs(ctx, n, false);
     if (rc) return rc;
     ctx->h_conv_c = -1;
     FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits,
@@ -377,7 +377,7 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     if (npix == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    int rc = clear_slabs(ctx, npix);
+    int rc = clear_slabs(ctx, npix, true);
     if (rc) return rc;
     FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
     ctx->h_conv_c = (int)c;

@@ -135,7 +135,7 @@ struct StageScope {
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits,
                       LaunchEvents ev = LaunchEvents());
 int xxt_pick_splits(int d);
-int xxt_slabs_touched(int d, int64_t n, int splits);
+int xxt_slabs_touched(int d, int64_t n, int splits, bool conv);
 hipError_t launch_clear_slabs(hipStream_t s, double* Hpart, int d, int first, int count);
 hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, int w, int c, int pad, float* out);
 hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,

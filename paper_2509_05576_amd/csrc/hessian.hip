@@ -3,12 +3,14 @@
 // xxt_kernel: fp32 X is read from HBM, staged through LDS as fp32, widened to
 // fp64 when the MFMA fragments are formed (products of two fp32 values are
 // exact in fp64), and accumulated with v_mfma_f64_16x16x4_f64.  Only the 128 x 128
-// tiles on or below the diagonal are computed.
+// tiles on or below the diagonal are computed, and of a diagonal tile only the
+// 16 x 16 MFMA tiles on or below its diagonal (36 of 64).
 //
 // Work decomposition ("stream-K"): the work items are (tile, 32-column chunk of
-// the calibration dimension) pairs in tile-major order; a fixed number of
-// persistent workgroups each take one contiguous, equally long range of items, so
-// every workgroup does the same amount of MFMA work whatever d and n are.  A
+// the calibration dimension) pairs in tile-major order, diagonal tiles first; a
+// fixed number of persistent workgroups each take one contiguous range of items,
+// all ranges equally expensive (an item of a diagonal tile is priced below one of
+// another tile), so every workgroup does the same amount of work whatever d and n are.  A
 // range can cross tile boundaries; the part of a tile done by one workgroup is a
 // "piece".  Piece p of a tile is added into slab p of Hpart (XXT_SLABS slabs of
 // d x d), and exactly one workgroup owns a given (tile, piece) in a launch, so
@@ -24,6 +26,8 @@
 // consecutive channels, which NHWC stores contiguously; the finalize kernel of this mode puts
 // H back into the (c, ky, kx) order.
 #include <hip/hip_ext.h>
+
+#include <type_traits>
 
 #include "fobq_internal.h"
 
@@ -105,7 +109,44 @@ static int xxt_tile(int d)
     return a64 * 6 < a128 * 5 ? 64 : 128;
 }
 
-// Order of the lower-triangle tiles: tile rows are taken in pairs (2r, 2r + 1) and a pair is walked
+// Price of one chunk of a diagonal tile in units of 1/16 of another tile's chunk.  A 128 x 128 diagonal tile
+// is 8 x 8 MFMA tiles of which the 36 on and below its diagonal are needed: 9 per wavefront (diag_mma), and one
+// operand panel instead of two.  By MFMA count that is 9/16; the loads, LDS stores and barriers per chunk stay,
+// and the ranges come out equally long in time at 10/16 (plain loader) and 12/16 (convolution loader: more
+// address arithmetic per chunk) -- measured: with 9 the workgroups on the diagonal tiles finish last.
+// A 64 x 64 tile has 4 x 4 MFMA tiles, 10 needed: no split over 4 wavefronts beats the 4 each of the full tile.
+constexpr int XXT_WD_PLAIN = 10, XXT_WD_CONV = 12;
+constexpr int xxt_diag_cost(int xt, bool conv) { return xt == 128 ? (conv ? XXT_WD_CONV : XXT_WD_PLAIN) : 16; }
+constexpr int xxt_diag_cost_min(int xt) { return xt == 128 ? (XXT_WD_CONV < XXT_WD_PLAIN ? XXT_WD_CONV : XXT_WD_PLAIN) : 16; }
+
+// One group of 16 calibration columns of a diagonal 128 x 128 tile for wavefront W (0..3): the MFMA tiles
+// (W, 0..W) and (7 - W, 0..7 - W) of the 8 x 8 grid -- rows W and 7 - W of its lower triangle, 9 tiles for
+// every W.  acc[0..W] are row W's, acc[W+1..8] row 7 - W's.  Both operands come from the one panel At.
+template <int W, class F>
+__device__ __forceinline__ void diag_mma(const float (*At)[XLD], int g, int fr, int fk, d4 (&acc)[9], F after_step)
+{
+    constexpr int RS = W, RL = 7 - W;
+    float4 fb[RL + 1];
+#pragma unroll
+    for (int j = 0; j <= RL; ++j) fb[j] = *reinterpret_cast<const float4*>(&At[j * 16 + fr][g * 16 + fk]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        double b[RL + 1];
+#pragma unroll
+        for (int j = 0; j <= RL; ++j)
+            b[j] = (double)(ks == 0 ? fb[j].x : ks == 1 ? fb[j].y : ks == 2 ? fb[j].z : fb[j].w);
+#pragma unroll
+        for (int j = 0; j <= RS; ++j) acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(b[RS], b[j], acc[j], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j <= RL; ++j)
+            acc[RS + 1 + j] = __builtin_amdgcn_mfma_f64_16x16x4f64(b[RL], b[j], acc[RS + 1 + j], 0, 0, 0);
+        after_step(ks);     // the convolution loader's share of this k-step
+    }
+}
+
+// Order of the tiles.  The nt diagonal tiles come first, in order; the tiles below the diagonal follow as the
+// lower triangle (with its diagonal) of an (nt - 1) x (nt - 1) grid whose row r stands for tile row r + 1, in
+// this order of such a triangle: tile rows are taken in pairs (2r, 2r + 1) and a pair is walked
 // column by column, (2r, J), (2r + 1, J), (2r, J + 1), ...  Consecutive tiles of the order then share a
 // panel of X: the column panel J with the tile just before or after, the row panel with the tile two
 // places away.  Pair r starts at index 2 r^2 + r and has 4 r + 3 tiles; an odd last row stands alone.
@@ -124,8 +165,8 @@ __device__ __forceinline__ void tile_decode(int t, int nt, int& I, int& J)
 // MODE 1: any ld / alignment.  MODE 2: X = feature maps, n = images * ho * wo (convolution mode).
 template <int MODE, int XT>
 __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
-                                                     double* __restrict__ Hpart, int chunks, int64_t per_wg,
-                                                     int64_t total_items, int classes, ConvP cp)
+                                                     double* __restrict__ Hpart, int chunks, int64_t range_cost,
+                                                     int64_t total_items, int classes, int splits, ConvP cp)
 {
     constexpr bool FAST = MODE == 0;
     constexpr bool CONV = MODE == 2;
@@ -173,8 +214,14 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
     // tile therefore starts at its chunk whose index is a multiple of per_wg and wraps around; a range
     // over two tiles takes the head of the later tile (chunks 0 ...) before the tail of the earlier
     // one.  The order of the sum over chunks is free; it stays fixed, so results are reproducible.
-    const int64_t g0 = (int64_t)vb * per_wg;
-    const int64_t g1 = min(total_items, g0 + per_wg);
+    // Items are laid out with the nt diagonal tiles first, then the tiles below the diagonal.  A chunk of
+    // a diagonal tile costs WD units of work (36 of the 64 MFMA tiles, see diag_mma), any other 16; the
+    // ranges are equally long in cost, and both ends of a range are rounded down to an item in the same way.
+    constexpr int WD = xxt_diag_cost(XT, CONV);
+    const int64_t diag_items = (int64_t)nt * chunks, diag_cost = diag_items * WD;
+    auto item_at = [&](int64_t x) { return x < diag_cost ? x / WD : diag_items + (x - diag_cost) / 16; };
+    const int64_t g0 = min(total_items, item_at((int64_t)vb * range_cost));
+    const int64_t g1 = min(total_items, item_at((int64_t)(vb + 1) * range_cost));
     if (g0 >= g1) return;
     const int t_first = (int)(g0 / chunks), t_last = (int)((g1 - 1) / chunks);
     const int npieces = t_last - t_first + 1;
@@ -185,6 +232,9 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
         const int c_begin = (int)(max(g0, tile_first) - tile_first);
         const int c_end = (int)(min(g1, tile_first + chunks) - tile_first);
         const int len = c_end - c_begin;
+        const bool diag = tile < nt;
+        const int64_t per_wg = max((int64_t)1, range_cost / (diag ? WD : 16));   // nominal range length in this tile's chunks
+        const bool load_b = !(XT == 128 && diag);     // a diagonal tile's two operand panels are one: only As is filled
         int rot = 0;
         if (npieces == 1) {
             const int64_t aligned = (c_begin + per_wg - 1) / per_wg * per_wg;
@@ -196,9 +246,13 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
             return c_begin + c;
         };
         // piece index of this range inside its tile: number of workgroup boundaries before it
-        const int piece = (int)(vb - tile_first / per_wg);    // 0 for the workgroup whose range reaches the tile first
+        // 0 for the workgroup whose range reaches the tile first
+        int64_t first_range = (diag ? tile_first * WD : diag_cost + (tile_first - diag_items) * 16) / range_cost;
+        while (first_range < vb && item_at((first_range + 1) * range_cost) <= tile_first) ++first_range;
+        const int piece = min((int)(vb - first_range), splits - 1);   // (the host sizes the ranges so that it is < splits)
         int I, J;
-        tile_decode(tile, nt, I, J);
+        if (diag) { I = tile; J = tile; }
+        else { tile_decode(tile - nt, nt - 1, I, J); ++I; }
         const int i0 = I * XT, j0 = J * XT;
 
         // plain modes: clamped row pointers (rows past d produce outputs that are never stored);
@@ -263,7 +317,7 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
 #pragma unroll
             for (int q = 0; q < QN; ++q) {
                 fa[q * 8 + j] = win[offA[q]];
-                fb[q * 8 + j] = win[offB[q]];
+                if (load_b) fb[q * 8 + j] = win[offB[q]];
             }
         };
         auto gload = [&](int c) {
@@ -277,7 +331,7 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
 #pragma unroll
                 for (int u = 0; u < RG; ++u) {
                     pa[u] = *reinterpret_cast<const float4*>(arow[u] + k);
-                    pb[u] = *reinterpret_cast<const float4*>(brow[u] + k);
+                    if (load_b) pb[u] = *reinterpret_cast<const float4*>(brow[u] + k);
                 }
             } else {
 #pragma unroll
@@ -299,115 +353,169 @@ __global__ __launch_bounds__(256, XT == 128 ? 2 : 4) void xxt_kernel(const float
                 for (int q = 0; q < QN; ++q) {
                     *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave]) = pa[2 * q];
                     *reinterpret_cast<float4*>(&As[buf][lane + 64 * q][8 * wave + 4]) = pa[2 * q + 1];
-                    *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave]) = pb[2 * q];
-                    *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave + 4]) = pb[2 * q + 1];
+                    if (load_b) {
+                        *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave]) = pb[2 * q];
+                        *reinterpret_cast<float4*>(&Bs[buf][lane + 64 * q][8 * wave + 4]) = pb[2 * q + 1];
+                    }
                 }
                 return;
             }
 #pragma unroll
             for (int u = 0; u < RG; ++u) {
                 *reinterpret_cast<float4*>(&As[buf][lr + 32 * u][lk]) = pa[u];
-                *reinterpret_cast<float4*>(&Bs[buf][lr + 32 * u][lk]) = pb[u];
+                if (load_b) *reinterpret_cast<float4*>(&Bs[buf][lr + 32 * u][lk]) = pb[u];
             }
         };
 
-        d4 acc[MT][MT];
+        double* __restrict__ out = Hpart + (int64_t)piece * d * d;
+        // The pipeline over the piece's chunks; DG: diagonal tile of XT = 128 (only the MFMA tiles on and
+        // below its diagonal are formed, 9 per wavefront instead of 16).
+        auto run_piece = [&](auto dg_tag) {
+            constexpr bool DG = decltype(dg_tag)::value;
+            d4 acc[MT][MT];
+            d4 accd[DG ? 9 : 1];
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < MT; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+                for (int j = 0; j < MT; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int i = 0; i < (DG ? 9 : 1); ++i) accd[i] = d4{0.0, 0.0, 0.0, 0.0};
 
-        __syncthreads();              // LDS free (previous tile's last stage consumed)
-        gload(chunk_at(0));
-        sstore(0);
-        __syncthreads();
-        int cur = 0;
-        for (int ci = 0; ci < len; ++ci) {
-            const bool more = ci + 1 < len;
-            // plain modes: 8 wide loads, issued up front.  Convolution mode: one pixel's loads per
-            // group of 16 MFMAs (after the last chunk of a range the same chunk is simply loaded
-            // again and not stored).
-            const int cn = chunk_at(more ? ci + 1 : ci);
-            if (!CONV && more) gload(cn);
+            __syncthreads();              // LDS free (previous tile's last stage consumed)
+            gload(chunk_at(0));
+            sstore(0);
+            __syncthreads();
+            int cur = 0;
+            for (int ci = 0; ci < len; ++ci) {
+                const bool more = ci + 1 < len;
+                // plain modes: 8 wide loads, issued up front.  Convolution mode: one pixel's loads per
+                // group of 16 MFMAs (after the last chunk of a range the same chunk is simply loaded
+                // again and not stored).
+                const int cn = chunk_at(more ? ci + 1 : ci);
+                if (!CONV && more) gload(cn);
 #pragma unroll
-            for (int g = 0; g < XK / 16; ++g) {
-                float4 fa[MT], fb[MT];
+                for (int g = 0; g < XK / 16; ++g) {
+                    if constexpr (DG) {
+                        auto after = [&](int ks) { if (CONV) gload_px(cn, g * 4 + ks); };
+                        if (wave_s == 0) diag_mma<0>(As[cur], g, fr, fk, accd, after);
+                        else if (wave_s == 1) diag_mma<1>(As[cur], g, fr, fk, accd, after);
+                        else if (wave_s == 2) diag_mma<2>(As[cur], g, fr, fk, accd, after);
+                        else diag_mma<3>(As[cur], g, fr, fk, accd, after);
+                    } else {
+                        float4 fa[MT], fb[MT];
 #pragma unroll
-                for (int i = 0; i < MT; ++i)
-                    fa[i] = *reinterpret_cast<const float4*>(&As[cur][wm * WT + i * 16 + fr][g * 16 + fk]);
-#pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    fb[j] = *reinterpret_cast<const float4*>(&Bs[cur][wn * WT + j * 16 + fr][g * 16 + fk]);
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    double a[MT], b[MT];
-#pragma unroll
-                    for (int i = 0; i < MT; ++i)
-                        a[i] = (double)(ks == 0 ? fa[i].x : ks == 1 ? fa[i].y : ks == 2 ? fa[i].z : fa[i].w);
-#pragma unroll
-                    for (int j = 0; j < MT; ++j)
-                        b[j] = (double)(ks == 0 ? fb[j].x : ks == 1 ? fb[j].y : ks == 2 ? fb[j].z : fb[j].w);
-#pragma unroll
-                    for (int i = 0; i < MT; ++i)
+                        for (int i = 0; i < MT; ++i)
+                            fa[i] = *reinterpret_cast<const float4*>(&As[cur][wm * WT + i * 16 + fr][g * 16 + fk]);
 #pragma unroll
                         for (int j = 0; j < MT; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
-                    if (CONV) gload_px(cn, g * 4 + ks);
+                            fb[j] = *reinterpret_cast<const float4*>(&Bs[cur][wn * WT + j * 16 + fr][g * 16 + fk]);
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) {
+                            double a[MT], b[MT];
+#pragma unroll
+                            for (int i = 0; i < MT; ++i)
+                                a[i] = (double)(ks == 0 ? fa[i].x : ks == 1 ? fa[i].y : ks == 2 ? fa[i].z : fa[i].w);
+#pragma unroll
+                            for (int j = 0; j < MT; ++j)
+                                b[j] = (double)(ks == 0 ? fb[j].x : ks == 1 ? fb[j].y : ks == 2 ? fb[j].z : fb[j].w);
+#pragma unroll
+                            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                                for (int j = 0; j < MT; ++j)
+                                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+                            if (CONV) gload_px(cn, g * 4 + ks);
+                        }
+                    }
                 }
+                if (more) sstore(cur ^ 1);
+                __syncthreads();
+                cur ^= 1;
             }
-            if (more) sstore(cur ^ 1);
-            __syncthreads();
-            cur ^= 1;
-        }
 
-        double* __restrict__ out = Hpart + (int64_t)piece * d * d;
+            if constexpr (DG) {
+                // wavefront w holds the MFMA tiles (w, 0..w) and (7 - w, 0..7 - w): see diag_mma
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+                for (int q = 0; q < 9; ++q) {
+                    const int sr = q <= wave_s ? wave_s : 7 - wave_s;
+                    const int sc = q <= wave_s ? q : q - wave_s - 1;
 #pragma unroll
-            for (int j = 0; j < MT; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int gr = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4);
-                    const int gc = j0 + wn * WT + j * 16 + (lane & 15);
-                    if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
+                    for (int v = 0; v < 4; ++v) {
+                        const int gr = i0 + sr * 16 + 4 * v + (lane >> 4);
+                        const int gc = j0 + sc * 16 + (lane & 15);
+                        if (gr < d && gc < d) out[(int64_t)gr * d + gc] += accd[q][v];
+                    }
                 }
+            } else {
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < MT; ++j)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int gr = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4);
+                            const int gc = j0 + wn * WT + j * 16 + (lane & 15);
+                            if (gr < d && gc < d) out[(int64_t)gr * d + gc] += acc[i][j][v];
+                        }
+            }
+        };
+        if constexpr (XT == 128) {
+            if (diag) run_piece(std::true_type{});
+            else run_piece(std::false_type{});
+        } else {
+            run_piece(std::false_type{});
+        }
     }
 }
 
-// Number of d x d slabs of partial sums = the most pieces a tile can be cut into:
-// with W equal ranges over tiles * chunks items, a tile spans at most ceil(W / tiles) ranges,
-// plus one when it starts inside a range.
+// The split of a launch over n calibration columns: W ranges of equal cost over the items (tile, chunk),
+// diagonal tiles first.  Cost units: 1/16 of a chunk of a tile below the diagonal (xxt_diag_cost for a
+// diagonal tile's).
+struct XxtPlan {
+    int xt, nt, chunks, wgs;
+    int64_t items;        // (tile, chunk) pairs
+    int64_t range_cost;   // cost of one workgroup's range
+};
+
+static int64_t xxt_cost_per_chunk_column(int xt, int nt, int wd)     // cost of one chunk of every tile
+{
+    return (int64_t)wd * nt + 16 * ((int64_t)nt * (nt - 1) / 2);
+}
+
+// Number of d x d slabs of partial sums = the most pieces a tile can be cut into: a tile below the
+// diagonal (the most expensive kind) spans at most ceil(its cost / range cost) ranges, plus one when it
+// starts inside a range; the range cost is at least the total cost / W.
 int xxt_pick_splits(int d)
 {
     const int xt = xxt_tile(d);
     const int nt = (d + xt - 1) / xt;
-    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
-    return (int)((xxt_wgs(xt) + tiles - 1) / tiles) + 1;
+    const int64_t per_column = xxt_cost_per_chunk_column(xt, nt, xxt_diag_cost_min(xt));   // either mode fits
+    return (int)((16 * (int64_t)xxt_wgs(xt) + per_column - 1) / per_column) + 1;
 }
 
-// length of one workgroup's range of (tile, chunk) items
-static int64_t xxt_range(int d, int64_t n, int splits, int* chunks_out)
+static XxtPlan xxt_plan(int d, int64_t n, int splits, bool conv)
 {
-    const int xt = xxt_tile(d);
-    const int nt = (d + xt - 1) / xt;
-    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
-    const int chunks = (int)((n + XK - 1) / XK);
-    const int64_t total = tiles * chunks;
-    // each workgroup's range must be long enough that no tile is cut into more than `splits` pieces
-    int64_t per_wg = (total + xxt_wgs(xt) - 1) / xxt_wgs(xt);
-    const int64_t min_per = splits > 1 ? (chunks + splits - 2) / (splits - 1) : chunks;
-    if (per_wg < min_per) per_wg = min_per;
-    *chunks_out = chunks;
-    return per_wg;
+    XxtPlan p;
+    p.xt = xxt_tile(d);
+    p.nt = (d + p.xt - 1) / p.xt;
+    p.chunks = (int)((n + XK - 1) / XK);
+    p.items = ((int64_t)p.nt * (p.nt + 1) / 2) * p.chunks;
+    const int64_t total_cost = xxt_cost_per_chunk_column(p.xt, p.nt, xxt_diag_cost(p.xt, conv)) * p.chunks;
+    p.range_cost = (total_cost + xxt_wgs(p.xt) - 1) / xxt_wgs(p.xt);
+    // a range must cost enough that no tile is cut into more than `splits` pieces
+    const int64_t tile_cost = 16 * (int64_t)p.chunks;
+    const int64_t min_cost = splits > 1 ? (tile_cost + splits - 2) / (splits - 1) : tile_cost;
+    if (p.range_cost < min_cost) p.range_cost = min_cost;
+    if (p.range_cost < 16) p.range_cost = 16;      // at least one whole chunk per range
+    p.wgs = (int)((total_cost + p.range_cost - 1) / p.range_cost);
+    return p;
 }
 
 // Slabs a launch over n calibration columns can write to (the rest of Hpart is not touched):
-// a tile of `chunks` items meets at most ceil(chunks / range) + 1 ranges.
-int xxt_slabs_touched(int d, int64_t n, int splits)
+// a tile meets at most ceil(its cost / range cost) + 1 ranges.
+int xxt_slabs_touched(int d, int64_t n, int splits, bool conv)
 {
-    int chunks;
-    const int64_t per_wg = xxt_range(d, n, splits, &chunks);
-    const int64_t p = (chunks + per_wg - 1) / per_wg + 1;
+    const XxtPlan pl = xxt_plan(d, n, splits, conv);
+    const int64_t p = (16 * (int64_t)pl.chunks + pl.range_cost - 1) / pl.range_cost + 1;
     return (int)(p < splits ? p : splits);
 }
 
@@ -429,34 +537,29 @@ hipError_t launch_clear_slabs(hipStream_t s, double* Hpart, int d, int first, in
 }
 
 template <int MODE>
-static void xxt_launch(hipStream_t s, int xt, int wgs, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
-                       int chunks, int64_t per_wg, int64_t total, const ConvP& cp, LaunchEvents ev)
+static void xxt_launch(hipStream_t s, const XxtPlan& pl, const float* X, int64_t ld, int d, int64_t n, double* Hpart,
+                       int splits, const ConvP& cp, LaunchEvents ev)
 {
-    // pieces per tile, rounded: the number of classes of ranges (see the kernel)
-    int classes = (int)((chunks + per_wg / 2) / per_wg);
-    classes = classes < 1 ? 1 : (classes > wgs ? wgs : classes);
-    if (xt == 128)
-        hipExtLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n, Hpart,
-                              chunks, per_wg, total, classes, cp);
+    // pieces per tile (below the diagonal), rounded: the number of classes of ranges (see the kernel)
+    const int64_t tile_cost = 16 * (int64_t)pl.chunks;
+    int classes = (int)((tile_cost + pl.range_cost / 2) / pl.range_cost);
+    classes = classes < 1 ? 1 : (classes > pl.wgs ? pl.wgs : classes);
+    if (pl.xt == 128)
+        hipExtLaunchKernelGGL((xxt_kernel<MODE, 128>), dim3(pl.wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n,
+                              Hpart, pl.chunks, pl.range_cost, pl.items, classes, splits, cp);
     else
-        hipExtLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n, Hpart,
-                              chunks, per_wg, total, classes, cp);
+        hipExtLaunchKernelGGL((xxt_kernel<MODE, 64>), dim3(pl.wgs), dim3(256), 0, s, ev.start, ev.stop, 0, X, ld, d, n,
+                              Hpart, pl.chunks, pl.range_cost, pl.items, classes, splits, cp);
 }
 
 hipError_t launch_xxt(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, double* Hpart, int splits,
                       LaunchEvents ev)
 {
-    const int xt = xxt_tile(d);
-    const int nt = (d + xt - 1) / xt;
-    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
-    int chunks;
-    const int64_t per_wg = xxt_range(d, n, splits, &chunks);
-    const int64_t total = tiles * chunks;
-    const int wgs = (int)((total + per_wg - 1) / per_wg);
+    const XxtPlan pl = xxt_plan(d, n, splits, false);
     const bool fast = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     ConvP none{};
-    if (fast) xxt_launch<0>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none, ev);
-    else      xxt_launch<1>(s, xt, wgs, X, ld, d, n, Hpart, chunks, per_wg, total, none, ev);
+    if (fast) xxt_launch<0>(s, pl, X, ld, d, n, Hpart, splits, none, ev);
+    else      xxt_launch<1>(s, pl, X, ld, d, n, Hpart, splits, none, ev);
     return hipGetLastError();
 }
 
@@ -467,13 +570,7 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
                            LaunchEvents ev)
 {
     const int d = c * k * k;
-    const int xt = xxt_tile(d);
-    const int nt = (d + xt - 1) / xt;
-    const int64_t tiles = (int64_t)nt * (nt + 1) / 2;
-    int chunks;
-    const int64_t per_wg = xxt_range(d, npix, splits, &chunks);
-    const int64_t total = tiles * chunks;
-    const int wgs = (int)((total + per_wg - 1) / per_wg);
+    const XxtPlan pl = xxt_plan(d, npix, splits, true);
     ConvP cp;
     cp.hp = hp; cp.wp = wp; cp.c = c; cp.k = k; cp.stride = stride; cp.ho = ho; cp.wo = wo;
     cp.zero_origin = (int64_t)n_img * hp * wp * c;
@@ -481,7 +578,7 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
     cp.div_row = fastdiv_make((uint32_t)wo);
     cp.div_c = fastdiv_make((uint32_t)c);
     cp.div_k = fastdiv_make((uint32_t)k);
-    xxt_launch<2>(s, xt, wgs, padded, 0, d, npix, Hpart, chunks, per_wg, total, cp, ev);
+    xxt_launch<2>(s, pl, padded, 0, d, npix, Hpart, splits, cp, ev);
     return hipGetLastError();
 }
 
