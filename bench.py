@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
 # HBM bytes per xxt_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain device copy of X (profiles/xxt_kernel_c2_counters.txt); one launch per step only
-MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 1.23e9}
+MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 2.28e9}
 # the same for step_kernel (--block 1), average per launch (profiles/step_kernel_c5_block1.txt)
 MEASURED_STEP_TRAFFIC_BYTES = {"c5_large_d": 1.349e8}
 
