@@ -97,7 +97,12 @@ def _compare_layer(out, ref, W, bits, exact=True):
 
 # --------------------------------------------------------------------------- stages
 @pytest.mark.parametrize("d,n,ld_pad,chunk", [(128, 512, 0, None), (200, 1000, 0, 256), (300, 777, 3, 100),
-                                              (64, 40, 0, None), (17, 5, 1, None)])
+                                              (64, 40, 0, None), (17, 5, 1, None),
+                                              # 128-wide tiles (triangular diagonal tiles, ranges of equal cost):
+                                              (384, 96, 0, None),      # three tile rows, three chunks
+                                              (512, 1500, 1, 400),     # unaligned rows, calls of different length
+                                              (1000, 2049, 0, 1000),   # eight tile rows, ragged last tile, a one-column call
+                                              (640, 700, 0, 33)])      # many short calls (two chunks each)
 def test_hessian_matches_oracle(fobq, ctx, d, n, ld_pad, chunk):
     _say(f"hessian d={d} n={n} ld_pad={ld_pad} chunk={chunk}")
     _, X = _problem(1, d, n, 100 + d)
