@@ -127,6 +127,17 @@ constexpr int64_t MAX_DROW = 65535;
 
 enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
 
+// The flag words; all of them start at zero when the buffer is made.
+static int ensure_flags(fobq_ctx* ctx)
+{
+    static_assert(FLAG_COUNT <= FLAG_WORD_MATE && FLAG_WORD_MATE < FLAG_WORDS, "flag words overlap");
+    if (ctx->flags.cap >= FLAG_WORDS * sizeof(int)) return FOBQ_OK;
+    FOBQ_TRY(ctx->flags.ensure(FLAG_WORDS * sizeof(int)), "workspace flags");
+    FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_WORDS, nullptr, 0), "clear flags");
+    ctx->mate_epoch = 0;
+    return FOBQ_OK;
+}
+
 static int ensure_factor_ws(fobq_ctx* ctx, int64_t d)
 {
     const size_t dd = (size_t)d * d * sizeof(double);
@@ -137,8 +148,7 @@ static int ensure_factor_ws(fobq_ctx* ctx, int64_t d)
     FOBQ_TRY(ctx->U.ensure(dd), "workspace U");
     FOBQ_TRY(ctx->Dblk.ensure((4 * 64 * 64 + 128) * sizeof(double)), "workspace Dblk");
     FOBQ_TRY(ctx->scal.ensure(16 * sizeof(double)), "workspace scal");
-    FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
-    return FOBQ_OK;
+    return ensure_flags(ctx);
 }
 
 // damped H -> Hinv (upper tiles valid).  Enqueue only.
@@ -449,7 +459,8 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int R = (int)d_row, d = (int)d_col;
-    FOBQ_TRY(ctx->flags.ensure(FLAG_COUNT * sizeof(int)), "workspace flags");
+    rc = ensure_flags(ctx);
+    if (rc) return rc;
     FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
     rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, nullptr, nullptr);
     if (rc) return rc;

@@ -37,7 +37,9 @@ constexpr int NB = 64;
 typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
 // launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
-constexpr int DENSE_LAUNCH_TILES = 600;
+constexpr int DENSE_LAUNCH_TILES = 300;
+constexpr int MATE_SLOT = 256, MATE_MAX_NAPS = 64;
+static_assert(MATE_SLOT < DENSE_LAUNCH_TILES, "the idle workgroup must exist in every dense launch");
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
 constexpr int CB0 = 48, CB_LEN = CB0 + 16 * 16 + 48;   // sweep column buffer: see chol_block
 constexpr int SWEEP_LDS = NB + CB_LEN + 16 * DL;   // doubles of LDS that chol_block / elim_block need besides the two tiles
@@ -555,20 +557,39 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
                                                        const double* __restrict__ Dinv, double* __restrict__ L,
                                                        double* __restrict__ Linv, double* __restrict__ Dinv_next,
                                                        int* __restrict__ flag, int ntrail, int ninv,
-                                                       double* __restrict__ Sacc, double* __restrict__ Hinv)
+                                                       double* __restrict__ Sacc, double* __restrict__ Hinv,
+                                                       int* __restrict__ mate_flag, int epoch)
 {
     // sweep scratch first (its broadcast reads then have constant addresses below 64 KB, i.e. no address
     // register), then two tiles: 2 workgroups per compute unit
     __shared__ double lds[SWEEP_LDS + 2 * NB * DL];
     double* tiles = lds + SWEEP_LDS;
-    if ((int)blockIdx.x >= ntrail + ninv) {
+    // Two workgroups fit a compute unit in this variant, and the one that lands beside workgroup 0 takes
+    // matrix-pipe and LDS time from the launch's critical path.  The first 256 workgroups go to distinct
+    // compute units, so that neighbour is workgroup MATE_SLOT (measured: leaving that index idle is the only
+    // one that shortens the launch).  It is not a tile: one of its wavefronts sleeps, holding the place,
+    // until workgroup 0 says that it is done (mate_flag reaches this launch's epoch) or MATE_MAX_NAPS naps of
+    // about 0.4 us have passed -- a bounded wait, it ends whatever workgroup 0 does.
+    if (WPS == 4 && (int)blockIdx.x == MATE_SLOT) {
+        if (threadIdx.x >= 64) return;
+        for (int i = 0; i < MATE_MAX_NAPS; ++i) {
+            if (__hip_atomic_load(mate_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch >= 0) break;
+            __builtin_amdgcn_s_sleep(16);
+        }
+        return;
+    }
+    const int bid = (int)blockIdx.x - ((WPS == 4 && (int)blockIdx.x > MATE_SLOT) ? 1 : 0);
+    if (bid >= ntrail + ninv) {
+        // tiles of the Hinv role in this launch; a workgroup past them has nothing to do
+        const int nlau = Sacc ? (o / NB) * (o / NB + 1) / 2 : 0;
+        if (bid - ntrail - ninv >= nlau) return;
         int nt, mt;
-        tri_decode((int)blockIdx.x - ntrail - ninv, nt, mt);          // mt <= nt <= o / 64 - 1
+        tri_decode(bid - ntrail - ninv, nt, mt);          // mt <= nt <= o / 64 - 1
         chol_lauum_tile(tiles, d, o / NB - 1, mt, nt, Linv, Hinv);
         return;
     }
-    if ((int)blockIdx.x >= ntrail) {
-        const int pcols = o / NB + 1, e = (int)blockIdx.x - ntrail;
+    if (bid >= ntrail) {
+        const int pcols = o / NB + 1, e = bid - ntrail;
         chol_inverse_tile(tiles, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
         return;
     }
@@ -578,7 +599,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     const int wr = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
-    tri_decode(blockIdx.x, ti, tj);
+    tri_decode(bid, ti, tj);
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
 
@@ -651,7 +672,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
 #pragma unroll
         for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Qj[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq], c[j]);
     }
-    if (blockIdx.x != 0) {
+    if (bid != 0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -676,6 +697,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     __syncthreads();
     chol_block(Am, Xm, lds, flag);
     chol_block_store(Am, Xm, d, r0, nbn, L, Linv, Dinv_next);
+    if (WPS == 4 && threadIdx.x == 0) __hip_atomic_store(mate_flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // H_d = L L^T.  One stand-alone launch for the first diagonal block, then one fused launch
@@ -685,6 +707,7 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
 {
     hipStream_t s = c->stream;
     double* Dinv[2] = {c->Dblk.as<double>(), c->Dblk.as<double>() + NB * NB};
+    int* mate_flag = c->flags.as<int>() + FLAG_WORD_MATE;
     hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Hd, (int64_t)d, 0, min(NB, d), L, Linv, Dinv[0],
                        flag);
     int it = 0;
@@ -696,10 +719,11 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         const int tiles = ntrail + ninv + nlau;
         if (tiles <= DENSE_LAUNCH_TILES)
             hipLaunchKernelGGL(chol_iter_kernel<2>, dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, 0);
         else
-            hipLaunchKernelGGL(chol_iter_kernel<4>, dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv);
+            // one workgroup more than tiles: see MATE_SLOT (tiles > DENSE_LAUNCH_TILES > MATE_SLOT)
+            hipLaunchKernelGGL(chol_iter_kernel<4>, dim3(tiles + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, ++c->mate_epoch);
     }
     if (Sacc && it > 0) {
         // last block row of L^-1: Linv[last][0 : last] = -Linv[last][last] S[last][0 : last]
@@ -946,9 +970,20 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
                                                        const double* __restrict__ G, const double* __restrict__ rinv,
                                                        double* __restrict__ U, double* __restrict__ Un,
                                                        double* __restrict__ G_next, double* __restrict__ rinv_next,
-                                                       int* __restrict__ flag)
+                                                       int* __restrict__ flag, int* __restrict__ mate_flag, int epoch)
 {
     __shared__ double lds[SWEEP_LDS + 2 * NB * DL];   // sweep scratch, two tiles: 2 workgroups per compute unit
+    // epoch != 0: the launch has one workgroup more than tiles, and workgroup MATE_SLOT only holds the place
+    // beside workgroup 0 (see chol_iter_kernel; both variants of this kernel fit two workgroups per compute unit)
+    if (epoch != 0 && (int)blockIdx.x == MATE_SLOT) {
+        if (threadIdx.x >= 64) return;
+        for (int i = 0; i < MATE_MAX_NAPS; ++i) {
+            if (__hip_atomic_load(mate_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch >= 0) break;
+            __builtin_amdgcn_s_sleep(16);
+        }
+        return;
+    }
+    const int bid = (int)blockIdx.x - ((epoch != 0 && (int)blockIdx.x > MATE_SLOT) ? 1 : 0);
     double* Pi = lds + SWEEP_LDS;
     double* Pj = Pi + NB * DL;
     double* rs = lds;
@@ -956,7 +991,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
-    tri_decode(blockIdx.x, tj, ti);          // ti <= tj
+    tri_decode(bid, tj, ti);          // ti <= tj
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
 
@@ -1035,7 +1070,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
 #pragma unroll
         for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Pj[(4 * ks + fq) * DL + w2 * 32 + j * 16 + fr], c[j]);
     }
-    if (blockIdx.x != 0) {
+    if (bid != 0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -1060,6 +1095,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     __syncthreads();
     elim_block(Am, Xm, rs, flag);
     elim_block_store(Am, Xm, rs, d, r0, nbn, U, Un, nullptr, G_next, rinv_next);
+    if (epoch != 0 && threadIdx.x == 0) __hip_atomic_store(mate_flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Shared-Hinv elimination of the first `steps` columns, `block` columns at a time.
@@ -1084,14 +1120,19 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
             // one): the block's event rides on the launch itself as its stop event -- a separate
             // hipEventRecord between two dependent launches costs about 4 us of bubble
             hipEvent_t done = (rows_ready && it < (int)rows_ready->size()) ? (*rows_ready)[it] : nullptr;
-            if (T * (T + 1) / 2 <= DENSE_LAUNCH_TILES)
-                hipExtLaunchKernelGGL(elim_iter_kernel<2>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
-                                      (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag);
+            const int tiles = T * (T + 1) / 2;
+            // a launch with a workgroup MATE_SLOT gets one more, which holds the place beside workgroup 0
+            const bool mate = tiles > MATE_SLOT;
+            const int epoch = mate ? ++c->mate_epoch : 0;
+            int* mate_flag = c->flags.as<int>() + FLAG_WORD_MATE;
+            if (tiles <= DENSE_LAUNCH_TILES)
+                hipExtLaunchKernelGGL(elim_iter_kernel<2>, dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
+                                      d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
             else
-                hipExtLaunchKernelGGL(elim_iter_kernel<4>, dim3(T * (T + 1) / 2), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
-                                      (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag);
+                hipExtLaunchKernelGGL(elim_iter_kernel<4>, dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
+                                      d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
         }
         ready(it);              // last block: only a diagonal part
         return hipGetLastError();

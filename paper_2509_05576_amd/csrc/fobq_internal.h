@@ -71,6 +71,8 @@ struct StageTimer {
 
 }  // namespace fobq
 
+constexpr int FLAG_WORDS = 16, FLAG_WORD_MATE = 8;
+
 struct fobq_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
@@ -93,7 +95,9 @@ struct fobq_ctx {
     fobq::DevBuf Hd, Linv, T, Hinv, A, U, Un;
     fobq::DevBuf Dblk;      // diagonal-block scratch: 2 x (64 x 64) L11^-1, 2 x (64 x 64) G, 2 x 64 reciprocal pivots
     fobq::DevBuf scal;      // a few fp64 scalars (lambda, loss)
-    fobq::DevBuf flags;     // int32 status flags written by kernels
+    fobq::DevBuf flags;     // FLAG_WORDS int32: status flags written by kernels (cleared per call), then words
+                            // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
+    int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
     // quantization workspace
     fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
     fobq::DevBuf DT;        // d x Rp fp64: (w - q) per processed column
