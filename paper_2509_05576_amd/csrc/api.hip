@@ -255,8 +255,13 @@ static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o, const 
 
 static int read_flags(fobq_ctx* ctx)
 {
-    int h[FLAG_COUNT] = {0, 0, 0, 0};
-    FOBQ_TRY(hipMemcpyAsync(h, ctx->flags.p, sizeof h, hipMemcpyDeviceToHost, ctx->stream), "read status flags");
+    // into pinned host memory of the context: a copy to pageable memory goes through a staging buffer
+    if (!ctx->h_flags && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_flags), 64, hipHostMallocDefault) != hipSuccess) {
+        ctx->h_flags = nullptr;
+        return set_err(ctx, FOBQ_ENOMEM, "cannot allocate pinned host memory for the status flags");
+    }
+    int* h = ctx->h_flags;
+    FOBQ_TRY(hipMemcpyAsync(h, ctx->flags.p, FLAG_COUNT * sizeof(int), hipMemcpyDeviceToHost, ctx->stream), "read status flags");
     FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
     if (h[FLAG_BADPERM]) return set_err(ctx, FOBQ_EINVAL, "perm_in is not a permutation of 0..d_col-1");
     if (h[FLAG_NOTPD_H]) return set_err(ctx, FOBQ_ENOTPD, "damped Hessian is not positive definite (Cholesky pivot <= 0)");
@@ -300,6 +305,7 @@ int fobq_destroy(fobq_ctx* ctx)
                       &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
                       &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
     for (DevBuf* b : bufs) b->release();
+    if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
     delete ctx;
     return FOBQ_OK;
 }

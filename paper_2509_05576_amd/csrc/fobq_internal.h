@@ -98,6 +98,7 @@ struct fobq_ctx {
     fobq::DevBuf flags;     // FLAG_WORDS int32: status flags written by kernels (cleared per call), then words
                             // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
     int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
+    int* h_flags = nullptr; // pinned host memory that the status flags are read back into
     // quantization workspace
     fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
     fobq::DevBuf DT;        // d x Rp fp64: (w - q) per processed column
