@@ -145,7 +145,9 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
  * (fobq_hessian_finalize must have been called with the same d_col).
  * The call enqueues all work on the context's stream, then SYNCHRONISES the
  * stream and reports device-detected failures (ENOTPD, bad custom permutation).
- * On error the contents of the outputs are unspecified.
+ * On error the contents of the outputs are unspecified; a call that fails after work was enqueued
+ * waits for that work (both of the context's streams) before it returns, so W, H and the outputs
+ * may be released and the context used again.
  */
 int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                         const double* H, const fobq_opts* opts, const fobq_out* out);
@@ -181,6 +183,12 @@ int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d, double* Hinv);
  * perm_in.  Synchronises. */
 int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                      const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);
+
+/* Test hook for the error paths: the n-th internal status check from now on this context (n >= 1;
+ * checks follow every HIP call and launch) reports FOBQ_EHIP although nothing failed; 0 disarms.
+ * A call that fails this way with work already enqueued waits for that work before it returns and
+ * leaves the context usable. */
+int fobq_debug_fail_after(fobq_ctx* ctx, int n);
 
 /* ---- stage timing ---------------------------------------------------------- */
 typedef enum {

@@ -65,11 +65,14 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_finish.argtypes = [vp]
     lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
+    lib.fobq_debug_fail_after.argtypes = [vp, i32]
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
     lib.fobq_profile_reset.argtypes = [vp]
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_accumulate",
-                 "fobq_hessian_finalize", "fobq_quantize_layer", "fobq_spd_inverse", "fobq_sensitivity",
+                 "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
+                 "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
+                 "fobq_debug_fail_after",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -206,17 +209,28 @@ def fobq_spd_inverse(ctx: int, H: torch.Tensor) -> torch.Tensor:
     return Hinv
 
 
-def fobq_sensitivity(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 4, group: int = 0,
-                     order: int = ORDER_SENSI_DESC, perm_in: Optional[torch.Tensor] = None):
+def _sensitivity(fn, ctx, W, Hinv, bits, group, order, perm_in, S, perm):
     r, d = W.shape
-    S = torch.empty((d,), dtype=torch.float64, device=W.device)
-    perm = torch.empty((d,), dtype=torch.int32, device=W.device)
+    if S is None:
+        S = torch.empty((d,), dtype=torch.float64, device=W.device)
+    if perm is None:
+        perm = torch.empty((d,), dtype=torch.int32, device=W.device)
     op = _opts(bits, group, 0.0, 0.0, order, 0, -1, perm_in)
-    rc = load_library().fobq_sensitivity(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")), r, d,
-                                         ctypes.c_void_p(_ptr(Hinv, torch.float64, "Hinv")), ctypes.byref(op),
-                                         ctypes.c_void_p(S.data_ptr()), ctypes.c_void_p(perm.data_ptr()))
+    rc = fn(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")), r, d,
+            ctypes.c_void_p(_ptr(Hinv, torch.float64, "Hinv")), ctypes.byref(op),
+            ctypes.c_void_p(_ptr(S, torch.float64, "S")), ctypes.c_void_p(_ptr(perm, torch.int32, "perm")))
     _check(ctx, rc)
     return S, perm
+
+
+def fobq_sensitivity(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 4, group: int = 0,
+                     order: int = ORDER_SENSI_DESC, perm_in: Optional[torch.Tensor] = None,
+                     S: Optional[torch.Tensor] = None, perm: Optional[torch.Tensor] = None):
+    return _sensitivity(load_library().fobq_sensitivity, ctx, W, Hinv, bits, group, order, perm_in, S, perm)
+
+
+def fobq_debug_fail_after(ctx: int, n: int) -> None:
+    _check(ctx, load_library().fobq_debug_fail_after(ctypes.c_void_p(ctx), n))
 
 
 def FOBQ_PROFILE_STAGE(stage: int) -> int:

@@ -100,10 +100,14 @@ static void fold_events(fobq_ctx* c)
     }
 }
 
-#define FOBQ_TRY(expr, what)                                   \
-    do {                                                       \
-        hipError_t e__ = (expr);                               \
-        if (e__ != hipSuccess) return hip_err(ctx, e__, what); \
+// `ctx->fail_countdown` (test hook, fobq_debug_fail_after): the n-th check from now reports a failure
+// without the HIP call having failed, so that the error paths can be exercised from the host.
+#define FOBQ_TRY(expr, what)                                                              \
+    do {                                                                                  \
+        hipError_t e__ = (expr);                                                          \
+        if (e__ != hipSuccess) return hip_err(ctx, e__, what);                            \
+        if (ctx->fail_countdown > 0 && --ctx->fail_countdown == 0)                        \
+            return set_err(ctx, FOBQ_EHIP, "%s: injected failure (test hook)", what);     \
     } while (0)
 
 struct DeviceGuard {
@@ -213,60 +217,92 @@ static int order_kind(const fobq_opts* o)
          : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
 }
 
-// The part of the ordering that needs W only (grid, per-chunk column sums), on stream `st`: in the
-// whole-layer path it runs beside the factorization.
-static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, int R, int d, const fobq_opts* o,
-                               float* scales_out, float* zeros_out, hipEvent_t done = nullptr)
+// Scratch of the ordering stage (grid, column scores, order).
+struct OrderBufs {
+    double* scale; double* zero;   // d_row x G
+    double* Spart;                 // sens_chunks(d_row) x d_col
+    double* S;                     // d_col
+    int* perm; int* invperm;       // d_col
+    int* flags;                    // FLAG_COUNT status words
+};
+
+static int ensure_order_bufs(fobq_ctx* ctx, int R, int d, int G, OrderBufs* b)
 {
-    const int G = o->group > 0 ? d / o->group : 1;
     FOBQ_TRY(ctx->scale.ensure((size_t)R * G * sizeof(double)), "workspace scale");
     FOBQ_TRY(ctx->zero.ensure((size_t)R * G * sizeof(double)), "workspace zero");
-    const int chunks = sens_chunks(R);
-    FOBQ_TRY(ctx->Spart.ensure((size_t)chunks * d * sizeof(double)), "workspace Spart");
-    FOBQ_TRY(launch_grid(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                         scales_out, zeros_out), "grid");
-    FOBQ_TRY(launch_sens_partial(st, W, R, d, o->bits, o->group, ctx->scale.as<double>(), ctx->zero.as<double>(),
-                                 ctx->Spart.as<double>(), chunks, order_kind(o), done), "sensitivity");
-    return FOBQ_OK;
-}
-
-// The rest, on the context's stream: scores (with the diagonal of Hinv, d x d) and the order.
-static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o, const double* Hinv)
-{
-    hipStream_t s = ctx->stream;
+    FOBQ_TRY(ctx->Spart.ensure((size_t)sens_chunks(R) * d * sizeof(double)), "workspace Spart");
     FOBQ_TRY(ctx->S.ensure((size_t)d * sizeof(double)), "workspace S");
     FOBQ_TRY(ctx->perm.ensure((size_t)d * sizeof(int)), "workspace perm");
     FOBQ_TRY(ctx->invperm.ensure((size_t)d * sizeof(int)), "workspace invperm");
-    StageScope sc(ctx, FOBQ_STAGE_ORDER);
-    const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC && o->order <= FOBQ_ORDER_W_ASC;
-    FOBQ_TRY(launch_sens_reduce(s, ctx->Spart.as<double>(), sens_chunks(R), d, Hinv, ctx->S.as<double>(),
-                                order_kind(o)), "sensitivity");
-    // the dynamic order starts from the identity and exchanges columns step by step
-    if (o->order == FOBQ_ORDER_NATURAL || o->order == FOBQ_ORDER_SENSI_DYNAMIC)
-        FOBQ_TRY(launch_iota(s, d, ctx->perm.as<int>(), ctx->invperm.as<int>()), "order");
-    else if (o->order != FOBQ_ORDER_CUSTOM)
-        FOBQ_TRY(launch_rank_sort(s, ctx->S.as<double>(), d, ctx->perm.as<int>(), ctx->invperm.as<int>(), ascending),
-                 "order");
-    else
-        FOBQ_TRY(launch_check_perm(s, o->perm_in, d, ctx->perm.as<int>(), ctx->invperm.as<int>(),
-                                   ctx->flags.as<int>() + FLAG_BADPERM), "order");
+    int rc = ensure_flags(ctx);
+    if (rc) return rc;
+    *b = OrderBufs{ctx->scale.as<double>(), ctx->zero.as<double>(), ctx->Spart.as<double>(), ctx->S.as<double>(),
+                   ctx->perm.as<int>(), ctx->invperm.as<int>(), ctx->flags.as<int>()};
     return FOBQ_OK;
 }
 
-static int read_flags(fobq_ctx* ctx)
+// The part of the ordering that needs W only (grid, per-chunk column sums), on stream `st`: in the
+// whole-layer path it runs beside the factorization.  Launches only.
+static int enqueue_grid_scores(fobq_ctx* ctx, hipStream_t st, const float* W, int R, int d, const fobq_opts* o,
+                               const OrderBufs& b, float* scales_out, float* zeros_out, hipEvent_t done = nullptr)
 {
-    // into pinned host memory of the context: a copy to pageable memory goes through a staging buffer
-    if (!ctx->h_flags && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_flags), 64, hipHostMallocDefault) != hipSuccess) {
+    FOBQ_TRY(launch_grid(st, W, R, d, o->bits, o->group, b.scale, b.zero, scales_out, zeros_out), "grid");
+    FOBQ_TRY(launch_sens_partial(st, W, R, d, o->bits, o->group, b.scale, b.zero, b.Spart, sens_chunks(R),
+                                 order_kind(o), done), "sensitivity");
+    return FOBQ_OK;
+}
+
+// The rest, on the context's stream: scores (with the diagonal of Hinv, d x d) and the order.  Launches only.
+static int enqueue_order(fobq_ctx* ctx, int R, int d, const fobq_opts* o, const double* Hinv, const OrderBufs& b)
+{
+    hipStream_t s = ctx->stream;
+    StageScope sc(ctx, FOBQ_STAGE_ORDER);
+    const int ascending = o->order >= FOBQ_ORDER_SENSI_ASC && o->order <= FOBQ_ORDER_W_ASC;
+    FOBQ_TRY(launch_sens_reduce(s, b.Spart, sens_chunks(R), d, Hinv, b.S, order_kind(o)), "sensitivity");
+    // the dynamic order starts from the identity and exchanges columns step by step
+    if (o->order == FOBQ_ORDER_NATURAL || o->order == FOBQ_ORDER_SENSI_DYNAMIC)
+        FOBQ_TRY(launch_iota(s, d, b.perm, b.invperm), "order");
+    else if (o->order != FOBQ_ORDER_CUSTOM)
+        FOBQ_TRY(launch_rank_sort(s, b.S, d, b.perm, b.invperm, ascending), "order");
+    else
+        FOBQ_TRY(launch_check_perm(s, o->perm_in, d, b.perm, b.invperm, b.flags + FLAG_BADPERM), "order");
+    return FOBQ_OK;
+}
+
+// pinned host memory that the status flags are read back into (a copy to pageable memory goes through
+// a staging buffer); made when the context is created
+static int ensure_host_flags(fobq_ctx* ctx)
+{
+    if (ctx->h_flags) return FOBQ_OK;
+    if (hipHostMalloc(reinterpret_cast<void**>(&ctx->h_flags), 64, hipHostMallocDefault) != hipSuccess) {
         ctx->h_flags = nullptr;
         return set_err(ctx, FOBQ_ENOMEM, "cannot allocate pinned host memory for the status flags");
     }
+    return FOBQ_OK;
+}
+
+// Synchronises the context's stream and turns the status words at `dev_flags` into a status.  Allocates nothing.
+static int read_flags(fobq_ctx* ctx, const int* dev_flags)
+{
     int* h = ctx->h_flags;
-    FOBQ_TRY(hipMemcpyAsync(h, ctx->flags.p, FLAG_COUNT * sizeof(int), hipMemcpyDeviceToHost, ctx->stream), "read status flags");
+    if (!h) return set_err(ctx, FOBQ_ESTATE, "the context has no host buffer for the status flags");
+    FOBQ_TRY(hipMemcpyAsync(h, dev_flags, FLAG_COUNT * sizeof(int), hipMemcpyDeviceToHost, ctx->stream), "read status flags");
     FOBQ_TRY(hipStreamSynchronize(ctx->stream), "synchronize");
     if (h[FLAG_BADPERM]) return set_err(ctx, FOBQ_EINVAL, "perm_in is not a permutation of 0..d_col-1");
     if (h[FLAG_NOTPD_H]) return set_err(ctx, FOBQ_ENOTPD, "damped Hessian is not positive definite (Cholesky pivot <= 0)");
     if (h[FLAG_NOTPD_HINV]) return set_err(ctx, FOBQ_ENOTPD, "shared inverse Hessian lost positive definiteness (elimination pivot <= 0)");
     return FOBQ_OK;
+}
+static int read_flags(fobq_ctx* ctx) { return read_flags(ctx, ctx->flags.as<int>()); }
+
+// After a failure with work already enqueued: wait for both streams, so that the caller may release its
+// buffers and the context's scratch is not in use when the next call starts.  Keeps the first error.
+static int drain_after_failure(fobq_ctx* ctx, int rc)
+{
+    if (ctx->side) (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->fail_countdown = 0;
+    return rc;
 }
 
 }  // namespace fobq
@@ -285,6 +321,18 @@ int fobq_create(fobq_ctx** out, int device, void* hip_stream)
     if (!c) return FOBQ_ENOMEM;
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    // the pinned status buffer
+    int rc = FOBQ_OK;
+    {
+        DeviceGuard g(device);
+        rc = g.ok ? FOBQ_OK : FOBQ_EHIP;
+        if (!rc) rc = ensure_host_flags(c);
+    }
+    if (rc) {
+        if (c->h_flags) (void)hipHostFree(c->h_flags);
+        delete c;
+        return rc;
+    }
     *out = c;
     return FOBQ_OK;
 }
@@ -442,18 +490,21 @@ int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d64, double* Hinv)
     const int d = (int)d64;
     int rc = ensure_factor_ws(ctx, d);
     if (rc) return rc;
-    FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
-    rc = enqueue_inverse(ctx, H, d, 0.0, 0.0);
-    if (rc) return rc;
-    // full symmetric copy out of the upper tiles
-    FOBQ_TRY(launch_hinv_work(ctx->stream, ctx->Hinv.as<double>(), d, 0, Hinv), "copy Hinv");
-    return read_flags(ctx);
+    rc = [&]() -> int {
+        FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
+        int r = enqueue_inverse(ctx, H, d, 0.0, 0.0);
+        if (r) return r;
+        // full symmetric copy out of the upper tiles
+        FOBQ_TRY(launch_hinv_work(ctx->stream, ctx->Hinv.as<double>(), d, 0, Hinv), "copy Hinv");
+        return read_flags(ctx);
+    }();
+    return (rc && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
 }
 
-int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
-                     const fobq_opts* opts, double* S, int32_t* perm)
+// argument checks of fobq_sensitivity
+static int check_sensitivity_args(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
+                                  const fobq_opts* opts, const int32_t* perm)
 {
-    if (!ctx) return FOBQ_EINVAL;
     if (ctx->pending) return set_err(ctx, FOBQ_ESTATE, "an enqueued layer is waiting for fobq_finish");
     if (!W || !Hinv) return set_err(ctx, FOBQ_EINVAL, "W or Hinv is NULL");
     int rc = check_shape(ctx, d_row, d_col);
@@ -462,108 +513,109 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     if (rc) return rc;
     if (perm && opts->order == FOBQ_ORDER_SENSI_DYNAMIC)
         return set_err(ctx, FOBQ_EINVAL, "the dynamic order is only known after the column loop (fobq_quantize_layer returns it)");
-    DeviceGuard g(ctx->device);
-    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    const int R = (int)d_row, d = (int)d_col;
-    rc = ensure_flags(ctx);
-    if (rc) return rc;
-    FOBQ_TRY(launch_clear_words(ctx->stream, ctx->flags.p, FLAG_COUNT, nullptr, 0), "clear flags");
-    rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, nullptr, nullptr);
-    if (rc) return rc;
-    rc = enqueue_order(ctx, R, d, opts, Hinv);
-    if (rc) return rc;
-    if (S) FOBQ_TRY(hipMemcpyAsync(S, ctx->S.p, (size_t)d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy S");
-    if (perm) FOBQ_TRY(hipMemcpyAsync(perm, ctx->perm.p, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, ctx->stream), "copy perm");
-    return read_flags(ctx);
+    return FOBQ_OK;
 }
 
-// everything of fobq_quantize_layer except the final synchronisation and status read
-static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
-                            const fobq_opts* opts, const fobq_out* out)
+// launches of the ordering stage on the context's stream with scratch `b`, results copied out by a kernel-free
+// device-to-device copy; synchronises and reports the flags
+static int run_sensitivity(fobq_ctx* ctx, const float* W, int R, int d, const double* Hinv, const fobq_opts* opts,
+                           const OrderBufs& b, double* S, int32_t* perm)
+{
+    FOBQ_TRY(launch_clear_words(ctx->stream, b.flags, FLAG_COUNT, nullptr, 0), "clear flags");
+    int rc = enqueue_grid_scores(ctx, ctx->stream, W, R, d, opts, b, nullptr, nullptr);
+    if (rc) return rc;
+    rc = enqueue_order(ctx, R, d, opts, Hinv, b);
+    if (rc) return rc;
+    if (S) FOBQ_TRY(hipMemcpyAsync(S, b.S, (size_t)d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy S");
+    if (perm) FOBQ_TRY(hipMemcpyAsync(perm, b.perm, (size_t)d * sizeof(int), hipMemcpyDeviceToDevice, ctx->stream), "copy perm");
+    return read_flags(ctx, b.flags);
+}
+
+int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
+                     const fobq_opts* opts, double* S, int32_t* perm)
 {
     if (!ctx) return FOBQ_EINVAL;
-    if (ctx->pending)
-        return set_err(ctx, FOBQ_ESTATE, "a layer enqueued with fobq_quantize_layer_enqueue is waiting for fobq_finish");
-    if (!W) return set_err(ctx, FOBQ_EINVAL, "W is NULL");
-    if (!out) return set_err(ctx, FOBQ_EINVAL, "out is NULL");
-    int rc = check_shape(ctx, d_row, d_col);
+    int rc = check_sensitivity_args(ctx, W, d_row, d_col, Hinv, opts, perm);
     if (rc) return rc;
-    rc = check_opts(ctx, opts, d_col);
-    if (rc) return rc;
-    if (!H) {
-        if (!ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "H is NULL and no finalized Hessian is held by the context");
-        if (ctx->h_d != d_col)
-            return set_err(ctx, FOBQ_EINVAL, "accumulated Hessian has d_col=%lld, layer has %lld", (long long)ctx->h_d, (long long)d_col);
-        H = ctx->H.as<double>();
-    }
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    ctx->err.clear();
-
-    hipStream_t s = ctx->stream;
     const int R = (int)d_row, d = (int)d_col;
-    const int G = opts->group > 0 ? d / opts->group : 1;
-    const int steps = opts->stop_after < 0 ? d : opts->stop_after;
-    const bool dynamic = opts->order == FOBQ_ORDER_SENSI_DYNAMIC;
-    const int block = dynamic ? 1 : (opts->block == 0 ? 64 : opts->block);   // re-sorting needs W after every column
-    const int Rp = (R + 63) / 64 * 64;
-    const size_t dd = (size_t)d * d * sizeof(double);
-
-    rc = ensure_factor_ws(ctx, d);
+    OrderBufs b;
+    rc = ensure_order_bufs(ctx, R, d, opts->group > 0 ? d / opts->group : 1, &b);
     if (rc) return rc;
-    FOBQ_TRY(ctx->A.ensure(dd), "workspace A");
-    FOBQ_TRY(ctx->Un.ensure(dd), "workspace Un");
-    FOBQ_TRY(ctx->Wp.ensure((size_t)R * d * sizeof(double)), "workspace Wp");
-    FOBQ_TRY(ctx->DT.ensure((size_t)d * Rp * sizeof(double)), "workspace DT");
-    FOBQ_TRY(ctx->corr.ensure(2 * (size_t)R * 64 * sizeof(double)), "workspace corr");
-    FOBQ_TRY(ctx->codesT.ensure((size_t)d * Rp), "workspace codesT");
-    FOBQ_TRY(ctx->lossrow.ensure((size_t)R * sizeof(double)), "workspace lossrow");
+    rc = run_sensitivity(ctx, W, R, d, Hinv, opts, b, S, perm);
+    return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
+}
+
+int fobq_debug_fail_after(fobq_ctx* ctx, int n)
+{
+    if (!ctx || n < 0) return FOBQ_EINVAL;
+    ctx->fail_countdown = n;
+    return FOBQ_OK;
+}
+
+// What one layer's launches need, fixed before the first of them is enqueued.
+struct LayerPlan {
+    const float* W; const double* H; const fobq_opts* opts; const fobq_out* out;
+    int R, d, G, steps, block, Rp, nblocks;
+    bool dynamic;
+    OrderBufs ob;
+};
+
+// events of a layer in ctx->sync_ev: the fork / join pair that sends the grid and the W-only part of the
+// scores to the side stream and back, then one "pivot rows ready" event per column block, then the start
+// and the end of the column loop.  No event serves two purposes within a layer.
+enum { EV_FORK = 0, EV_JOIN = 1, EV_ROWS0 = 2 };
+
+// All launches of a layer (no allocation in here: a failure leaves work in flight, see quantize_enqueue).
+static int enqueue_layer_launches(fobq_ctx* ctx, const LayerPlan& p)
+{
+    hipStream_t s = ctx->stream;
+    const fobq_opts* opts = p.opts;
+    const fobq_out* out = p.out;
+    const int R = p.R, d = p.d, G = p.G, steps = p.steps, block = p.block, Rp = p.Rp, nblocks = p.nblocks;
     // grid and the W-only part of the column scores: on the side stream, beside the factorization.  The
     // events that order the streams ride on launches (see gemm64's `done`), here on the clearing kernel.
-    rc = ensure_sync_events(ctx, 2);
-    if (rc) return rc;
-    FOBQ_TRY(launch_clear_words(s, ctx->flags.p, FLAG_COUNT, ctx->lossrow.p, 2 * (int64_t)R, ctx->sync_ev[0]),
+    FOBQ_TRY(launch_clear_words(s, ctx->flags.p, FLAG_COUNT, ctx->lossrow.p, 2 * (int64_t)R, ctx->sync_ev[EV_FORK]),
              "clear flags and loss");
-    FOBQ_TRY(hipStreamWaitEvent(ctx->side, ctx->sync_ev[0], 0), "stream wait");
-    rc = enqueue_grid_scores(ctx, ctx->side, W, R, d, opts, out->scales, out->zeros, ctx->sync_ev[1]);
+    FOBQ_TRY(hipStreamWaitEvent(ctx->side, ctx->sync_ev[EV_FORK], 0), "stream wait");
+    int rc = enqueue_grid_scores(ctx, ctx->side, p.W, R, d, opts, p.ob, out->scales, out->zeros, ctx->sync_ev[EV_JOIN]);
     if (rc) return rc;
     // damp, Cholesky, inverse
-    rc = enqueue_inverse(ctx, H, d, opts->damp, opts->damp_abs);
+    rc = enqueue_inverse(ctx, p.H, d, opts->damp, opts->damp_abs);
     if (rc) return rc;
-    FOBQ_TRY(hipStreamWaitEvent(s, ctx->sync_ev[1], 0), "stream wait");
+    FOBQ_TRY(hipStreamWaitEvent(s, ctx->sync_ev[EV_JOIN], 0), "stream wait");
     // column scores, order
-    rc = enqueue_order(ctx, R, d, opts, ctx->Hinv.as<double>());
+    rc = enqueue_order(ctx, R, d, opts, ctx->Hinv.as<double>(), p.ob);
     if (rc) return rc;
     // blocked path: the event that lets the column loop's stream start rides on the gather launch
-    const int nblocks = block == 1 ? 0 : (steps + block - 1) / block;
-    if (nblocks > 0) {
-        rc = ensure_sync_events(ctx, (size_t)nblocks + 2);
-        if (rc) return rc;
-    }
+    hipEvent_t ev_start = block != 1 ? ctx->sync_ev[EV_ROWS0 + nblocks] : nullptr;
+    hipEvent_t ev_done = block != 1 ? ctx->sync_ev[EV_ROWS0 + nblocks + 1] : nullptr;
     {
         StageScope sc(ctx, FOBQ_STAGE_PERMUTE);
-        FOBQ_TRY(launch_gather(s, W, R, d, ctx->perm.as<int>(), ctx->Hinv.as<double>(), ctx->Wp.as<double>(),
-                               ctx->A.as<double>(), nblocks > 0 ? ctx->sync_ev[nblocks] : nullptr), "permute");
+        FOBQ_TRY(launch_gather(s, p.W, R, d, p.ob.perm, ctx->Hinv.as<double>(), ctx->Wp.as<double>(),
+                               ctx->A.as<double>(), ev_start), "permute");
     }
     double* A = ctx->A.as<double>();
     double* Wp = ctx->Wp.as<double>();
-    const double* scale = ctx->scale.as<double>();
-    const double* zero = ctx->zero.as<double>();
-    int* perm = ctx->perm.as<int>();
+    const double* scale = p.ob.scale;
+    const double* zero = p.ob.zero;
+    int* perm = p.ob.perm;
     uint8_t* codesT = ctx->codesT.as<uint8_t>();
     double* lossrow = ctx->lossrow.as<double>();
 
     if (block == 1) {
         // Eq. 9 / 11 and Eq. 12 one column at a time
         StageScope sc(ctx, FOBQ_STAGE_COLUMNS);
+        int* pivot_flag = ctx->flags.as<int>() + FLAG_NOTPD_HINV;
         for (int t = 0; t < steps; ++t) {
-            if (dynamic)
+            if (p.dynamic)
                 FOBQ_TRY(launch_dyn_select(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits,
-                                           ctx->Spart.as<double>(), sens_chunks(R)), "column choice");
-            FOBQ_TRY(launch_step(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits, codesT, Rp, lossrow),
-                     "column step");
+                                           p.ob.Spart, sens_chunks(R)), "column choice");
+            FOBQ_TRY(launch_step(s, Wp, R, d, t, A, scale, zero, G, opts->group, perm, opts->bits, codesT, Rp, lossrow,
+                                 pivot_flag), "column step");
         }
-        if (dynamic) FOBQ_TRY(launch_invert_perm(s, perm, d, ctx->invperm.as<int>()), "order");
+        if (p.dynamic) FOBQ_TRY(launch_invert_perm(s, perm, d, p.ob.invperm), "order");
     } else {
         double* U = ctx->U.as<double>();
         double* Un = ctx->Un.as<double>();
@@ -572,8 +624,7 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
         // column loop follows on the side stream, block k as soon as the pivot rows of block k exist
         // (both are chains of short dependent launches that leave most of the GPU idle).
         hipStream_t side = ctx->side;
-        std::vector<hipEvent_t> rows_ready(ctx->sync_ev.begin(), ctx->sync_ev.begin() + nblocks);
-        hipEvent_t ev_start = ctx->sync_ev[nblocks], ev_done = ctx->sync_ev[nblocks + 1];
+        std::vector<hipEvent_t> rows_ready(ctx->sync_ev.begin() + EV_ROWS0, ctx->sync_ev.begin() + EV_ROWS0 + nblocks);
         FOBQ_TRY(hipStreamWaitEvent(side, ev_start, 0), "stream wait");
         {
             StageScope sc(ctx, FOBQ_STAGE_ELIMINATE);
@@ -612,7 +663,7 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     {
         StageScope sc(ctx, FOBQ_STAGE_EMIT);
         if (out->codes || out->Q)
-            FOBQ_TRY(launch_emit(s, codesT, Rp, R, d, steps, ctx->invperm.as<int>(), scale, zero, G, opts->group,
+            FOBQ_TRY(launch_emit(s, codesT, Rp, R, d, steps, p.ob.invperm, scale, zero, G, opts->group,
                                  out->codes, out->Q, lossrow, out->loss), "emit");
         else if (out->loss) FOBQ_TRY(launch_loss(s, lossrow, R, out->loss), "loss");
         if (out->perm)
@@ -622,6 +673,62 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
         if (out->Hinv_work) FOBQ_TRY(launch_hinv_work(s, A, d, steps, out->Hinv_work), "copy Hinv_work");
     }
     return FOBQ_OK;
+}
+
+// everything of fobq_quantize_layer except the final synchronisation and status read
+static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,
+                            const fobq_opts* opts, const fobq_out* out)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending)
+        return set_err(ctx, FOBQ_ESTATE, "a layer enqueued with fobq_quantize_layer_enqueue is waiting for fobq_finish");
+    if (!W) return set_err(ctx, FOBQ_EINVAL, "W is NULL");
+    if (!out) return set_err(ctx, FOBQ_EINVAL, "out is NULL");
+    int rc = check_shape(ctx, d_row, d_col);
+    if (rc) return rc;
+    rc = check_opts(ctx, opts, d_col);
+    if (rc) return rc;
+    if (!H) {
+        if (!ctx->h_final) return set_err(ctx, FOBQ_ESTATE, "H is NULL and no finalized Hessian is held by the context");
+        if (ctx->h_d != d_col)
+            return set_err(ctx, FOBQ_EINVAL, "accumulated Hessian has d_col=%lld, layer has %lld", (long long)ctx->h_d, (long long)d_col);
+        H = ctx->H.as<double>();
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    ctx->err.clear();
+
+    LayerPlan p;
+    p.W = W; p.H = H; p.opts = opts; p.out = out;
+    p.R = (int)d_row; p.d = (int)d_col;
+    p.G = opts->group > 0 ? p.d / opts->group : 1;
+    p.steps = opts->stop_after < 0 ? p.d : opts->stop_after;
+    p.dynamic = opts->order == FOBQ_ORDER_SENSI_DYNAMIC;
+    p.block = p.dynamic ? 1 : (opts->block == 0 ? 64 : opts->block);   // re-sorting needs W after every column
+    p.Rp = (p.R + 63) / 64 * 64;
+    p.nblocks = p.block == 1 ? 0 : (p.steps + p.block - 1) / p.block;
+    const size_t dd = (size_t)p.d * p.d * sizeof(double);
+
+    // Every allocation (scratch growth, streams, events) comes before the first launch: scratch growth may
+    // free a buffer, and a failure in here leaves nothing in flight.
+    rc = ensure_factor_ws(ctx, p.d);
+    if (rc) return rc;
+    FOBQ_TRY(ctx->A.ensure(dd), "workspace A");
+    FOBQ_TRY(ctx->Un.ensure(dd), "workspace Un");
+    FOBQ_TRY(ctx->Wp.ensure((size_t)p.R * p.d * sizeof(double)), "workspace Wp");
+    FOBQ_TRY(ctx->DT.ensure((size_t)p.d * p.Rp * sizeof(double)), "workspace DT");
+    FOBQ_TRY(ctx->corr.ensure(2 * (size_t)p.R * 64 * sizeof(double)), "workspace corr");
+    FOBQ_TRY(ctx->codesT.ensure((size_t)p.d * p.Rp), "workspace codesT");
+    FOBQ_TRY(ctx->lossrow.ensure((size_t)p.R * sizeof(double)), "workspace lossrow");
+    rc = ensure_order_bufs(ctx, p.R, p.d, p.G, &p.ob);
+    if (rc) return rc;
+    rc = ensure_sync_events(ctx, (size_t)EV_ROWS0 + p.nblocks + 2);
+    if (rc) return rc;
+
+    rc = enqueue_layer_launches(ctx, p);
+    // a failure past this point has work in flight on both streams that reads W / H and writes the outputs
+    // and the context's scratch: wait for it, so that the caller may free its buffers and use the context again
+    return rc ? drain_after_failure(ctx, rc) : FOBQ_OK;
 }
 
 int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,

@@ -98,7 +98,8 @@ struct fobq_ctx {
     fobq::DevBuf flags;     // FLAG_WORDS int32: status flags written by kernels (cleared per call), then words
                             // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
     int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
-    int* h_flags = nullptr; // pinned host memory that the status flags are read back into
+    int* h_flags = nullptr; // pinned host memory that the status flags are read back into (made by fobq_create)
+    int fail_countdown = 0; // test hook: > 0 = the n-th status check from now reports an injected failure
     // quantization workspace
     fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
     fobq::DevBuf DT;        // d x Rp fp64: (w - q) per processed column
@@ -188,7 +189,7 @@ hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, dou
                              const double* zero, int G, int group, int* perm, int bits, double* Spart, int chunks);
 hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
                        const double* scale, const double* zero, int G, int group, const int* perm, int bits,
-                       uint8_t* codesT, int Rp, double* lossrow);
+                       uint8_t* codesT, int Rp, double* lossrow, int* flag);   // *flag = 1 when the pivot is not > 0
 hipError_t launch_emit(hipStream_t s, const uint8_t* codesT, int Rp, int R, int d, int steps,
                        const int* invperm, const double* scale, const double* zero, int G, int group,
                        uint8_t* codes, float* Q, const double* lossrow, double* loss);   // loss may be null

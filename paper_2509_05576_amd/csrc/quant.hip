@@ -512,7 +512,8 @@ template <bool VEC2>
 __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int R, int d, int t, double* __restrict__ A,
                                                    const double* __restrict__ scale, const double* __restrict__ zero,
                                                    int G, int gs, const int* __restrict__ perm, double maxq,
-                                                   uint8_t* __restrict__ codesT, int Rp, double* __restrict__ lossrow)
+                                                   uint8_t* __restrict__ codesT, int Rp, double* __restrict__ lossrow,
+                                                   int* __restrict__ flag)
 {
     const int lane = threadIdx.x & 63;
     const int rid = blockIdx.y * 4 + (threadIdx.x >> 6);
@@ -520,6 +521,9 @@ __global__ __launch_bounds__(256) void step_kernel(double* __restrict__ Wp, int 
     const int c_base = (strip0 + blockIdx.x) * STEP_SW;
     const double* __restrict__ rowt = A + (int64_t)t * d;
     const double p = rowt[t];
+    // the pivot of Eq. 12 must be positive and finite (the call then fails; the arithmetic below goes on
+    // with whatever the division gives, every access stays in bounds)
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && !(p > 0.0 && p < 1.0e300)) *flag = 1;
     double* __restrict__ row;      // the row this wavefront updates
     double f;                      // row[k] -= f * rowt[k]
     int first;                     // first column to update
@@ -698,7 +702,7 @@ hipError_t launch_dyn_select(hipStream_t s, double* Wp, int R, int d, int t, dou
 
 hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A,
                        const double* scale, const double* zero, int G, int group, const int* perm, int bits,
-                       uint8_t* codesT, int Rp, double* lossrow)
+                       uint8_t* codesT, int Rp, double* lossrow, int* flag)
 {
     const int gs = group > 0 ? group : d;
     const double maxq = (double)((1 << bits) - 1);
@@ -709,10 +713,10 @@ hipError_t launch_step(hipStream_t s, double* Wp, int R, int d, int t, double* A
     dim3 grid(strips, (rows + 3) / 4), block(256);
     if (d % 2 == 0)
         hipLaunchKernelGGL((step_kernel<true>), grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq,
-                           codesT, Rp, lossrow);
+                           codesT, Rp, lossrow, flag);
     else
         hipLaunchKernelGGL((step_kernel<false>), grid, block, 0, s, Wp, R, d, t, A, scale, zero, G, gs, perm, maxq,
-                           codesT, Rp, lossrow);
+                           codesT, Rp, lossrow, flag);
     return hipGetLastError();
 }
 

@@ -346,13 +346,43 @@ def test_argument_errors(fobq, ctx):
     ctx.quantize_layer(Wd)                          # and the context still works
 
 
-def test_rank_deficient_without_damping_is_enotpd(fobq, ctx):
+@pytest.mark.parametrize("block", [0, 1])
+def test_rank_deficient_without_damping_is_enotpd(fobq, ctx, block):
     W, X = _problem(8, 96, 32, 9)
     ctx.hessian(_dev(X))
     with pytest.raises(fobq.FobqError) as e:
-        ctx.quantize_layer(_dev(W), damp=0.0)
+        ctx.quantize_layer(_dev(W), damp=0.0, block=block)
     assert e.value.code == fobq.ENOTPD
-    ctx.quantize_layer(_dev(W), damp=0.01)
+    ctx.quantize_layer(_dev(W), damp=0.01, block=block)
+
+
+@pytest.mark.parametrize("block", [0, 1])
+def test_failure_with_work_in_flight_leaves_the_context_usable(fobq, ctx, block):
+    # the n-th internal status check reports a failure (host-side test hook; every kernel that was
+    # launched still runs to its end): the call must wait for what it enqueued, and a good layer on
+    # the same context must then match the oracle
+    r, d, n = 40, 200, 500
+    W, X = _problem(r, d, n, 77, w_std=0.05)
+    Wd, Xd = _dev(W), _dev(X)
+    ref = oracle.quantize_layer(W, X=X, bits=4)
+    ctx.hessian(Xd)
+    ctx.quantize_layer(Wd, bits=4, block=block)          # workspace exists: later checks are launches
+    for nth in (1, 5, 12, 20, 26, 33):
+        _say(f"injected failure at check {nth}, block={block}")
+        fobq.fobq_debug_fail_after(ctx.handle, nth)
+        with pytest.raises(fobq.FobqError) as e:
+            ctx.quantize_layer(Wd, bits=4, block=block)
+        assert e.value.code == fobq.EHIP and "injected" in str(e.value)
+        out = ctx.quantize_layer(Wd, bits=4, block=block)
+        _compare_layer(out, ref, W, 4)
+    # enqueue / finish: a failed enqueue leaves nothing pending
+    fobq.fobq_debug_fail_after(ctx.handle, 15)
+    with pytest.raises(fobq.FobqError):
+        ctx.quantize_layer(Wd, bits=4, block=block, wait=False)
+    ctx.finish()
+    out = ctx.quantize_layer(Wd, bits=4, block=block, wait=False)
+    ctx.finish()
+    _compare_layer(out, ref, W, 4)
 
 
 @pytest.mark.parametrize("block", [0, 1, 16])
