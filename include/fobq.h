@@ -184,6 +184,23 @@ int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d, double* Hinv);
 int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                      const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);
 
+/*
+ * fobq_sensitivity for callers that cannot allocate device memory (code under HIP graph capture
+ * elsewhere in the process, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and results, but the scratch (grids, partial column sums, S, perm, status words) lives
+ * in one file-scope device array of the library, about 4.1 MiB per GPU, held until the process
+ * ends.  Its address on the context's GPU and the pinned status buffer are set up by fobq_create;
+ * this call itself calls no hipMalloc / hipFree / hipHostMalloc, creates no stream and no event
+ * (stage timing must be off: ESTATE otherwise).
+ * Limits (EINVAL beyond them, with the numbers in fobq_last_error): d_col <= 8192,
+ * d_row * G <= 131072 (G = d_col / group, 1 if group == 0), ceil(d_row / 64) * d_col <= 262144.
+ * All calls on one GPU share the array, whatever their context: calls that overlap in time on one
+ * GPU race; what must start at zero is cleared by the call itself.  Inputs, outputs, errors and
+ * the synchronisation are those of fobq_sensitivity.
+ */
+int fobq_sensitivity_static(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
+                            const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);
+
 /* Test hook for the error paths: the n-th internal status check from now on this context (n >= 1;
  * checks follow every HIP call and launch) reports FOBQ_EHIP although nothing failed; 0 disarms.
  * A call that fails this way with work already enqueued waits for that work before it returns and

@@ -65,6 +65,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_finish.argtypes = [vp]
     lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
+    lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
@@ -72,7 +73,7 @@ def load_library() -> ctypes.CDLL:
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_debug_fail_after",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -227,6 +228,13 @@ def fobq_sensitivity(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int
                      order: int = ORDER_SENSI_DESC, perm_in: Optional[torch.Tensor] = None,
                      S: Optional[torch.Tensor] = None, perm: Optional[torch.Tensor] = None):
     return _sensitivity(load_library().fobq_sensitivity, ctx, W, Hinv, bits, group, order, perm_in, S, perm)
+
+
+def fobq_sensitivity_static(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 4, group: int = 0,
+                            order: int = ORDER_SENSI_DESC, perm_in: Optional[torch.Tensor] = None,
+                            S: Optional[torch.Tensor] = None, perm: Optional[torch.Tensor] = None):
+    """The entry point that allocates nothing; pass S and perm to keep torch from allocating either."""
+    return _sensitivity(load_library().fobq_sensitivity_static, ctx, W, Hinv, bits, group, order, perm_in, S, perm)
 
 
 def fobq_debug_fail_after(ctx: int, n: int) -> None:

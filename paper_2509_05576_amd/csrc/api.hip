@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "fobq_internal.h"
@@ -217,7 +218,8 @@ static int order_kind(const fobq_opts* o)
          : (o->order == FOBQ_ORDER_W_DESC || o->order == FOBQ_ORDER_W_ASC)   ? 2 : 0;
 }
 
-// Scratch of the ordering stage (grid, column scores, order).
+// Scratch of the ordering stage (grid, column scores, order), either the context's own buffers or the
+// library's static scratch array (fobq_sensitivity_static).
 struct OrderBufs {
     double* scale; double* zero;   // d_row x G
     double* Spart;                 // sens_chunks(d_row) x d_col
@@ -305,6 +307,45 @@ static int drain_after_failure(fobq_ctx* ctx, int rc)
     return rc;
 }
 
+// ---- static scratch of fobq_sensitivity_static -------------------------------------------------
+// One array per GPU, held until the process ends.  The name `scratch` is only a host-side stand-in
+// for the symbol: host code uses the address hipGetSymbolAddress returns for the current device.
+constexpr int64_t STATIC_MAX_DCOL = 8192;        // columns
+constexpr int64_t STATIC_MAX_GRIDS = 131072;     // d_row * G grids
+constexpr int64_t STATIC_MAX_SPART = 262144;     // ceil(d_row / 64) * d_col partial column sums
+constexpr size_t STATIC_OFF_FLAGS = 0;
+constexpr size_t STATIC_OFF_S = 256;
+constexpr size_t STATIC_OFF_PERM = STATIC_OFF_S + STATIC_MAX_DCOL * sizeof(double);
+constexpr size_t STATIC_OFF_INVPERM = STATIC_OFF_PERM + STATIC_MAX_DCOL * sizeof(int);
+constexpr size_t STATIC_OFF_SCALE = STATIC_OFF_INVPERM + STATIC_MAX_DCOL * sizeof(int);
+constexpr size_t STATIC_OFF_ZERO = STATIC_OFF_SCALE + STATIC_MAX_GRIDS * sizeof(double);
+constexpr size_t STATIC_OFF_SPART = STATIC_OFF_ZERO + STATIC_MAX_GRIDS * sizeof(double);
+constexpr size_t STATIC_SCRATCH_BYTES = STATIC_OFF_SPART + STATIC_MAX_SPART * sizeof(double);   // about 4.1 MiB
+static_assert(STATIC_OFF_S % 256 == 0 && STATIC_OFF_PERM % 256 == 0 && STATIC_OFF_INVPERM % 256 == 0 &&
+              STATIC_OFF_SCALE % 256 == 0 && STATIC_OFF_ZERO % 256 == 0 && STATIC_OFF_SPART % 256 == 0, "alignment");
+static_assert(FLAG_COUNT * sizeof(int) <= STATIC_OFF_S, "flag words");
+
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[STATIC_MAX_DEVICES] = {nullptr};   // per device: where its copy of `scratch` lives
+
+// With `device` current: the device address of this GPU's copy of `scratch` (looked up once per device).
+static int static_scratch_lookup(fobq_ctx* ctx, int device)
+{
+    if (device < 0 || device >= STATIC_MAX_DEVICES) { ctx->static_scratch = nullptr; return FOBQ_OK; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_err(ctx, e == hipSuccess ? hipErrorInvalidSymbol : e, "address of the static scratch array");
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    ctx->static_scratch = g_scratch_ptr[device];
+    return FOBQ_OK;
+}
+
 }  // namespace fobq
 
 using namespace fobq;
@@ -321,12 +362,14 @@ int fobq_create(fobq_ctx** out, int device, void* hip_stream)
     if (!c) return FOBQ_ENOMEM;
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
-    // the pinned status buffer
+    // set-up that the entry points which must not allocate rely on: the pinned status buffer and the
+    // address of this GPU's copy of the static scratch array
     int rc = FOBQ_OK;
     {
         DeviceGuard g(device);
         rc = g.ok ? FOBQ_OK : FOBQ_EHIP;
         if (!rc) rc = ensure_host_flags(c);
+        if (!rc) rc = static_scratch_lookup(c, device);
     }
     if (rc) {
         if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -501,7 +544,7 @@ int fobq_spd_inverse(fobq_ctx* ctx, const double* H, int64_t d64, double* Hinv)
     return (rc && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
 }
 
-// argument checks of fobq_sensitivity
+// argument checks shared by fobq_sensitivity and fobq_sensitivity_static
 static int check_sensitivity_args(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
                                   const fobq_opts* opts, const int32_t* perm)
 {
@@ -544,6 +587,31 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
     rc = ensure_order_bufs(ctx, R, d, opts->group > 0 ? d / opts->group : 1, &b);
     if (rc) return rc;
     rc = run_sensitivity(ctx, W, R, d, Hinv, opts, b, S, perm);
+    return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
+}
+
+int fobq_sensitivity_static(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
+                            const fobq_opts* opts, double* S, int32_t* perm)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    int rc = check_sensitivity_args(ctx, W, d_row, d_col, Hinv, opts, perm);
+    if (rc) return rc;
+    const int64_t G = opts->group > 0 ? d_col / opts->group : 1;
+    if (d_col > STATIC_MAX_DCOL || d_row * G > STATIC_MAX_GRIDS || (int64_t)sens_chunks((int)d_row) * d_col > STATIC_MAX_SPART)
+        return set_err(ctx, FOBQ_EINVAL,
+                       "fobq_sensitivity_static: shape beyond the static scratch (needs d_col <= %lld, d_row * groups <= %lld, "
+                       "ceil(d_row / 64) * d_col <= %lld); use fobq_sensitivity",
+                       (long long)STATIC_MAX_DCOL, (long long)STATIC_MAX_GRIDS, (long long)STATIC_MAX_SPART);
+    if (ctx->profiling) return set_err(ctx, FOBQ_ESTATE, "fobq_sensitivity_static: stage timing creates events; turn it off");
+    unsigned char* base = ctx->static_scratch;
+    if (!base) return set_err(ctx, FOBQ_ESTATE, "no static scratch array on device %d", ctx->device);
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const OrderBufs b{reinterpret_cast<double*>(base + STATIC_OFF_SCALE), reinterpret_cast<double*>(base + STATIC_OFF_ZERO),
+                      reinterpret_cast<double*>(base + STATIC_OFF_SPART), reinterpret_cast<double*>(base + STATIC_OFF_S),
+                      reinterpret_cast<int*>(base + STATIC_OFF_PERM), reinterpret_cast<int*>(base + STATIC_OFF_INVPERM),
+                      reinterpret_cast<int*>(base + STATIC_OFF_FLAGS)};
+    rc = run_sensitivity(ctx, W, (int)d_row, (int)d_col, Hinv, opts, b, S, perm);
     return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
 }
 

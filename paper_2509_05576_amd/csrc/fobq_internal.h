@@ -99,6 +99,7 @@ struct fobq_ctx {
                             // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
     int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
     int* h_flags = nullptr; // pinned host memory that the status flags are read back into (made by fobq_create)
+    unsigned char* static_scratch = nullptr;   // this GPU's copy of the library's static scratch array
     int fail_countdown = 0; // test hook: > 0 = the n-th status check from now reports an injected failure
     // quantization workspace
     fobq::DevBuf Wp;        // d_row x d fp64, columns in processing order
