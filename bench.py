@@ -32,15 +32,28 @@ MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 2.28e9}
 MEASURED_STEP_TRAFFIC_BYTES = {"c5_large_d": 1.349e8}
 
 
-def sweep(model: str, steps: int, warmup: int, concurrency: int) -> int:
-    """Whole-model sweep: every layer of a ResNet-50- or YOLOv5s-shaped network (4-bit, per-row grids);
-    activations are ReLU(N(0,1)) drawn on the device (torch generator, seed 0), all layers' inputs resident
-    in HBM before anything is timed.
+def _median(v):
+    v = sorted(v)
+    n = len(v)
+    return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
-    Two measurements: (1) one layer after the other on one context, each layer timed on its own (the sum is
-    `sequential_ms`); (2) the whole model in one timed region with up to `concurrency` layers in flight on as
-    many contexts / streams (layers are independent of each other; most of a layer is a chain of short dependent
-    launches that leaves the GPU nearly idle, so layers overlap): `ms_per_step`, the whole-model time."""
+
+def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool) -> int:
+    """Whole-model sweep: every layer of a ResNet-50- or YOLOv5s-shaped network (4-bit, per-row grids,
+    128 images), each layer fed as the network would feed it: a k x k or strided convolution accumulates
+    its Hessian straight from its seeded ReLU-Gaussian input maps (fobq_hessian_accumulate_conv, a bounded
+    number of images per call), a 1 x 1 convolution of stride 1 and the classifier from X (d_col x N).
+    Weights and inputs come from the seeded counter-based generator of workloads.py, evaluated on the
+    device; everything is resident in HBM before anything is timed.  `iid` = the earlier variant that feeds
+    every layer an unfolded matrix of independent activations (no spatial correlation between taps).
+
+    Two measurements, each the MEDIAN over `steps` whole-model runs after `warmup`: (1) one layer after the
+    other on one context (`sequential_ms`); (2) up to `concurrency` layers in flight on as many contexts /
+    streams (layers are independent of each other; most of a layer is a chain of short dependent launches
+    that leaves the GPU nearly idle, so layers overlap): `ms_per_step`, the whole-model time.
+    After the timed region every layer is run once more and checked on the device: `perm` is a permutation,
+    Q = scale * (code - zero), codes within the grid, and the loss the path reports equals
+    1/2 tr(dW H_d dW^T) evaluated from the path's own Hessian; a miss fails the run."""
     import torch
 
     import paper_2509_05576_amd as fobq
@@ -48,74 +61,121 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int) -> int:
 
     fobq.load_library()
     layers = workloads.sweep_layers(model)
-    gen = torch.Generator(device="cuda")
-    chunk_elems = 1 << 28                          # calibration columns are accumulated in chunks of <= 1 GiB
-    Ws, Xs, chunks = [], [], []
+    pad_budget = 1 << 28                           # floats in the padded copy of one accumulate_conv call (1 GiB)
+    chunk_elems = 1 << 28                          # elements of X per accumulate call (1 GiB)
+    Ws, Ins, per_call = [], [], []
     for spec in layers:
-        gen.manual_seed(spec.layer_index)
-        Ws.append(torch.randn((spec.d_row, spec.d_col), generator=gen, device="cuda") * (2.0 / spec.d_col) ** 0.5)
-        Xs.append(torch.randn((spec.d_col, spec.n), generator=gen, device="cuda").relu_())
-        chunks.append(max(32, (chunk_elems // spec.d_col) // 32 * 32))
+        Ws.append(spec.make_w_device())
+        if iid or spec.conv is None:
+            Ins.append(workloads.device_normal_f32((spec.d_col, spec.n), 1.0, spec.seed,
+                                                   workloads.STREAM_ACT + 16 * spec.layer_index, relu=True))
+            per_call.append(max(32, (chunk_elems // spec.d_col) // 32 * 32))
+        else:
+            Ins.append(spec.make_input_device())
+            images, side, ch, k, pad = spec.conv
+            per_img = (side + 2 * pad) ** 2 * ch
+            per_call.append(max(1, min(images, pad_budget // per_img - 1)))
     torch.cuda.synchronize()
     total_weights = sum(spec.weights for spec in layers)
+    input_bytes = sum(int(t.numel()) * 4 for t in Ins)
 
-    # (1) one layer at a time
+    def hessian(ctx, spec, inp, pc, H_out=None):
+        if inp.dim() == 4:
+            ctx.hessian_conv(inp, spec.conv[3], spec.stride, spec.conv[4], images_per_call=pc, H_out=H_out)
+        else:
+            ctx.hessian(inp, chunk=pc, H_out=H_out)
+
+    # (1) one layer at a time; per-layer time = median over the runs
     ctx = fobq.Ctx(0)
-    per_layer = []
-    sequential_ms = 0.0
-    for spec, W, X, chunk in zip(layers, Ws, Xs, chunks):
-        out = None
-        best = None
-        for it in range(warmup + steps):
-            torch.cuda.synchronize()
+    outs = [None] * len(layers)
+    layer_ms = [[] for _ in layers]
+    seq_runs = []
+    for it in range(warmup + steps):
+        torch.cuda.synchronize()
+        t_run = time.perf_counter()
+        for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
             t0 = time.perf_counter()
-            ctx.hessian(X, chunk=chunk)
-            out = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=out)
+            hessian(ctx, spec, inp, pc)
+            outs[i] = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
             torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3
             if it >= warmup:
-                best = ms if best is None else min(best, ms)
-        per_layer.append({"layer": spec.name, "d_row": spec.d_row, "d_col": spec.d_col, "n": spec.n, "ms": round(best, 3)})
-        sequential_ms += best
+                layer_ms[i].append((time.perf_counter() - t0) * 1e3)
+        if it >= warmup:
+            seq_runs.append((time.perf_counter() - t_run) * 1e3)
+    workspace_seq = ctx.workspace_bytes()
+    per_layer = [{"layer": spec.name, "d_row": spec.d_row, "d_col": spec.d_col, "n": spec.n,
+                  "input": "maps" if inp.dim() == 4 else "X", "ms": round(_median(ms), 3)}
+                 for spec, inp, ms in zip(layers, Ins, layer_ms)]
+
+    # validity of every layer, on the device, from the path's own Hessian
+    checked = 0
+    for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
+        d = spec.d_col
+        H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+        hessian(ctx, spec, inp, pc, H_out=H)
+        o = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
+        torch.cuda.synchronize()
+        perm = o.perm.long()
+        ok_perm = bool(torch.equal(torch.sort(perm).values, torch.arange(d, device="cuda")))
+        codes = o.codes.to(torch.float64)
+        Q = o.Q.to(torch.float64)
+        sc, ze = o.scales.to(torch.float64), o.zeros.to(torch.float64)
+        ok_q = bool(torch.allclose(Q, sc * (codes - ze), rtol=1e-6, atol=1e-12)) and int(o.codes.max()) <= 2 ** spec.bits - 1
+        lam = spec.damp * float(torch.diagonal(H).mean())
+        dW = W.to(torch.float64) - Q
+        expect = 0.5 * float(((dW @ H) * dW).sum()) + 0.5 * lam * float((dW * dW).sum())
+        got = float(o.loss[0])
+        ok_loss = abs(got - expect) <= 1e-6 * abs(expect)
+        if not (ok_perm and ok_q and ok_loss):
+            print(f"bench.py: sweep check failed on {spec.name}: perm {ok_perm}, Q {ok_q}, loss {got} vs {expect}",
+                  file=sys.stderr)
+            return 1
+        checked += 1
+        del H
     ctx.close()
 
     # (2) the whole model, several layers in flight
     K = max(1, concurrency)
     streams = [torch.cuda.Stream() for _ in range(K)]
     ctxs = [fobq.Ctx(0, stream=st.cuda_stream) for st in streams]
-    outs = [None] * len(layers)
 
     def whole_model():
         busy = [False] * K
-        for i, (spec, W, X, chunk) in enumerate(zip(layers, Ws, Xs, chunks)):
+        for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
             k = i % K
             if busy[k]:
                 ctxs[k].finish()
-            ctxs[k].hessian(X, chunk=chunk)
+            hessian(ctxs[k], spec, inp, pc)
             outs[i] = ctxs[k].quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i], wait=False)
             busy[k] = True
         for k in range(K):
             if busy[k]:
                 ctxs[k].finish()
 
-    best = None
+    runs = []
     for it in range(warmup + steps):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         whole_model()
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3
         if it >= warmup:
-            best = ms if best is None else min(best, ms)
+            runs.append((time.perf_counter() - t0) * 1e3)
+    workspace_flight = sum(c.workspace_bytes() for c in ctxs)
     for c in ctxs:
         c.close()
+    med = _median(runs)
     line = {"metric": f"whole-model quantization time, {model}-shaped network ({len(layers)} layers)",
-            "value": round(total_weights / (best * 1e-3), 1), "unit": "weights/s", "n_gpus": 1, "steps": steps,
-            "warmup": warmup, "ms_per_step": round(best, 3), "higher_is_better": True, "scaling": "weak",
+            "value": round(total_weights / (med * 1e-3), 1), "unit": "weights/s", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": round(med, 3), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-            "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images",
-                       "weights": total_weights, "layers_in_flight": K},
-            "whole_model_seconds": round(best * 1e-3, 4), "sequential_ms": round(sequential_ms, 3),
+            "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images, "
+                                   + ("every layer from an unfolded matrix of independent activations"
+                                      if iid else "k x k and strided convolutions from their input maps"),
+                       "weights": total_weights, "layers_in_flight": K, "input_bytes": input_bytes},
+            "whole_model_seconds": round(med * 1e-3, 4), "runs_ms": [round(r, 2) for r in runs],
+            "sequential_ms": round(_median(seq_runs), 3), "sequential_runs_ms": [round(r, 2) for r in seq_runs],
+            "layers_checked": checked,
+            "workspace_bytes": {"one_context": workspace_seq, "contexts_in_flight": workspace_flight},
             "per_layer": per_layer}
     print(json.dumps(line))
     return 0
@@ -134,6 +194,9 @@ def main() -> int:
                          "(fobq_hessian_accumulate_conv) instead of the unfolded X")
     ap.add_argument("--concurrency", type=int, default=8,
                     help="whole-model sweeps: layers in flight at once (one context and stream each)")
+    ap.add_argument("--iid", action="store_true",
+                    help="whole-model sweeps: feed every layer an unfolded matrix of independent activations "
+                         "instead of the convolutions' input maps (the earlier variant, kept for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--obq-rows", type=int, default=0,
                     help="with the CPU baseline: also run the per-row OBQ baseline (own inverse Hessian per row) "
@@ -156,7 +219,8 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 2
     if args.workload in ("sweep_resnet50", "sweep_yolov5s"):
-        return sweep(args.workload[len("sweep_"):], min(args.steps, 3), min(args.warmup, 1), args.concurrency)
+        return sweep(args.workload[len("sweep_"):], max(5, min(args.steps, 9)), min(args.warmup, 2), args.concurrency,
+                     args.iid)
     fobq.load_library()
     spec = workloads.configs()[args.workload]
     W = spec.make_w()
@@ -182,7 +246,7 @@ def main() -> int:
     def step():
         nonlocal out
         if Md is not None:
-            ctx.hessian_conv(Md, spec.conv[3], 1, spec.conv[4])
+            ctx.hessian_conv(Md, spec.conv[3], spec.stride, spec.conv[4])
         else:
             ctx.hessian(Xd, chunk=args.chunk or None)
         out = ctx.quantize_layer(Wd, bits=spec.bits, group=spec.group, damp=spec.damp, block=args.block, out=out)

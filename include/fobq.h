@@ -99,6 +99,11 @@ int fobq_destroy(fobq_ctx* ctx);
 /* Text of the last error on this context ("" if none).  Valid until the next call. */
 const char* fobq_last_error(const fobq_ctx* ctx);
 
+/* Device scratch the context holds right now, in bytes.  Scratch grows on demand and is only
+ * released by fobq_destroy, so after a run this is the run's peak (the "Mem." column of the
+ * paper's Tables 1-3 reports the same kind of figure for whole models).  Host call, no GPU work. */
+int fobq_workspace_bytes(fobq_ctx* ctx, int64_t* bytes);
+
 /*
  * Hessian of the layer objective (Section 3, Eq. 2): H = (2 / N) X X^T, N the
  * total number of calibration columns, accumulated over chunks of columns.

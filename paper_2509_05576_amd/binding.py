@@ -67,13 +67,14 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
     lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
+    lib.fobq_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
     lib.fobq_profile_reset.argtypes = [vp]
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_sensitivity_static", "fobq_debug_fail_after",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -237,6 +238,12 @@ def fobq_sensitivity_static(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bi
     return _sensitivity(load_library().fobq_sensitivity_static, ctx, W, Hinv, bits, group, order, perm_in, S, perm)
 
 
+def fobq_workspace_bytes(ctx: int) -> int:
+    b = ctypes.c_int64(0)
+    _check(ctx, load_library().fobq_workspace_bytes(ctypes.c_void_p(ctx), ctypes.byref(b)))
+    return b.value
+
+
 def fobq_debug_fail_after(ctx: int, n: int) -> None:
     _check(ctx, load_library().fobq_debug_fail_after(ctypes.c_void_p(ctx), n))
 
@@ -307,6 +314,9 @@ class Ctx:
 
     def finish(self) -> None:
         fobq_finish(self.handle)
+
+    def workspace_bytes(self) -> int:
+        return fobq_workspace_bytes(self.handle)
 
     def stage_ms(self):
         return {name: fobq_profile_get(self.handle, i) for i, name in enumerate(STAGES)}

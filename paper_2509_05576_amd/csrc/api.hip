@@ -350,6 +350,13 @@ static int static_scratch_lookup(fobq_ctx* ctx, int device)
 
 using namespace fobq;
 
+static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
+{
+    return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
+            &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
+}
+
 extern "C" {
 
 int fobq_create(fobq_ctx** out, int device, void* hip_stream)
@@ -392,16 +399,22 @@ int fobq_destroy(fobq_ctx* ctx)
         (void)hipStreamDestroy(ctx->side);
     }
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
-    DevBuf* bufs[] = {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
-                      &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-                      &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
-    for (DevBuf* b : bufs) b->release();
+    for (DevBuf* b : all_buffers(ctx)) b->release();
     if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
     delete ctx;
     return FOBQ_OK;
 }
 
 const char* fobq_last_error(const fobq_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+int fobq_workspace_bytes(fobq_ctx* ctx, int64_t* bytes)
+{
+    if (!ctx || !bytes) return FOBQ_EINVAL;
+    size_t total = 0;
+    for (DevBuf* b : all_buffers(ctx)) total += b->cap;
+    *bytes = (int64_t)total;
+    return FOBQ_OK;
+}
 
 int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
 {

@@ -578,21 +578,44 @@ def _run_config(fobq, ctx, name, rows=None, block=0, chunk=None, spec=None):
     spec = spec if spec is not None else workloads.configs()[name]
     _say(f"config {name}: generating inputs")
     W = spec.make_w()
-    X = spec.make_x()
-    Xd = _dev(X)
-    _say(f"config {name}: GPU path")
-    if chunk is not None:
-        # accumulation over several calls gives the same Hessian as one call (up to summation order)
-        ctx.hessian(Xd, chunk=chunk)
-        Hc = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
-        fobq.fobq_hessian_finalize(ctx.handle, Hc)
-        torch.cuda.synchronize()
-        Hc = Hc.cpu().numpy()
-    ctx.hessian(Xd)          # one launch over all calibration columns: the configuration bench.py times
-    out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp, block=block)
-    del Xd
+    from_maps = spec.conv is not None and name != "c2_resnet50_3x3"
+    if from_maps:
+        # a sweep layer that is a k x k or strided convolution: the GPU path gets the input maps
+        # (`chunk` = images per call), the oracle their unfolding
+        maps = spec.make_maps()
+        _images, _side, _ch, k, pad = spec.conv
+        Md = _dev(maps)
+        _say(f"config {name}: GPU path from the feature maps (k={k} stride={spec.stride} pad={pad})")
+        if chunk is not None:
+            ctx.hessian_conv(Md, k, spec.stride, pad, images_per_call=chunk)
+            Hc = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
+            fobq.fobq_hessian_finalize(ctx.handle, Hc)
+            torch.cuda.synchronize()
+            Hc = Hc.cpu().numpy()
+        ctx.hessian_conv(Md, k, spec.stride, pad)
+        out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp, block=block)
+        del Md
+        _say(f"config {name}: unfolding the maps for the oracle")
+        X = workloads.im2col(maps, k, spec.stride, pad)
+        del maps
+        assert X.shape == (spec.d_col, spec.n)
+    else:
+        X = spec.make_x()
+        Xd = _dev(X)
+        _say(f"config {name}: GPU path")
+        if chunk is not None:
+            # accumulation over several calls gives the same Hessian as one call (up to summation order)
+            ctx.hessian(Xd, chunk=chunk)
+            Hc = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
+            fobq.fobq_hessian_finalize(ctx.handle, Hc)
+            torch.cuda.synchronize()
+            Hc = Hc.cpu().numpy()
+        ctx.hessian(Xd)          # one launch over all calibration columns: the configuration bench.py times
+        out = ctx.quantize_layer(_dev(W), bits=spec.bits, group=spec.group, damp=spec.damp, block=block)
+        del Xd
     _say(f"config {name}: oracle")
     H = oracle.hessian(X)
+    del X
     Hg = torch.empty((spec.d_col, spec.d_col), dtype=torch.float64, device="cuda")
     fobq.fobq_hessian_finalize(ctx.handle, Hg)
     torch.cuda.synchronize()
@@ -692,17 +715,28 @@ def test_config_with_dynamic_order(fobq, ctx, name):
 
 @pytest.mark.slow
 def test_config_c5_large_d(fobq, ctx):
-    _run_config(fobq, ctx, "c5_large_d", rows=64)
+    # every one of the 2048 rows against the oracle
+    _run_config(fobq, ctx, "c5_large_d")
 
 
-# config 4 (whole-model sweep): parity on layers of the sweep that add something the other
-# configs do not -- ragged d_col (147), ragged d_row (255), a very long calibration set
-# accumulated in chunks, d_col = 4608 with N barely above d_col, and N << d_col.
+# config 4 (whole-model sweep): parity on layers of the sweep, fed as the sweep feeds them (k x k and
+# strided convolutions from their seeded input maps, the rest from X), one per kernel path that the other
+# configs do not reach: ragged d_col (147, 108) and d_row (255), very long calibration sets accumulated
+# over several calls, the 64-wide tiles of X X^T (d_col = 64, 288, 576), strided 3 x 3 and 1 x 1
+# convolutions, d_col = 1152 and 1024, d_col = 4608 with N barely above d_col, and N << d_col.
+# (model, layer, images or columns per call of the chunked accumulation)
 SWEEP_CASES = [
-    ("resnet50", "resnet50_64x147_n1605632_0", 1 << 18),
-    ("yolov5s", "yolov5s_255x128_n819200_0", 200000),
-    ("resnet50", "resnet50_512x4608_n6272_0", None),
-    ("resnet50", "resnet50_1000x2048_n128_0", None),
+    ("resnet50", "resnet50_64x147_n1605632_0", 48),        # 7 x 7 stride 2 stem
+    ("resnet50", "resnet50_64x576_n401408_0", None),       # 3 x 3, 64-wide tiles
+    ("resnet50", "resnet50_128x1152_n100352_0", 50),       # 3 x 3 stride 2
+    ("resnet50", "resnet50_512x256_n100352_0", None),      # 1 x 1 stride 2 (projection shortcut)
+    ("resnet50", "resnet50_512x1024_n25088_0", 10000),     # 1 x 1, d_row 512
+    ("resnet50", "resnet50_512x4608_n6272_0", None),       # 3 x 3 stride 2, N barely above d_col
+    ("resnet50", "resnet50_1000x2048_n128_0", None),       # classifier, N << d_col
+    ("yolov5s", "yolov5s_32x108_n13107200_0", 40),         # 6 x 6 stride 2 stem, 13.1 M columns
+    ("yolov5s", "yolov5s_64x288_n3276800_0", None),        # 3 x 3 stride 2, 64-wide tiles
+    ("yolov5s", "yolov5s_32x64_n3276800_0", 1 << 20),      # 1 x 1, one 64-wide tile
+    ("yolov5s", "yolov5s_255x128_n819200_0", 200000),      # detection head, ragged d_row
 ]
 
 
@@ -710,4 +744,4 @@ SWEEP_CASES = [
 @pytest.mark.parametrize("model,layer,chunk", SWEEP_CASES)
 def test_config_c4_sweep_layers(fobq, ctx, model, layer, chunk):
     spec = next(l for l in workloads.sweep_layers(model) if l.name == layer)
-    _run_config(fobq, ctx, layer, rows=None if spec.d_col < 4000 else 96, chunk=chunk, spec=spec)
+    _run_config(fobq, ctx, layer, chunk=chunk, spec=spec)
