@@ -25,11 +25,33 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
-# HBM bytes per xxt_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
-# counter reads for a plain device copy of X (profiles/xxt_kernel_c2_counters.txt); one launch per step only
-MEASURED_TRAFFIC_BYTES = {"c2_resnet50_3x3": 2.28e9}
-# the same for step_kernel (--block 1), average per launch (profiles/step_kernel_c5_block1.txt)
-MEASURED_STEP_TRAFFIC_BYTES = {"c5_large_d": 1.349e8}
+PEAK_HBM_GBS = 8000.0
+
+
+def _blob_hash(path: str) -> str:
+    """git's blob hash of a file's current contents."""
+    import hashlib
+    data = open(path, "rb").read()
+    return hashlib.sha1(b"blob %d\0" % len(data) + data).hexdigest()
+
+
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload` from the counter runs recorded in profiles/traffic.json
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads for a plain device
+    copy of known size).  None when no record exists or when the kernel's source file has changed since the
+    counters were read (the record carries the file's git blob hash)."""
+    try:
+        records = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))["records"]
+    except (OSError, ValueError, KeyError):
+        return None
+    for r in records:
+        if r.get("kernel") == kernel and r.get("workload") == workload:
+            try:
+                if _blob_hash(os.path.join(ROOT, r["source"])) == r["source_blob"]:
+                    return float(r["bytes_per_launch"])
+            except OSError:
+                pass
+    return None
 
 
 def _median(v):
@@ -289,24 +311,47 @@ def main() -> int:
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"kernel": "xxt_kernel", "bound": "mfma", "achieved": round(achieved, 3),
                 "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(spec.name) if launches_per_step == 1 else None,
+                "traffic": measured_traffic("xxt_kernel", spec.name) if launches_per_step == 1 and not args.from_maps else None,
                 "avg_launch_ms": round(avg_ms, 4),
                 "algorithmic_flops_per_launch": flops_per_launch}
 
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
+    R, d = spec.d_row, spec.d_col
     if args.block == 1:
-        # the literal rank-1 path: step_kernel (one launch per column) dominates and is HBM-bound.
-        # Algorithmic bytes per layer: fp64 W read + write and the upper triangle of the fp64 running
-        # inverse read + write, 8 R d^2 + (8/3) d^3; one launch = one column.  The launches are timed
-        # together (HIP events around the stage on the library's stream), so launch gaps are included.
-        R, d = spec.d_row, spec.d_col
-        bytes_per_launch = (8.0 * R * d * d + 8.0 / 3.0 * d ** 3) / d
+        # the literal rank-1 path: step_kernel (one launch per column) dominates and is HBM-bound.  The
+        # launches are timed together (HIP events around the stage on the library's stream), so launch gaps
+        # are included.  Two byte counts per layer: the algorithmic one of the streaming formulation with
+        # fp32 weights, 4 R d^2 + (8/3) d^3 (W read + write, upper triangle of the fp64 running inverse read +
+        # write) -- `achieved` and `frac` -- and what this kernel really moves, whose running weights are
+        # fp64: 8 R d^2 + (8/3) d^3 (`moved_*`).  One launch = one column.
+        bytes_per_launch = (4.0 * R * d * d + 8.0 / 3.0 * d ** 3) / d
+        moved_per_launch = (8.0 * R * d * d + 8.0 / 3.0 * d ** 3) / d
         col_ms, _ = stages["columns"]
         avg_ms = col_ms / (args.steps * d)
         ach = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        roofline = {"kernel": "step_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
-                    "frac": round(ach / 8000.0, 4), "traffic": MEASURED_STEP_TRAFFIC_BYTES.get(spec.name),
-                    "avg_launch_ms": round(avg_ms, 6), "algorithmic_bytes_per_launch": bytes_per_launch}
+        moved = moved_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": "step_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": measured_traffic("step_kernel", spec.name),
+                    "avg_launch_ms": round(avg_ms, 6), "algorithmic_bytes_per_launch": bytes_per_launch,
+                    "moved_bytes_per_launch": moved_per_launch, "moved_GBs": round(moved, 1),
+                    "moved_frac": round(moved / PEAK_HBM_GBS, 4)}
+    # The other contractions of the path, from the stage events of the second pass (each stage is many short
+    # dependent launches, so these are stage-level rates, launch gaps included), against the fp64 matrix
+    # peak: shared-Hinv elimination d^3 / 3 flop (symmetric trailing updates), column loop R d^2 (deferred
+    # compensation), Cholesky + triangular inverse + L^-T L^-1 d^3.
+    secondary = []
+    if args.block != 1:
+        for name, stage_names, flops in (("eliminate (elim_iter_kernel)", ("eliminate",), d ** 3 / 3.0),
+                                         ("columns (col_block_kernel)", ("columns",), float(R) * d * d),
+                                         ("cholesky + inverse (chol_iter_kernel, gemm64_kernel)",
+                                          ("cholesky", "inverse"), float(d) ** 3)):
+            ms = sum(stages[n][0] for n in stage_names) / args.steps
+            if ms > 0:
+                tf = flops / (ms * 1e-3) / 1e12
+                secondary.append({"stage": name, "bound": "mfma", "algorithmic_flops": flops, "ms": round(ms, 4),
+                                  "achieved": round(tf, 3), "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": round(tf / PEAK_FP64_MFMA_TFLOPS, 4)})
+    workspace = ctx.workspace_bytes()
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -344,6 +389,8 @@ def main() -> int:
                    "hessian_input": "feature maps (implicit unfold)" if args.from_maps else "unfolded X"},
         "stages_ms": stage_ms,
         "roofline": roofline,
+        "roofline_secondary": secondary,
+        "workspace_bytes": workspace,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
