@@ -117,6 +117,25 @@ int fobq_workspace_bytes(fobq_ctx* ctx, int64_t* bytes);
  * Errors: EINVAL on bad sizes/NULL, ESTATE on wrong call order, ENOMEM, EHIP.
  */
 int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col);
+
+/*
+ * How fobq_hessian_accumulate forms X_c X_c^T (Section 3, Eq. 2):
+ *   FOBQ_HESSIAN_FP64         fp64 matrix instructions on the exactly widened fp32 inputs (default):
+ *                             the sum differs from the exact one by fp64 rounding only.
+ *   FOBQ_HESSIAN_INT8_SLICES  every row of X_c as a 40-bit fixed-point number under a per-row power of
+ *                             two, cut into five signed 8-bit digits; the 19 digit-by-digit products
+ *                             whose weights are 256^0 .. 256^-5 relative to the leading one are formed
+ *                             exactly on the int8 matrix cores (int32 sums, folded into fp64), the rest
+ *                             dropped.  H differs from the fp64 result by about 3e-13 of its largest
+ *                             entry; several times faster on large layers.  Applies to calls with
+ *                             d_col >= 256 and n >= 2048; other calls, and
+ *                             fobq_hessian_accumulate_conv, use the fp64 form.  An Inf or NaN in X makes
+ *                             H NaN throughout (the layer then fails with ENOTPD).  Scratch: 1.25 bytes
+ *                             per element of X_c.
+ * Stays in force until changed; not while an accumulation has begun (ESTATE).
+ */
+typedef enum { FOBQ_HESSIAN_FP64 = 0, FOBQ_HESSIAN_INT8_SLICES = 1 } fobq_hessian_mode;
+int fobq_hessian_set_mode(fobq_ctx* ctx, int mode);
 int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld);
 int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
 
@@ -223,7 +242,8 @@ typedef enum {
     FOBQ_STAGE_ELIMINATE = 6,/* shared-Hinv elimination (blocked form only)                 */
     FOBQ_STAGE_COLUMNS = 7,  /* column loop: quantize + compensate (+ Eq. 12 when unblocked)*/
     FOBQ_STAGE_EMIT = 8,     /* scatter to original order, loss                             */
-    FOBQ_STAGE_COUNT = 9
+    FOBQ_STAGE_SLICE = 9,    /* integer-slice mode: row exponents and digits of X           */
+    FOBQ_STAGE_COUNT = 10
 } fobq_stage;
 
 /* Turn hipEvent timing of the stages on or off (off by default): on = 0 none, 1 every stage,

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC, ORDER_SENSI_DYNAMIC,
     STAGES, lib_path, load_library,
     fobq_create, fobq_destroy, fobq_last_error,
+    HESSIAN_FP64, HESSIAN_INT8_SLICES, fobq_hessian_set_mode,
     fobq_hessian_begin, fobq_hessian_accumulate, fobq_hessian_accumulate_conv, fobq_hessian_finalize,
     fobq_quantize_layer, fobq_finish, fobq_spd_inverse, fobq_sensitivity, fobq_sensitivity_static,
     fobq_debug_fail_after, fobq_workspace_bytes,

@@ -15,7 +15,8 @@ OK, EINVAL, ENOMEM, EHIP, ENOTPD, ESTATE = 0, -1, -2, -3, -4, -5
 ORDER_NATURAL, ORDER_SENSI_DESC, ORDER_CUSTOM = 0, 1, 2
 ORDER_ERR_DESC, ORDER_W_DESC, ORDER_SENSI_ASC, ORDER_ERR_ASC, ORDER_W_ASC = 3, 4, 5, 6, 7
 ORDER_SENSI_DYNAMIC = 8
-STAGES = ("xxt", "finalize", "cholesky", "inverse", "order", "permute", "eliminate", "columns", "emit")
+STAGES = ("xxt", "finalize", "cholesky", "inverse", "order", "permute", "eliminate", "columns", "emit", "slice")
+HESSIAN_FP64, HESSIAN_INT8_SLICES = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -57,6 +58,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_last_error.argtypes = [vp]
     lib.fobq_last_error.restype = ctypes.c_char_p
     lib.fobq_hessian_begin.argtypes = [vp, i64]
+    lib.fobq_hessian_set_mode.argtypes = [vp, i32]
     lib.fobq_hessian_accumulate.argtypes = [vp, vp, i64, i64]
     lib.fobq_hessian_accumulate_conv.argtypes = [vp, vp, i64, i64, i64, i64, i32, i32, i32]
     lib.fobq_hessian_finalize.argtypes = [vp, vp]
@@ -71,7 +73,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
     lib.fobq_profile_reset.argtypes = [vp]
-    for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_accumulate",
+    for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
                  "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes",
@@ -122,6 +124,10 @@ def _check(ctx: int, rc: int) -> None:
 
 def fobq_hessian_begin(ctx: int, d_col: int) -> None:
     _check(ctx, load_library().fobq_hessian_begin(ctypes.c_void_p(ctx), d_col))
+
+
+def fobq_hessian_set_mode(ctx: int, mode: int) -> None:
+    _check(ctx, load_library().fobq_hessian_set_mode(ctypes.c_void_p(ctx), mode))
 
 
 def fobq_hessian_accumulate(ctx: int, X: torch.Tensor) -> None:
@@ -289,6 +295,9 @@ class Ctx:
             self.close()
         except Exception:
             pass
+
+    def set_hessian_mode(self, mode: int) -> None:
+        fobq_hessian_set_mode(self.handle, mode)
 
     def hessian(self, X: torch.Tensor, chunk: Optional[int] = None, H_out: Optional[torch.Tensor] = None) -> None:
         """begin / accumulate (optionally in column chunks) / finalize."""

@@ -129,6 +129,8 @@ constexpr int64_t MAX_DCOL = 32768;
 // three products per inverse tile against one, and the launches are full without them)
 constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
+constexpr int I8_MIN_D = 256;
+constexpr int64_t I8_MIN_N = 2048;
 
 enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
 
@@ -354,7 +356,7 @@ static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
 {
     return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
             &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad};
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh};
 }
 
 extern "C" {
@@ -416,6 +418,16 @@ int fobq_workspace_bytes(fobq_ctx* ctx, int64_t* bytes)
     return FOBQ_OK;
 }
 
+int fobq_hessian_set_mode(fobq_ctx* ctx, int mode)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (mode != FOBQ_HESSIAN_FP64 && mode != FOBQ_HESSIAN_INT8_SLICES) return set_err(ctx, FOBQ_EINVAL, "unknown Hessian mode %d", mode);
+    if (ctx->h_d != 0 && !ctx->h_final && ctx->h_n > 0)
+        return set_err(ctx, FOBQ_ESTATE, "the mode cannot change in the middle of an accumulation");
+    ctx->h_mode = mode;
+    return FOBQ_OK;
+}
+
 int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
 {
     if (!ctx) return FOBQ_EINVAL;
@@ -426,6 +438,11 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
     const size_t dd = (size_t)d_col * d_col * sizeof(double);
     FOBQ_TRY(ctx->Hpart.ensure(dd * splits), "workspace Hpart");
     FOBQ_TRY(ctx->H.ensure(dd), "workspace H");
+    {
+        int rc = ensure_flags(ctx);
+        if (rc) return rc;
+    }
+    ctx->h_i8_used = false;
     ctx->h_zeroed = 0;      // slabs are cleared when a launch first needs them
     ctx->h_conv_c = 0;      // plain or convolution mode is fixed by the first accumulate call
     ctx->h_conv_k = 0;
@@ -438,9 +455,10 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
 }
 
 // clears the slabs of Hpart that a launch over n calibration columns can touch for the first time
-static int clear_slabs(fobq_ctx* ctx, int64_t n, bool conv)
+static int clear_slabs(fobq_ctx* ctx, int64_t n, bool conv, bool i8 = false)
 {
-    const int need = xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits, conv);
+    const int need = i8 ? xxt_i8_slabs_touched((int)ctx->h_d, n, ctx->h_splits)
+                        : xxt_slabs_touched((int)ctx->h_d, n, ctx->h_splits, conv);
     if (need > ctx->h_zeroed) {
         FOBQ_TRY(launch_clear_slabs(ctx->stream, ctx->Hpart.as<double>(), (int)ctx->h_d, ctx->h_zeroed, need - ctx->h_zeroed),
                  "clear Hessian accumulator");
@@ -460,11 +478,32 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     if (n == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    int rc = clear_slabs(ctx, n, false);
+    const int d = (int)ctx->h_d;
+    // integer slices pay where the fp64 kernel is bound by the matrix pipes: 128-wide tiles and a call long
+    // enough to amortise the slicing pass
+    const bool i8 = ctx->h_mode == FOBQ_HESSIAN_INT8_SLICES && d >= I8_MIN_D && n >= I8_MIN_N;
+    if (i8) {
+        FOBQ_TRY(ctx->i8planes.ensure(i8_planes_bytes(d, n)), "workspace digit planes");
+        FOBQ_TRY(ctx->i8sh.ensure((size_t)i8_dpad(d) * sizeof(int)), "workspace row shifts");
+    }
+    int rc = clear_slabs(ctx, n, false, i8);
     if (rc) return rc;
     ctx->h_conv_c = -1;
-    FOBQ_TRY(launch_xxt(ctx->stream, X, ld, (int)ctx->h_d, n, ctx->Hpart.as<double>(), ctx->h_splits,
-                        stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt");
+    if (i8) {
+        int* nonfinite = ctx->flags.as<int>() + FLAG_WORD_NONFINITE;
+        if (!ctx->h_i8_used) FOBQ_TRY(launch_clear_words(ctx->stream, nonfinite, 1, nullptr, 0), "clear flag");
+        ctx->h_i8_used = true;
+        {
+            StageScope sc(ctx, FOBQ_STAGE_SLICE);
+            FOBQ_TRY(launch_i8_slices(ctx->stream, X, ld, d, n, ctx->i8sh.as<int>(), ctx->i8planes.as<signed char>(),
+                                      nonfinite), "integer slices");
+        }
+        FOBQ_TRY(launch_xxt_i8(ctx->stream, ctx->i8planes.as<signed char>(), ctx->i8sh.as<int>(), d, n,
+                               ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (int8)");
+    } else {
+        FOBQ_TRY(launch_xxt(ctx->stream, X, ld, d, n, ctx->Hpart.as<double>(), ctx->h_splits,
+                            stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt");
+    }
     ctx->h_n += n;
     return FOBQ_OK;
 }
@@ -526,7 +565,8 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
         StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
         FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d,
                                          2.0 / (double)ctx->h_n, ctx->H.as<double>(), ctx->h_conv_c > 0 ? ctx->h_conv_c : 0,
-                                         ctx->h_conv_k * ctx->h_conv_k), "hessian finalize");
+                                         ctx->h_conv_k * ctx->h_conv_k,
+                                         ctx->h_i8_used ? ctx->flags.as<int>() + FLAG_WORD_NONFINITE : nullptr), "hessian finalize");
         if (H_out)
             FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice,
                                     ctx->stream), "copy H");

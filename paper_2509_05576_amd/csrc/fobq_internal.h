@@ -71,7 +71,7 @@ struct StageTimer {
 
 }  // namespace fobq
 
-constexpr int FLAG_WORDS = 16, FLAG_WORD_MATE = 8;
+constexpr int FLAG_WORDS = 16, FLAG_WORD_MATE = 8, FLAG_WORD_NONFINITE = 9;
 
 struct fobq_ctx {
     int device = 0;
@@ -86,6 +86,10 @@ struct fobq_ctx {
     bool    h_final = false;
     int     h_conv_c = 0;   // > 0: accumulation in convolution mode with this many channels ...
     int     h_conv_k = 0;   // ... and this kernel size; -1 in h_conv_c: plain mode
+    int     h_mode = 0;     // fobq_hessian_mode
+    bool    h_i8_used = false;  // the integer-slice kernels ran in this accumulation
+    fobq::DevBuf i8planes;  // digits of one accumulate call (see hessian_i8.hip)
+    fobq::DevBuf i8sh;      // per-row shifts of that call
 
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
     fobq::DevBuf maps_pad;  // zero-padded copy of the feature maps of one accumulate_conv call (+ 1 zero image)
@@ -149,7 +153,16 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
                            int ho, int wo, int64_t npix, double* Hpart, int splits,
                            LaunchEvents ev = LaunchEvents());
 hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
-                                   int conv_c, int conv_kk);
+                                   int conv_c, int conv_kk, const int* poison);   // *poison != 0: H = NaN
+
+// hessian_i8.hip: X X^T by exact integer slices on the int8 matrix cores
+int i8_dpad(int d);
+size_t i8_planes_bytes(int d, int64_t n);
+int xxt_i8_slabs_touched(int d, int64_t n, int splits);
+hipError_t launch_i8_slices(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, signed char* planes,
+                            int* nonfinite);
+hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh, int d, int64_t n, double* Hpart,
+                         int splits, LaunchEvents ev = LaunchEvents());
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
 
 // factor.hip

@@ -583,8 +583,11 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
 }
 
 // H[a][b] = H[b][a] = factor * sum_s Hpart[s][a][b]   for b <= a (lower slabs hold the sums)
+// poison (may be null): a word that is non-zero when an input of the integer-slice path held an Inf or NaN;
+// H then becomes NaN throughout, as the floating-point sum would have made the rows concerned.
 __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __restrict__ Hpart, int splits, int d,
-                                                               double factor, double* __restrict__ H)
+                                                               double factor, double* __restrict__ H,
+                                                               const int* __restrict__ poison)
 {
     const int b = blockIdx.x * 16 + (threadIdx.x & 15);
     const int a = blockIdx.y * 16 + (threadIdx.x >> 4);
@@ -592,6 +595,7 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __r
     double s = 0.0;
     for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * d * d + (int64_t)a * d + b];
     s *= factor;
+    if (poison && *poison) s = __builtin_nan("");
     H[(int64_t)a * d + b] = s;
     H[(int64_t)b * d + a] = s;
 }
@@ -599,7 +603,7 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __r
 // Convolution mode: the slabs are in tap-major row order; H is written in (c, ky, kx) order.
 __global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double* __restrict__ Hpart, int splits, int d,
                                                                     double factor, double* __restrict__ H, int c,
-                                                                    int kk)
+                                                                    int kk, const int* __restrict__ poison)
 {
     const int b = blockIdx.x * 16 + (threadIdx.x & 15);
     const int a = blockIdx.y * 16 + (threadIdx.x >> 4);
@@ -609,19 +613,20 @@ __global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double
     double s = 0.0;
     for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * d * d + (int64_t)hi * d + lo];
     s *= factor;
+    if (poison && *poison) s = __builtin_nan("");
     H[(int64_t)a * d + b] = s;
     H[(int64_t)b * d + a] = s;
 }
 
 // conv_c > 0: the slabs were accumulated in convolution mode with conv_c channels and conv_kk taps
 hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
-                                   int conv_c, int conv_kk)
+                                   int conv_c, int conv_kk, const int* poison)
 {
     dim3 grid((d + 15) / 16, (d + 15) / 16), block(256);
     if (conv_c > 0)
-        hipLaunchKernelGGL(hessian_finalize_conv_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, conv_c, conv_kk);
+        hipLaunchKernelGGL(hessian_finalize_conv_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, conv_c, conv_kk, poison);
     else
-        hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, d, factor, H);
+        hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, poison);
     return hipGetLastError();
 }
 

@@ -1,0 +1,381 @@
+// X X^T of the layer Hessian (Section 3, Eq. 2) on the int8 matrix cores, by exact integer slices.
+//
+// Every row i of the fp32 X handed to one accumulate call is written as a fixed-point integer under a
+// per-row power of two, Y = rint(x * 2^sh_i), |Y| <= 2^38, and Y is cut into NS = 5 balanced base-256
+// digits D_0 (most significant) .. D_4, each in [-128, 127]:  Y = sum_s D_s 256^(4 - s).  Then
+//     x_i . x_j  =  2^-(sh_i + sh_j)  sum_{s,t} 256^(8 - s - t)  (D_s[i] . D_t[j])
+// and every slice product D_s[i] . D_t[j] is an int8 dot product that the matrix cores accumulate
+// exactly in int32 (v_mfma_i32_32x32x32_i8).  Products with the same s + t = m share a scale and an
+// accumulator; the antidiagonals m = 0 .. 5 are kept (19 slice products), m >= 6 dropped.  (Splitting a
+// floating-point product into exact integer slice products is the published "Ozaki scheme" for matrix
+// units; the choice of 5 digits and 6 antidiagonals is this library's.)  What that costs in accuracy,
+// measured against the fp64 sum on the benchmark layers: H differs by 3e-13 relative, the column scores
+// by 2e-11 relative at most; with one antidiagonal less (15 products) the scores move by 1e-9, which is
+// the size of the smallest gap between two column scores of those layers -- the processing order must
+// not change, so the sixth antidiagonal stays.
+//
+// int32 accumulators are folded into the fp64 slabs of partial sums after at most I8_FOLD_STEPS k-steps:
+// at most 5 products per accumulator, |D D'| <= 2^14, 2^14 columns  ->  |sum| <= 5 * 2^28 < 2^31.
+//
+// Three kernels: row_shift_kernel (per-row exponent of a call), slice_kernel (digits, in the order the
+// matrix kernel wants them), xxt_i8_kernel (persistent workgroups, one contiguous range of
+// (tile, k-step) items each, 128 x 128 tiles on and below the diagonal, operands copied global -> LDS
+// without passing through registers).
+#include <hip/hip_ext.h>
+
+#include "fobq_internal.h"
+
+namespace fobq {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int NS = 5;               // digits per value
+constexpr int NM = 6;               // antidiagonals s + t = 0 .. NM - 1 kept
+constexpr int YBITS = 8 * NS - 2;   // |Y| <= 2^YBITS
+constexpr int IK = 32;              // calibration columns per k-step (one MFMA)
+constexpr int IT = 128;             // tile edge
+constexpr int I8_FOLD_STEPS = 512;  // k-steps between folds (16384 columns)
+constexpr int I8_WGS = 256;         // persistent workgroups: one per compute unit (4 wavefronts, one per SIMD)
+
+// Digit storage.  For k-step q (32 columns), block of 32 rows b, digit s: one 1 KiB block of 64 slots of
+// 16 bytes; slot l holds row 32 b + (l % 32), columns 32 q + 16 (l / 32) .. + 15.  That is the order in which
+// the 64 lanes of a wavefront hold one MFMA operand (lane l: row l % 32, k = 16 (l / 32) ..), so a block
+// goes global -> LDS -> registers as 64 consecutive 16-byte pieces at every stage.
+// Block index = (q * (dpad / 32) + b) * NS + s;  dpad = d rounded up to 128 (rows past d hold zeros).
+int i8_dpad(int d) { return (d + IT - 1) / IT * IT; }
+int64_t i8_ksteps(int64_t n) { return (n + IK - 1) / IK; }
+size_t i8_planes_bytes(int d, int64_t n) { return (size_t)i8_ksteps(n) * (size_t)(i8_dpad(d) / 32) * NS * 1024; }
+
+// ---------------------------------------------------------------------------
+// sh[row] = YBITS - e, 2^e > max_j |x_row,j| (e from the exponent field of the largest magnitude).
+// A row with an Inf or NaN raises *nonfinite (the Hessian is then poisoned by the finalize kernel).
+// One workgroup per row; VEC: rows are 16-byte aligned (ld % 4 == 0, base aligned).
+template <bool VEC>
+__global__ __launch_bounds__(256) void row_shift_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
+                                                        int* __restrict__ sh, int* __restrict__ nonfinite)
+{
+    __shared__ unsigned part[256];
+    const int row = blockIdx.x;
+    const float* __restrict__ x = X + (int64_t)row * ld;
+    unsigned m = 0;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const uint4* __restrict__ x4 = reinterpret_cast<const uint4*>(x);
+        int64_t j = threadIdx.x;
+        auto mag4 = [](const uint4& a) {
+            return max(max(a.x & 0x7fffffffu, a.y & 0x7fffffffu), max(a.z & 0x7fffffffu, a.w & 0x7fffffffu));
+        };
+        for (; j + 768 < n4; j += 1024) {
+            const uint4 a = x4[j], b = x4[j + 256], c = x4[j + 512], e = x4[j + 768];
+            m = max(max(m, mag4(a)), max(mag4(b), max(mag4(c), mag4(e))));
+        }
+        for (; j < n4; j += 256) m = max(m, mag4(x4[j]));
+        for (int64_t k = (n4 << 2) + threadIdx.x; k < n; k += 256) m = max(m, __float_as_uint(x[k]) & 0x7fffffffu);
+    } else {
+        for (int64_t j = threadIdx.x; j < n; j += 256) m = max(m, __float_as_uint(x[j]) & 0x7fffffffu);
+    }
+    part[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] = max(part[threadIdx.x], part[threadIdx.x + w]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        int E = (int)(part[0] >> 23);
+        if (E == 255) { *nonfinite = 1; E = 254; }
+        E = max(E, 1);                       // zero and subnormal rows: exponent of the smallest normal
+        sh[row] = YBITS - (E - 126);         // |x| < 2^(E - 126)
+    }
+}
+
+// Y = rint(x * 2^sh) (round half to even) from the bits of x; |Y| <= 2^YBITS when 2^(YBITS - sh) bounds |x|.
+__device__ __forceinline__ long long fixed_point(unsigned b, int sh)
+{
+    const int E = (int)((b >> 23) & 255u);
+    const unsigned M = (E == 255) ? 0u : ((b & 0x7fffffu) | (E ? 0x800000u : 0u));   // Inf / NaN count as 0 (flagged elsewhere)
+    const int shift = max(E, 1) - 150 + sh;                  // x = M * 2^(max(E,1) - 150)
+    long long y;
+    if (shift >= 0) {
+        y = (long long)M << min(shift, 39);
+    } else {
+        const int r = min(-shift, 26);                       // M < 2^24: everything from r = 26 on rounds to 0
+        const unsigned q = M >> r, rem = M & ((1u << r) - 1u), half = 1u << (r - 1);
+        y = (long long)(q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u));
+    }
+    return (b >> 31) ? -y : y;
+}
+
+// One workgroup: 32 rows x 256 columns (8 k-steps).  Thread (row, k-step) reads its 32 consecutive values
+// (a full 128-byte line per lane), turns them into 5 x 32 digits, written to LDS as the 8 x 5 output blocks,
+// which leave 16 bytes per thread, 5 KiB contiguous per k-step.
+// Digits: with C = 0x8080808080, the bytes of Y + C are the balanced digits plus 128 (adding 128 to every
+// digit absorbs the borrows), i.e. the digits are the bytes of (Y + C) ^ C, the least significant first.
+constexpr int SL_STEPS = 8;
+template <bool VEC>
+__global__ __launch_bounds__(256) void slice_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
+                                                    const int* __restrict__ sh, int dpad, int64_t ksteps,
+                                                    signed char* __restrict__ P)
+{
+    __shared__ __attribute__((aligned(16))) signed char blk[SL_STEPS][NS][1024];
+    const int rb = blockIdx.x;                      // block of 32 rows
+    const int64_t q0 = (int64_t)blockIdx.y * SL_STEPS;
+    const int r = threadIdx.x & 31, qs = threadIdx.x >> 5;
+    const int row = rb * 32 + r;
+    const int64_t c0 = (q0 + qs) * IK;
+    const bool row_ok = row < d;
+    const int s_row = row_ok ? sh[row] : 0;
+    const float* __restrict__ x = X + (int64_t)(row_ok ? row : 0) * ld + c0;
+    uint4 in[8];
+    if (VEC && row_ok && c0 + IK <= n) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) in[g] = reinterpret_cast<const uint4*>(x)[g];
+    } else {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            unsigned v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (row_ok && c0 + 4 * g + e < n) ? __float_as_uint(x[4 * g + e]) : 0u;
+            in[g] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        unsigned w[NS][4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint4 v4 = in[4 * h + g];
+            const unsigned vv[4] = {v4.x, v4.y, v4.z, v4.w};
+            unsigned lo[4], hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned long long z = (unsigned long long)(fixed_point(vv[e], s_row) + 0x8080808080ll);
+                lo[e] = (unsigned)z;
+                hi[e] = (unsigned)(z >> 32);
+            }
+            // 4 x 4 byte transpose of lo[0..3]: word k collects byte k of the four values
+            const unsigned t0 = __builtin_amdgcn_perm(lo[1], lo[0], 0x05010400u), t1 = __builtin_amdgcn_perm(lo[1], lo[0], 0x07030602u);
+            const unsigned t2 = __builtin_amdgcn_perm(lo[3], lo[2], 0x05010400u), t3 = __builtin_amdgcn_perm(lo[3], lo[2], 0x07030602u);
+            w[4][g] = __builtin_amdgcn_perm(t2, t0, 0x05040100u) ^ 0x80808080u;
+            w[3][g] = __builtin_amdgcn_perm(t2, t0, 0x07060302u) ^ 0x80808080u;
+            w[2][g] = __builtin_amdgcn_perm(t3, t1, 0x05040100u) ^ 0x80808080u;
+            w[1][g] = __builtin_amdgcn_perm(t3, t1, 0x07060302u) ^ 0x80808080u;
+            w[0][g] = ((hi[0] & 255u) | ((hi[1] & 255u) << 8) | ((hi[2] & 255u) << 16) | (hi[3] << 24)) ^ 0x80808080u;
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            *reinterpret_cast<uint4*>(&blk[qs][s][(h * 32 + r) * 16]) = make_uint4(w[s][0], w[s][1], w[s][2], w[s][3]);
+    }
+    __syncthreads();
+    // copy out: k-step q0 + qs owns 5 KiB at block index ((q0 + qs) * (dpad / 32) + rb) * NS
+    const signed char* __restrict__ src = &blk[0][0][0];
+#pragma unroll
+    for (int pass = 0; pass < SL_STEPS * NS * 1024 / (256 * 16); ++pass) {
+        const int off = (pass * 256 + (int)threadIdx.x) * 16;
+        const int q = off / (NS * 1024), within = off % (NS * 1024);
+        if (q0 + q < ksteps)
+            *reinterpret_cast<uint4*>(P + (((q0 + q) * (dpad / 32) + rb) * NS) * 1024 + within) =
+                *reinterpret_cast<const uint4*>(src + off);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The matrix kernel.  Items are (tile, k-step) pairs, tile-major over the 128 x 128 tiles on and below the
+// diagonal; persistent workgroup vb takes items [vb * per_wg, (vb + 1) * per_wg).  The part of a tile done by
+// one workgroup is a piece; piece p of a tile goes to slab p of Hpart, and one workgroup owns a given
+// (tile, piece), so the fp64 sums do not depend on the order in which workgroups finish.
+// A workgroup is 4 wavefronts (one per SIMD), wavefront (wm, wn) owns 64 x 64 of the tile = 2 x 2 MFMA tiles
+// of 32 x 32 for each of the 6 antidiagonals: 384 accumulator registers per lane, which is why exactly one
+// wavefront runs per SIMD and why the operands are copied global -> LDS directly (global_load_lds_dwordx4:
+// no staging registers); the copy of k-step q + 1 runs while the 76 MFMAs of k-step q issue.
+// 16 bytes per lane from global memory straight into LDS: lane l's bytes land at dst_block + OFF + 16 l, read
+// from src_lane + OFF (the instruction's immediate offset applies to both addresses).
+template <int OFF>
+__device__ __forceinline__ void lds_copy_block(const signed char* __restrict__ src_lane, signed char* dst_block)
+{
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_lane,
+                                     (void __attribute__((address_space(3)))*)dst_block, 16, OFF, 0);
+}
+
+// TN = tile width: 128 (8 wavefronts, two per SIMD) or 64 (4 wavefronts).  A wavefront owns 64 rows x 32 columns
+// of the tile = 2 MFMA tiles of 32 x 32 for each of the 6 antidiagonals: 192 accumulator registers, all of
+// them in the accumulation register file (the compiler keeps MFMA accumulators nowhere else).
+template <int TN>
+__global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __restrict__ P, const int* __restrict__ sh, int d,
+                                                        int dpad, int64_t ksteps, double* __restrict__ Hpart, int64_t per_wg,
+                                                        int64_t items)
+{
+    constexpr int NB = TN / 32;          // row blocks of the B operand
+    // [buffer][block of 32 rows][digit]: the 5 digit blocks of a row block are consecutive, as in global memory
+    __shared__ __attribute__((aligned(16))) signed char As[2][4][NS][1024];
+    __shared__ __attribute__((aligned(16))) signed char Bs[2][NB][NS][1024];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / NB, wn = wave % NB;     // rows 64 wm .., columns 32 wn ..
+
+    // workgroups are dealt to the 8 XCDs round-robin: give each XCD one contiguous run of ranges, so that the
+    // workgroups sharing an L2 work on neighbouring tiles (which share operand panels)
+    const int nx = 8, gq = (int)gridDim.x / nx, grem = (int)gridDim.x % nx;
+    const int xcd = (int)blockIdx.x % nx;
+    const int64_t vb = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+
+    const int64_t g0 = vb * per_wg, g1 = min(items, g0 + per_wg);
+    if (g0 >= g1) return;
+    const int t_first = (int)(g0 / ksteps), t_last = (int)((g1 - 1) / ksteps);
+    const int64_t step_bytes = (int64_t)(dpad / 32) * NS * 1024;     // one k-step of all rows
+
+    for (int tile = t_first; tile <= t_last; ++tile) {
+        const int64_t tile_first = (int64_t)tile * ksteps;
+        const int64_t c_begin = max(g0, tile_first) - tile_first, c_end = min(g1, tile_first + ksteps) - tile_first;
+        const int piece = (int)(vb - tile_first / per_wg);      // ranges that reached this tile before this one
+        // tile -> (I, J): block row I of 128 rows, block column J of TN columns, row-major over the tiles that
+        // touch the lower triangle (row I has (I + 1) * 128 / TN of them)
+        int I, J;
+        if (TN == 128) {
+            I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+            while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+            while (I * (I + 1) / 2 > tile) --I;
+            J = tile - I * (I + 1) / 2;
+        } else {
+            I = (int)((sqrtf(4.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+            while ((I + 1) * (I + 2) <= tile) ++I;
+            while (I * (I + 1) > tile) --I;
+            J = tile - I * (I + 1);
+        }
+        const int i0 = I * IT, j0 = J * TN;
+        double* __restrict__ out = Hpart + (int64_t)piece * d * d;
+
+        // one wavefront copies one row block of an operand, all 5 digits (5 KiB contiguous in global memory and
+        // in LDS); the addresses point at digit 2 so that the five immediates are -2048 .. 2048
+        auto copy5 = [&](const signed char* __restrict__ g, signed char* l) {
+            lds_copy_block<-2048>(g, l); lds_copy_block<-1024>(g, l); lds_copy_block<0>(g, l);
+            lds_copy_block<1024>(g, l);  lds_copy_block<2048>(g, l);
+        };
+        const signed char* __restrict__ pa = P + ((int64_t)(i0 / 32 + (wave & 3)) * NS + 2) * 1024 + lane * 16;
+        const signed char* __restrict__ pb = P + ((int64_t)(j0 / 32 + (wave % NB)) * NS + 2) * 1024 + lane * 16;
+        auto issue = [&](int buf, int64_t q) {
+            if (TN == 128) {                    // 8 wavefronts: 0..3 take A's row blocks, 4..7 B's
+                if (wave < 4) copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
+                else copy5(pb + q * step_bytes, &Bs[buf][wave - 4][2][0]);
+            } else {                            // 4 wavefronts: each A's row block, the first two also B's
+                copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
+                if (wave < NB) copy5(pb + q * step_bytes, &Bs[buf][wave][2][0]);
+            }
+        };
+
+        for (int64_t cb = c_begin; cb < c_end; cb += I8_FOLD_STEPS) {
+            const int64_t ce = min(c_end, cb + I8_FOLD_STEPS);
+            i32x16 acc[NM][2];
+#pragma unroll
+            for (int m = 0; m < NM; ++m)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[m][i][v] = 0;
+
+            __syncthreads();                 // LDS free (the stage before is consumed)
+            issue(0, cb);
+            __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): the copies have landed
+            __syncthreads();
+            int buf = 0;
+            for (int64_t q = cb; q < ce; ++q) {
+                if (q + 1 < ce) issue(buf ^ 1, q + 1);
+                i32x4 fb[NS];
+#pragma unroll
+                for (int t = 0; t < NS; ++t)
+                    fb[t] = *reinterpret_cast<const i32x4*>(&Bs[buf][wn][t][lane * 16]);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    i32x4 fa[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        fa[i] = *reinterpret_cast<const i32x4*>(&As[buf][wm * 2 + i][s][lane * 16]);
+#pragma unroll
+                    for (int t = 0; t < NS; ++t) {
+                        if (s + t < NM) {
+#pragma unroll
+                            for (int i = 0; i < 2; ++i)
+                                acc[s + t][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[t], acc[s + t][i], 0, 0, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+                buf ^= 1;
+            }
+
+            // fold: sum_m acc_m 256^(8 - m), times 2^-(sh_row + sh_col), added into the fp64 slab (lower triangle)
+            const int col = j0 + wn * 32 + (lane & 31);
+            const int sc = col < d ? sh[col] : 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = i0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    if (row < d && col <= row) {
+                        double sum = 0.0;
+#pragma unroll
+                        for (int m = NM - 1; m >= 0; --m)
+                            sum += (double)acc[m][i][v] * __builtin_ldexp(1.0, 8 * (2 * (NS - 1) - m));
+                        out[(int64_t)row * d + col] += ldexp(sum, -(sh[row] + sc));
+                    }
+                }
+            }
+        }
+    }
+}
+
+constexpr int I8_TN = 128;           // tile width in use
+
+struct I8Plan { int nt, wgs; int64_t ksteps, items, per_wg; };
+
+static I8Plan i8_plan(int d, int64_t n, int splits)
+{
+    I8Plan p;
+    p.nt = i8_dpad(d) / IT;
+    p.ksteps = i8_ksteps(n);
+    p.items = (I8_TN == 128 ? (int64_t)p.nt * (p.nt + 1) / 2 : (int64_t)p.nt * (p.nt + 1)) * p.ksteps;
+    p.per_wg = (p.items + I8_WGS - 1) / I8_WGS;
+    // a tile meets at most ceil(ksteps / per_wg) + 1 ranges; that must not exceed the slabs
+    const int64_t min_len = splits > 1 ? (p.ksteps + splits - 2) / (splits - 1) : p.ksteps;
+    if (p.per_wg < min_len) p.per_wg = min_len;
+    if (p.per_wg < 1) p.per_wg = 1;
+    p.wgs = (int)((p.items + p.per_wg - 1) / p.per_wg);
+    return p;
+}
+
+int xxt_i8_slabs_touched(int d, int64_t n, int splits)
+{
+    const I8Plan pl = i8_plan(d, n, splits);
+    const int64_t p = (pl.ksteps + pl.per_wg - 1) / pl.per_wg + 1;
+    return (int)(p < splits ? p : splits);
+}
+
+// sh: i8_dpad(d) ints; planes: i8_planes_bytes(d, n) bytes; *nonfinite is raised when X holds an Inf or NaN
+hipError_t launch_i8_slices(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, signed char* planes,
+                            int* nonfinite)
+{
+    const int dpad = i8_dpad(d);
+    const int64_t ksteps = i8_ksteps(n);
+    const bool vec = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const dim3 grid(dpad / 32, (unsigned)((ksteps + SL_STEPS - 1) / SL_STEPS));
+    if (vec) {
+        hipLaunchKernelGGL(row_shift_kernel<true>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
+        hipLaunchKernelGGL(slice_kernel<true>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
+    } else {
+        hipLaunchKernelGGL(row_shift_kernel<false>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
+        hipLaunchKernelGGL(slice_kernel<false>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh, int d, int64_t n, double* Hpart,
+                         int splits, LaunchEvents ev)
+{
+    const I8Plan pl = i8_plan(d, n, splits);
+    hipExtLaunchKernelGGL((xxt_i8_kernel<I8_TN>), dim3(pl.wgs), dim3(I8_TN * 4), 0, s, ev.start, ev.stop, 0, planes, sh, d,
+                          i8_dpad(d), pl.ksteps, Hpart, pl.per_wg, pl.items);
+    return hipGetLastError();
+}
+
+}  // namespace fobq
