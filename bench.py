@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix peak
 PEAK_HBM_GBS = 8000.0
+PEAK_INT8_MFMA_TOPS = 5000.0    # MI355X dense int8 matrix peak (5.0 POP/s)
 
 
 def _blob_hash(path: str) -> str:
@@ -216,6 +217,10 @@ def main() -> int:
                          "(fobq_hessian_accumulate_conv) instead of the unfolded X")
     ap.add_argument("--concurrency", type=int, default=8,
                     help="whole-model sweeps: layers in flight at once (one context and stream each)")
+    ap.add_argument("--hessian", choices=("i8", "f64"), default="i8",
+                    help="how X X^T is formed: i8 = exact int8 slice products on the matrix cores where the mode "
+                         "applies (d_col >= 256, n >= 2048 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
+                         "matrix instructions")
     ap.add_argument("--iid", action="store_true",
                     help="whole-model sweeps: feed every layer an unfolded matrix of independent activations "
                          "instead of the convolutions' input maps (the earlier variant, kept for comparison)")
@@ -263,6 +268,7 @@ def main() -> int:
         del probe
 
     ctx = fobq.Ctx(0)
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES if args.hessian == "i8" else fobq.HESSIAN_FP64)
     out = None
 
     def step():
@@ -302,18 +308,31 @@ def main() -> int:
     weights = spec.d_row * spec.d_col
     value = weights / (ms_per_step * 1e-3)
 
-    # dominant kernel: xxt_kernel, one launch per accumulate call
+    # dominant kernel: the X X^T kernel, one launch per accumulate call
     xxt_ms, xxt_launches = stages["xxt"]
     launches_per_step = xxt_launches / args.steps
     n_per_launch = spec.n / launches_per_step
     flops_per_launch = spec.d_col * (spec.d_col + 1) * n_per_launch     # one triangle: d(d+1)/2 entries x 2N flop
     avg_ms = xxt_ms / xxt_launches
-    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
-    roofline = {"kernel": "xxt_kernel", "bound": "mfma", "achieved": round(achieved, 3),
-                "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),
-                "traffic": measured_traffic("xxt_kernel", spec.name) if launches_per_step == 1 and not args.from_maps else None,
-                "avg_launch_ms": round(avg_ms, 4),
-                "algorithmic_flops_per_launch": flops_per_launch}
+    int8 = args.hessian == "i8" and not args.from_maps and spec.d_col >= 256 and n_per_launch >= 2048
+    if int8:
+        # integer-slice formulation: 19 int8 slice products per entry of the triangle, against the dense int8 peak
+        ops_per_launch = 19.0 * flops_per_launch
+        achieved = ops_per_launch / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": "xxt_i8_kernel", "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_MFMA_TOPS,
+                    "unit": "TOP/s", "frac": round(achieved / PEAK_INT8_MFMA_TOPS, 4),
+                    "traffic": measured_traffic("xxt_i8_kernel", spec.name) if launches_per_step == 1 else None,
+                    "avg_launch_ms": round(avg_ms, 4), "algorithmic_ops_per_launch": ops_per_launch,
+                    "slice_products": 19,
+                    "fp64_equivalent_TFLOPs": round(flops_per_launch / (avg_ms * 1e-3) / 1e12, 2),
+                    "fp64_equivalent_over_fp64_mfma_peak": round(flops_per_launch / (avg_ms * 1e-3) / 1e12 / PEAK_FP64_MFMA_TFLOPS, 3)}
+    else:
+        achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": "xxt_kernel", "bound": "mfma", "achieved": round(achieved, 3),
+                    "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),
+                    "traffic": measured_traffic("xxt_kernel", spec.name) if launches_per_step == 1 and not args.from_maps else None,
+                    "avg_launch_ms": round(avg_ms, 4),
+                    "algorithmic_flops_per_launch": flops_per_launch}
 
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
     R, d = spec.d_row, spec.d_col
@@ -382,11 +401,12 @@ def main() -> int:
                   + (" (ResNet-50 3x3 shape)" if spec.name == "c2_resnet50_3x3" else f" ({spec.name})"),
         "value": round(value, 1), "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
+        "dtype": "f64 (X X^T: exact int8 slice products, int32 sums)" if int8 else "f64", "data": "synthetic",
         "config": {"workload": f"{spec.name}: W {spec.d_row}x{spec.d_col} fp32, X {spec.d_col}x{spec.n} fp32, "
                                f"{spec.bits}-bit, group {spec.group}, damp {spec.damp}, sensitivity order",
                    "block": args.block or 64, "accumulate_calls_per_step": launches_per_step,
-                   "hessian_input": "feature maps (implicit unfold)" if args.from_maps else "unfolded X"},
+                   "hessian_input": "feature maps (implicit unfold)" if args.from_maps else "unfolded X",
+                   "hessian_arithmetic": "int8 slices (5 digits, 19 products), fp64 fold" if int8 else "fp64 MFMA"},
         "stages_ms": stage_ms,
         "roofline": roofline,
         "roofline_secondary": secondary,

@@ -197,15 +197,17 @@ __device__ __forceinline__ void lds_copy_block(const signed char* __restrict__ s
                                      (void __attribute__((address_space(3)))*)dst_block, 16, OFF, 0);
 }
 
-// TN = tile width: 128 (8 wavefronts, two per SIMD) or 64 (4 wavefronts).  A wavefront owns 64 rows x 32 columns
-// of the tile = 2 MFMA tiles of 32 x 32 for each of the 6 antidiagonals: 192 accumulator registers, all of
-// them in the accumulation register file (the compiler keeps MFMA accumulators nowhere else).
-template <int TN>
-__global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __restrict__ P, const int* __restrict__ sh, int d,
+// 8 wavefronts, two per SIMD; a wavefront owns 64 rows x 32 columns of the tile = 2 MFMA tiles of 32 x 32 for
+// each of the 6 antidiagonals: 192 accumulator registers of the 256 a wavefront has at this occupancy, which
+// leaves room for the 5 digits of one operand and 2 fragments of the other, not for a second set of fragments.
+// (Tried and slower: 128 x 64 tiles with 4 wavefronts, a ring of three LDS stages and the next k-step's
+// fragments prefetched into a second register set -- the compiler shuffles accumulators between the two
+// register files in that loop, 1.38 ms against 0.80 on the 2304 x 25088 layer.)
+__global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restrict__ P, const int* __restrict__ sh, int d,
                                                         int dpad, int64_t ksteps, double* __restrict__ Hpart, int64_t per_wg,
-                                                        int64_t items)
+                                                        int64_t items, int classes)
 {
-    constexpr int NB = TN / 32;          // row blocks of the B operand
+    constexpr int TN = IT, NB = TN / 32;  // row blocks of the B operand
     // [buffer][block of 32 rows][digit]: the 5 digit blocks of a row block are consecutive, as in global memory
     __shared__ __attribute__((aligned(16))) signed char As[2][4][NS][1024];
     __shared__ __attribute__((aligned(16))) signed char Bs[2][NB][NS][1024];
@@ -213,35 +215,58 @@ __global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __res
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / NB, wn = wave % NB;     // rows 64 wm .., columns 32 wn ..
 
-    // workgroups are dealt to the 8 XCDs round-robin: give each XCD one contiguous run of ranges, so that the
-    // workgroups sharing an L2 work on neighbouring tiles (which share operand panels)
+    // Workgroups are dealt to the 8 XCDs round-robin; vpos = the workgroup's place in an order in which each
+    // XCD owns one contiguous run.  Position -> range index vb, class-major: when a tile is cut into `classes`
+    // pieces, the ranges vb = c, c + classes, c + 2 classes, ... cover the same part of the calibration
+    // dimension of consecutive tiles, and only they can share fetches in the XCD's L2: ordering the ranges
+    // by (vb mod classes, vb) puts up to 32 of them on one XCD instead of 32 / classes.
     const int nx = 8, gq = (int)gridDim.x / nx, grem = (int)gridDim.x % nx;
     const int xcd = (int)blockIdx.x % nx;
-    const int64_t vb = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+    const int vpos = xcd * gq + min(xcd, grem) + (int)blockIdx.x / nx;
+    int64_t vb = vpos;
+    if (classes > 1) {
+        int cls = 0, before = 0;
+        for (;;) {
+            const int cnt = ((int)gridDim.x - cls + classes - 1) / classes;   // ranges with vb mod classes == cls
+            if (vpos < before + cnt) break;
+            before += cnt;
+            ++cls;
+        }
+        vb = cls + classes * (vpos - before);
+    }
 
     const int64_t g0 = vb * per_wg, g1 = min(items, g0 + per_wg);
     if (g0 >= g1) return;
     const int t_first = (int)(g0 / ksteps), t_last = (int)((g1 - 1) / ksteps);
+    const int npieces = t_last - t_first + 1;
     const int64_t step_bytes = (int64_t)(dpad / 32) * NS * 1024;     // one k-step of all rows
 
-    for (int tile = t_first; tile <= t_last; ++tile) {
+    for (int pi = 0; pi < npieces; ++pi) {
+        // All workgroups start together and advance one k-step per step, so k-step k is best visited at step
+        // k mod per_wg: workgroups on neighbouring tiles (same class, same XCD) then read the same columns at
+        // the same time.  A range inside one tile starts at its k-step whose index is a multiple of per_wg
+        // and wraps around; a range over two tiles takes the head of the later tile before the tail of the
+        // earlier one.  The order of the sum is fixed, so results are reproducible.
+        const int tile = npieces == 2 ? t_last - pi : t_first + pi;
         const int64_t tile_first = (int64_t)tile * ksteps;
         const int64_t c_begin = max(g0, tile_first) - tile_first, c_end = min(g1, tile_first + ksteps) - tile_first;
-        const int piece = (int)(vb - tile_first / per_wg);      // ranges that reached this tile before this one
-        // tile -> (I, J): block row I of 128 rows, block column J of TN columns, row-major over the tiles that
-        // touch the lower triangle (row I has (I + 1) * 128 / TN of them)
-        int I, J;
-        if (TN == 128) {
-            I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
-            while ((I + 1) * (I + 2) / 2 <= tile) ++I;
-            while (I * (I + 1) / 2 > tile) --I;
-            J = tile - I * (I + 1) / 2;
-        } else {
-            I = (int)((sqrtf(4.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
-            while ((I + 1) * (I + 2) <= tile) ++I;
-            while (I * (I + 1) > tile) --I;
-            J = tile - I * (I + 1);
+        const int64_t len = c_end - c_begin;
+        int64_t rot = 0;
+        if (npieces == 1) {
+            const int64_t aligned = (c_begin + per_wg - 1) / per_wg * per_wg;
+            if (aligned < c_end) rot = aligned - c_begin;
         }
+        auto kstep_at = [&](int64_t i) {
+            int64_t c = i + rot;
+            if (c >= len) c -= len;
+            return c_begin + c;
+        };
+        const int piece = (int)(vb - tile_first / per_wg);      // ranges that reached this tile before this one
+        // tile -> (I, J), I >= J, row-major over the lower triangle
+        int I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+        while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+        while (I * (I + 1) / 2 > tile) --I;
+        const int J = tile - I * (I + 1) / 2;
         const int i0 = I * IT, j0 = J * TN;
         double* __restrict__ out = Hpart + (int64_t)piece * d * d;
 
@@ -253,18 +278,13 @@ __global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __res
         };
         const signed char* __restrict__ pa = P + ((int64_t)(i0 / 32 + (wave & 3)) * NS + 2) * 1024 + lane * 16;
         const signed char* __restrict__ pb = P + ((int64_t)(j0 / 32 + (wave % NB)) * NS + 2) * 1024 + lane * 16;
-        auto issue = [&](int buf, int64_t q) {
-            if (TN == 128) {                    // 8 wavefronts: 0..3 take A's row blocks, 4..7 B's
-                if (wave < 4) copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
-                else copy5(pb + q * step_bytes, &Bs[buf][wave - 4][2][0]);
-            } else {                            // 4 wavefronts: each A's row block, the first two also B's
-                copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
-                if (wave < NB) copy5(pb + q * step_bytes, &Bs[buf][wave][2][0]);
-            }
+        auto issue = [&](int buf, int64_t q) {      // wavefronts 0..3 take A's row blocks, 4..7 B's
+            if (wave < 4) copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
+            else copy5(pb + q * step_bytes, &Bs[buf][wave - 4][2][0]);
         };
 
-        for (int64_t cb = c_begin; cb < c_end; cb += I8_FOLD_STEPS) {
-            const int64_t ce = min(c_end, cb + I8_FOLD_STEPS);
+        for (int64_t ib = 0; ib < len; ib += I8_FOLD_STEPS) {
+            const int64_t ie = min(len, ib + I8_FOLD_STEPS);
             i32x16 acc[NM][2];
 #pragma unroll
             for (int m = 0; m < NM; ++m)
@@ -274,12 +294,12 @@ __global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __res
                     for (int v = 0; v < 16; ++v) acc[m][i][v] = 0;
 
             __syncthreads();                 // LDS free (the stage before is consumed)
-            issue(0, cb);
+            issue(0, kstep_at(ib));
             __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): the copies have landed
             __syncthreads();
             int buf = 0;
-            for (int64_t q = cb; q < ce; ++q) {
-                if (q + 1 < ce) issue(buf ^ 1, q + 1);
+            for (int64_t it = ib; it < ie; ++it) {
+                if (it + 1 < ie) issue(buf ^ 1, kstep_at(it + 1));
                 i32x4 fb[NS];
 #pragma unroll
                 for (int t = 0; t < NS; ++t)
@@ -325,7 +345,6 @@ __global__ __launch_bounds__(TN * 4) void xxt_i8_kernel(const signed char* __res
     }
 }
 
-constexpr int I8_TN = 128;           // tile width in use
 
 struct I8Plan { int nt, wgs; int64_t ksteps, items, per_wg; };
 
@@ -334,7 +353,7 @@ static I8Plan i8_plan(int d, int64_t n, int splits)
     I8Plan p;
     p.nt = i8_dpad(d) / IT;
     p.ksteps = i8_ksteps(n);
-    p.items = (I8_TN == 128 ? (int64_t)p.nt * (p.nt + 1) / 2 : (int64_t)p.nt * (p.nt + 1)) * p.ksteps;
+    p.items = (int64_t)p.nt * (p.nt + 1) / 2 * p.ksteps;
     p.per_wg = (p.items + I8_WGS - 1) / I8_WGS;
     // a tile meets at most ceil(ksteps / per_wg) + 1 ranges; that must not exceed the slabs
     const int64_t min_len = splits > 1 ? (p.ksteps + splits - 2) / (splits - 1) : p.ksteps;
@@ -373,8 +392,11 @@ hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh
                          int splits, LaunchEvents ev)
 {
     const I8Plan pl = i8_plan(d, n, splits);
-    hipExtLaunchKernelGGL((xxt_i8_kernel<I8_TN>), dim3(pl.wgs), dim3(I8_TN * 4), 0, s, ev.start, ev.stop, 0, planes, sh, d,
-                          i8_dpad(d), pl.ksteps, Hpart, pl.per_wg, pl.items);
+    // pieces per tile, rounded: the number of classes of ranges (see the kernel)
+    int classes = (int)((pl.ksteps + pl.per_wg / 2) / pl.per_wg);
+    classes = classes < 1 ? 1 : (classes > pl.wgs ? pl.wgs : classes);
+    hipExtLaunchKernelGGL(xxt_i8_kernel, dim3(pl.wgs), dim3(512), 0, s, ev.start, ev.stop, 0, planes, sh, d, i8_dpad(d),
+                          pl.ksteps, Hpart, pl.per_wg, pl.items, classes);
     return hipGetLastError();
 }
 
