@@ -61,7 +61,7 @@ def _median(v):
     return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
 
-def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool) -> int:
+def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8: bool) -> int:
     """Whole-model sweep: every layer of a ResNet-50- or YOLOv5s-shaped network (4-bit, per-row grids,
     128 images), each layer fed as the network would feed it: a k x k or strided convolution accumulates
     its Hessian straight from its seeded ReLU-Gaussian input maps (fobq_hessian_accumulate_conv, a bounded
@@ -108,8 +108,10 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool) -> i
         else:
             ctx.hessian(inp, chunk=pc, H_out=H_out)
 
+    hmode = fobq.HESSIAN_INT8_SLICES if int8 else fobq.HESSIAN_FP64
     # (1) one layer at a time; per-layer time = median over the runs
     ctx = fobq.Ctx(0)
+    ctx.set_hessian_mode(hmode)
     outs = [None] * len(layers)
     layer_ms = [[] for _ in layers]
     seq_runs = []
@@ -161,6 +163,8 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool) -> i
     K = max(1, concurrency)
     streams = [torch.cuda.Stream() for _ in range(K)]
     ctxs = [fobq.Ctx(0, stream=st.cuda_stream) for st in streams]
+    for c in ctxs:
+        c.set_hessian_mode(hmode)
 
     def whole_model():
         busy = [False] * K
@@ -194,6 +198,7 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool) -> i
             "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images, "
                                    + ("every layer from an unfolded matrix of independent activations"
                                       if iid else "k x k and strided convolutions from their input maps"),
+                       "hessian_arithmetic": "int8 slices where d_col >= 384 (else fp64 MFMA)" if int8 else "fp64 MFMA",
                        "weights": total_weights, "layers_in_flight": K, "input_bytes": input_bytes},
             "whole_model_seconds": round(med * 1e-3, 4), "runs_ms": [round(r, 2) for r in runs],
             "sequential_ms": round(_median(seq_runs), 3), "sequential_runs_ms": [round(r, 2) for r in seq_runs],
@@ -219,7 +224,7 @@ def main() -> int:
                     help="whole-model sweeps: layers in flight at once (one context and stream each)")
     ap.add_argument("--hessian", choices=("i8", "f64"), default="i8",
                     help="how X X^T is formed: i8 = exact int8 slice products on the matrix cores where the mode "
-                         "applies (d_col >= 256, n >= 2048 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
+                         "applies (d_col >= 384, n >= 2048 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
                          "matrix instructions")
     ap.add_argument("--iid", action="store_true",
                     help="whole-model sweeps: feed every layer an unfolded matrix of independent activations "
@@ -247,7 +252,7 @@ def main() -> int:
         return 2
     if args.workload in ("sweep_resnet50", "sweep_yolov5s"):
         return sweep(args.workload[len("sweep_"):], max(5, min(args.steps, 9)), min(args.warmup, 2), args.concurrency,
-                     args.iid)
+                     args.iid, args.hessian == "i8")
     fobq.load_library()
     spec = workloads.configs()[args.workload]
     W = spec.make_w()
@@ -314,7 +319,7 @@ def main() -> int:
     n_per_launch = spec.n / launches_per_step
     flops_per_launch = spec.d_col * (spec.d_col + 1) * n_per_launch     # one triangle: d(d+1)/2 entries x 2N flop
     avg_ms = xxt_ms / xxt_launches
-    int8 = args.hessian == "i8" and not args.from_maps and spec.d_col >= 256 and n_per_launch >= 2048
+    int8 = args.hessian == "i8" and not args.from_maps and spec.d_col >= 384 and n_per_launch >= 2048
     if int8:
         # integer-slice formulation: 19 int8 slice products per entry of the triangle, against the dense int8 peak
         ops_per_launch = 19.0 * flops_per_launch

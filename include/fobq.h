@@ -128,10 +128,12 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col);
  *                             exactly on the int8 matrix cores (int32 sums, folded into fp64), the rest
  *                             dropped.  H differs from the fp64 result by about 3e-13 of its largest
  *                             entry; several times faster on large layers.  Applies to calls with
- *                             d_col >= 256 and n >= 2048; other calls, and
- *                             fobq_hessian_accumulate_conv, use the fp64 form.  An Inf or NaN in X makes
+ *                             d_col >= 384 and n >= 2048 (for
+ *                             fobq_hessian_accumulate_conv: output pixels of the call); other calls use the
+ *                             fp64 form.  An Inf or NaN in X makes
  *                             H NaN throughout (the layer then fails with ENOTPD).  Scratch: 1.25 bytes
- *                             per element of X_c.
+ *                             per element of X_c (of the unfolded input for a convolution), at most 2 GiB:
+ *                             longer calls run as several launches.
  * Stays in force until changed; not while an accumulation has begun (ESTATE).
  */
 typedef enum { FOBQ_HESSIAN_FP64 = 0, FOBQ_HESSIAN_INT8_SLICES = 1 } fobq_hessian_mode;

@@ -129,7 +129,7 @@ constexpr int64_t MAX_DCOL = 32768;
 // three products per inverse tile against one, and the launches are full without them)
 constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
-constexpr int I8_MIN_D = 256;
+constexpr int I8_MIN_D = 384;     // below: too few 128-wide tiles for the digit traffic to pay (measured on 256- and 288-column layers)
 constexpr int64_t I8_MIN_N = 2048;
 
 enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
@@ -356,7 +356,7 @@ static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
 {
     return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
             &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh};
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax};
 }
 
 extern "C" {
@@ -482,11 +482,13 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
     // integer slices pay where the fp64 kernel is bound by the matrix pipes: 128-wide tiles and a call long
     // enough to amortise the slicing pass
     const bool i8 = ctx->h_mode == FOBQ_HESSIAN_INT8_SLICES && d >= I8_MIN_D && n >= I8_MIN_N;
+    const int64_t blk = i8 ? i8_block_columns(d) : n;        // columns per launch of the int8 kernel
     if (i8) {
-        FOBQ_TRY(ctx->i8planes.ensure(i8_planes_bytes(d, n)), "workspace digit planes");
+        FOBQ_TRY(ctx->i8planes.ensure(i8_planes_bytes(d, n < blk ? n : blk)), "workspace digit planes");
         FOBQ_TRY(ctx->i8sh.ensure((size_t)i8_dpad(d) * sizeof(int)), "workspace row shifts");
     }
-    int rc = clear_slabs(ctx, n, false, i8);
+    int rc = clear_slabs(ctx, n < blk ? n : blk, false, i8);
+    if (!rc && n > blk && n % blk) rc = clear_slabs(ctx, n % blk, false, i8);    // the shorter last launch
     if (rc) return rc;
     ctx->h_conv_c = -1;
     if (i8) {
@@ -495,11 +497,18 @@ int fobq_hessian_accumulate(fobq_ctx* ctx, const float* X, int64_t n, int64_t ld
         ctx->h_i8_used = true;
         {
             StageScope sc(ctx, FOBQ_STAGE_SLICE);
-            FOBQ_TRY(launch_i8_slices(ctx->stream, X, ld, d, n, ctx->i8sh.as<int>(), ctx->i8planes.as<signed char>(),
-                                      nonfinite), "integer slices");
+            FOBQ_TRY(launch_i8_row_shifts(ctx->stream, X, ld, d, n, ctx->i8sh.as<int>(), nonfinite), "row exponents");
         }
-        FOBQ_TRY(launch_xxt_i8(ctx->stream, ctx->i8planes.as<signed char>(), ctx->i8sh.as<int>(), d, n,
-                               ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (int8)");
+        for (int64_t c0 = 0; c0 < n; c0 += blk) {
+            const int64_t nb = n - c0 < blk ? n - c0 : blk;
+            {
+                StageScope sc(ctx, FOBQ_STAGE_SLICE);
+                FOBQ_TRY(launch_i8_slice(ctx->stream, X + c0, ld, d, nb, ctx->i8sh.as<int>(), ctx->i8planes.as<signed char>()),
+                         "integer slices");
+            }
+            FOBQ_TRY(launch_xxt_i8(ctx->stream, ctx->i8planes.as<signed char>(), ctx->i8sh.as<int>(), d, nb,
+                                   ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (int8)");
+        }
     } else {
         FOBQ_TRY(launch_xxt(ctx->stream, X, ld, d, n, ctx->Hpart.as<double>(), ctx->h_splits,
                             stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt");
@@ -536,15 +545,46 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     if (npix == 0) return FOBQ_OK;
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
-    int rc = clear_slabs(ctx, npix, true);
-    if (rc) return rc;
+    const int d = (int)ctx->h_d;
+    const bool i8 = ctx->h_mode == FOBQ_HESSIAN_INT8_SLICES && d >= I8_MIN_D && npix >= I8_MIN_N;
+    const int64_t blk = i8 ? i8_block_columns(d) : npix;
     FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
+    if (i8) {
+        FOBQ_TRY(ctx->i8planes.ensure(i8_planes_bytes(d, npix < blk ? npix : blk)), "workspace digit planes");
+        FOBQ_TRY(ctx->i8sh.ensure((size_t)i8_dpad(d) * sizeof(int)), "workspace row shifts");
+        FOBQ_TRY(ctx->i8amax.ensure((size_t)c * sizeof(unsigned)), "workspace channel maxima");
+    }
+    int rc = clear_slabs(ctx, npix < blk ? npix : blk, true, i8);
+    if (!rc && npix > blk && npix % blk) rc = clear_slabs(ctx, npix % blk, true, i8);    // the shorter last launch
+    if (rc) return rc;
     ctx->h_conv_c = (int)c;
     ctx->h_conv_k = k;
-    {
-        // the padded copy is stream-ordered: a later call reuses the buffer only after this launch
-        FOBQ_TRY(launch_pad_maps(ctx->stream, maps, (int)n_img, (int)h, (int)w, (int)c, pad, ctx->maps_pad.as<float>()),
-                 "pad maps");
+    // the padded copy is stream-ordered: a later call reuses the buffer only after this call's launches
+    FOBQ_TRY(launch_pad_maps(ctx->stream, maps, (int)n_img, (int)h, (int)w, (int)c, pad, ctx->maps_pad.as<float>()),
+             "pad maps");
+    if (i8) {
+        // the digits of the unfolded input are written out (1.25 bytes per element of the unfolded X, a block of
+        // columns at a time) and the matrix kernel runs on them as it does on a plain X
+        int* nonfinite = ctx->flags.as<int>() + FLAG_WORD_NONFINITE;
+        if (!ctx->h_i8_used) FOBQ_TRY(launch_clear_words(ctx->stream, nonfinite, 1, nullptr, 0), "clear flag");
+        ctx->h_i8_used = true;
+        {
+            StageScope sc(ctx, FOBQ_STAGE_SLICE);
+            FOBQ_TRY(launch_i8_chan_shifts(ctx->stream, ctx->maps_pad.as<float>(), (n_img + 1) * hp * wp, (int)c, d,
+                                           ctx->i8amax.as<unsigned>(), ctx->i8sh.as<int>(), nonfinite), "channel exponents");
+        }
+        for (int64_t p0 = 0; p0 < npix; p0 += blk) {
+            const int64_t nb = npix - p0 < blk ? npix - p0 : blk;
+            {
+                StageScope sc(ctx, FOBQ_STAGE_SLICE);
+                FOBQ_TRY(launch_i8_slice_conv(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, k,
+                                              stride, (int)ho, (int)wo, npix, p0, nb, ctx->i8sh.as<int>(),
+                                              ctx->i8planes.as<signed char>()), "integer slices (convolution)");
+            }
+            FOBQ_TRY(launch_xxt_i8(ctx->stream, ctx->i8planes.as<signed char>(), ctx->i8sh.as<int>(), d, nb,
+                                   ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (int8)");
+        }
+    } else {
         FOBQ_TRY(launch_xxt_conv(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, k, stride,
                                  (int)ho, (int)wo, npix, ctx->Hpart.as<double>(), ctx->h_splits,
                                  stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (convolution)");

@@ -90,6 +90,7 @@ struct fobq_ctx {
     bool    h_i8_used = false;  // the integer-slice kernels ran in this accumulation
     fobq::DevBuf i8planes;  // digits of one accumulate call (see hessian_i8.hip)
     fobq::DevBuf i8sh;      // per-row shifts of that call
+    fobq::DevBuf i8amax;    // per-channel maxima (convolution input)
 
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
     fobq::DevBuf maps_pad;  // zero-padded copy of the feature maps of one accumulate_conv call (+ 1 zero image)
@@ -159,8 +160,13 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
 int i8_dpad(int d);
 size_t i8_planes_bytes(int d, int64_t n);
 int xxt_i8_slabs_touched(int d, int64_t n, int splits);
-hipError_t launch_i8_slices(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, signed char* planes,
-                            int* nonfinite);
+int64_t i8_block_columns(int d);      // most columns one launch of the matrix kernel takes (bounds the digit scratch)
+hipError_t launch_i8_row_shifts(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, int* nonfinite);
+hipError_t launch_i8_slice(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, const int* sh, signed char* planes);
+hipError_t launch_i8_chan_shifts(hipStream_t s, const float* padded, int64_t pixels, int c, int d, unsigned* amax, int* sh,
+                                 int* nonfinite);
+hipError_t launch_i8_slice_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
+                                int ho, int wo, int64_t npix, int64_t pix0, int64_t n, const int* sh, signed char* planes);
 hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh, int d, int64_t n, double* Hpart,
                          int splits, LaunchEvents ev = LaunchEvents());
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);

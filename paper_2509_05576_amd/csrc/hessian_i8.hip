@@ -45,6 +45,8 @@ constexpr int I8_WGS = 256;         // persistent workgroups: one per compute un
 // Block index = (q * (dpad / 32) + b) * NS + s;  dpad = d rounded up to 128 (rows past d hold zeros).
 int i8_dpad(int d) { return (d + IT - 1) / IT * IT; }
 int64_t i8_ksteps(int64_t n) { return (n + IK - 1) / IK; }
+// most columns per launch: 2 GiB of digits
+int64_t i8_block_columns(int d) { return ((int64_t)2 << 30) / ((int64_t)i8_dpad(d) * NS) / 256 * 256; }
 size_t i8_planes_bytes(int d, int64_t n) { return (size_t)i8_ksteps(n) * (size_t)(i8_dpad(d) / 32) * NS * 1024; }
 
 // ---------------------------------------------------------------------------
@@ -112,33 +114,13 @@ __device__ __forceinline__ long long fixed_point(unsigned b, int sh)
 // Digits: with C = 0x8080808080, the bytes of Y + C are the balanced digits plus 128 (adding 128 to every
 // digit absorbs the borrows), i.e. the digits are the bytes of (Y + C) ^ C, the least significant first.
 constexpr int SL_STEPS = 8;
-template <bool VEC>
-__global__ __launch_bounds__(256) void slice_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
-                                                    const int* __restrict__ sh, int dpad, int64_t ksteps,
-                                                    signed char* __restrict__ P)
+
+// The 32 values `in` (bit patterns) of thread (row r of the block, k-step qs of the workgroup's 8) -> digits in
+// blk; then the whole workgroup copies blk out.  q0 = first k-step of the workgroup, rb = block of 32 rows.
+__device__ __forceinline__ void slice_store(const uint4 (&in)[8], int s_row, int r, int qs, int rb, int64_t q0,
+                                            int dpad, int64_t ksteps, signed char (&blk)[SL_STEPS][NS][1024],
+                                            signed char* __restrict__ P)
 {
-    __shared__ __attribute__((aligned(16))) signed char blk[SL_STEPS][NS][1024];
-    const int rb = blockIdx.x;                      // block of 32 rows
-    const int64_t q0 = (int64_t)blockIdx.y * SL_STEPS;
-    const int r = threadIdx.x & 31, qs = threadIdx.x >> 5;
-    const int row = rb * 32 + r;
-    const int64_t c0 = (q0 + qs) * IK;
-    const bool row_ok = row < d;
-    const int s_row = row_ok ? sh[row] : 0;
-    const float* __restrict__ x = X + (int64_t)(row_ok ? row : 0) * ld + c0;
-    uint4 in[8];
-    if (VEC && row_ok && c0 + IK <= n) {
-#pragma unroll
-        for (int g = 0; g < 8; ++g) in[g] = reinterpret_cast<const uint4*>(x)[g];
-    } else {
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            unsigned v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (row_ok && c0 + 4 * g + e < n) ? __float_as_uint(x[4 * g + e]) : 0u;
-            in[g] = make_uint4(v[0], v[1], v[2], v[3]);
-        }
-    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         unsigned w[NS][4];
@@ -177,6 +159,122 @@ __global__ __launch_bounds__(256) void slice_kernel(const float* __restrict__ X,
             *reinterpret_cast<uint4*>(P + (((q0 + q) * (dpad / 32) + rb) * NS) * 1024 + within) =
                 *reinterpret_cast<const uint4*>(src + off);
     }
+}
+
+// X: the columns of this launch start at X[.][0]; n of them; ksteps = ceil(n / 32).
+template <bool VEC>
+__global__ __launch_bounds__(256) void slice_kernel(const float* __restrict__ X, int64_t ld, int d, int64_t n,
+                                                    const int* __restrict__ sh, int dpad, int64_t ksteps,
+                                                    signed char* __restrict__ P)
+{
+    __shared__ __attribute__((aligned(16))) signed char blk[SL_STEPS][NS][1024];
+    const int rb = blockIdx.x;                      // block of 32 rows
+    const int64_t q0 = (int64_t)blockIdx.y * SL_STEPS;
+    const int r = threadIdx.x & 31, qs = threadIdx.x >> 5;
+    const int row = rb * 32 + r;
+    const int64_t c0 = (q0 + qs) * IK;
+    const bool row_ok = row < d;
+    const int s_row = row_ok ? sh[row] : 0;
+    const float* __restrict__ x = X + (int64_t)(row_ok ? row : 0) * ld + c0;
+    uint4 in[8];
+    if (VEC && row_ok && c0 + IK <= n) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) in[g] = reinterpret_cast<const uint4*>(x)[g];
+    } else {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            unsigned v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (row_ok && c0 + 4 * g + e < n) ? __float_as_uint(x[4 * g + e]) : 0u;
+            in[g] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+    }
+    slice_store(in, s_row, r, qs, rb, q0, dpad, ksteps, blk, P);
+}
+
+// ---- convolution input: the digits of the unfolded X, straight from the zero-padded feature maps -------------
+// Rows are taken tap-major, row' = (ky * k + kx) * C + c (consecutive rows = consecutive channels, which the maps
+// store contiguously; the finalize kernel of the convolution mode puts H back into (c, ky, kx) order).  All k^2
+// rows of a channel share the channel's exponent, taken over the whole padded copy.
+struct SliceConvP {
+    int hp, wp, c, k, stride, ho, wo;
+    int64_t zero_origin;     // element offset of the all-zero image
+    int64_t npix;            // output pixels of the whole call
+};
+
+// amax[c] = max over all pixels of |maps[.][c]| as a bit pattern (integer max: order-free).  blockIdx.x = chunk of
+// pixels.  c <= 256: the workgroup walks its chunk T = c * (256 / c) elements at a time, so a thread stays on one
+// channel; c > 256: thread = channel (strided), one pixel at a time.
+__global__ __launch_bounds__(256) void chan_amax_kernel(const float* __restrict__ padded, int64_t pixels, int c,
+                                                        unsigned* __restrict__ amax)
+{
+    const int64_t per = (pixels + gridDim.x - 1) / gridDim.x;
+    const int64_t p0 = (int64_t)blockIdx.x * per, p1 = min(pixels, p0 + per);
+    if (p0 >= p1) return;
+    if (c <= 256) {
+        const int T = c * (256 / c);
+        if ((int)threadIdx.x >= T) return;
+        unsigned m = 0;
+        for (int64_t e = p0 * c + threadIdx.x; e < p1 * c; e += T) m = max(m, __float_as_uint(padded[e]) & 0x7fffffffu);
+        atomicMax(&amax[threadIdx.x % c], m);
+    } else {
+        for (int ch = threadIdx.x; ch < c; ch += 256) {
+            unsigned m = 0;
+            for (int64_t p = p0; p < p1; ++p) m = max(m, __float_as_uint(padded[p * c + ch]) & 0x7fffffffu);
+            atomicMax(&amax[ch], m);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void chan_shift_kernel(const unsigned* __restrict__ amax, int c, int d, int* __restrict__ sh,
+                                                         int* __restrict__ nonfinite)
+{
+    const int row = blockIdx.x * 256 + threadIdx.x;      // tap-major row
+    if (row >= d) return;
+    int E = (int)(amax[row % c] >> 23);
+    if (E == 255) { *nonfinite = 1; E = 254; }
+    E = max(E, 1);
+    sh[row] = YBITS - (E - 126);
+}
+
+// The columns of this launch are the output pixels pix0 .. pix0 + n - 1 of the call.
+__global__ __launch_bounds__(256) void slice_conv_kernel(const float* __restrict__ padded, SliceConvP cp, int d, int64_t pix0,
+                                                         int64_t n, const int* __restrict__ sh, int dpad, int64_t ksteps,
+                                                         signed char* __restrict__ P)
+{
+    __shared__ __attribute__((aligned(16))) signed char blk[SL_STEPS][NS][1024];
+    const int rb = blockIdx.x;
+    const int64_t q0 = (int64_t)blockIdx.y * SL_STEPS;
+    const int r = threadIdx.x & 31, qs = threadIdx.x >> 5;
+    const int row = rb * 32 + r;
+    const bool row_ok = row < d;
+    const int s_row = row_ok ? sh[row] : 0;
+    // this row's offset from a window's top-left element in the padded copy
+    const int rr = row_ok ? row : 0;
+    const int tap = rr / cp.c, ch = rr - tap * cp.c, ky = tap / cp.k, kx = tap - ky * cp.k;
+    const int64_t off = ((int64_t)ky * cp.wp + kx) * cp.c + ch;
+    // first pixel of this thread's k-step, then stepping
+    const int64_t c0 = (q0 + qs) * IK;
+    const int64_t pfirst = min(pix0 + c0, cp.npix - 1);
+    int64_t img = pfirst / ((int64_t)cp.ho * cp.wo);
+    int rem = (int)(pfirst - img * ((int64_t)cp.ho * cp.wo));
+    int yo = rem / cp.wo, xo = rem - yo * cp.wo;
+    uint4 in[8];
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        unsigned v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t col = c0 + 4 * g + e;
+            const bool ok = row_ok && col < n && pix0 + col < cp.npix;
+            const int64_t origin = ((img * cp.hp + (int64_t)yo * cp.stride) * cp.wp + (int64_t)xo * cp.stride) * cp.c;
+            v[e] = __float_as_uint(padded[(ok ? origin : cp.zero_origin) + off]);
+            v[e] = ok ? v[e] : 0u;
+            if (++xo == cp.wo) { xo = 0; if (++yo == cp.ho) { yo = 0; ++img; } }
+        }
+        in[g] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    slice_store(in, s_row, r, qs, rb, q0, dpad, ksteps, blk, P);
 }
 
 // ---------------------------------------------------------------------------
@@ -370,21 +468,53 @@ int xxt_i8_slabs_touched(int d, int64_t n, int splits)
     return (int)(p < splits ? p : splits);
 }
 
-// sh: i8_dpad(d) ints; planes: i8_planes_bytes(d, n) bytes; *nonfinite is raised when X holds an Inf or NaN
-hipError_t launch_i8_slices(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, signed char* planes,
-                            int* nonfinite)
+// Per call: sh (i8_dpad(d) ints) from all n columns of X; *nonfinite is raised when X holds an Inf or NaN.
+hipError_t launch_i8_row_shifts(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, int* nonfinite)
+{
+    const bool vec = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    if (vec) hipLaunchKernelGGL(row_shift_kernel<true>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
+    else     hipLaunchKernelGGL(row_shift_kernel<false>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
+    return hipGetLastError();
+}
+
+// Digits of the n columns that start at X (planes: i8_planes_bytes(d, n) bytes).
+hipError_t launch_i8_slice(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, const int* sh, signed char* planes)
 {
     const int dpad = i8_dpad(d);
     const int64_t ksteps = i8_ksteps(n);
     const bool vec = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     const dim3 grid(dpad / 32, (unsigned)((ksteps + SL_STEPS - 1) / SL_STEPS));
-    if (vec) {
-        hipLaunchKernelGGL(row_shift_kernel<true>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
-        hipLaunchKernelGGL(slice_kernel<true>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
-    } else {
-        hipLaunchKernelGGL(row_shift_kernel<false>, dim3(d), dim3(256), 0, s, X, ld, d, n, sh, nonfinite);
-        hipLaunchKernelGGL(slice_kernel<false>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
-    }
+    if (vec) hipLaunchKernelGGL(slice_kernel<true>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
+    else     hipLaunchKernelGGL(slice_kernel<false>, grid, dim3(256), 0, s, X, ld, d, n, sh, dpad, ksteps, planes);
+    return hipGetLastError();
+}
+
+// Convolution input, per call: channel maxima over the padded copy ((n_img + 1) x hp x wp x c), then sh for the
+// d = c k^2 tap-major rows.  amax: c words of scratch.
+hipError_t launch_i8_chan_shifts(hipStream_t s, const float* padded, int64_t pixels, int c, int d, unsigned* amax, int* sh,
+                                 int* nonfinite)
+{
+    hipError_t e = launch_clear_words(s, amax, c, nullptr, 0);
+    if (e != hipSuccess) return e;
+    const int64_t chunks = (pixels + 63) / 64;           // at least 64 pixels per workgroup
+    hipLaunchKernelGGL(chan_amax_kernel, dim3((unsigned)(chunks < 4096 ? (chunks < 1 ? 1 : chunks) : 4096)), dim3(256), 0, s,
+                       padded, pixels, c, amax);
+    hipLaunchKernelGGL(chan_shift_kernel, dim3((d + 255) / 256), dim3(256), 0, s, amax, c, d, sh, nonfinite);
+    return hipGetLastError();
+}
+
+// Digits of the unfolded input for the output pixels pix0 .. pix0 + n - 1 (tap-major rows).
+hipError_t launch_i8_slice_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
+                                int ho, int wo, int64_t npix, int64_t pix0, int64_t n, const int* sh, signed char* planes)
+{
+    const int d = c * k * k, dpad = i8_dpad(d);
+    const int64_t ksteps = i8_ksteps(n);
+    SliceConvP cp;
+    cp.hp = hp; cp.wp = wp; cp.c = c; cp.k = k; cp.stride = stride; cp.ho = ho; cp.wo = wo;
+    cp.zero_origin = (int64_t)n_img * hp * wp * c;
+    cp.npix = npix;
+    hipLaunchKernelGGL(slice_conv_kernel, dim3(dpad / 32, (unsigned)((ksteps + SL_STEPS - 1) / SL_STEPS)), dim3(256), 0, s,
+                       padded, cp, d, pix0, n, sh, dpad, ksteps, planes);
     return hipGetLastError();
 }
 

@@ -157,9 +157,9 @@ def _check_int8_hessian(Hg, H):
 
 
 @pytest.mark.parametrize("d,n,ld_pad,chunk,kind", [
-    (256, 2048, 0, None, "relu"),          # the smallest call the mode applies to: 3 tiles, 64 k-steps
-    (300, 5000, 0, None, "relu"),          # ragged rows and columns
-    (300, 5000, 3, None, "scaled"),        # unaligned rows; signed values, row magnitudes over 12 decades
+    (384, 2048, 0, None, "relu"),          # the smallest call the mode applies to: 6 tiles, 64 k-steps
+    (500, 5000, 0, None, "relu"),          # ragged rows and columns
+    (500, 5000, 3, None, "scaled"),        # unaligned rows; signed values, row magnitudes over 12 decades
     (1000, 20001, 0, 7000, "relu"),        # three calls (the last one 6001 columns), own row exponents per call
     (640, 9000, 0, 4000, "const"),         # constant rows: every slice product adds coherently; last call below
                                            # the mode's minimum length, so it runs the fp64 kernel into the same slabs
@@ -188,11 +188,33 @@ def test_hessian_int8_slices_matches_oracle(fobq, ctx, d, n, ld_pad, chunk, kind
     assert torch.equal(H, H2)
 
 
+@pytest.mark.parametrize("n,h,w,c,k,stride,pad,per_call", [
+    (6, 20, 20, 64, 3, 1, 1, None),      # d = 576: channels fill two row blocks exactly
+    (12, 47, 41, 44, 3, 2, 1, 5),        # d = 396: row blocks straddle taps; stride 2; calls of 5, 5, 2 images, the
+                                         # last one short enough to run the fp64 kernel into the same slabs
+    (3, 30, 30, 16, 5, 1, 2, None),      # d = 400, 5 x 5 kernel
+    (8, 33, 33, 512, 1, 2, 0, None),     # 1 x 1, stride 2 (projection shortcut)
+])
+def test_hessian_int8_slices_from_feature_maps_matches_oracle(fobq, ctx, n, h, w, c, k, stride, pad, per_call):
+    _say(f"int8-slice hessian_conv n={n} h={h} w={w} c={c} k={k} stride={stride} pad={pad} per_call={per_call}")
+    rng = np.random.default_rng(800 + c + k)
+    maps = (np.maximum(rng.standard_normal((n, h, w, c)), 0) * 10.0 ** rng.uniform(-3, 3, size=c)).astype(np.float32)
+    X = workloads.im2col(maps, k, stride, pad)
+    assert X.shape[1] // n * (per_call or n) >= 2048       # else every call falls back to the fp64 kernel
+    ref = oracle.hessian(X)
+    d = c * k * k
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)
+    ctx.hessian_conv(_dev(maps), k, stride, pad, images_per_call=per_call, H_out=H)
+    torch.cuda.synchronize()
+    _check_int8_hessian(H.cpu().numpy(), ref)
+
+
 @pytest.mark.slow
 def test_hessian_int8_slices_long_pieces_fold_in_between(fobq, ctx):
-    # 256 rows x 1.44 M columns: 3 tiles x 45056 k-steps over 256 workgroups = 528 k-steps per piece, more than
+    # 384 rows x 0.72 M columns: 6 tiles x 22528 k-steps over 256 workgroups = 528 k-steps per piece, more than
     # the 512 after which the int32 sums are folded into fp64
-    d, n = 256, 1441792
+    d, n = 384, 720896
     _say(f"int8-slice hessian, long pieces d={d} n={n}")
     X = workloads.relu_normal_f32((d, n), 5, 77)
     ref = oracle.hessian(X)
@@ -207,8 +229,8 @@ def test_hessian_int8_slices_mode_errors_and_non_finite_input(fobq, ctx):
     with pytest.raises(fobq.FobqError) as e:
         ctx.set_hessian_mode(7)
     assert e.value.code == fobq.EINVAL
-    X = torch.relu(torch.randn((256, 4096), device="cuda"))
-    fobq.fobq_hessian_begin(ctx.handle, 256)
+    X = torch.relu(torch.randn((384, 4096), device="cuda"))
+    fobq.fobq_hessian_begin(ctx.handle, 384)
     fobq.fobq_hessian_accumulate(ctx.handle, X)
     with pytest.raises(fobq.FobqError) as e:
         ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)      # not in the middle of an accumulation
@@ -219,11 +241,11 @@ def test_hessian_int8_slices_mode_errors_and_non_finite_input(fobq, ctx):
     # works again afterwards
     Xb = X.clone()
     Xb[17, 1234] = float("inf")
-    H = torch.empty((256, 256), dtype=torch.float64, device="cuda")
+    H = torch.empty((384, 384), dtype=torch.float64, device="cuda")
     ctx.hessian(Xb, H_out=H)
     torch.cuda.synchronize()
     assert bool(torch.isnan(H).all())
-    W = torch.randn((8, 256), device="cuda")
+    W = torch.randn((8, 384), device="cuda")
     with pytest.raises(fobq.FobqError) as e:
         ctx.quantize_layer(W)
     assert e.value.code == fobq.ENOTPD
@@ -774,6 +796,18 @@ def test_config_with_int8_slice_hessian(fobq, ctx, name, chunk):
 @pytest.mark.slow
 def test_config_c5_large_d_with_int8_slice_hessian(fobq, ctx):
     _run_config(fobq, ctx, "c5_large_d", int8=True)
+
+
+@pytest.mark.slow
+@pytest.mark.parametrize("model,layer,chunk", [
+    ("resnet50", "resnet50_64x576_n401408_0", None),       # 3 x 3 from maps, 925 MB of unfolded input in one call
+    ("resnet50", "resnet50_128x1152_n100352_0", 50),       # 3 x 3 stride 2, calls of 50, 50, 28 images
+    ("resnet50", "resnet50_512x4608_n6272_0", None),       # N barely above d_col
+    ("yolov5s", "yolov5s_128x576_n819200_0", None),        # 1.9 GB of unfolded input: two launches of the matrix kernel
+])
+def test_config_c4_sweep_layers_with_int8_slice_hessian(fobq, ctx, model, layer, chunk):
+    spec = next(l for l in workloads.sweep_layers(model) if l.name == layer)
+    _run_config(fobq, ctx, layer, chunk=chunk, spec=spec, int8=True)
 
 
 def test_config_c2_hessian_from_feature_maps(fobq, ctx):
