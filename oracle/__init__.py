@@ -22,11 +22,21 @@ _LIB = os.path.join(_HERE, "libfobq_oracle.so")
 OK, EINVAL, ENOMEM, ENOTPD = 0, -1, -2, -4
 
 
+# FOBQ_ORACLE_SANITIZE=1 in the environment: the oracle is compiled with AddressSanitizer and
+# UndefinedBehaviorSanitizer into a library of its own (the process must then run with the
+# sanitizer runtime preloaded; tests/test_oracle_sanitizers.py does that in a subprocess).
+_SANITIZE = os.environ.get("FOBQ_ORACLE_SANITIZE", "") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libfobq_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (strict IEEE: no fast-math, no contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if _SANITIZE
+                 else ["-O2"])
         subprocess.check_call([
-            "gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off",
+            "gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off",
             "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
