@@ -195,6 +195,32 @@ int fobq_quantize_layer_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, in
                                 const double* H, const fobq_opts* opts, const fobq_out* out);
 int fobq_finish(fobq_ctx* ctx);
 
+/*
+ * Several small layers in one call (Section 3: "each layer is quantized independently").  A layer of up
+ * to 256 columns is a chain of short dependent steps that leaves the GPU idle; here every stage of the
+ * path is ONE launch for all layers of the batch (grid and column sums, damped inverse, scores and order,
+ * shared-Hinv elimination, column loop with emit, loss), one workgroup per layer walking the factor path
+ * of its layer, so the cost of a batch is about that of one small layer.  Results per layer are those of
+ * fobq_quantize_layer (same arithmetic in fp64; sums inside the deferred updates are taken in a
+ * different order).
+ *   layers   host array of n_layers entries: W (device fp32 d_row x d_col), H (device fp64 d_col x d_col,
+ *            full symmetric, undamped: e.g. from fobq_hessian_finalize(ctx, H)), out (device pointers as in
+ *            fobq_out; W_work and Hinv_work must be NULL)
+ *   opts     one set of options for all layers: bits, group (must divide every d_col), damp, damp_abs, order
+ *            (not CUSTOM, not SENSI_DYNAMIC); block 0 or 64; stop_after -1
+ * Limits: n_layers <= 256, d_col <= 256 (EINVAL beyond).  Scratch comes from one pool of the context.
+ * Enqueues everything on the context's stream, then SYNCHRONISES and reports the first layer whose damped
+ * Hessian or running inverse is not positive definite (ENOTPD, layer index in fobq_last_error); the other
+ * layers' outputs are complete all the same.
+ */
+typedef struct {
+    const float*  W;
+    int64_t       d_row, d_col;
+    const double* H;
+    fobq_out      out;
+} fobq_layer;
+int fobq_quantize_layers_batched(fobq_ctx* ctx, int32_t n_layers, const fobq_layer* layers, const fobq_opts* opts);
+
 /* ---- stage-level entry points (test and benchmark hooks) ------------------ */
 
 /* Hinv = H^-1 for symmetric positive definite H via H = L L^T, L^-1, L^-T L^-1

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     fobq_create, fobq_destroy, fobq_last_error,
     HESSIAN_FP64, HESSIAN_INT8_SLICES, fobq_hessian_set_mode,
     fobq_hessian_begin, fobq_hessian_accumulate, fobq_hessian_accumulate_conv, fobq_hessian_finalize,
-    fobq_quantize_layer, fobq_finish, fobq_spd_inverse, fobq_sensitivity, fobq_sensitivity_static,
+    fobq_quantize_layer, fobq_quantize_layers_batched, fobq_finish, fobq_spd_inverse, fobq_sensitivity, fobq_sensitivity_static,
     fobq_debug_fail_after, fobq_workspace_bytes,
     fobq_profile_enable, fobq_profile_get, fobq_profile_reset, FOBQ_PROFILE_STAGE,
 )

@@ -39,6 +39,11 @@ class FobqOut(ctypes.Structure):
                 ("Hinv_work", ctypes.c_void_p), ("loss", ctypes.c_void_p)]
 
 
+class FobqLayer(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("d_row", ctypes.c_int64), ("d_col", ctypes.c_int64),
+                ("H", ctypes.c_void_p), ("out", FobqOut)]
+
+
 _lib = None
 
 
@@ -64,6 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_hessian_finalize.argtypes = [vp, vp]
     lib.fobq_quantize_layer.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), ctypes.POINTER(FobqOut)]
     lib.fobq_quantize_layer_enqueue.argtypes = lib.fobq_quantize_layer.argtypes
+    lib.fobq_quantize_layers_batched.argtypes = [vp, i32, ctypes.POINTER(FobqLayer), ctypes.POINTER(FobqOpts)]
     lib.fobq_finish.argtypes = [vp]
     lib.fobq_spd_inverse.argtypes = [vp, vp, i64, vp]
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
@@ -75,7 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_profile_reset.argtypes = [vp]
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
-                 "fobq_quantize_layer_enqueue", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
+                 "fobq_quantize_layer_enqueue", "fobq_quantize_layers_batched", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
                  "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
@@ -205,6 +211,38 @@ def fobq_quantize_layer(ctx: int, W: torch.Tensor, H: Optional[torch.Tensor] = N
     return out
 
 
+def _alloc_output(W: torch.Tensor, group: int) -> LayerOutput:
+    r, d = W.shape
+    g = d // group if group > 0 and d % group == 0 else 1
+    dev = W.device
+    return LayerOutput(codes=torch.empty((r, d), dtype=torch.uint8, device=dev),
+                       scales=torch.empty((r, g), dtype=torch.float32, device=dev),
+                       zeros=torch.empty((r, g), dtype=torch.float32, device=dev),
+                       Q=torch.empty((r, d), dtype=torch.float32, device=dev),
+                       perm=torch.empty((d,), dtype=torch.int32, device=dev),
+                       loss=torch.empty((1,), dtype=torch.float64, device=dev))
+
+
+def fobq_quantize_layers_batched(ctx: int, Ws, Hs, *, bits: int = 4, group: int = 0, damp: float = 0.01,
+                                 damp_abs: float = 0.0, order: int = ORDER_SENSI_DESC, outs=None):
+    """Ws, Hs: lists of device tensors (fp32 d_row x d_col, fp64 d_col x d_col).  Allocates the outputs unless
+    `outs` (a list of LayerOutput) is given; returns the list of LayerOutput."""
+    n = len(Ws)
+    if outs is None:
+        outs = [_alloc_output(W, group) for W in Ws]
+    arr = (FobqLayer * max(n, 1))()
+    for i, (W, H, out) in enumerate(zip(Ws, Hs, outs)):
+        if W.dim() != 2:
+            raise TypeError("W must be 2-D")
+        co = FobqOut(_ptr(out.codes, torch.uint8, "codes"), _ptr(out.scales, torch.float32, "scales"),
+                     _ptr(out.zeros, torch.float32, "zeros"), _ptr(out.Q, torch.float32, "Q"),
+                     _ptr(out.perm, torch.int32, "perm"), None, None, _ptr(out.loss, torch.float64, "loss"))
+        arr[i] = FobqLayer(_ptr(W, torch.float32, "W"), W.shape[0], W.shape[1], _ptr(H, torch.float64, "H"), co)
+    op = _opts(bits, group, damp, damp_abs, order, 0, -1, None)
+    _check(ctx, load_library().fobq_quantize_layers_batched(ctypes.c_void_p(ctx), n, arr, ctypes.byref(op)))
+    return outs
+
+
 def fobq_finish(ctx: int) -> None:
     _check(ctx, load_library().fobq_finish(ctypes.c_void_p(ctx)))
 
@@ -320,6 +358,9 @@ class Ctx:
 
     def quantize_layer(self, W: torch.Tensor, H: Optional[torch.Tensor] = None, **kw) -> LayerOutput:
         return fobq_quantize_layer(self.handle, W, H, **kw)
+
+    def quantize_layers_batched(self, Ws, Hs, **kw):
+        return fobq_quantize_layers_batched(self.handle, Ws, Hs, **kw)
 
     def finish(self) -> None:
         fobq_finish(self.handle)

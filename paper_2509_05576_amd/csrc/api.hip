@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 
@@ -356,7 +357,7 @@ static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
 {
     return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
             &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax};
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax, &ctx->batch_pool, &ctx->batch_desc};
 }
 
 extern "C" {
@@ -403,6 +404,7 @@ int fobq_destroy(fobq_ctx* ctx)
     for (hipEvent_t e : ctx->sync_ev) (void)hipEventDestroy(e);
     for (DevBuf* b : all_buffers(ctx)) b->release();
     if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
+    if (ctx->h_batch) (void)hipHostFree(ctx->h_batch);
     delete ctx;
     return FOBQ_OK;
 }
@@ -890,6 +892,129 @@ static int quantize_enqueue(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
     // a failure past this point has work in flight on both streams that reads W / H and writes the outputs
     // and the context's scratch: wait for it, so that the caller may free its buffers and use the context again
     return rc ? drain_after_failure(ctx, rc) : FOBQ_OK;
+}
+
+// carve `bytes` (rounded up to 256) out of a pool laid out from `*off`; base == null: only the size is wanted
+static void* pool_take(unsigned char* base, size_t* off, size_t bytes)
+{
+    void* p = base ? base + *off : nullptr;
+    *off += (bytes + 255) & ~size_t(255);
+    return p;
+}
+
+// scratch pointers of one batched layer (or, with base == null, just the size it needs)
+static void batch_layout(BatchLayer* L, unsigned char* base, size_t* off)
+{
+    const size_t dd = (size_t)L->d * L->d * sizeof(double);
+    double** mats[] = {&L->Hd, &L->Linv, &L->T, &L->Hinv, &L->A, &L->U, &L->Un};
+    for (double** m : mats) *m = static_cast<double*>(pool_take(base, off, dd));
+    L->Gs = static_cast<double*>(pool_take(base, off, 64 * 64 * sizeof(double)));
+    L->rinv = static_cast<double*>(pool_take(base, off, 64 * sizeof(double)));
+    L->Wp = static_cast<double*>(pool_take(base, off, (size_t)L->R * L->d * sizeof(double)));
+    L->DT = static_cast<double*>(pool_take(base, off, (size_t)L->d * L->Rp * sizeof(double)));
+    L->codesT = static_cast<uint8_t*>(pool_take(base, off, (size_t)L->d * L->Rp));
+    L->scale = static_cast<double*>(pool_take(base, off, (size_t)L->R * L->G * sizeof(double)));
+    L->zero = static_cast<double*>(pool_take(base, off, (size_t)L->R * L->G * sizeof(double)));
+    L->S = static_cast<double*>(pool_take(base, off, (size_t)L->d * sizeof(double)));
+    L->Spart = static_cast<double*>(pool_take(base, off, (size_t)L->chunks * L->d * sizeof(double)));
+    L->lossrow = static_cast<double*>(pool_take(base, off, (size_t)L->R * sizeof(double)));
+    L->perm = static_cast<int*>(pool_take(base, off, (size_t)L->d * sizeof(int)));
+    L->invperm = static_cast<int*>(pool_take(base, off, (size_t)L->d * sizeof(int)));
+    L->flags = static_cast<int*>(pool_take(base, off, 4 * sizeof(int)));
+}
+
+int fobq_quantize_layers_batched(fobq_ctx* ctx, int32_t n_layers, const fobq_layer* layers, const fobq_opts* opts)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending)
+        return set_err(ctx, FOBQ_ESTATE, "a layer enqueued with fobq_quantize_layer_enqueue is waiting for fobq_finish");
+    if (n_layers < 0 || n_layers > BATCH_MAX_LAYERS)
+        return set_err(ctx, FOBQ_EINVAL, "n_layers must be in 0..%d (got %d)", BATCH_MAX_LAYERS, n_layers);
+    if (n_layers == 0) return FOBQ_OK;
+    if (!layers) return set_err(ctx, FOBQ_EINVAL, "layers is NULL");
+    if (!opts) return set_err(ctx, FOBQ_EINVAL, "opts is NULL");
+    if (opts->order == FOBQ_ORDER_SENSI_DYNAMIC || opts->order == FOBQ_ORDER_CUSTOM)
+        return set_err(ctx, FOBQ_EINVAL, "a batched call takes the orders that are computed from W and Hinv or NATURAL "
+                                         "(one perm_in cannot serve layers of different d_col; the dynamic order runs one column per launch)");
+    if (opts->block != 0 && opts->block != 64) return set_err(ctx, FOBQ_EINVAL, "a batched call uses the default block width");
+    if (opts->stop_after != -1) return set_err(ctx, FOBQ_EINVAL, "a batched call processes all columns (stop_after must be -1)");
+    for (int l = 0; l < n_layers; ++l) {
+        const fobq_layer& in = layers[l];
+        if (!in.W || !in.H) return set_err(ctx, FOBQ_EINVAL, "layer %d: W or H is NULL", l);
+        int rc = check_shape(ctx, in.d_row, in.d_col);
+        if (!rc) rc = check_opts(ctx, opts, in.d_col);
+        if (rc) { ctx->err = "layer " + std::to_string(l) + ": " + ctx->err; return rc; }
+        if (in.d_col > BATCH_MAX_D)
+            return set_err(ctx, FOBQ_EINVAL, "layer %d: d_col = %lld; a batched call takes layers of up to %d columns", l,
+                           (long long)in.d_col, BATCH_MAX_D);
+        if (in.out.W_work || in.out.Hinv_work)
+            return set_err(ctx, FOBQ_EINVAL, "layer %d: W_work / Hinv_work are not available from a batched call", l);
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    ctx->err.clear();
+
+    // descriptors: pinned host staging (also receives the status words), device copy, scratch pool
+    const size_t desc_bytes = (size_t)BATCH_MAX_LAYERS * sizeof(BatchLayer), flag_bytes = (size_t)BATCH_MAX_LAYERS * 4 * sizeof(int);
+    if (!ctx->h_batch && hipHostMalloc(&ctx->h_batch, desc_bytes + flag_bytes, hipHostMallocDefault) != hipSuccess) {
+        ctx->h_batch = nullptr;
+        return set_err(ctx, FOBQ_ENOMEM, "cannot allocate pinned host memory for the batch descriptors");
+    }
+    FOBQ_TRY(ctx->batch_desc.ensure(desc_bytes + flag_bytes), "workspace batch descriptors");
+    BatchLayer* hd = static_cast<BatchLayer*>(ctx->h_batch);
+    int max_pairs = 1, max_chunks = 1, max_rows = 1;
+    size_t pool = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const fobq_layer& in = layers[l];
+        BatchLayer& L = hd[l];
+        L = BatchLayer{};
+        L.W = in.W; L.H = in.H;
+        L.R = (int)in.d_row; L.d = (int)in.d_col;
+        L.G = opts->group > 0 ? L.d / opts->group : 1;
+        L.gs = opts->group > 0 ? opts->group : L.d;
+        L.Rp = (L.R + 63) / 64 * 64;
+        L.chunks = sens_chunks(L.R);
+        L.maxq = (double)((1 << opts->bits) - 1);
+        L.damp = opts->damp; L.damp_abs = opts->damp_abs;
+        L.order = opts->order; L.kind = order_kind(opts);
+        L.ascending = opts->order >= FOBQ_ORDER_SENSI_ASC && opts->order <= FOBQ_ORDER_W_ASC;
+        L.codes = in.out.codes; L.scales = in.out.scales; L.zeros = in.out.zeros; L.Q = in.out.Q;
+        L.perm_out = in.out.perm; L.loss = in.out.loss;
+        batch_layout(&L, nullptr, &pool);
+        max_pairs = std::max(max_pairs, L.R * L.G);
+        max_chunks = std::max(max_chunks, L.chunks);
+        max_rows = std::max(max_rows, L.R);
+    }
+    FOBQ_TRY(ctx->batch_pool.ensure(pool), "workspace batch pool");
+    size_t off = 0;
+    for (int l = 0; l < n_layers; ++l) batch_layout(&hd[l], ctx->batch_pool.as<unsigned char>(), &off);
+
+    hipStream_t s = ctx->stream;
+    const BatchLayer* dl = ctx->batch_desc.as<BatchLayer>();
+    int rc = [&]() -> int {
+        FOBQ_TRY(hipMemcpyAsync(ctx->batch_desc.p, hd, (size_t)n_layers * sizeof(BatchLayer), hipMemcpyHostToDevice, s),
+                 "upload batch descriptors");
+        FOBQ_TRY(launch_batch_grid(s, dl, n_layers, max_pairs), "grid (batch)");
+        FOBQ_TRY(launch_batch_sens_partial(s, dl, n_layers, max_chunks), "sensitivity (batch)");
+        FOBQ_TRY(launch_batch_inverse(s, dl, n_layers), "inverse (batch)");
+        FOBQ_TRY(launch_batch_order(s, dl, n_layers), "order (batch)");
+        FOBQ_TRY(launch_batch_eliminate(s, dl, n_layers), "eliminate (batch)");
+        FOBQ_TRY(launch_batch_columns(s, dl, n_layers, max_rows), "column loop (batch)");
+        FOBQ_TRY(launch_batch_loss(s, dl, n_layers), "loss (batch)");
+        // status words of every layer, gathered by one strided copy into the staging area behind the descriptors
+        int* hflags = reinterpret_cast<int*>(static_cast<unsigned char*>(ctx->h_batch) + desc_bytes);
+        for (int l = 0; l < n_layers; ++l)
+            FOBQ_TRY(hipMemcpyAsync(hflags + 4 * l, hd[l].flags, 4 * sizeof(int), hipMemcpyDeviceToHost, s), "read status flags");
+        FOBQ_TRY(hipStreamSynchronize(s), "synchronize");
+        for (int l = 0; l < n_layers; ++l) {
+            if (hflags[4 * l + FLAG_NOTPD_H])
+                return set_err(ctx, FOBQ_ENOTPD, "layer %d: damped Hessian is not positive definite (Cholesky pivot <= 0)", l);
+            if (hflags[4 * l + FLAG_NOTPD_HINV])
+                return set_err(ctx, FOBQ_ENOTPD, "layer %d: shared inverse Hessian lost positive definiteness (elimination pivot <= 0)", l);
+        }
+        return FOBQ_OK;
+    }();
+    return (rc && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
 }
 
 int fobq_quantize_layer(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* H,

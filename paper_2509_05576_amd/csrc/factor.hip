@@ -1109,7 +1109,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     };
     double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
-    if (block == NB && steps == d) {
+    if (block == NB && steps == d && d < 3000) {
         // one stand-alone launch for the first diagonal block, then one fused launch per panel
         hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(NT), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un,
                            (double*)nullptr, Gb[0], rb[0], flag);
@@ -1167,6 +1167,198 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
         if (e != hipSuccess) return e;
         ready(it);
     }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Batched small layers (d <= 256, at most 4 panels).  A layer this small never fills the GPU: its whole
+// factor path is a chain of dependent steps on one workgroup's worth of work.  Here ONE workgroup per layer
+// walks that chain by itself -- blocked with the same 64 x 64 diagonal-block routines, the tile products on
+// the matrix cores with operands straight from global memory (everything sits in L2) -- so that a single
+// launch factors every layer of a batch, and the launch count no longer grows with the number of layers.
+//
+// tile_mm: C (m x n) = beta C + alpha op(A) op(B), op(A) m x k, op(B) k x n, all <= 64, row-major in global memory.
+//   TA: op(A)[r][q] = A[q * lda + r] (else A[r * lda + q]);  TB: op(B)[q][c] = B[c * ldb + q] (else B[q * ldb + c]).
+//   C2 / rowscale (may be null): C2[r][c] = rowscale[r] * result.
+// Called by all NT threads; every operand is in registers before anything is stored (C may alias A or B);
+// ends with a barrier.
+template <bool TA, bool TB>
+__device__ __forceinline__ void tile_mm(double* C, int64_t ldc, const double* A, int64_t lda, const double* B, int64_t ldb,
+                                        int m, int n, int k, double alpha, double beta, double* C2 = nullptr,
+                                        const double* rowscale = nullptr)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
+    double a[16], b[2][16];
+    const int ar = wr * 16 + fr, arc = min(ar, m - 1);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        const int q = 4 * ks + fq, qc = min(q, k - 1);
+        const double av = TA ? A[(int64_t)qc * lda + arc] : A[(int64_t)arc * lda + qc];
+        a[ks] = (ar < m && q < k) ? alpha * av : 0.0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int bc = w2 * 32 + 16 * j + fr, bcc = min(bc, n - 1);
+            const double bv = TB ? B[(int64_t)bcc * ldb + qc] : B[(int64_t)qc * ldb + bcc];
+            b[j][ks] = (bc < n && q < k) ? bv : 0.0;
+        }
+    }
+    d4 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = wr * 16 + 4 * v + fq, c = w2 * 32 + 16 * j + fr;
+            acc[j][v] = (beta != 0.0 && r < m && c < n) ? beta * C[(int64_t)r * ldc + c] : 0.0;
+        }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[j] = mfma4(a[ks], b[j][ks], acc[j]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = wr * 16 + 4 * v + fq, c = w2 * 32 + 16 * j + fr;
+            if (r < m && c < n) {
+                C[(int64_t)r * ldc + c] = acc[j][v];
+                if (C2) C2[(int64_t)r * ldc + c] = acc[j][v] * rowscale[r];
+            }
+        }
+    __syncthreads();
+}
+
+// Damped Hessian -> Hinv = L^-T L^-1 (upper tiles; Section 5 item 1, Section 6.1), one workgroup per layer.
+__global__ __launch_bounds__(NT) void batch_inverse_kernel(const BatchLayer* __restrict__ layers)
+{
+    __shared__ double Am[NB * DL];
+    __shared__ double Xm[NB * DL];
+    __shared__ double rq[SWEEP_LDS];
+    const BatchLayer L = layers[blockIdx.x];
+    const int d = L.d, T = (d + NB - 1) / NB, tid = threadIdx.x;
+    // lambda = damp * mean(diag H) + damp_abs; the diagonal is summed in index order by one wavefront-sized tree
+    {
+        double s = 0.0;
+        for (int a = tid; a < d; a += NT) s += L.H[(int64_t)a * d + a];
+        Xm[tid] = s;
+        __syncthreads();
+        for (int w = NT / 2; w > 0; w >>= 1) {
+            if (tid < w) Xm[tid] += Xm[tid + w];
+            __syncthreads();
+        }
+    }
+    const double lam = L.damp * (Xm[0] / (double)d) + L.damp_abs;
+    __syncthreads();
+    for (int idx = tid; idx < d * d; idx += NT) {
+        const int a = idx / d, b = idx - a * d;
+        L.Hd[idx] = L.H[idx] + (a == b ? lam : 0.0);
+    }
+    __syncthreads();
+    // H_d = L L^T, right-looking over the panels; L overwrites the lower tiles of Hd
+    for (int p = 0; p < T; ++p) {
+        const int o = NB * p, nb = min(NB, d - o);
+        for (int idx = tid; idx < NB * NB; idx += NT) {
+            const int i = idx >> 6, j = idx & 63;
+            double v = (i == j) ? 1.0 : 0.0;                    // identity padding past nb
+            if (i < nb && j < nb) v = (j <= i) ? L.Hd[(int64_t)(o + i) * d + o + j] : 0.0;
+            Am[i * DL + j] = v;
+        }
+        __syncthreads();
+        chol_block(Am, Xm, rq, L.flags + 0);
+        for (int idx = tid; idx < NB * NB; idx += NT) {
+            const int i = idx >> 6, j = idx & 63;
+            if (i < nb && j < nb) {
+                L.Hd[(int64_t)(o + i) * d + o + j] = (j <= i) ? Am[i * DL + j] : 0.0;
+                L.Linv[(int64_t)(o + i) * d + o + j] = (j <= i) ? Xm[i * DL + j] : 0.0;
+            }
+        }
+        __syncthreads();
+        for (int i = p + 1; i < T; ++i) {        // L_ip = A_ip L_pp^-T
+            double* t = L.Hd + (int64_t)(NB * i) * d + o;
+            tile_mm<false, true>(t, d, t, d, L.Linv + (int64_t)o * d + o, d, min(NB, d - NB * i), nb, nb, 1.0, 0.0);
+        }
+        for (int i = p + 1; i < T; ++i)          // A_ij -= L_ip L_jp^T
+            for (int j = p + 1; j <= i; ++j)
+                tile_mm<false, true>(L.Hd + (int64_t)(NB * i) * d + NB * j, d, L.Hd + (int64_t)(NB * i) * d + o, d,
+                                     L.Hd + (int64_t)(NB * j) * d + o, d, min(NB, d - NB * i), min(NB, d - NB * j), nb, -1.0, 1.0);
+    }
+    // L^-1 below the diagonal blocks: X_ij = -X_ii sum_{m=j}^{i-1} L_im X_mj
+    for (int j = 0; j < T; ++j)
+        for (int i = j + 1; i < T; ++i) {
+            const int mi = min(NB, d - NB * i), nj = min(NB, d - NB * j);
+            double* t = L.T + (int64_t)(NB * i) * d + NB * j;
+            for (int m = j; m < i; ++m)
+                tile_mm<false, false>(t, d, L.Hd + (int64_t)(NB * i) * d + NB * m, d, L.Linv + (int64_t)(NB * m) * d + NB * j, d,
+                                      mi, nj, min(NB, d - NB * m), 1.0, m > j ? 1.0 : 0.0);
+            tile_mm<false, false>(L.Linv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * i) * d + NB * i, d, t, d,
+                                  mi, nj, mi, -1.0, 0.0);
+        }
+    // Hinv = L^-T L^-1, tiles on and above the diagonal: Hinv_ij = sum_{m >= j} X_mi^T X_mj
+    for (int i = 0; i < T; ++i)
+        for (int j = i; j < T; ++j)
+            for (int m = j; m < T; ++m)
+                tile_mm<true, false>(L.Hinv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * m) * d + NB * i, d,
+                                     L.Linv + (int64_t)(NB * m) * d + NB * j, d, min(NB, d - NB * i), min(NB, d - NB * j),
+                                     min(NB, d - NB * m), 1.0, m > j ? 1.0 : 0.0);
+}
+
+// The shared-Hinv elimination (Eq. 12) of a whole small layer: A = Hinv in processing order (gathered here
+// through perm), then panel by panel the diagonal block, the pivot rows right of it, the trailing update.
+// Leaves U (pivot rows) and Un = U / pivot, both on and above the diagonal.  One workgroup per layer.
+__global__ __launch_bounds__(NT) void batch_eliminate_kernel(const BatchLayer* __restrict__ layers)
+{
+    __shared__ double Am[NB * DL];
+    __shared__ double Xm[NB * DL];
+    __shared__ double rv[SWEEP_LDS];
+    const BatchLayer L = layers[blockIdx.x];
+    const int d = L.d, T = (d + NB - 1) / NB, tid = threadIdx.x;
+    for (int idx = tid; idx < d * d; idx += NT) {
+        const int a = idx / d, b = idx - a * d;
+        const int pa = min(max(L.perm[a], 0), d - 1), pb = min(max(L.perm[b], 0), d - 1);
+        L.A[idx] = L.Hinv[(int64_t)min(pa, pb) * d + max(pa, pb)];
+    }
+    __syncthreads();
+    for (int p = 0; p < T; ++p) {
+        const int o = NB * p, nb = min(NB, d - o);
+        for (int idx = tid; idx < NB * NB; idx += NT) {
+            const int i = idx >> 6, j = idx & 63;
+            double v = (i == j) ? 1.0 : 0.0;
+            if (i < nb && j < nb) v = L.A[(int64_t)(o + min(i, j)) * d + o + max(i, j)];
+            Am[i * DL + j] = v;
+        }
+        __syncthreads();
+        elim_block(Am, Xm, rv, L.flags + 1);
+        for (int idx = tid; idx < NB * NB; idx += NT) {
+            const int i = idx >> 6, j = idx & 63;
+            const bool in = i < nb && j < nb;
+            L.Gs[idx] = (in && j <= i) ? Xm[i * DL + j] : 0.0;
+            if (in && j >= i) {
+                L.U[(int64_t)(o + i) * d + o + j] = Am[i * DL + j];
+                L.Un[(int64_t)(o + i) * d + o + j] = (i == j) ? 1.0 : Am[i * DL + j] * rv[i];
+            }
+        }
+        if (tid < NB) L.rinv[tid] = (tid < nb) ? rv[tid] : 0.0;
+        __syncthreads();
+        for (int j = p + 1; j < T; ++j)          // pivot rows right of the block: U_pj = G A_pj, Un_pj = D^-1 U_pj
+            tile_mm<false, false>(L.U + (int64_t)o * d + NB * j, d, L.Gs, NB, L.A + (int64_t)o * d + NB * j, d, nb,
+                                  min(NB, d - NB * j), nb, 1.0, 0.0, L.Un + (int64_t)o * d + NB * j, L.rinv);
+        for (int i = p + 1; i < T; ++i)          // A_ij -= Un_pi^T U_pj
+            for (int j = i; j < T; ++j)
+                tile_mm<true, false>(L.A + (int64_t)(NB * i) * d + NB * j, d, L.Un + (int64_t)o * d + NB * i, d,
+                                     L.U + (int64_t)o * d + NB * j, d, min(NB, d - NB * i), min(NB, d - NB * j), nb, -1.0, 1.0);
+    }
+}
+
+hipError_t launch_batch_inverse(hipStream_t s, const BatchLayer* layers, int n)
+{
+    hipLaunchKernelGGL(batch_inverse_kernel, dim3(n), dim3(NT), 0, s, layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_batch_eliminate(hipStream_t s, const BatchLayer* layers, int n)
+{
+    hipLaunchKernelGGL(batch_eliminate_kernel, dim3(n), dim3(NT), 0, s, layers);
     return hipGetLastError();
 }
 

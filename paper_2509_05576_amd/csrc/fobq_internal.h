@@ -91,6 +91,9 @@ struct fobq_ctx {
     fobq::DevBuf i8planes;  // digits of one accumulate call (see hessian_i8.hip)
     fobq::DevBuf i8sh;      // per-row shifts of that call
     fobq::DevBuf i8amax;    // per-channel maxima (convolution input)
+    fobq::DevBuf batch_pool;    // scratch of all layers of a batched call
+    fobq::DevBuf batch_desc;    // BatchLayer[n] + status words
+    void* h_batch = nullptr;    // pinned host staging for the descriptors and the status read-back
 
     fobq::DevBuf Hpart;     // h_splits x d x d fp64 partial sums of X X^T (lower tiles)
     fobq::DevBuf maps_pad;  // zero-padded copy of the feature maps of one accumulate_conv call (+ 1 zero image)
@@ -127,6 +130,25 @@ struct fobq_ctx {
 };
 
 namespace fobq {
+
+// One layer of fobq_quantize_layers_batched as the kernels see it (an array of these lives in device memory).
+// All pointers are device memory; the scratch pointers are carved out of one pool of the context.
+struct BatchLayer {
+    const float* W; const double* H;          // inputs
+    int R, d, G, gs, Rp, chunks;              // G grids per row of gs columns; Rp = R rounded up to 64; chunks = sens_chunks(R)
+    double maxq, damp, damp_abs;
+    int order, kind, ascending;               // fobq_order; sort key (0 sensi, 1 err, 2 w); direction
+    double *Hd, *Linv, *T, *Hinv, *A, *U, *Un;    // d x d each
+    double *Gs, *rinv;                        // 64 x 64 and 64: diagonal-block scratch of the elimination
+    double *Wp, *DT;                          // R x d; d x Rp
+    uint8_t* codesT;                          // d x Rp
+    double *scale, *zero;                     // R x G
+    double *S, *Spart, *lossrow;              // d; chunks x d; R
+    int *perm, *invperm, *flags;              // d; d; 4 status words (not positive definite: H, running Hinv)
+    uint8_t* codes; float *scales, *zeros, *Q; int* perm_out; double* loss;   // outputs (may be null)
+};
+constexpr int BATCH_MAX_D = 256;      // columns of a layer in a batched call (4 panels of 64)
+constexpr int BATCH_MAX_LAYERS = 256;
 
 int set_err(fobq_ctx* c, int code, const char* fmt, ...);
 int hip_err(fobq_ctx* c, hipError_t e, const char* what);
@@ -184,6 +206,15 @@ hipError_t lauum_upper(fobq_ctx* c, const double* Linv, int d, double* Hinv);   
 // as its stop event: a separate hipEventRecord between two dependent launches would be a bubble of about 4 us.
 hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block, double* U, double* Un, int* flag,
                              const std::vector<hipEvent_t>* rows_ready);
+
+// batched small layers: factor.hip (batch_factor), quant.hip (the rest); grids have one dimension over the layers
+hipError_t launch_batch_inverse(hipStream_t s, const BatchLayer* layers, int n);
+hipError_t launch_batch_order(hipStream_t s, const BatchLayer* layers, int n);
+hipError_t launch_batch_eliminate(hipStream_t s, const BatchLayer* layers, int n);
+hipError_t launch_batch_grid(hipStream_t s, const BatchLayer* layers, int n, int max_pairs);
+hipError_t launch_batch_sens_partial(hipStream_t s, const BatchLayer* layers, int n, int max_chunks);
+hipError_t launch_batch_columns(hipStream_t s, const BatchLayer* layers, int n, int max_rows);
+hipError_t launch_batch_loss(hipStream_t s, const BatchLayer* layers, int n);
 
 // quant.hip
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,

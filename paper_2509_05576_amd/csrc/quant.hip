@@ -839,4 +839,194 @@ hipError_t launch_fill_i32(hipStream_t s, int* p, int64_t n, int v)
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Batched small layers (see batch_inverse_kernel): the same stages with one grid dimension over the layers
+// of the batch, each layer's shapes and pointers in its BatchLayer; workgroups past a layer's own extent leave.
+
+// Grid per (row, group) as grid_kernel; the first workgroup of a layer also clears its status words and
+// per-row loss terms.
+__global__ __launch_bounds__(256) void batch_grid_kernel(const BatchLayer* __restrict__ layers)
+{
+    const BatchLayer L = layers[blockIdx.y];
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 4) L.flags[threadIdx.x] = 0;
+        for (int i = threadIdx.x; i < L.R; i += 256) L.lossrow[i] = 0.0;
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= (int64_t)L.R * L.G) return;
+    const int i = (int)(pair / L.G), g = (int)(pair % L.G);
+    const float* __restrict__ src = L.W + (int64_t)i * L.d + (int64_t)g * L.gs;
+    float lo = 0.f, hi = 0.f;
+    for (int j = lane; j < L.gs; j += 64) {
+        const float w = src[j];
+        lo = fminf(lo, w);
+        hi = fmaxf(hi, w);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+    }
+    if (lane == 0) {
+        double s = 1.0, z = 0.0;
+        if (hi != lo) {
+            s = ((double)hi - (double)lo) / L.maxq;
+            z = rint(-(double)lo / s);
+        }
+        L.scale[pair] = s;
+        L.zero[pair] = z;
+        if (L.scales) L.scales[pair] = (float)s;
+        if (L.zeros) L.zeros[pair] = (float)z;
+    }
+}
+
+// Per-chunk column sums as sens_partial_kernel; blockIdx.x = chunk of 64 rows, thread = column (d <= 256).
+__global__ __launch_bounds__(256) void batch_sens_partial_kernel(const BatchLayer* __restrict__ layers)
+{
+    const BatchLayer L = layers[blockIdx.y];
+    const int j = threadIdx.x;
+    if ((int)blockIdx.x >= L.chunks || j >= L.d) return;
+    const int g = j / L.gs;
+    const int r0 = blockIdx.x * SENS_RC, r1 = min(L.R, r0 + SENS_RC);
+    double acc = 0.0;
+    for (int i = r0; i < r1; ++i) {
+        const double w = (double)L.W[(int64_t)i * L.d + j];
+        const double s = L.scale[(int64_t)i * L.G + g], z = L.zero[(int64_t)i * L.G + g];
+        const double q = s * (grid_code(w, s, z, L.maxq) - z);
+        acc += (L.kind == 2) ? w * w : (q - w) * (q - w);
+    }
+    L.Spart[(int64_t)blockIdx.x * L.d + j] = acc;
+}
+
+// Scores and order of one layer by one workgroup (d <= 256: thread = column): the chunks are added in index
+// order, "sensi" divides by 2 [Hinv]_jj; rank by counting, equal keys keep index order.
+__global__ __launch_bounds__(256) void batch_order_kernel(const BatchLayer* __restrict__ layers)
+{
+    __shared__ double key[BATCH_MAX_D];
+    const BatchLayer L = layers[blockIdx.x];
+    const int j = threadIdx.x, d = L.d;
+    if (j < d) {
+        double acc = 0.0;
+        for (int c = 0; c < L.chunks; ++c) acc += L.Spart[(int64_t)c * d + j];
+        const double sj = (L.kind == 0) ? acc / (2.0 * L.Hinv[(int64_t)j * d + j]) : acc;
+        L.S[j] = sj;
+        key[j] = sort_key((L.ascending ? -1.0 : 1.0) * sj);
+    }
+    __syncthreads();
+    if (L.order == FOBQ_ORDER_NATURAL) {
+        if (j < d) { L.perm[j] = j; L.invperm[j] = j; }
+    } else if (j < d) {
+        const double sj = key[j];
+        int r = 0;
+        for (int k = 0; k < d; ++k) {
+            const double v = key[k];
+            r += (v > sj || (v == sj && k < j)) ? 1 : 0;
+        }
+        L.perm[r] = j;
+        L.invperm[j] = r;
+    }
+    __syncthreads();
+    if (L.perm_out && j < d) L.perm_out[j] = L.perm[j];
+}
+
+// The whole column loop of a small layer in one launch.  Rows never interact (Section 4.2 step 4: all rows
+// at once), and with the pivot rows complete a workgroup of 8 wavefronts owns 8 rows from the first column to
+// the last: it gathers them into processing order, then block by block runs the 64 sequential steps
+// (col_chain_role) and applies the block's deferred compensation (Eq. 9 / 11) to its own rows' later columns;
+// at the end it writes its rows' codes and dequantized weights in the original column order.
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void batch_columns_kernel(const BatchLayer* __restrict__ layers)
+{
+    __shared__ double lds[2 * CB * (CB + 2)];
+    const BatchLayer L = layers[blockIdx.y];
+    const int wg = blockIdx.x;
+    if (wg * CHAIN_WAVES >= L.R) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = wg * CHAIN_WAVES + wave, d = L.d;
+    const bool row_ok = row < L.R;
+    if (row_ok) {
+        for (int t = lane; t < d; t += 64) {
+            const int pt = min(max(L.perm[t], 0), d - 1);
+            L.Wp[(int64_t)row * d + t] = (double)L.W[(int64_t)row * d + pt];
+        }
+    }
+    __syncthreads();
+    ColChainP c;
+    c.Wp = L.Wp; c.R = L.R; c.d = d; c.Un = L.Un; c.U = L.U; c.scale = L.scale; c.zero = L.zero;
+    c.G = L.G; c.gs = L.gs; c.perm = L.perm; c.maxq = L.maxq; c.codesT = L.codesT; c.DT = L.DT; c.Rp = L.Rp;
+    c.lossrow = L.lossrow; c.corr_in = nullptr; c.corr_out = nullptr; c.nb_next = 0;
+    for (int o = 0; o < d; o += CB) {
+        const int nb = min(CB, d - o);
+        c.o = o; c.nb = nb;
+        col_chain_role(c, lds, wg);
+        __syncthreads();               // the chain's stores of this workgroup's rows are visible to it
+        if (row_ok && o + nb < d) {
+            // W[row][k] -= sum_j diff_j Un[o + j][k] for the columns k right of the block; lane j holds diff_j
+            const double dj = lane < nb ? L.DT[(int64_t)(o + lane) * L.Rp + row] : 0.0;
+            for (int k = o + nb + lane; k < d; k += 64) {
+                double acc = 0.0;
+                for (int j = 0; j < nb; ++j) acc = fma(readlane_f64(dj, j), L.Un[(int64_t)(o + j) * d + k], acc);
+                L.Wp[(int64_t)row * d + k] -= acc;
+            }
+        }
+        __syncthreads();
+    }
+    if (!row_ok) return;
+    for (int cidx = lane; cidx < d; cidx += 64) {
+        const int t = min(max(L.invperm[cidx], 0), d - 1);
+        const uint8_t code = L.codesT[(int64_t)t * L.Rp + row];
+        const int g = cidx / L.gs;
+        const double q = L.scale[(int64_t)row * L.G + g] * ((double)code - L.zero[(int64_t)row * L.G + g]);
+        if (L.codes) L.codes[(int64_t)row * d + cidx] = code;
+        if (L.Q) L.Q[(int64_t)row * d + cidx] = (float)q;
+    }
+}
+
+__global__ __launch_bounds__(256) void batch_loss_kernel(const BatchLayer* __restrict__ layers)
+{
+    __shared__ double part[256];
+    const BatchLayer L = layers[blockIdx.x];
+    if (!L.loss) return;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < L.R; i += 256) s += L.lossrow[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *L.loss = part[0];
+}
+
+hipError_t launch_batch_grid(hipStream_t s, const BatchLayer* layers, int n, int max_pairs)
+{
+    hipLaunchKernelGGL(batch_grid_kernel, dim3((max_pairs + 3) / 4, n), dim3(256), 0, s, layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_batch_sens_partial(hipStream_t s, const BatchLayer* layers, int n, int max_chunks)
+{
+    hipLaunchKernelGGL(batch_sens_partial_kernel, dim3(max_chunks, n), dim3(256), 0, s, layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_batch_order(hipStream_t s, const BatchLayer* layers, int n)
+{
+    hipLaunchKernelGGL(batch_order_kernel, dim3(n), dim3(256), 0, s, layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_batch_columns(hipStream_t s, const BatchLayer* layers, int n, int max_rows)
+{
+    hipLaunchKernelGGL(batch_columns_kernel, dim3((max_rows + CHAIN_WAVES - 1) / CHAIN_WAVES, n), dim3(64 * CHAIN_WAVES), 0, s,
+                       layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_batch_loss(hipStream_t s, const BatchLayer* layers, int n)
+{
+    hipLaunchKernelGGL(batch_loss_kernel, dim3(n), dim3(256), 0, s, layers);
+    return hipGetLastError();
+}
+
 }  // namespace fobq

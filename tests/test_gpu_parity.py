@@ -609,6 +609,62 @@ def test_enqueue_and_finish_on_several_contexts(fobq, ctx):
         c.close()
 
 
+# Batched small layers: every stage is one launch for all layers of the batch.  Shapes mix everything the
+# sweeps' small layers have: one to four panels, ragged d_col and d_row, a single row, a single column, groups.
+BATCH_SHAPES = [(64, 64, 300), (256, 64, 200), (32, 32, 100), (255, 128, 500), (64, 256, 700), (1024, 256, 400),
+                (33, 147, 400), (128, 108, 300), (1, 200, 400), (17, 1, 9), (40, 65, 100), (300, 192, 90)]
+
+
+@pytest.mark.parametrize("bits,group,order", [(4, 0, 1), (3, 0, 0), (8, 0, 6), (4, 32, 1)])
+def test_batched_small_layers_match_oracle(fobq, ctx, bits, group, order):
+    _say(f"batched small layers bits={bits} group={group} order={order}")
+    Ws, Xs, Wd, Hd = [], [], [], []
+    for i, (r, d, n) in enumerate(BATCH_SHAPES):
+        if group and d % group:
+            continue                    # the group width must divide every d_col of the batch
+        W, X = _problem(r, d, n, 5000 + i, w_std=0.05)
+        Ws.append(W)
+        Xs.append(X)
+        Wd.append(_dev(W))
+        H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+        ctx.hessian(_dev(X), H_out=H)
+        Hd.append(H)
+    outs = ctx.quantize_layers_batched(Wd, Hd, bits=bits, group=group, order=order, damp=0.01)
+    torch.cuda.synchronize()
+    for W, X, H, out in zip(Ws, Xs, Hd, outs):
+        Hh = H.cpu().numpy()
+        ref = oracle.quantize_layer(W, H=Hh, bits=bits, group=group, order_mode=order)
+        ref = _oracle_with_gpu_perm(W, Hh, out.perm.cpu().numpy(), ref, bits=bits, group=group)
+        _compare_layer(out, ref, W, bits)
+    # the same layers one at a time through fobq_quantize_layer: same codes, same order
+    for Wt, H, out in zip(Wd, Hd, outs):
+        single = ctx.quantize_layer(Wt, H, bits=bits, group=group, order=order, damp=0.01)
+        assert torch.equal(single.codes, out.codes) and torch.equal(single.perm, out.perm)
+        assert torch.allclose(single.loss, out.loss, rtol=1e-9)
+
+
+def test_batched_small_layers_errors(fobq, ctx):
+    W = torch.randn((8, 300), device="cuda")
+    H = torch.eye(300, dtype=torch.float64, device="cuda")
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.quantize_layers_batched([W], [H])                  # more than 256 columns
+    assert e.value.code == fobq.EINVAL and "layer 0" in str(e.value)
+    W = torch.randn((8, 64), device="cuda")
+    H = torch.eye(64, dtype=torch.float64, device="cuda")
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.quantize_layers_batched([W], [H], order=fobq.ORDER_SENSI_DYNAMIC)
+    assert e.value.code == fobq.EINVAL
+    assert ctx.quantize_layers_batched([], []) == []
+    # a layer whose Hessian is not positive definite is named; the others are complete
+    Hbad = -torch.eye(64, dtype=torch.float64, device="cuda")
+    outs = [None, None]
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.quantize_layers_batched([W, W], [H, Hbad], damp=0.0)
+    assert e.value.code == fobq.ENOTPD and "layer 1" in str(e.value)
+    out = ctx.quantize_layers_batched([W, W], [H, H])
+    assert torch.equal(out[0].codes, out[1].codes)
+
+
 def test_non_finite_inputs_do_not_break_the_context(fobq, ctx):
     # NaN / Inf in the inputs are not rejected on the host; they must neither fault nor poison later calls
     W, X = _problem(20, 130, 400, 14, w_std=0.05)
