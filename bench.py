@@ -61,7 +61,7 @@ def _median(v):
     return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
 
-def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8: bool) -> int:
+def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8: bool, batch_small: bool) -> int:
     """Whole-model sweep: every layer of a ResNet-50- or YOLOv5s-shaped network (4-bit, per-row grids,
     128 images), each layer fed as the network would feed it: a k x k or strided convolution accumulates
     its Hessian straight from its seeded ReLU-Gaussian input maps (fobq_hessian_accumulate_conv, a bounded
@@ -108,37 +108,66 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
         else:
             ctx.hessian(inp, chunk=pc, H_out=H_out)
 
+    # layers of up to 256 columns go through fobq_quantize_layers_batched, all of them in one call: their
+    # Hessians are accumulated one by one into buffers of their own, then every stage of the path is one launch
+    # for the whole batch
+    small = [i for i, spec in enumerate(layers) if batch_small and spec.d_col <= 256]
+    big = [i for i in range(len(layers)) if i not in set(small)]
+    Hs = {i: torch.empty((layers[i].d_col, layers[i].d_col), dtype=torch.float64, device="cuda") for i in small}
+    outs = [None] * len(layers)
+    batch_outs = None
+
+    def run_small_batch(ctx):
+        nonlocal batch_outs
+        if small:
+            batch_outs = ctx.quantize_layers_batched([Ws[i] for i in small], [Hs[i] for i in small], bits=layers[small[0]].bits,
+                                                     group=0, damp=layers[small[0]].damp, outs=batch_outs)
+            for i, o in zip(small, batch_outs):
+                outs[i] = o
+
     hmode = fobq.HESSIAN_INT8_SLICES if int8 else fobq.HESSIAN_FP64
-    # (1) one layer at a time; per-layer time = median over the runs
+    # (1) one layer at a time; per-layer time = median over the runs (a batched layer: its Hessian's time plus
+    # its share of the batched call)
     ctx = fobq.Ctx(0)
     ctx.set_hessian_mode(hmode)
-    outs = [None] * len(layers)
     layer_ms = [[] for _ in layers]
-    seq_runs = []
+    seq_runs, batch_ms = [], []
     for it in range(warmup + steps):
         torch.cuda.synchronize()
         t_run = time.perf_counter()
         for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
             t0 = time.perf_counter()
-            hessian(ctx, spec, inp, pc)
-            outs[i] = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
+            if i in Hs:
+                hessian(ctx, spec, inp, pc, H_out=Hs[i])
+            else:
+                hessian(ctx, spec, inp, pc)
+                outs[i] = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
             torch.cuda.synchronize()
             if it >= warmup:
                 layer_ms[i].append((time.perf_counter() - t0) * 1e3)
+        t0 = time.perf_counter()
+        run_small_batch(ctx)
+        torch.cuda.synchronize()
         if it >= warmup:
+            batch_ms.append((time.perf_counter() - t0) * 1e3)
             seq_runs.append((time.perf_counter() - t_run) * 1e3)
     workspace_seq = ctx.workspace_bytes()
+    share = _median(batch_ms) / len(small) if small else 0.0
     per_layer = [{"layer": spec.name, "d_row": spec.d_row, "d_col": spec.d_col, "n": spec.n,
-                  "input": "maps" if inp.dim() == 4 else "X", "ms": round(_median(ms), 3)}
-                 for spec, inp, ms in zip(layers, Ins, layer_ms)]
+                  "input": "maps" if inp.dim() == 4 else "X", "batched": i in Hs,
+                  "ms": round(_median(ms) + (share if i in Hs else 0.0), 3)}
+                 for i, (spec, inp, ms) in enumerate(zip(layers, Ins, layer_ms))]
 
     # validity of every layer, on the device, from the path's own Hessian
     checked = 0
     for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
         d = spec.d_col
-        H = torch.empty((d, d), dtype=torch.float64, device="cuda")
-        hessian(ctx, spec, inp, pc, H_out=H)
-        o = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
+        if i in Hs:
+            H, o = Hs[i], outs[i]            # the batched call's own inputs and outputs
+        else:
+            H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+            hessian(ctx, spec, inp, pc, H_out=H)
+            o = ctx.quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i])
         torch.cuda.synchronize()
         perm = o.perm.long()
         ok_perm = bool(torch.equal(torch.sort(perm).values, torch.arange(d, device="cuda")))
@@ -156,7 +185,6 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
                   file=sys.stderr)
             return 1
         checked += 1
-        del H
     ctx.close()
 
     # (2) the whole model, several layers in flight
@@ -172,12 +200,18 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
             k = i % K
             if busy[k]:
                 ctxs[k].finish()
+                busy[k] = False
+            if i in Hs:
+                hessian(ctxs[k], spec, inp, pc, H_out=Hs[i])
+                continue
             hessian(ctxs[k], spec, inp, pc)
             outs[i] = ctxs[k].quantize_layer(W, bits=spec.bits, group=spec.group, damp=spec.damp, out=outs[i], wait=False)
             busy[k] = True
         for k in range(K):
             if busy[k]:
                 ctxs[k].finish()
+        torch.cuda.synchronize()            # every Hessian of the batched layers is complete
+        run_small_batch(ctxs[0])
 
     runs = []
     for it in range(warmup + steps):
@@ -202,7 +236,8 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
                        "weights": total_weights, "layers_in_flight": K, "input_bytes": input_bytes},
             "whole_model_seconds": round(med * 1e-3, 4), "runs_ms": [round(r, 2) for r in runs],
             "sequential_ms": round(_median(seq_runs), 3), "sequential_runs_ms": [round(r, 2) for r in seq_runs],
-            "layers_checked": checked,
+            "layers_checked": checked, "layers_batched": len(small),
+            "batched_call_ms": round(_median(batch_ms), 3) if small else None,
             "workspace_bytes": {"one_context": workspace_seq, "contexts_in_flight": workspace_flight},
             "per_layer": per_layer}
     print(json.dumps(line))
@@ -226,6 +261,9 @@ def main() -> int:
                     help="how X X^T is formed: i8 = exact int8 slice products on the matrix cores where the mode "
                          "applies (d_col >= 384, n >= 2048 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
                          "matrix instructions")
+    ap.add_argument("--no-batch", action="store_true",
+                    help="whole-model sweeps: quantize the layers of up to 256 columns one by one instead of all of "
+                         "them in one fobq_quantize_layers_batched call")
     ap.add_argument("--iid", action="store_true",
                     help="whole-model sweeps: feed every layer an unfolded matrix of independent activations "
                          "instead of the convolutions' input maps (the earlier variant, kept for comparison)")
@@ -252,7 +290,7 @@ def main() -> int:
         return 2
     if args.workload in ("sweep_resnet50", "sweep_yolov5s"):
         return sweep(args.workload[len("sweep_"):], max(5, min(args.steps, 9)), min(args.warmup, 2), args.concurrency,
-                     args.iid, args.hessian == "i8")
+                     args.iid, args.hessian == "i8", not args.no_batch)
     fobq.load_library()
     spec = workloads.configs()[args.workload]
     W = spec.make_w()

@@ -1180,28 +1180,23 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
 // tile_mm: C (m x n) = beta C + alpha op(A) op(B), op(A) m x k, op(B) k x n, all <= 64, row-major in global memory.
 //   TA: op(A)[r][q] = A[q * lda + r] (else A[r * lda + q]);  TB: op(B)[q][c] = B[c * ldb + q] (else B[q * ldb + c]).
 //   C2 / rowscale (may be null): C2[r][c] = rowscale[r] * result.
-// Called by all NT threads; every operand is in registers before anything is stored (C may alias A or B);
-// ends with a barrier.
+// The two operand tiles are staged in LDS as they lie in memory (coalesced rows; Pa, Pb: NB * DL doubles each)
+// and the MFMA fragments are read in the orientation the product needs.  Called by all NT threads; every
+// operand is in LDS before anything is stored (C may alias A or B); ends with a barrier.
 template <bool TA, bool TB>
-__device__ __forceinline__ void tile_mm(double* C, int64_t ldc, const double* A, int64_t lda, const double* B, int64_t ldb,
-                                        int m, int n, int k, double alpha, double beta, double* C2 = nullptr,
-                                        const double* rowscale = nullptr)
+__device__ __forceinline__ void tile_mm(double* Pa, double* Pb, double* C, int64_t ldc, const double* A, int64_t lda,
+                                        const double* B, int64_t ldb, int m, int n, int k, double alpha, double beta,
+                                        double* C2 = nullptr, const double* rowscale = nullptr)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
-    double a[16], b[2][16];
-    const int ar = wr * 16 + fr, arc = min(ar, m - 1);
+    const int arows = TA ? k : m, acols = TA ? m : k, brows = TB ? n : k, bcols = TB ? k : n;
+    double pa[8], pb[8];
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-        const int q = 4 * ks + fq, qc = min(q, k - 1);
-        const double av = TA ? A[(int64_t)qc * lda + arc] : A[(int64_t)arc * lda + qc];
-        a[ks] = (ar < m && q < k) ? alpha * av : 0.0;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int bc = w2 * 32 + 16 * j + fr, bcc = min(bc, n - 1);
-            const double bv = TB ? B[(int64_t)bcc * ldb + qc] : B[(int64_t)qc * ldb + bcc];
-            b[j][ks] = (bc < n && q < k) ? bv : 0.0;
-        }
+    for (int u = 0; u < 8; ++u) {
+        const int y = wave + 8 * u, x = lane;
+        pa[u] = (y < arows && x < acols) ? A[(int64_t)y * lda + x] : 0.0;
+        pb[u] = (y < brows && x < bcols) ? B[(int64_t)y * ldb + x] : 0.0;
     }
     d4 acc[2];
 #pragma unroll
@@ -1211,11 +1206,23 @@ __device__ __forceinline__ void tile_mm(double* C, int64_t ldc, const double* A,
             const int r = wr * 16 + 4 * v + fq, c = w2 * 32 + 16 * j + fr;
             acc[j][v] = (beta != 0.0 && r < m && c < n) ? beta * C[(int64_t)r * ldc + c] : 0.0;
         }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        Pa[(wave + 8 * u) * DL + lane] = alpha * pa[u];
+        Pb[(wave + 8 * u) * DL + lane] = pb[u];
+    }
     __syncthreads();
+    const int ar = wr * 16 + fr;
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks)
+    for (int ks = 0; ks < 16; ++ks) {
+        const int q = 4 * ks + fq;
+        const double av = TA ? Pa[q * DL + ar] : Pa[ar * DL + q];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[j] = mfma4(a[ks], b[j][ks], acc[j]);
+        for (int j = 0; j < 2; ++j) {
+            const int bc = w2 * 32 + 16 * j + fr;
+            acc[j] = mfma4(av, TB ? Pb[bc * DL + q] : Pb[q * DL + bc], acc[j]);
+        }
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -1276,11 +1283,11 @@ __global__ __launch_bounds__(NT) void batch_inverse_kernel(const BatchLayer* __r
         __syncthreads();
         for (int i = p + 1; i < T; ++i) {        // L_ip = A_ip L_pp^-T
             double* t = L.Hd + (int64_t)(NB * i) * d + o;
-            tile_mm<false, true>(t, d, t, d, L.Linv + (int64_t)o * d + o, d, min(NB, d - NB * i), nb, nb, 1.0, 0.0);
+            tile_mm<false, true>(Am, Xm, t, d, t, d, L.Linv + (int64_t)o * d + o, d, min(NB, d - NB * i), nb, nb, 1.0, 0.0);
         }
         for (int i = p + 1; i < T; ++i)          // A_ij -= L_ip L_jp^T
             for (int j = p + 1; j <= i; ++j)
-                tile_mm<false, true>(L.Hd + (int64_t)(NB * i) * d + NB * j, d, L.Hd + (int64_t)(NB * i) * d + o, d,
+                tile_mm<false, true>(Am, Xm, L.Hd + (int64_t)(NB * i) * d + NB * j, d, L.Hd + (int64_t)(NB * i) * d + o, d,
                                      L.Hd + (int64_t)(NB * j) * d + o, d, min(NB, d - NB * i), min(NB, d - NB * j), nb, -1.0, 1.0);
     }
     // L^-1 below the diagonal blocks: X_ij = -X_ii sum_{m=j}^{i-1} L_im X_mj
@@ -1289,16 +1296,16 @@ __global__ __launch_bounds__(NT) void batch_inverse_kernel(const BatchLayer* __r
             const int mi = min(NB, d - NB * i), nj = min(NB, d - NB * j);
             double* t = L.T + (int64_t)(NB * i) * d + NB * j;
             for (int m = j; m < i; ++m)
-                tile_mm<false, false>(t, d, L.Hd + (int64_t)(NB * i) * d + NB * m, d, L.Linv + (int64_t)(NB * m) * d + NB * j, d,
+                tile_mm<false, false>(Am, Xm, t, d, L.Hd + (int64_t)(NB * i) * d + NB * m, d, L.Linv + (int64_t)(NB * m) * d + NB * j, d,
                                       mi, nj, min(NB, d - NB * m), 1.0, m > j ? 1.0 : 0.0);
-            tile_mm<false, false>(L.Linv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * i) * d + NB * i, d, t, d,
+            tile_mm<false, false>(Am, Xm, L.Linv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * i) * d + NB * i, d, t, d,
                                   mi, nj, mi, -1.0, 0.0);
         }
     // Hinv = L^-T L^-1, tiles on and above the diagonal: Hinv_ij = sum_{m >= j} X_mi^T X_mj
     for (int i = 0; i < T; ++i)
         for (int j = i; j < T; ++j)
             for (int m = j; m < T; ++m)
-                tile_mm<true, false>(L.Hinv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * m) * d + NB * i, d,
+                tile_mm<true, false>(Am, Xm, L.Hinv + (int64_t)(NB * i) * d + NB * j, d, L.Linv + (int64_t)(NB * m) * d + NB * i, d,
                                      L.Linv + (int64_t)(NB * m) * d + NB * j, d, min(NB, d - NB * i), min(NB, d - NB * j),
                                      min(NB, d - NB * m), 1.0, m > j ? 1.0 : 0.0);
 }
@@ -1341,11 +1348,11 @@ __global__ __launch_bounds__(NT) void batch_eliminate_kernel(const BatchLayer* _
         if (tid < NB) L.rinv[tid] = (tid < nb) ? rv[tid] : 0.0;
         __syncthreads();
         for (int j = p + 1; j < T; ++j)          // pivot rows right of the block: U_pj = G A_pj, Un_pj = D^-1 U_pj
-            tile_mm<false, false>(L.U + (int64_t)o * d + NB * j, d, L.Gs, NB, L.A + (int64_t)o * d + NB * j, d, nb,
+            tile_mm<false, false>(Am, Xm, L.U + (int64_t)o * d + NB * j, d, L.Gs, NB, L.A + (int64_t)o * d + NB * j, d, nb,
                                   min(NB, d - NB * j), nb, 1.0, 0.0, L.Un + (int64_t)o * d + NB * j, L.rinv);
         for (int i = p + 1; i < T; ++i)          // A_ij -= Un_pi^T U_pj
             for (int j = i; j < T; ++j)
-                tile_mm<true, false>(L.A + (int64_t)(NB * i) * d + NB * j, d, L.Un + (int64_t)o * d + NB * i, d,
+                tile_mm<true, false>(Am, Xm, L.A + (int64_t)(NB * i) * d + NB * j, d, L.Un + (int64_t)o * d + NB * i, d,
                                      L.U + (int64_t)o * d + NB * j, d, min(NB, d - NB * i), min(NB, d - NB * j), nb, -1.0, 1.0);
     }
 }

@@ -960,16 +960,24 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void batch_columns_kernel(const B
         c.o = o; c.nb = nb;
         col_chain_role(c, lds, wg);
         __syncthreads();               // the chain's stores of this workgroup's rows are visible to it
-        if (row_ok && o + nb < d) {
-            // W[row][k] -= sum_j diff_j Un[o + j][k] for the columns k right of the block; lane j holds diff_j
-            const double dj = lane < nb ? L.DT[(int64_t)(o + lane) * L.Rp + row] : 0.0;
-            for (int k = o + nb + lane; k < d; k += 64) {
-                double acc = 0.0;
-                for (int j = 0; j < nb; ++j) acc = fma(readlane_f64(dj, j), L.Un[(int64_t)(o + j) * d + k], acc);
-                L.Wp[(int64_t)row * d + k] -= acc;
+        // W[row][k] -= sum_j diff_j Un[o + j][k] for the columns k right of the block, 64 columns at a time: the
+        // block's pivot rows above those columns go through LDS once for the workgroup's 8 rows; lane j holds diff_j
+        const double dj = (row_ok && lane < nb) ? L.DT[(int64_t)(o + lane) * L.Rp + row] : 0.0;
+        double (*Us)[CB + 1] = reinterpret_cast<double (*)[CB + 1]>(lds);
+        for (int k0 = o + nb; k0 < d; k0 += CB) {
+            const int nk = min(CB, d - k0);
+#pragma unroll
+            for (int i = 0; i < CB / CHAIN_WAVES; ++i) {
+                const int j = wave + CHAIN_WAVES * i;
+                Us[j][lane] = (j < nb && lane < nk) ? L.Un[(int64_t)(o + j) * d + k0 + lane] : 0.0;
             }
+            __syncthreads();
+            double acc = 0.0;
+#pragma unroll
+            for (int j = 0; j < CB; ++j) acc = fma(readlane_f64(dj, j), Us[j][lane], acc);
+            if (row_ok && lane < nk) L.Wp[(int64_t)row * d + k0 + lane] -= acc;
+            __syncthreads();
         }
-        __syncthreads();
     }
     if (!row_ok) return;
     for (int cidx = lane; cidx < d; cidx += 64) {
