@@ -357,14 +357,14 @@ def main() -> int:
     n_per_launch = spec.n / launches_per_step
     flops_per_launch = spec.d_col * (spec.d_col + 1) * n_per_launch     # one triangle: d(d+1)/2 entries x 2N flop
     avg_ms = xxt_ms / xxt_launches
-    int8 = args.hessian == "i8" and not args.from_maps and spec.d_col >= 384 and n_per_launch >= 2048
+    int8 = args.hessian == "i8" and spec.d_col >= 384 and n_per_launch >= 2048
     if int8:
         # integer-slice formulation: 19 int8 slice products per entry of the triangle, against the dense int8 peak
         ops_per_launch = 19.0 * flops_per_launch
         achieved = ops_per_launch / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": "xxt_i8_kernel", "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_MFMA_TOPS,
                     "unit": "TOP/s", "frac": round(achieved / PEAK_INT8_MFMA_TOPS, 4),
-                    "traffic": measured_traffic("xxt_i8_kernel", spec.name) if launches_per_step == 1 else None,
+                    "traffic": measured_traffic("xxt_i8_kernel", spec.name) if launches_per_step == 1 and not args.from_maps else None,
                     "avg_launch_ms": round(avg_ms, 4), "algorithmic_ops_per_launch": ops_per_launch,
                     "slice_products": 19,
                     "fp64_equivalent_TFLOPs": round(flops_per_launch / (avg_ms * 1e-3) / 1e12, 2),

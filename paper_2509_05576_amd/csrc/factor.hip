@@ -1109,7 +1109,7 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
     };
     double* Gb[2] = {c->Dblk.as<double>() + 2 * NB * NB, c->Dblk.as<double>() + 3 * NB * NB};
     double* rb[2] = {c->Dblk.as<double>() + 4 * NB * NB, c->Dblk.as<double>() + 4 * NB * NB + NB};
-    if (block == NB && steps == d && d < 3000) {
+    if (block == NB && steps == d) {
         // one stand-alone launch for the first diagonal block, then one fused launch per panel
         hipLaunchKernelGGL(elim_diag_kernel, dim3(1), dim3(NT), 0, s, A, (int64_t)d, 0, min(NB, d), U, Un,
                            (double*)nullptr, Gb[0], rb[0], flag);
