@@ -38,6 +38,9 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int NT = 512;   // threads per workgroup of every kernel in this file (8 wavefronts)
 // launches with more tiles than this use the two-workgroups-per-compute-unit variant of the panel kernels
 constexpr int DENSE_LAUNCH_TILES = 300;
+// launches with at least this many trailing tiles are bound by tile throughput: the panel is stored by a launch of
+// its own and every tile does one product instead of three (see chol_iter_kernel)
+constexpr int STORED_PANEL_TILES = 800;
 constexpr int MATE_SLOT = 256, MATE_MAX_NAPS = 64;
 static_assert(MATE_SLOT < DENSE_LAUNCH_TILES, "the idle workgroup must exist in every dense launch");
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
@@ -552,7 +555,12 @@ __device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int 
 // WPS = wavefronts per SIMD the register budget allows: 2 (one workgroup per compute unit, workgroup 0 has
 // its matrix pipes to itself: faster while the launch's tiles fit in workgroup 0's shadow anyway) or 4
 // (two workgroups per compute unit: more tile throughput for the large launches).
-template <int WPS>
+// MODE: PANEL_FUSED as described; for launches so large that tile throughput, not workgroup 0, bounds them, the
+// panel is stored once instead of being recomputed by every tile (one product per tile instead of three):
+// PANEL_ONLY = workgroup i computes and stores L21_i (nothing else), PANEL_STORED = the trailing launch that
+// follows it and takes L21_i, L21_j from L (L must not be null; no inverse tiles ride along).
+enum { PANEL_FUSED = 0, PANEL_ONLY = 1, PANEL_STORED = 2 };
+template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
                                                        const double* __restrict__ Dinv, double* __restrict__ L,
                                                        double* __restrict__ Linv, double* __restrict__ Dinv_next,
@@ -579,7 +587,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
         return;
     }
     const int bid = (int)blockIdx.x - ((WPS == 4 && (int)blockIdx.x > MATE_SLOT) ? 1 : 0);
-    if (bid >= ntrail + ninv) {
+    if (MODE == PANEL_FUSED && bid >= ntrail + ninv) {
         // tiles of the Hinv role in this launch; a workgroup past them has nothing to do
         const int nlau = Sacc ? (o / NB) * (o / NB + 1) / 2 : 0;
         if (bid - ntrail - ninv >= nlau) return;
@@ -588,21 +596,48 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
         chol_lauum_tile(tiles, d, o / NB - 1, mt, nt, Linv, Hinv);
         return;
     }
-    if (bid >= ntrail) {
+    if (MODE == PANEL_FUSED && bid >= ntrail) {
         const int pcols = o / NB + 1, e = bid - ntrail;
         chol_inverse_tile(tiles, Hd, d, o, o / NB + 1 + e / pcols, e % pcols, Dinv, Linv, Sacc);
         return;
     }
+    if (MODE != PANEL_FUSED && bid >= ntrail) return;
     double* Pi = tiles;
     double* Pj = tiles + NB * DL;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wn = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
-    tri_decode(bid, ti, tj);
+    if (MODE == PANEL_ONLY) { ti = bid; tj = bid; }      // workgroup i: row tile i of the panel (ntrail = row tiles)
+    else tri_decode(bid, ti, tj);
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
 
+    d4 c[2];
+    if (MODE == PANEL_STORED) {
+        // the panel blocks L21_i, L21_j as the panel launch stored them; the tile itself in flight meanwhile
+        double pa[8], pb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
+            pa[u] = L[(int64_t)min(mi0 + y, d - 1) * d + o + x];
+            pb[u] = L[(int64_t)min(mj0 + y, d - 1) * d + o + x];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wr * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+                c[j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+            }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
+            Pi[y * DL + x] = pa[u];
+            if (!diag_tile) Pj[y * DL + x] = pb[u];
+        }
+        __syncthreads();
+    } else {
     // Panel product L21 = A21 L11^-T: L11^-1 is lower triangular, so the 16 columns of column tile ct
     // (of 4) only need the k-steps 0 .. 4 ct + 3.  The wavefronts with wn = 0 take the column tiles
     // 0 and 3, those with wn = 1 the tiles 1 and 2: 20 of 32 (k-step, tile) pairs each.
@@ -635,14 +670,15 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     }
     __syncthreads();
     // the tile itself: in flight during the panel product
-    d4 c[2];
+    if (MODE == PANEL_FUSED) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int gm = mi0 + wr * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
-            c[j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
-        }
+            for (int v = 0; v < 4; ++v) {
+                const int gm = mi0 + wr * 16 + 4 * v + fq, gn = mj0 + wn * 32 + j * 16 + fr;
+                c[j][v] = Hd[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+            }
+    }
 
     d4 li[2], lj[2];
 #pragma unroll
@@ -662,9 +698,11 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
             const int m = wr * 16 + 4 * v + fq, n = ct[j] * 16 + fr;
             Pi[m * DL + n] = li[j][v];
             if (!diag_tile) Pj[m * DL + n] = lj[j][v];
-            if (L && tj == 0 && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[j][v];
+            if (L && (tj == 0 || MODE == PANEL_ONLY) && mi0 + m < d) L[(int64_t)(mi0 + m) * d + o + n] = li[j][v];
         }
+    if (MODE == PANEL_ONLY) return;
     __syncthreads();
+    }
     const double* Qj = diag_tile ? Pi : Pj;
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
@@ -717,12 +755,18 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         const int ninv = Sacc ? T * (it + 1) : 0;      // tiles of the triangular inverse (row below, column up to the panel)
         const int nlau = Sacc ? it * (it + 1) / 2 : 0;  // tiles of Hinv that block row it - 1 of L^-1 adds to
         const int tiles = ntrail + ninv + nlau;
-        if (tiles <= DENSE_LAUNCH_TILES)
-            hipLaunchKernelGGL(chol_iter_kernel<2>, dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+        if (!Sacc && L && ntrail >= STORED_PANEL_TILES) {
+            // throughput-bound launch: the panel once (T workgroups), then one product per trailing tile
+            hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                               Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0);
+            hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED>), dim3(ntrail + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L,
+                               Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch);
+        } else if (tiles <= DENSE_LAUNCH_TILES)
+            hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_FUSED>), dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
                                Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, 0);
         else
             // one workgroup more than tiles: see MATE_SLOT (tiles > DENSE_LAUNCH_TILES > MATE_SLOT)
-            hipLaunchKernelGGL(chol_iter_kernel<4>, dim3(tiles + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+            hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_FUSED>), dim3(tiles + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
                                Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, ++c->mate_epoch);
     }
     if (Sacc && it > 0) {
@@ -965,7 +1009,9 @@ __global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict_
 //      Un12 = D^-1 U12; the tiles of the first tile row also store them into U and Un;
 //   2. A22(ti, tj) -= Un12_i^T U12_j        (Eq. 12 for the 64 columns of the panel at once);
 //   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
-template <int WPS>
+// MODE as for chol_iter_kernel: PANEL_ONLY = workgroup j computes and stores the pivot rows U12_j, Un12_j right of the
+// block for its tile column; PANEL_STORED = the trailing launch that follows and takes them from U and Un.
+template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__ A, int d, int o,
                                                        const double* __restrict__ G, const double* __restrict__ rinv,
                                                        double* __restrict__ U, double* __restrict__ Un,
@@ -991,10 +1037,36 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     const int wr = wave >> 1, w2 = wave & 1, fr = lane & 15, fq = lane >> 4;
     const int r0 = o + NB;
     int ti, tj;
-    tri_decode(bid, tj, ti);          // ti <= tj
+    if (MODE == PANEL_ONLY) { ti = bid; tj = bid; }      // workgroup j: tile column j of the pivot rows
+    else tri_decode(bid, tj, ti);     // ti <= tj
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
 
+    d4 c[2];
+    if (MODE == PANEL_STORED) {
+        // Un12_i and U12_j as the panel launch stored them; the trailing tile itself in flight meanwhile
+        double pa[8], pb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
+            pa[u] = Un[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
+            pb[u] = U[(int64_t)(o + y) * d + min(cj0 + x, d - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gm = ci0 + wr * 16 + 4 * v + fq, gn = cj0 + w2 * 32 + j * 16 + fr;
+                c[j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+            }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int y = wave + 8 * u, x = lane;
+            Pi[y * DL + x] = pa[u];
+            Pj[y * DL + x] = pb[u];
+        }
+        __syncthreads();
+    } else {
     // Pivot rows U12 = G A12: G is lower triangular, so the 16 rows of row tile rt (of 4) only need
     // the k-steps 0 .. 4 rt + 3.  The wavefronts with w2 = 0 take the row tiles 0 and 3, those with
     // w2 = 1 the tiles 1 and 2 (20 of 32 (k-step, tile) pairs each), for the 16 columns of slice wr.
@@ -1028,14 +1100,15 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     if (tid < NB) rs[tid] = rsv;
     __syncthreads();
     // the trailing tile itself (rows of slice wr, the 32 columns of half w2): in flight during the product
-    d4 c[2];
+    if (MODE == PANEL_FUSED) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int gm = ci0 + wr * 16 + 4 * v + fq, gn = cj0 + w2 * 32 + j * 16 + fr;
-            c[j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
-        }
+            for (int v = 0; v < 4; ++v) {
+                const int gm = ci0 + wr * 16 + 4 * v + fq, gn = cj0 + w2 * 32 + j * 16 + fr;
+                c[j][v] = A[(int64_t)min(gm, d - 1) * d + min(gn, d - 1)];
+            }
+    }
 
     d4 ui[2], uj[2];
 #pragma unroll
@@ -1058,12 +1131,14 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
             const double ujv = diag_tile ? uiv : uj[i][v];
             Pi[m * DL + n] = uiv * rs[m];
             Pj[m * DL + n] = ujv;
-            if (ti == 0 && cj0 + n < d) {
+            if ((ti == 0 || MODE == PANEL_ONLY) && cj0 + n < d) {
                 U[(int64_t)(o + m) * d + cj0 + n] = ujv;
                 Un[(int64_t)(o + m) * d + cj0 + n] = ujv * rs[m];
             }
         }
+    if (MODE == PANEL_ONLY) return;
     __syncthreads();
+    }
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         const double a = -Pi[(4 * ks + fq) * DL + wr * 16 + fr];
@@ -1125,12 +1200,19 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
             const bool mate = tiles > MATE_SLOT;
             const int epoch = mate ? ++c->mate_epoch : 0;
             int* mate_flag = c->flags.as<int>() + FLAG_WORD_MATE;
-            if (tiles <= DENSE_LAUNCH_TILES)
-                hipExtLaunchKernelGGL(elim_iter_kernel<2>, dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
+            if (tiles >= STORED_PANEL_TILES) {
+                // throughput-bound launch: the pivot rows once (T workgroups), then one product per trailing tile
+                hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, A, d, o, (const double*)Gb[it & 1],
+                                   (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag, mate_flag, 0);
+                hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED>), dim3(tiles + 1), dim3(NT), 0, s, nullptr, done, 0, A,
+                                      d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
+            } else if (tiles <= DENSE_LAUNCH_TILES)
+                hipExtLaunchKernelGGL((elim_iter_kernel<2, PANEL_FUSED>), dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
                                       rb[(it + 1) & 1], flag, mate_flag, epoch);
             else
-                hipExtLaunchKernelGGL(elim_iter_kernel<4>, dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
+                hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_FUSED>), dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
                                       rb[(it + 1) & 1], flag, mate_flag, epoch);
         }
