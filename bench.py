@@ -369,6 +369,16 @@ def main() -> int:
                     "slice_products": 19,
                     "fp64_equivalent_TFLOPs": round(flops_per_launch / (avg_ms * 1e-3) / 1e12, 2),
                     "fp64_equivalent_over_fp64_mfma_peak": round(flops_per_launch / (avg_ms * 1e-3) / 1e12 / PEAK_FP64_MFMA_TFLOPS, 3)}
+        # What the int8 matrix cores sustain on this machine, outside the timed region: the kernel's inner loop
+        # with its operands fixed in LDS (no fetches, no barriers).  The rate depends on the operand bytes -- the
+        # chip holds its power limit by slowing the matrix pipes -- so `frac` (against the published peak) has a
+        # ceiling well below 1 that no kernel change moves; `frac_of_sustained` is against the probe on operands
+        # distributed like this workload's digits.
+        probe = {name: round(ctx.probe_int8_matrix_rate(kind), 1)
+                 for name, kind in (("equal_bytes", fobq.PROBE_EQUAL_BYTES), ("random_bytes", fobq.PROBE_RANDOM_BYTES),
+                                    ("relu_normal_digits", fobq.PROBE_RELU_DIGITS))}
+        roofline["sustained_matrix_rate_TOPs"] = probe
+        roofline["frac_of_sustained"] = round(achieved / probe["relu_normal_digits"], 4)
     else:
         achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": "xxt_kernel", "bound": "mfma", "achieved": round(achieved, 3),

@@ -259,6 +259,23 @@ int fobq_sensitivity_static(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
  * leaves the context usable. */
 int fobq_debug_fail_after(fobq_ctx* ctx, int n);
 
+/* Measurement aid for the X X^T kernel of the int8-slice mode (no part of the method): the rate, in
+ * 1e12 int8 operations per second (multiply and add counted separately), at which this GPU's matrix
+ * cores run that kernel's inner loop -- the 19 digit products of a k-step on 32 x 32 x 32 int8
+ * matrix instructions, 8 wavefronts per compute unit -- when the operands sit in LDS and nothing is
+ * fetched or synchronised.  The rate depends on the operand bytes (the chip holds its power limit by
+ * slowing the matrix pipes), hence operand_kind: all bytes equal; uniformly random bytes; the digits
+ * of ReLU(N(0,1)) values as the workloads' activations have them (half of the values zero).
+ * Allocates a few KiB of device memory for the duration of the call, runs on the context's stream
+ * and waits for it.  FOBQ_EINVAL for an unknown kind or a NULL pointer, FOBQ_EHIP / FOBQ_ENOMEM
+ * from the runtime. */
+typedef enum {
+    FOBQ_PROBE_EQUAL_BYTES = 0,
+    FOBQ_PROBE_RANDOM_BYTES = 1,
+    FOBQ_PROBE_RELU_DIGITS = 2
+} fobq_probe_operands;
+int fobq_probe_int8_matrix_rate(fobq_ctx* ctx, int operand_kind, double* tera_ops_per_second);
+
 /* ---- stage timing ---------------------------------------------------------- */
 typedef enum {
     FOBQ_STAGE_XXT = 0,      /* the X X^T kernel launches only                              */

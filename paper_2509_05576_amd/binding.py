@@ -76,13 +76,14 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
     lib.fobq_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.fobq_probe_int8_matrix_rate.argtypes = [vp, i32, ctypes.POINTER(dbl)]
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
     lib.fobq_profile_reset.argtypes = [vp]
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_quantize_layers_batched", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -288,6 +289,16 @@ def fobq_workspace_bytes(ctx: int) -> int:
     return b.value
 
 
+PROBE_EQUAL_BYTES, PROBE_RANDOM_BYTES, PROBE_RELU_DIGITS = 0, 1, 2
+
+
+def fobq_probe_int8_matrix_rate(ctx: int, operand_kind: int) -> float:
+    """1e12 int8 operations per second of the X X^T kernel's inner loop with its operands fixed in LDS."""
+    r = ctypes.c_double(0.0)
+    _check(ctx, load_library().fobq_probe_int8_matrix_rate(ctypes.c_void_p(ctx), operand_kind, ctypes.byref(r)))
+    return r.value
+
+
 def fobq_debug_fail_after(ctx: int, n: int) -> None:
     _check(ctx, load_library().fobq_debug_fail_after(ctypes.c_void_p(ctx), n))
 
@@ -367,6 +378,9 @@ class Ctx:
 
     def workspace_bytes(self) -> int:
         return fobq_workspace_bytes(self.handle)
+
+    def probe_int8_matrix_rate(self, operand_kind: int) -> float:
+        return fobq_probe_int8_matrix_rate(self.handle, operand_kind)
 
     def stage_ms(self):
         return {name: fobq_profile_get(self.handle, i) for i, name in enumerate(STAGES)}

@@ -282,10 +282,8 @@ __global__ __launch_bounds__(256) void slice_conv_kernel(const float* __restrict
 // diagonal; persistent workgroup vb takes items [vb * per_wg, (vb + 1) * per_wg).  The part of a tile done by
 // one workgroup is a piece; piece p of a tile goes to slab p of Hpart, and one workgroup owns a given
 // (tile, piece), so the fp64 sums do not depend on the order in which workgroups finish.
-// A workgroup is 4 wavefronts (one per SIMD), wavefront (wm, wn) owns 64 x 64 of the tile = 2 x 2 MFMA tiles
-// of 32 x 32 for each of the 6 antidiagonals: 384 accumulator registers per lane, which is why exactly one
-// wavefront runs per SIMD and why the operands are copied global -> LDS directly (global_load_lds_dwordx4:
-// no staging registers); the copy of k-step q + 1 runs while the 76 MFMAs of k-step q issue.
+// A workgroup is 8 wavefronts (see the kernel); the operands are copied global -> LDS directly
+// (global_load_lds_dwordx4: no staging registers), the copy of k-step q + 1 running while the MFMAs of k-step q issue.
 // 16 bytes per lane from global memory straight into LDS: lane l's bytes land at dst_block + OFF + 16 l, read
 // from src_lane + OFF (the instruction's immediate offset applies to both addresses).
 template <int OFF>

@@ -942,3 +942,14 @@ SWEEP_CASES = [
 def test_config_c4_sweep_layers(fobq, ctx, model, layer, chunk):
     spec = next(l for l in workloads.sweep_layers(model) if l.name == layer)
     _run_config(fobq, ctx, layer, chunk=chunk, spec=spec)
+
+
+def test_int8_matrix_rate_probe(fobq, ctx):
+    """The measurement aid returns a rate between zero and the published int8 peak for every operand kind,
+    the loop on equal bytes is not slower than on random ones, and an unknown kind is an error."""
+    _say("int8 matrix rate probe")
+    rates = [ctx.probe_int8_matrix_rate(k) for k in (fobq.PROBE_EQUAL_BYTES, fobq.PROBE_RANDOM_BYTES, fobq.PROBE_RELU_DIGITS)]
+    assert all(100.0 < r < 5200.0 for r in rates), rates
+    assert rates[0] >= 0.95 * rates[1], rates
+    with pytest.raises(fobq.FobqError):
+        ctx.probe_int8_matrix_rate(7)
