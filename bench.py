@@ -448,6 +448,22 @@ def main() -> int:
                           "obq_over_fastobq_time": round(obq_s * spec.d_row / nr / cpu_s, 1),
                           "obq_over_fastobq_gpu_time": round(obq_s * spec.d_row / nr / (ms_per_step * 1e-3), 1),
                           "fastobq_over_obq_loss_same_rows": round(fast_loss / float(ob.lossrow[:nr].sum()), 4)}
+            if spec.d_col <= 4096:
+                # the same baseline on the GPU (fobq_obq_rows: one workgroup per row), same rows, same Hinv
+                Hinv_dev = torch.from_numpy(ref.Hinv).cuda()
+                ctx.obq_rows(Wd, Hinv_dev, bits=spec.bits, group=spec.group, rows=(0, 1))
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                g_codes, _, g_order, g_loss = ctx.obq_rows(Wd, Hinv_dev, bits=spec.bits, group=spec.group, rows=(0, nr))
+                torch.cuda.synchronize()
+                g_s = time.perf_counter() - t
+                same = (g_order[:nr].cpu().numpy() == ob.order[:nr]).all(axis=1)
+                cpu["obq"]["gpu"] = {"rows": nr, "seconds": round(g_s, 4),
+                                     "rows_with_the_oracles_order": int(same.sum()),
+                                     "codes_differ_vs_oracle": float((g_codes[:nr].cpu().numpy().astype(np.int64) != ob.codes[:nr]).mean()),
+                                     "loss_rel_diff": float(abs(float(g_loss[:nr].sum()) - float(ob.lossrow[:nr].sum())) / float(ob.lossrow[:nr].sum())),
+                                     "note": "one workgroup per row, rows side by side; a row's d x d inverse sits in LDS up to d = 128, "
+                                             "in device memory beyond (then the kernel streams d^3 x 16 bytes per row)"}
 
     line = {
         "metric": "weights quantized per second, whole layer path"

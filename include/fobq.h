@@ -253,6 +253,25 @@ int fobq_sensitivity(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col
 int fobq_sensitivity_static(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col,
                             const double* Hinv, const fobq_opts* opts, double* S, int32_t* perm);
 
+/* The baseline the method replaces (Section 4.2, first paragraphs; Eq. 9 - 12 per row): OBQ
+ * quantizes every row on its own, with its own copy of the inverse Hessian and its own greedy
+ * order -- at every step the not-yet-quantized weight of the row with the smallest loss term
+ * (quant(w_p) - w_p)^2 / (2 [Hinv]_pp) (Eq. 10; the first in index order among equal ones) is
+ * quantized, the rest of the row compensated (Eq. 9 / 11) and index p eliminated from the row's
+ * inverse (Eq. 12).  Same frozen min-max grid as fobq_quantize_layer (opts: bits and group are
+ * used, the order fields are ignored).  Cost O(d_col^3) per row: a measurement baseline for small
+ * layers, d_col <= 4096 (FOBQ_EINVAL beyond).
+ * W: device fp32 d_row x d_col.  Hinv: device fp64 d_col x d_col, full symmetric (what
+ * fobq_spd_inverse returns for the damped Hessian); not modified.  Rows row_begin .. row_end - 1
+ * are processed (rows do not interact); of the outputs only those rows are written:
+ * codes (uint8, d_row x d_col), Q (fp32, d_row x d_col), order (int32, d_row x d_col: per row the
+ * index processed at each step; may be NULL), lossrow (fp64, d_row: the row's summed loss terms).
+ * All device pointers.  Scratch (the rows' running inverses beyond d_col = 128, at most 4 GiB at a
+ * time) belongs to the context.  Synchronises; FOBQ_ENOTPD if a row meets a pivot <= 0. */
+int fobq_obq_rows(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv,
+                  const fobq_opts* opts, int64_t row_begin, int64_t row_end, uint8_t* codes, float* Q,
+                  int32_t* order, double* lossrow);
+
 /* Test hook for the error paths: the n-th internal status check from now on this context (n >= 1;
  * checks follow every HIP call and launch) reports FOBQ_EHIP although nothing failed; 0 disarms.
  * A call that fails this way with work already enqueued waits for that work before it returns and

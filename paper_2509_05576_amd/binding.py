@@ -76,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
     lib.fobq_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.fobq_obq_rows.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), i64, i64, vp, vp, vp, vp]
     lib.fobq_probe_int8_matrix_rate.argtypes = [vp, i32, ctypes.POINTER(dbl)]
     lib.fobq_profile_enable.argtypes = [vp, i32]
     lib.fobq_profile_get.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
@@ -83,7 +84,7 @@ def load_library() -> ctypes.CDLL:
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_quantize_layers_batched", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate", "fobq_obq_rows",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -283,6 +284,26 @@ def fobq_sensitivity_static(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bi
     return _sensitivity(load_library().fobq_sensitivity_static, ctx, W, Hinv, bits, group, order, perm_in, S, perm)
 
 
+def fobq_obq_rows(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 4, group: int = 0,
+                  rows: Optional[tuple] = None):
+    """The per-row baseline (own inverse and own greedy order per row) on rows[0] .. rows[1] - 1 (default: all).
+    Returns codes (uint8), Q (fp32), order (int32), lossrow (fp64); only the processed rows are written."""
+    r, d = W.shape
+    lo, hi = (0, r) if rows is None else rows
+    codes = torch.zeros((r, d), dtype=torch.uint8, device=W.device)
+    Q = torch.zeros((r, d), dtype=torch.float32, device=W.device)
+    order = torch.zeros((r, d), dtype=torch.int32, device=W.device)
+    lossrow = torch.zeros((r,), dtype=torch.float64, device=W.device)
+    op = _opts(bits, group, 0.0, 0.0, ORDER_NATURAL, 0, -1, None)
+    rc = load_library().fobq_obq_rows(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(W, torch.float32, "W")), r, d,
+                                      ctypes.c_void_p(_ptr(Hinv, torch.float64, "Hinv")), ctypes.byref(op), lo, hi,
+                                      ctypes.c_void_p(_ptr(codes, torch.uint8, "codes")), ctypes.c_void_p(_ptr(Q, torch.float32, "Q")),
+                                      ctypes.c_void_p(_ptr(order, torch.int32, "order")),
+                                      ctypes.c_void_p(_ptr(lossrow, torch.float64, "lossrow")))
+    _check(ctx, rc)
+    return codes, Q, order, lossrow
+
+
 def fobq_workspace_bytes(ctx: int) -> int:
     b = ctypes.c_int64(0)
     _check(ctx, load_library().fobq_workspace_bytes(ctypes.c_void_p(ctx), ctypes.byref(b)))
@@ -378,6 +399,9 @@ class Ctx:
 
     def workspace_bytes(self) -> int:
         return fobq_workspace_bytes(self.handle)
+
+    def obq_rows(self, W, Hinv, **kw):
+        return fobq_obq_rows(self.handle, W, Hinv, **kw)
 
     def probe_int8_matrix_rate(self, operand_kind: int) -> float:
         return fobq_probe_int8_matrix_rate(self.handle, operand_kind)

@@ -357,7 +357,7 @@ static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
 {
     return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
             &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax, &ctx->batch_pool, &ctx->batch_desc};
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax, &ctx->batch_pool, &ctx->batch_desc, &ctx->obq};
 }
 
 extern "C" {
@@ -707,6 +707,49 @@ int fobq_sensitivity_static(fobq_ctx* ctx, const float* W, int64_t d_row, int64_
                       reinterpret_cast<int*>(base + STATIC_OFF_PERM), reinterpret_cast<int*>(base + STATIC_OFF_INVPERM),
                       reinterpret_cast<int*>(base + STATIC_OFF_FLAGS)};
     rc = run_sensitivity(ctx, W, (int)d_row, (int)d_col, Hinv, opts, b, S, perm);
+    return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
+}
+
+int fobq_obq_rows(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, const double* Hinv, const fobq_opts* opts,
+                  int64_t row_begin, int64_t row_end, uint8_t* codes, float* Q, int32_t* order, double* lossrow)
+{
+    if (!ctx) return FOBQ_EINVAL;
+    if (ctx->pending) return set_err(ctx, FOBQ_ESTATE, "an enqueued layer is waiting for fobq_finish");
+    if (!W || !Hinv || !codes || !Q || !lossrow) return set_err(ctx, FOBQ_EINVAL, "W, Hinv, codes, Q or lossrow is NULL");
+    int rc = check_shape(ctx, d_row, d_col);
+    if (rc) return rc;
+    rc = check_opts(ctx, opts, d_col);
+    if (rc) return rc;
+    if (d_col > OBQ_MAX_D)
+        return set_err(ctx, FOBQ_EINVAL, "fobq_obq_rows is a baseline for small layers: d_col <= %d (got %lld)", OBQ_MAX_D, (long long)d_col);
+    if (row_begin < 0 || row_end > d_row || row_begin > row_end)
+        return set_err(ctx, FOBQ_EINVAL, "rows %lld..%lld are not inside 0..%lld", (long long)row_begin, (long long)row_end, (long long)d_row);
+    if (row_begin == row_end) return FOBQ_OK;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
+    const int R = (int)d_row, d = (int)d_col, G = opts->group > 0 ? d / opts->group : 1;
+    // rows per launch: at most 4 GiB of running inverses at a time
+    const size_t per_row = obq_scratch_per_row(d);
+    const int64_t rows_total = row_end - row_begin;
+    int64_t batch = per_row ? (int64_t)(((size_t)4 << 30) / per_row) : rows_total;
+    batch = batch < 1 ? 1 : (batch > rows_total ? rows_total : batch);
+    FOBQ_TRY(ctx->scale.ensure((size_t)R * G * sizeof(double)), "workspace scale");
+    FOBQ_TRY(ctx->zero.ensure((size_t)R * G * sizeof(double)), "workspace zero");
+    FOBQ_TRY(ctx->obq.ensure(per_row ? per_row * (size_t)batch : 256), "workspace of the per-row inverses");
+    rc = ensure_flags(ctx);
+    if (rc) return rc;
+    hipStream_t s = ctx->stream;
+    int* flags = ctx->flags.as<int>();
+    rc = [&]() -> int {
+        FOBQ_TRY(launch_clear_words(s, flags, FLAG_COUNT, nullptr, 0), "clear flags");
+        FOBQ_TRY(launch_grid(s, W, R, d, opts->bits, opts->group, ctx->scale.as<double>(), ctx->zero.as<double>(), nullptr, nullptr), "grid");
+        for (int64_t r0 = row_begin; r0 < row_end; r0 += batch) {
+            const int rows = (int)(row_end - r0 < batch ? row_end - r0 : batch);
+            FOBQ_TRY(launch_obq_rows(s, W, d, opts->bits, opts->group, Hinv, ctx->scale.as<double>(), ctx->zero.as<double>(), (int)r0,
+                                     rows, ctx->obq.as<double>(), codes, Q, order, lossrow, flags + FLAG_NOTPD_HINV), "per-row baseline");
+        }
+        return read_flags(ctx);
+    }();
     return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
 }
 

@@ -9,6 +9,15 @@
 
 namespace fobq {
 
+// code = clamp(rint(w / scale) + zero, 0, maxq), rint = round half to even, all fp64 (Section 3: the fixed grid)
+__device__ __forceinline__ double grid_code(double w, double scale, double zero, double maxq)
+{
+    double c = rint(w / scale) + zero;
+    c = c < 0.0 ? 0.0 : c;
+    c = c > maxq ? maxq : c;
+    return c;
+}
+
 // ---------------------------------------------------------------------------
 // Device buffer owned by the context; grows, never shrinks.
 struct DevBuf {
@@ -103,6 +112,7 @@ struct fobq_ctx {
     fobq::DevBuf Hd, Linv, T, Hinv, A, U, Un;
     fobq::DevBuf Dblk;      // diagonal-block scratch: 2 x (64 x 64) L11^-1, 2 x (64 x 64) G, 2 x 64 reciprocal pivots
     fobq::DevBuf scal;      // a few fp64 scalars (lambda, loss)
+    fobq::DevBuf obq;       // running inverses of the per-row baseline (fobq_obq_rows), rows x d x d fp64
     fobq::DevBuf flags;     // FLAG_WORDS int32: status flags written by kernels (cleared per call), then words
                             // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
     int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
@@ -215,6 +225,13 @@ hipError_t launch_batch_grid(hipStream_t s, const BatchLayer* layers, int n, int
 hipError_t launch_batch_sens_partial(hipStream_t s, const BatchLayer* layers, int n, int max_chunks);
 hipError_t launch_batch_columns(hipStream_t s, const BatchLayer* layers, int n, int max_rows);
 hipError_t launch_batch_loss(hipStream_t s, const BatchLayer* layers, int n);
+
+// per-row baseline (obq.hip)
+constexpr int OBQ_MAX_D = 4096;        // columns: a row's weights, pivot row and flags live in LDS
+size_t obq_scratch_per_row(int d);
+hipError_t launch_obq_rows(hipStream_t s, const float* W, int d, int bits, int group, const double* Hinv0, const double* scale,
+                           const double* zero, int row_begin, int rows, double* Hscratch, uint8_t* codes, float* Q, int* order,
+                           double* lossrow, int* flag);
 
 // quant.hip
 hipError_t launch_grid(hipStream_t s, const float* W, int R, int d, int bits, int group,

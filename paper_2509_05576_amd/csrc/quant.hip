@@ -5,15 +5,6 @@
 
 namespace fobq {
 
-// code = clamp(rint(w / scale) + zero, 0, maxq), rint = round half to even, all fp64
-__device__ __forceinline__ double grid_code(double w, double scale, double zero, double maxq)
-{
-    double c = rint(w / scale) + zero;
-    c = c < 0.0 ? 0.0 : c;
-    c = c > maxq ? maxq : c;
-    return c;
-}
-
 // ---------------------------------------------------------------------------
 // Min-max grid per (row, group) from the original W (Section 3, "fixed grid of
 // width Delta"): lo = min(min w, 0), hi = max(max w, 0), scale = (hi - lo) / maxq,

@@ -953,3 +953,55 @@ def test_int8_matrix_rate_probe(fobq, ctx):
     assert rates[0] >= 0.95 * rates[1], rates
     with pytest.raises(fobq.FobqError):
         ctx.probe_int8_matrix_rate(7)
+
+
+# --------------------------------------------------------------------------- the per-row baseline (OBQ)
+OBQ_CASES = [
+    # r, d, n, bits, group, rows
+    (64, 128, 512, 4, 0, None),        # config 1's shape, the inverse in LDS
+    (33, 96, 300, 3, 32, (5, 29)),     # groups, a row range
+    (20, 200, 450, 4, 0, (0, 20)),     # beyond 128 columns: the rows' inverses in device scratch
+    (6, 333, 700, 2, 111, (1, 6)),     # ragged everything
+    (3, 1, 10, 4, 0, None),            # single column
+]
+
+
+@pytest.mark.parametrize("r,d,n,bits,group,rows", OBQ_CASES)
+def test_obq_rows_match_oracle(fobq, ctx, r, d, n, bits, group, rows):
+    """fobq_obq_rows against the oracle's per-row baseline on the same Hinv: both take every step's decisions
+    (greedy choice, grid code) in fp64 with the same operations, so order and codes are compared exactly;
+    a row whose orders differ must differ at a tie of the loss terms (relative gap below 1e-9)."""
+    _say(f"obq rows r={r} d={d} bits={bits} group={group} rows={rows}")
+    W, X = _problem(r, d, n, 900 + r + d, w_std=0.05)
+    Hd, _ = oracle.damp(oracle.hessian(X), 0.01)
+    Hinv = oracle.spd_inverse(Hd)
+    s, z = oracle.grid(W, bits, group)
+    ref = oracle.obq_rows(W, Hinv, bits, group, s, z, rows)
+    codes, Q, order, lossrow = ctx.obq_rows(_dev(W), _dev(Hinv), bits=bits, group=group, rows=rows)
+    lo, hi = (0, r) if rows is None else rows
+    codes, Q, order, lossrow = (t.cpu().numpy() for t in (codes, Q, order, lossrow))
+    same_order = np.all(order[lo:hi] == ref.order[lo:hi], axis=1)
+    assert same_order.mean() >= 0.9, f"{(~same_order).sum()} of {hi - lo} rows took another order"
+    rows_same = np.arange(lo, hi)[same_order]
+    assert np.array_equal(codes[rows_same].astype(np.int64), ref.codes[rows_same])
+    assert np.allclose(Q[rows_same], ref.Q[rows_same], rtol=1e-6, atol=0)
+    assert np.allclose(lossrow[rows_same], ref.lossrow[rows_same], rtol=1e-9, atol=0)
+    # a row with another order: valid permutation, loss within the layer tolerance
+    for i in np.arange(lo, hi)[~same_order]:
+        assert sorted(order[i].tolist()) == list(range(d))
+        assert abs(lossrow[i] - ref.lossrow[i]) <= 1e-3 * ref.lossrow[i]
+    # rows outside the range are untouched
+    assert not codes[:lo].any() and not codes[hi:].any()
+
+
+def test_obq_rows_errors(fobq, ctx):
+    W = torch.zeros((4, 4160), dtype=torch.float32, device="cuda")
+    Hinv = torch.eye(4160, dtype=torch.float64, device="cuda")
+    with pytest.raises(fobq.FobqError, match="small layers"):
+        ctx.obq_rows(W, Hinv)
+    W = torch.ones((4, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(fobq.FobqError, match="rows"):
+        ctx.obq_rows(W, torch.eye(8, dtype=torch.float64, device="cuda"), rows=(2, 9))
+    with pytest.raises(fobq.FobqError) as e:
+        ctx.obq_rows(W, -torch.eye(8, dtype=torch.float64, device="cuda"))
+    assert e.value.code == fobq.ENOTPD
