@@ -23,6 +23,8 @@
 // without passing through registers).
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "fobq_internal.h"
 
 namespace fobq {
@@ -393,32 +395,45 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
             issue(0, kstep_at(ib));
             __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): the copies have landed
             __syncthreads();
-            int buf = 0;
-            for (int64_t it = ib; it < ie; ++it) {
-                if (it + 1 < ie) issue(buf ^ 1, kstep_at(it + 1));
-                i32x4 fb[NS];
+            // On a diagonal tile only the MFMA tiles on and below the diagonal are formed (10 of the workgroup's 16:
+            // row block 2 wm + i against column block wn needs wn <= 2 wm + i); the wavefronts with less to do still
+            // copy and meet the others.  The matrix pipes run against a power limit, so what is not multiplied is
+            // time for the rest of the chip even where this workgroup's own k-step is no shorter.
+            auto ksteps_loop = [&](auto first_block, auto second_block) {
+                constexpr bool DO0 = decltype(first_block)::value, DO1 = decltype(second_block)::value;
+                int buf = 0;
+                for (int64_t it = ib; it < ie; ++it) {
+                    if (it + 1 < ie) issue(buf ^ 1, kstep_at(it + 1));
+                    if (DO1) {
+                        i32x4 fb[NS];
 #pragma unroll
-                for (int t = 0; t < NS; ++t)
-                    fb[t] = *reinterpret_cast<const i32x4*>(&Bs[buf][wn][t][lane * 16]);
+                        for (int t = 0; t < NS; ++t)
+                            fb[t] = *reinterpret_cast<const i32x4*>(&Bs[buf][wn][t][lane * 16]);
 #pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    i32x4 fa[2];
+                        for (int s = 0; s < NS; ++s) {
+                            i32x4 fa[2];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        fa[i] = *reinterpret_cast<const i32x4*>(&As[buf][wm * 2 + i][s][lane * 16]);
+                            for (int i = DO0 ? 0 : 1; i < 2; ++i)
+                                fa[i] = *reinterpret_cast<const i32x4*>(&As[buf][wm * 2 + i][s][lane * 16]);
 #pragma unroll
-                    for (int t = 0; t < NS; ++t) {
-                        if (s + t < NM) {
+                            for (int t = 0; t < NS; ++t) {
+                                if (s + t < NM) {
 #pragma unroll
-                            for (int i = 0; i < 2; ++i)
-                                acc[s + t][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[t], acc[s + t][i], 0, 0, 0);
+                                    for (int i = DO0 ? 0 : 1; i < 2; ++i)
+                                        acc[s + t][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[t], acc[s + t][i], 0, 0, 0);
+                                }
+                            }
                         }
                     }
+                    __builtin_amdgcn_s_waitcnt(0);
+                    __syncthreads();
+                    buf ^= 1;
                 }
-                __builtin_amdgcn_s_waitcnt(0);
-                __syncthreads();
-                buf ^= 1;
-            }
+            };
+            const bool need0 = I != J || wn <= 2 * wm, need1 = I != J || wn <= 2 * wm + 1;
+            if (need0) ksteps_loop(std::true_type(), std::true_type());
+            else if (need1) ksteps_loop(std::false_type(), std::true_type());
+            else ksteps_loop(std::false_type(), std::false_type());
 
             // fold: sum_m acc_m 256^(8 - m), times 2^-(sh_row + sh_col), added into the fp64 slab (lower triangle)
             const int col = j0 + wn * 32 + (lane & 31);
