@@ -354,6 +354,22 @@ def test_quantize_layer_matches_oracle(fobq, ctx, r, d, n, bits, group, order, b
     _compare_layer(out, ref, W, bits)
 
 
+# Layers whose first panels have 800 or more trailing tiles: the panel is stored by a launch of its own and the
+# trailing tiles take one product each.  3001 columns: the elimination's launches are of that kind, the Cholesky's
+# carry the inverse and are not; 4200 columns (beyond 4096: separate inverse): both.  Ragged last blocks.
+@pytest.mark.parametrize("r,d,n,int8", [(16, 3001, 3300, False), (12, 4200, 4500, True)])
+def test_stored_panel_layers_match_oracle(fobq, ctx, r, d, n, int8):
+    _say(f"stored-panel layer r={r} d={d} n={n} int8={int8}")
+    W, X = _problem(r, d, n, 7000 + d, w_std=0.02)
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES if int8 else fobq.HESSIAN_FP64)
+    ctx.hessian(_dev(X))
+    out = ctx.quantize_layer(_dev(W), bits=4, group=0, damp=0.01)
+    _say("stored-panel layer: oracle")
+    ref = oracle.quantize_layer(W, X=X, bits=4, group=0)
+    ref = _oracle_with_gpu_perm(W, ref.H, out.perm.cpu().numpy(), ref, bits=4, group=0)
+    _compare_layer(out, ref, W, 4)
+
+
 def test_random_small_layers_match_oracle(fobq, ctx):
     # seeded draw of shapes and options: block counts from 1 to 10 with ragged tails, every bit width,
     # groups, the blocked, narrow-block and unblocked column loops
