@@ -259,7 +259,7 @@ def main() -> int:
                     help="whole-model sweeps: layers in flight at once (one context and stream each)")
     ap.add_argument("--hessian", choices=("i8", "f64"), default="i8",
                     help="how X X^T is formed: i8 = exact int8 slice products on the matrix cores where the mode "
-                         "applies (d_col >= 384, n >= 2048 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
+                         "applies (d_col >= 384, n >= 512 per call; H within 3e-13 of the fp64 sum), f64 = fp64 "
                          "matrix instructions")
     ap.add_argument("--no-batch", action="store_true",
                     help="whole-model sweeps: quantize the layers of up to 256 columns one by one instead of all of "
@@ -357,7 +357,7 @@ def main() -> int:
     n_per_launch = spec.n / launches_per_step
     flops_per_launch = spec.d_col * (spec.d_col + 1) * n_per_launch     # one triangle: d(d+1)/2 entries x 2N flop
     avg_ms = xxt_ms / xxt_launches
-    int8 = args.hessian == "i8" and spec.d_col >= 384 and n_per_launch >= 2048
+    int8 = stages["slice"][1] > 0          # the digit kernels ran: the library took the int8-slice form for this shape
     if int8:
         # integer-slice formulation: 19 int8 slice products per entry of the triangle, against the dense int8 peak
         ops_per_launch = 19.0 * flops_per_launch

@@ -128,7 +128,7 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col);
  *                             exactly on the int8 matrix cores (int32 sums, folded into fp64), the rest
  *                             dropped.  H differs from the fp64 result by about 3e-13 of its largest
  *                             entry; several times faster on large layers.  Applies to calls with
- *                             d_col >= 384 and n >= 2048 (for
+ *                             d_col >= 384 and n >= 512 (for
  *                             fobq_hessian_accumulate_conv: output pixels of the call); other calls use the
  *                             fp64 form.  An Inf or NaN in X makes
  *                             H NaN throughout (the layer then fails with ENOTPD).  Scratch: 1.25 bytes

@@ -131,7 +131,7 @@ constexpr int64_t MAX_DCOL = 32768;
 constexpr int FUSED_INVERSE_MAX_D = 4096;
 constexpr int64_t MAX_DROW = 65535;
 constexpr int I8_MIN_D = 384;     // below: too few 128-wide tiles for the digit traffic to pay (measured on 256- and 288-column layers)
-constexpr int64_t I8_MIN_N = 2048;
+constexpr int64_t I8_MIN_N = 512;
 
 enum { FLAG_NOTPD_H = 0, FLAG_NOTPD_HINV = 1, FLAG_BADPERM = 2, FLAG_COUNT = 4 };
 
