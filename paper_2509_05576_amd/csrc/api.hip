@@ -750,7 +750,8 @@ int fobq_obq_rows(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, c
         }
         return read_flags(ctx);
     }();
-    return (rc && rc != FOBQ_EINVAL && rc != FOBQ_ENOTPD) ? drain_after_failure(ctx, rc) : rc;
+    if (rc == FOBQ_ENOTPD) return set_err(ctx, FOBQ_ENOTPD, "a row's own inverse Hessian met a pivot <= 0 (is Hinv positive definite?)");
+    return (rc && rc != FOBQ_EINVAL) ? drain_after_failure(ctx, rc) : rc;
 }
 
 int fobq_debug_fail_after(fobq_ctx* ctx, int n)

@@ -38,7 +38,7 @@ constexpr int YBITS = 8 * NS - 2;   // |Y| <= 2^YBITS
 constexpr int IK = 32;              // calibration columns per k-step (one MFMA)
 constexpr int IT = 128;             // tile edge
 constexpr int I8_FOLD_STEPS = 512;  // k-steps between folds (16384 columns)
-constexpr int I8_WGS = 256;         // persistent workgroups: one per compute unit (4 wavefronts, one per SIMD)
+constexpr int I8_WGS = 256;         // persistent workgroups: one per compute unit (8 wavefronts, two per SIMD)
 
 // Digit storage.  For k-step q (32 columns), block of 32 rows b, digit s: one 1 KiB block of 64 slots of
 // 16 bytes; slot l holds row 32 b + (l % 32), columns 32 q + 16 (l / 32) .. + 15.  That is the order in which
