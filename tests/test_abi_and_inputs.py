@@ -120,3 +120,14 @@ def test_config_shapes_and_model_totals():
     assert len(r50) == 54 and len(y5) == 60
     assert abs(sum(l.weights for l in r50) / 1e6 - 25.50) < 0.05
     assert abs(sum(l.weights for l in y5) / 1e6 - 7.22) < 0.05
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before it touches the GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr
+    assert res.stdout.strip() == ""
