@@ -380,6 +380,8 @@ int fobq_create(fobq_ctx** out, int device, void* hip_stream)
         rc = g.ok ? FOBQ_OK : FOBQ_EHIP;
         if (!rc) rc = ensure_host_flags(c);
         if (!rc) rc = static_scratch_lookup(c, device);
+        int cus = 0;
+        if (!rc && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->cus = cus;
     }
     if (rc) {
         if (c->h_flags) (void)hipHostFree(c->h_flags);

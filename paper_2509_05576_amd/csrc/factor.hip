@@ -41,8 +41,9 @@ constexpr int DENSE_LAUNCH_TILES = 300;
 // launches with at least this many trailing tiles are bound by tile throughput: the panel is stored by a launch of
 // its own and every tile does one product instead of three (see chol_iter_kernel)
 constexpr int STORED_PANEL_TILES = 800;
-constexpr int MATE_SLOT = 256, MATE_MAX_NAPS = 64;
-static_assert(MATE_SLOT < DENSE_LAUNCH_TILES, "the idle workgroup must exist in every dense launch");
+// The workgroup that holds the place beside workgroup 0 (see chol_iter_kernel) has the index `mate_slot` = the number
+// of compute units of the device (the first that many workgroups of a launch go to distinct compute units).
+constexpr int MATE_MAX_NAPS = 64;
 constexpr int DL = 66;    // LDS row stride (doubles): conflict-free 8-byte MFMA fragment reads per half-wave
 constexpr int CB0 = 48, CB_LEN = CB0 + 16 * 16 + 48;   // sweep column buffer: see chol_block
 constexpr int SWEEP_LDS = NB + CB_LEN + 16 * DL;   // doubles of LDS that chol_block / elim_block need besides the two tiles
@@ -566,7 +567,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
                                                        double* __restrict__ Linv, double* __restrict__ Dinv_next,
                                                        int* __restrict__ flag, int ntrail, int ninv,
                                                        double* __restrict__ Sacc, double* __restrict__ Hinv,
-                                                       int* __restrict__ mate_flag, int epoch)
+                                                       int* __restrict__ mate_flag, int epoch, int mate_slot)
 {
     // sweep scratch first (its broadcast reads then have constant addresses below 64 KB, i.e. no address
     // register), then two tiles: 2 workgroups per compute unit
@@ -574,11 +575,11 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     double* tiles = lds + SWEEP_LDS;
     // Two workgroups fit a compute unit in this variant, and the one that lands beside workgroup 0 takes
     // matrix-pipe and LDS time from the launch's critical path.  The first 256 workgroups go to distinct
-    // compute units, so that neighbour is workgroup MATE_SLOT (measured: leaving that index idle is the only
+    // compute units, so that neighbour is workgroup `mate_slot` (measured: leaving that index idle is the only
     // one that shortens the launch).  It is not a tile: one of its wavefronts sleeps, holding the place,
     // until workgroup 0 says that it is done (mate_flag reaches this launch's epoch) or MATE_MAX_NAPS naps of
     // about 0.4 us have passed -- a bounded wait, it ends whatever workgroup 0 does.
-    if (WPS == 4 && (int)blockIdx.x == MATE_SLOT) {
+    if (WPS == 4 && (int)blockIdx.x == mate_slot) {
         if (threadIdx.x >= 64) return;
         for (int i = 0; i < MATE_MAX_NAPS; ++i) {
             if (__hip_atomic_load(mate_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch >= 0) break;
@@ -586,7 +587,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
         }
         return;
     }
-    const int bid = (int)blockIdx.x - ((WPS == 4 && (int)blockIdx.x > MATE_SLOT) ? 1 : 0);
+    const int bid = (int)blockIdx.x - ((WPS == 4 && (int)blockIdx.x > mate_slot) ? 1 : 0);
     if (MODE == PANEL_FUSED && bid >= ntrail + ninv) {
         // tiles of the Hinv role in this launch; a workgroup past them has nothing to do
         const int nlau = Sacc ? (o / NB) * (o / NB + 1) / 2 : 0;
@@ -758,16 +759,17 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         if (!Sacc && L && ntrail >= STORED_PANEL_TILES) {
             // throughput-bound launch: the panel once (T workgroups), then one product per trailing tile
             hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0);
+                               Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0, c->cus);
             hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED>), dim3(ntrail + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L,
-                               Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch);
+                               Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
         } else if (tiles <= DENSE_LAUNCH_TILES)
             hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_FUSED>), dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, 0);
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, 0, c->cus);
         else
-            // one workgroup more than tiles: see MATE_SLOT (tiles > DENSE_LAUNCH_TILES > MATE_SLOT)
+            // one workgroup more than tiles: the place holder (when the device has more compute units than the launch has
+            // tiles, the extra workgroup has no tile and returns)
             hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_FUSED>), dim3(tiles + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, ++c->mate_epoch);
+                               Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
     }
     if (Sacc && it > 0) {
         // last block row of L^-1: Linv[last][0 : last] = -Linv[last][last] S[last][0 : last]
@@ -1016,12 +1018,12 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
                                                        const double* __restrict__ G, const double* __restrict__ rinv,
                                                        double* __restrict__ U, double* __restrict__ Un,
                                                        double* __restrict__ G_next, double* __restrict__ rinv_next,
-                                                       int* __restrict__ flag, int* __restrict__ mate_flag, int epoch)
+                                                       int* __restrict__ flag, int* __restrict__ mate_flag, int epoch, int mate_slot)
 {
     __shared__ double lds[SWEEP_LDS + 2 * NB * DL];   // sweep scratch, two tiles: 2 workgroups per compute unit
-    // epoch != 0: the launch has one workgroup more than tiles, and workgroup MATE_SLOT only holds the place
+    // epoch != 0: the launch has one workgroup more than tiles, and workgroup `mate_slot` only holds the place
     // beside workgroup 0 (see chol_iter_kernel; both variants of this kernel fit two workgroups per compute unit)
-    if (epoch != 0 && (int)blockIdx.x == MATE_SLOT) {
+    if (epoch != 0 && (int)blockIdx.x == mate_slot) {
         if (threadIdx.x >= 64) return;
         for (int i = 0; i < MATE_MAX_NAPS; ++i) {
             if (__hip_atomic_load(mate_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch >= 0) break;
@@ -1029,7 +1031,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
         }
         return;
     }
-    const int bid = (int)blockIdx.x - ((epoch != 0 && (int)blockIdx.x > MATE_SLOT) ? 1 : 0);
+    const int bid = (int)blockIdx.x - ((epoch != 0 && (int)blockIdx.x > mate_slot) ? 1 : 0);
     double* Pi = lds + SWEEP_LDS;
     double* Pj = Pi + NB * DL;
     double* rs = lds;
@@ -1196,25 +1198,25 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
             // hipEventRecord between two dependent launches costs about 4 us of bubble
             hipEvent_t done = (rows_ready && it < (int)rows_ready->size()) ? (*rows_ready)[it] : nullptr;
             const int tiles = T * (T + 1) / 2;
-            // a launch with a workgroup MATE_SLOT gets one more, which holds the place beside workgroup 0
-            const bool mate = tiles > MATE_SLOT;
+            // a launch with a workgroup of index `cus` gets one more, which holds the place beside workgroup 0
+            const bool mate = tiles > c->cus;
             const int epoch = mate ? ++c->mate_epoch : 0;
             int* mate_flag = c->flags.as<int>() + FLAG_WORD_MATE;
             if (tiles >= STORED_PANEL_TILES) {
                 // throughput-bound launch: the pivot rows once (T workgroups), then one product per trailing tile
                 hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, A, d, o, (const double*)Gb[it & 1],
-                                   (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag, mate_flag, 0);
+                                   (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
                 hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED>), dim3(tiles + 1), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
             } else if (tiles <= DENSE_LAUNCH_TILES)
                 hipExtLaunchKernelGGL((elim_iter_kernel<2, PANEL_FUSED>), dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
             else
                 hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_FUSED>), dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag, mate_flag, epoch);
+                                      rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
         }
         ready(it);              // last block: only a diagonal part
         return hipGetLastError();

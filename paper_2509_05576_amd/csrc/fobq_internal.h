@@ -116,6 +116,7 @@ struct fobq_ctx {
     fobq::DevBuf flags;     // FLAG_WORDS int32: status flags written by kernels (cleared per call), then words
                             // that live as long as the context (FLAG_WORD_MATE: see chol_iter_kernel)
     int mate_epoch = 0;     // number of the last launch that used FLAG_WORD_MATE
+    int cus = 256;          // compute units of the device (fobq_create)
     int* h_flags = nullptr; // pinned host memory that the status flags are read back into (made by fobq_create)
     unsigned char* static_scratch = nullptr;   // this GPU's copy of the library's static scratch array
     int fail_countdown = 0; // test hook: > 0 = the n-th status check from now reports an injected failure
