@@ -232,7 +232,8 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
             "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images, "
                                    + ("every layer from an unfolded matrix of independent activations"
                                       if iid else "k x k and strided convolutions from their input maps"),
-                       "hessian_arithmetic": "int8 slices where d_col >= 384 (else fp64 MFMA)" if int8 else "fp64 MFMA",
+                       "hessian_arithmetic": "int8 slices where d_col >= 384 (stride-1 k x k convolutions with a multiple of 128 channels by tap "
+                                             "offsets), else fp64 MFMA" if int8 else "fp64 MFMA",
                        "weights": total_weights, "layers_in_flight": K, "input_bytes": input_bytes},
             "whole_model_seconds": round(med * 1e-3, 4), "runs_ms": [round(r, 2) for r in runs],
             "sequential_ms": round(_median(seq_runs), 3), "sequential_runs_ms": [round(r, 2) for r in seq_runs],
@@ -357,16 +358,22 @@ def main() -> int:
     n_per_launch = spec.n / launches_per_step
     flops_per_launch = spec.d_col * (spec.d_col + 1) * n_per_launch     # one triangle: d(d+1)/2 entries x 2N flop
     avg_ms = xxt_ms / xxt_launches
-    int8 = stages["slice"][1] > 0          # the digit kernels ran: the library took the int8-slice form for this shape
+    form = ctx.hessian_form()              # what the library took for this shape and input
+    int8 = form != fobq.FORM_FP64
+    offsets = form == fobq.FORM_INT8_TAP_OFFSETS
     if int8:
-        # integer-slice formulation: 19 int8 slice products per entry of the triangle, against the dense int8 peak
-        ops_per_launch = 19.0 * flops_per_launch
+        # integer-slice formulation: 19 int8 slice products per entry the kernel forms, against the dense int8 peak.
+        # Entries: the lower triangle, d (d + 1) / 2 -- or, for a convolution taken by tap offsets, the two block
+        # rows of c channels that hold every offset, 2 c d (the rest of H comes from them by corrections).
+        channels = spec.conv[2] if (offsets and spec.conv is not None) else 0
+        entries2 = 4.0 * channels * spec.d_col if offsets else float(spec.d_col) * (spec.d_col + 1)    # 2 x entries
+        ops_per_launch = 19.0 * entries2 * n_per_launch
         achieved = ops_per_launch / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": "xxt_i8_kernel", "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_MFMA_TOPS,
                     "unit": "TOP/s", "frac": round(achieved / PEAK_INT8_MFMA_TOPS, 4),
                     "traffic": measured_traffic("xxt_i8_kernel", spec.name) if launches_per_step == 1 and not args.from_maps else None,
                     "avg_launch_ms": round(avg_ms, 4), "algorithmic_ops_per_launch": ops_per_launch,
-                    "slice_products": 19,
+                    "slice_products": 19, "entries_formed": "two block rows (tap offsets)" if offsets else "lower triangle",
                     "fp64_equivalent_TFLOPs": round(flops_per_launch / (avg_ms * 1e-3) / 1e12, 2),
                     "fp64_equivalent_over_fp64_mfma_peak": round(flops_per_launch / (avg_ms * 1e-3) / 1e12 / PEAK_FP64_MFMA_TFLOPS, 3)}
         # What the int8 matrix cores sustain on this machine, outside the timed region: the kernel's inner loop
@@ -475,7 +482,8 @@ def main() -> int:
                                f"{spec.bits}-bit, group {spec.group}, damp {spec.damp}, sensitivity order",
                    "block": args.block or 64, "accumulate_calls_per_step": launches_per_step,
                    "hessian_input": "feature maps (implicit unfold)" if args.from_maps else "unfolded X",
-                   "hessian_arithmetic": "int8 slices (5 digits, 19 products), fp64 fold" if int8 else "fp64 MFMA"},
+                   "hessian_arithmetic": ("int8 slices (5 digits, 19 products) of two block rows, the other blocks by tap offsets"
+                                          if offsets else "int8 slices (5 digits, 19 products), fp64 fold") if int8 else "fp64 MFMA"},
         "stages_ms": stage_ms,
         "roofline": roofline,
         "roofline_secondary": secondary,

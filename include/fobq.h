@@ -153,10 +153,24 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
  * zero-padded copy of the maps of one call ((n_img + 1) (h + 2 pad) (w + 2 pad) c floats of scratch):
  * pass fewer images per call to bound it.  N grows by n_img * ho * wo (< 2^31 per call).  One accumulation uses
  * either this call (always with the same c and k) or fobq_hessian_accumulate, not both (ESTATE).
+ * In the mode FOBQ_HESSIAN_INT8_SLICES a convolution with stride 1, k = 2 or 3 and a multiple of 128
+ * channels is accumulated by tap offsets: a block of H depends on its two taps through their
+ * offset and the window of the padded map the first one sweeps, so the block rows of the taps
+ * (0, 0) and (0, k - 1) are formed by exact digit products and every other block from one of
+ * theirs by adding and removing single rows and columns of the map (fp64).  Same H to the
+ * mode's accuracy, about half the matrix work.  The first call of an accumulation decides; if it
+ * took this form, a later call with another stride fails with ESTATE.
  * Enqueues work and returns; maps must stay valid until the stream reaches that work.
  */
 int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img, int64_t h, int64_t w,
                                  int64_t c, int32_t k, int32_t stride, int32_t pad);
+
+/* Which arithmetic the accumulation that is running (or was finalized last) on this context took,
+ * decided by its accumulate calls: FOBQ_FORM_FP64 (no call yet, or fp64 products only),
+ * FOBQ_FORM_INT8_SLICES (digit products over the lower triangle in at least one call),
+ * FOBQ_FORM_INT8_TAP_OFFSETS (convolution by tap offsets).  For reports. */
+typedef enum { FOBQ_FORM_FP64 = 0, FOBQ_FORM_INT8_SLICES = 1, FOBQ_FORM_INT8_TAP_OFFSETS = 2 } fobq_hessian_form_t;
+int fobq_hessian_form(fobq_ctx* ctx, int32_t* form);
 
 /*
  * Quantize one layer (Section 4.2, steps 1-5):

@@ -76,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
     lib.fobq_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.fobq_hessian_form.argtypes = [vp, ctypes.POINTER(i32)]
     lib.fobq_obq_rows.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), i64, i64, vp, vp, vp, vp]
     lib.fobq_probe_int8_matrix_rate.argtypes = [vp, i32, ctypes.POINTER(dbl)]
     lib.fobq_profile_enable.argtypes = [vp, i32]
@@ -84,7 +85,7 @@ def load_library() -> ctypes.CDLL:
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_quantize_layers_batched", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate", "fobq_obq_rows",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate", "fobq_obq_rows", "fobq_hessian_form",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -304,6 +305,16 @@ def fobq_obq_rows(ctx: int, W: torch.Tensor, Hinv: torch.Tensor, *, bits: int = 
     return codes, Q, order, lossrow
 
 
+FORM_FP64, FORM_INT8_SLICES, FORM_INT8_TAP_OFFSETS = 0, 1, 2
+
+
+def fobq_hessian_form(ctx: int) -> int:
+    """The arithmetic the running (or last finalized) accumulation took: FORM_FP64 / _INT8_SLICES / _INT8_TAP_OFFSETS."""
+    f = ctypes.c_int32(0)
+    _check(ctx, load_library().fobq_hessian_form(ctypes.c_void_p(ctx), ctypes.byref(f)))
+    return f.value
+
+
 def fobq_workspace_bytes(ctx: int) -> int:
     b = ctypes.c_int64(0)
     _check(ctx, load_library().fobq_workspace_bytes(ctypes.c_void_p(ctx), ctypes.byref(b)))
@@ -399,6 +410,9 @@ class Ctx:
 
     def workspace_bytes(self) -> int:
         return fobq_workspace_bytes(self.handle)
+
+    def hessian_form(self) -> int:
+        return fobq_hessian_form(self.handle)
 
     def obq_rows(self, W, Hinv, **kw):
         return fobq_obq_rows(self.handle, W, Hinv, **kw)

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfobq.so")
-SOURCES = ["api.hip", "gemm64.hip", "hessian.hip", "hessian_i8.hip", "factor.hip", "quant.hip", "obq.hip", "probe.hip"]
+SOURCES = ["api.hip", "gemm64.hip", "hessian.hip", "hessian_i8.hip", "hessian_offsets.hip", "factor.hip", "quant.hip", "obq.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

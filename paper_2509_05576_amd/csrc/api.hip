@@ -357,7 +357,7 @@ static std::vector<DevBuf*> all_buffers(fobq_ctx* ctx)
 {
     return {&ctx->Hpart, &ctx->H, &ctx->Hd, &ctx->Linv, &ctx->T, &ctx->Hinv, &ctx->A, &ctx->U, &ctx->Un,
             &ctx->Dblk, &ctx->scal, &ctx->flags, &ctx->Wp, &ctx->DT, &ctx->corr, &ctx->codesT, &ctx->scale, &ctx->zero,
-            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax, &ctx->batch_pool, &ctx->batch_desc, &ctx->obq};
+            &ctx->S, &ctx->Spart, &ctx->perm, &ctx->invperm, &ctx->lossrow, &ctx->maps_pad, &ctx->i8planes, &ctx->i8sh, &ctx->i8amax, &ctx->batch_pool, &ctx->batch_desc, &ctx->obq, &ctx->hcorr, &ctx->strips};
 }
 
 extern "C" {
@@ -447,6 +447,7 @@ int fobq_hessian_begin(fobq_ctx* ctx, int64_t d_col)
         if (rc) return rc;
     }
     ctx->h_i8_used = false;
+    ctx->h_offsets = false;
     ctx->h_zeroed = 0;      // slabs are cleared when a launch first needs them
     ctx->h_conv_c = 0;      // plain or convolution mode is fixed by the first accumulate call
     ctx->h_conv_k = 0;
@@ -550,7 +551,21 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int d = (int)ctx->h_d;
-    const bool i8 = ctx->h_mode == FOBQ_HESSIAN_INT8_SLICES && d >= I8_MIN_D && npix >= I8_MIN_N;
+    bool i8 = ctx->h_mode == FOBQ_HESSIAN_INT8_SLICES && d >= I8_MIN_D && npix >= I8_MIN_N;
+    // Stride 1 with whole 128-row tiles per tap: the Hessian by tap offsets (hessian_offsets.hip) -- two block rows
+    // from the digit-product kernel, the rest by corrections over single rows and columns of the padded maps.
+    // Decided by the first call of an accumulation; the later calls have to fit it.
+    OffsetTables tab;
+    const bool first_call = ctx->h_conv_c == 0;
+    bool offsets = false;
+    if (first_call ? (i8 && stride == 1 && k >= 2 && c % 128 == 0) : ctx->h_offsets) {
+        offsets = stride == 1 && offset_tables_build(k, pad, (int)h, (int)w, &tab);
+        if (!offsets && !first_call)
+            return set_err(ctx, FOBQ_ESTATE, "this accumulation takes the convolution by tap offsets (stride 1): a later call "
+                                             "must have stride 1 and a map of at least k x k");
+    }
+    if (offsets) i8 = true;
+    const I8Rect rect = offsets ? I8Rect{(int)(c / 128), (int)((k - 1) * (c / 128))} : I8Rect();
     const int64_t blk = i8 ? i8_block_columns(d) : npix;
     FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
     if (i8) {
@@ -558,11 +573,31 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
         FOBQ_TRY(ctx->i8sh.ensure((size_t)i8_dpad(d) * sizeof(int)), "workspace row shifts");
         FOBQ_TRY(ctx->i8amax.ensure((size_t)c * sizeof(unsigned)), "workspace channel maxima");
     }
-    int rc = clear_slabs(ctx, npix < blk ? npix : blk, true, i8);
-    if (!rc && npix > blk && npix % blk) rc = clear_slabs(ctx, npix % blk, true, i8);    // the shorter last launch
-    if (rc) return rc;
+    if (offsets) {
+        FOBQ_TRY(ctx->hcorr.ensure((size_t)d * d * sizeof(double)), "workspace corrections");
+        FOBQ_TRY(ctx->strips.ensure(offset_strips_bytes(tab.njobs, (int)c)), "workspace strips");
+        if (first_call) FOBQ_TRY(launch_clear_words(ctx->stream, ctx->hcorr.p, (int64_t)d * d * 2, nullptr, 0), "clear corrections");
+        // the slabs a launch can touch for the first time: the rows of the two base taps, all columns
+        auto clear_rect = [&](int64_t n) -> int {
+            const int need = xxt_i8_slabs_touched(d, n, ctx->h_splits, rect);
+            if (need > ctx->h_zeroed) {
+                FOBQ_TRY(launch_clear_slab_rows(ctx->stream, ctx->Hpart.as<double>(), d, ctx->h_zeroed, need - ctx->h_zeroed, 0,
+                                                (int)((k - 1) * c), (int)c), "clear Hessian accumulator");
+                ctx->h_zeroed = need;
+            }
+            return FOBQ_OK;
+        };
+        int rc = clear_rect(npix < blk ? npix : blk);
+        if (!rc && npix > blk && npix % blk) rc = clear_rect(npix % blk);
+        if (rc) return rc;
+    } else {
+        int rc = clear_slabs(ctx, npix < blk ? npix : blk, true, i8);
+        if (!rc && npix > blk && npix % blk) rc = clear_slabs(ctx, npix % blk, true, i8);    // the shorter last launch
+        if (rc) return rc;
+    }
     ctx->h_conv_c = (int)c;
     ctx->h_conv_k = k;
+    if (first_call) ctx->h_offsets = offsets;
     // the padded copy is stream-ordered: a later call reuses the buffer only after this call's launches
     FOBQ_TRY(launch_pad_maps(ctx->stream, maps, (int)n_img, (int)h, (int)w, (int)c, pad, ctx->maps_pad.as<float>()),
              "pad maps");
@@ -586,7 +621,12 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
                                               ctx->i8planes.as<signed char>()), "integer slices (convolution)");
             }
             FOBQ_TRY(launch_xxt_i8(ctx->stream, ctx->i8planes.as<signed char>(), ctx->i8sh.as<int>(), d, nb,
-                                   ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (int8)");
+                                   ctx->Hpart.as<double>(), ctx->h_splits, stage_launch_events(ctx, FOBQ_STAGE_XXT), rect), "xxt (int8)");
+        }
+        if (offsets) {
+            StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
+            FOBQ_TRY(launch_offset_corrections(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, d, tab,
+                                               ctx->strips.as<double>(), ctx->hcorr.as<double>()), "offset corrections");
         }
     } else {
         FOBQ_TRY(launch_xxt_conv(ctx->stream, ctx->maps_pad.as<float>(), (int)n_img, (int)hp, (int)wp, (int)c, k, stride,
@@ -594,6 +634,13 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
                                  stage_launch_events(ctx, FOBQ_STAGE_XXT)), "xxt (convolution)");
     }
     ctx->h_n += npix;
+    return FOBQ_OK;
+}
+
+int fobq_hessian_form(fobq_ctx* ctx, int32_t* form)
+{
+    if (!ctx || !form) return FOBQ_EINVAL;
+    *form = ctx->h_offsets ? FOBQ_FORM_INT8_TAP_OFFSETS : (ctx->h_i8_used ? FOBQ_FORM_INT8_SLICES : FOBQ_FORM_FP64);
     return FOBQ_OK;
 }
 
@@ -607,10 +654,15 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
     const int d = (int)ctx->h_d;
     {
         StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
-        FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d,
-                                         2.0 / (double)ctx->h_n, ctx->H.as<double>(), ctx->h_conv_c > 0 ? ctx->h_conv_c : 0,
-                                         ctx->h_conv_k * ctx->h_conv_k,
-                                         ctx->h_i8_used ? ctx->flags.as<int>() + FLAG_WORD_NONFINITE : nullptr), "hessian finalize");
+        const int* poison = ctx->h_i8_used ? ctx->flags.as<int>() + FLAG_WORD_NONFINITE : nullptr;
+        if (ctx->h_offsets)
+            FOBQ_TRY(launch_hessian_finalize_offsets(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d, 2.0 / (double)ctx->h_n,
+                                                     ctx->H.as<double>(), ctx->h_conv_c, ctx->h_conv_k, ctx->hcorr.as<double>(),
+                                                     poison), "hessian finalize (tap offsets)");
+        else
+            FOBQ_TRY(launch_hessian_finalize(ctx->stream, ctx->Hpart.as<double>(), ctx->h_zeroed, d,
+                                             2.0 / (double)ctx->h_n, ctx->H.as<double>(), ctx->h_conv_c > 0 ? ctx->h_conv_c : 0,
+                                             ctx->h_conv_k * ctx->h_conv_k, poison), "hessian finalize");
         if (H_out)
             FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice,
                                     ctx->stream), "copy H");

@@ -97,6 +97,9 @@ struct fobq_ctx {
     int     h_conv_k = 0;   // ... and this kernel size; -1 in h_conv_c: plain mode
     int     h_mode = 0;     // fobq_hessian_mode
     bool    h_i8_used = false;  // the integer-slice kernels ran in this accumulation
+    bool    h_offsets = false;  // convolution mode by tap offsets (hessian_offsets.hip) in this accumulation
+    fobq::DevBuf hcorr;     // d x d fp64: the corrections of that mode, tap-major
+    fobq::DevBuf strips;    // jobs x c x c fp64: the strips of one call
     fobq::DevBuf i8planes;  // digits of one accumulate call (see hessian_i8.hip)
     fobq::DevBuf i8sh;      // per-row shifts of that call
     fobq::DevBuf i8amax;    // per-channel maxima (convolution input)
@@ -192,7 +195,10 @@ hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int split
 // hessian_i8.hip: X X^T by exact integer slices on the int8 matrix cores
 int i8_dpad(int d);
 size_t i8_planes_bytes(int d, int64_t n);
-int xxt_i8_slabs_touched(int d, int64_t n, int splits);
+// rect.cb > 0: instead of the lower triangle, all tile columns of two groups of rect.cb tile rows (the second group
+// starts at tile row rect.gap), every entry stored
+struct I8Rect { int cb = 0, gap = 0; };
+int xxt_i8_slabs_touched(int d, int64_t n, int splits, I8Rect rect = I8Rect());
 int64_t i8_block_columns(int d);      // most columns one launch of the matrix kernel takes (bounds the digit scratch)
 hipError_t launch_i8_row_shifts(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, int* nonfinite);
 hipError_t launch_i8_slice(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, const int* sh, signed char* planes);
@@ -201,8 +207,30 @@ hipError_t launch_i8_chan_shifts(hipStream_t s, const float* padded, int64_t pix
 hipError_t launch_i8_slice_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
                                 int ho, int wo, int64_t npix, int64_t pix0, int64_t n, const int* sh, signed char* planes);
 hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh, int d, int64_t n, double* Hpart,
-                         int splits, LaunchEvents ev = LaunchEvents());
+                         int splits, LaunchEvents ev = LaunchEvents(), I8Rect rect = I8Rect());
 hipError_t launch_damp(hipStream_t s, const double* H, int d, double damp, double damp_abs, double* Hd, double* lam_out);
+// hessian_offsets.hip: Hessian of a stride-1 convolution by tap offsets (two block rows from the digit-product kernel,
+// the other blocks by corrections over single rows and columns of the padded maps)
+constexpr int OFFSET_MAX_TAPS = 9, OFFSET_MAX_JOBS = 128, OFFSET_MAX_PAIRS = 81, OFFSET_MAX_TERMS = 384;
+// one strip: kind 0 = row `coord` of the padded map, columns start .. start + len - 1; kind 1 = column `coord`, rows
+// start .. start + len - 1; (dy, dx) = the offset of the second factor
+struct OffsetJob { int coord, start, len; signed char kind, dy, dx, unused; };
+// passed to the kernels by value (about 3 KiB)
+struct OffsetTables {
+    int njobs, npairs, nterms;
+    OffsetJob jobs[OFFSET_MAX_JOBS];
+    unsigned char pair_ta[OFFSET_MAX_PAIRS], pair_tb[OFFSET_MAX_PAIRS];   // tap indices ky * k + kx of a pair with corrections
+    short pair_begin[OFFSET_MAX_PAIRS + 1];                               // its terms: [pair_begin[p], pair_begin[p + 1])
+    unsigned char term_job[OFFSET_MAX_TERMS];
+    signed char term_sign[OFFSET_MAX_TERMS];
+};
+bool offset_tables_build(int k, int pad, int h, int w, OffsetTables* tab);
+size_t offset_strips_bytes(int njobs, int c);
+hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first, int count, int row0, int row1, int nrows);
+hipError_t launch_offset_corrections(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int d,
+                                     const OffsetTables& tab, double* strips, double* corr);
+hipError_t launch_hessian_finalize_offsets(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H, int c,
+                                           int k, const double* corr, const int* poison);
 
 // factor.hip
 // Sacc != null (d x d scratch): L^-1 and the upper tiles of Hinv = L^-T L^-1 are completed alongside the

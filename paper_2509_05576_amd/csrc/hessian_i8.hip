@@ -303,7 +303,7 @@ __device__ __forceinline__ void lds_copy_block(const signed char* __restrict__ s
 // register files in that loop, 1.38 ms against 0.80 on the 2304 x 25088 layer.)
 __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restrict__ P, const int* __restrict__ sh, int d,
                                                         int dpad, int64_t ksteps, double* __restrict__ Hpart, int64_t per_wg,
-                                                        int64_t items, int classes)
+                                                        int64_t items, int classes, I8Rect rect)
 {
     constexpr int TN = IT, NB = TN / 32;  // row blocks of the B operand
     // [buffer][block of 32 rows][digit]: the 5 digit blocks of a row block are consecutive, as in global memory
@@ -360,11 +360,20 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
             return c_begin + c;
         };
         const int piece = (int)(vb - tile_first / per_wg);      // ranges that reached this tile before this one
-        // tile -> (I, J), I >= J, row-major over the lower triangle
-        int I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
-        while ((I + 1) * (I + 2) / 2 <= tile) ++I;
-        while (I * (I + 1) / 2 > tile) --I;
-        const int J = tile - I * (I + 1) / 2;
+        // tile -> (I, J): I >= J, row-major over the lower triangle; or, for a list of tile rows (rect.cb > 0: two
+        // groups of rect.cb tile rows, the second starting at tile row rect.gap), all tile columns of those rows
+        int I, J;
+        if (rect.cb > 0) {
+            const int ntj = dpad / IT, ri = tile / ntj;
+            J = tile - ri * ntj;
+            I = ri < rect.cb ? ri : ri - rect.cb + rect.gap;
+        } else {
+            I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+            while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+            while (I * (I + 1) / 2 > tile) --I;
+            J = tile - I * (I + 1) / 2;
+        }
+        const bool tri = rect.cb == 0;       // only the lower triangle is wanted (and stored)
         const int i0 = I * IT, j0 = J * TN;
         double* __restrict__ out = Hpart + (int64_t)piece * d * d;
 
@@ -430,7 +439,7 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
                     buf ^= 1;
                 }
             };
-            const bool need0 = I != J || wn <= 2 * wm, need1 = I != J || wn <= 2 * wm + 1;
+            const bool need0 = !tri || I != J || wn <= 2 * wm, need1 = !tri || I != J || wn <= 2 * wm + 1;
             if (need0) ksteps_loop(std::true_type(), std::true_type());
             else if (need1) ksteps_loop(std::false_type(), std::true_type());
             else ksteps_loop(std::false_type(), std::false_type());
@@ -443,7 +452,7 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = i0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    if (row < d && col <= row) {
+                    if (row < d && col < d && (!tri || col <= row)) {
                         double sum = 0.0;
 #pragma unroll
                         for (int m = NM - 1; m >= 0; --m)
@@ -459,12 +468,13 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
 
 struct I8Plan { int nt, wgs; int64_t ksteps, items, per_wg; };
 
-static I8Plan i8_plan(int d, int64_t n, int splits)
+static I8Plan i8_plan(int d, int64_t n, int splits, I8Rect rect)
 {
     I8Plan p;
     p.nt = i8_dpad(d) / IT;
     p.ksteps = i8_ksteps(n);
-    p.items = (int64_t)p.nt * (p.nt + 1) / 2 * p.ksteps;
+    const int64_t tiles = rect.cb > 0 ? (int64_t)2 * rect.cb * p.nt : (int64_t)p.nt * (p.nt + 1) / 2;
+    p.items = tiles * p.ksteps;
     p.per_wg = (p.items + I8_WGS - 1) / I8_WGS;
     // a tile meets at most ceil(ksteps / per_wg) + 1 ranges; that must not exceed the slabs
     const int64_t min_len = splits > 1 ? (p.ksteps + splits - 2) / (splits - 1) : p.ksteps;
@@ -474,9 +484,9 @@ static I8Plan i8_plan(int d, int64_t n, int splits)
     return p;
 }
 
-int xxt_i8_slabs_touched(int d, int64_t n, int splits)
+int xxt_i8_slabs_touched(int d, int64_t n, int splits, I8Rect rect)
 {
-    const I8Plan pl = i8_plan(d, n, splits);
+    const I8Plan pl = i8_plan(d, n, splits, rect);
     const int64_t p = (pl.ksteps + pl.per_wg - 1) / pl.per_wg + 1;
     return (int)(p < splits ? p : splits);
 }
@@ -532,14 +542,14 @@ hipError_t launch_i8_slice_conv(hipStream_t s, const float* padded, int n_img, i
 }
 
 hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh, int d, int64_t n, double* Hpart,
-                         int splits, LaunchEvents ev)
+                         int splits, LaunchEvents ev, I8Rect rect)
 {
-    const I8Plan pl = i8_plan(d, n, splits);
+    const I8Plan pl = i8_plan(d, n, splits, rect);
     // pieces per tile, rounded: the number of classes of ranges (see the kernel)
     int classes = (int)((pl.ksteps + pl.per_wg / 2) / pl.per_wg);
     classes = classes < 1 ? 1 : (classes > pl.wgs ? pl.wgs : classes);
     hipExtLaunchKernelGGL(xxt_i8_kernel, dim3(pl.wgs), dim3(512), 0, s, ev.start, ev.stop, 0, planes, sh, d, i8_dpad(d),
-                          pl.ksteps, Hpart, pl.per_wg, pl.items, classes);
+                          pl.ksteps, Hpart, pl.per_wg, pl.items, classes, rect);
     return hipGetLastError();
 }
 

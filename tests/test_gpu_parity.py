@@ -210,6 +210,48 @@ def test_hessian_int8_slices_from_feature_maps_matches_oracle(fobq, ctx, n, h, w
     _check_int8_hessian(H.cpu().numpy(), ref)
 
 
+# Stride 1 with 128 or 256 channels: the Hessian by tap offsets (two block rows from the digit-product kernel, every
+# other block by corrections over single rows and columns of the padded maps).  Same bar as the other int8 cases.
+@pytest.mark.parametrize("n,h,w,c,k,pad,per_call", [
+    (16, 14, 14, 128, 3, 1, None),       # the usual 3 x 3, pad 1
+    (9, 11, 17, 256, 3, 1, 4),           # not square; calls of 4, 4 and 1 image (the last one short)
+    (10, 13, 12, 128, 3, 0, None),       # no padding: no strip vanishes
+    (6, 12, 15, 128, 3, 2, 3),           # padding wider than the kernel needs
+    (12, 16, 9, 128, 2, 1, None),        # 2 x 2 kernel, padding on both sides
+    (5, 5, 40, 256, 3, 1, None),         # maps barely taller than the kernel
+])
+def test_hessian_by_tap_offsets_matches_oracle(fobq, ctx, n, h, w, c, k, pad, per_call):
+    _say(f"hessian by tap offsets n={n} h={h} w={w} c={c} k={k} pad={pad} per_call={per_call}")
+    rng = np.random.default_rng(900 + c + k + pad + h)
+    maps = (np.maximum(rng.standard_normal((n, h, w, c)), 0) * 10.0 ** rng.uniform(-3, 3, size=c)).astype(np.float32)
+    X = workloads.im2col(maps, k, 1, pad)
+    assert X.shape[1] // n * (per_call or n) >= 512        # the first call decides: it has to take the int8 form
+    ref = oracle.hessian(X)
+    d = c * k * k
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)
+    ctx.hessian_conv(_dev(maps), k, 1, pad, images_per_call=per_call, H_out=H)
+    torch.cuda.synchronize()
+    Hh = H.cpu().numpy()
+    _check_int8_hessian(Hh, ref)
+    assert np.array_equal(Hh, Hh.T)
+    # a second accumulation on the same context (slabs and corrections start from zero again)
+    ctx.hessian_conv(_dev(maps), k, 1, pad, images_per_call=per_call, H_out=H)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.cpu().numpy(), Hh)
+
+
+def test_hessian_by_tap_offsets_rejects_a_strided_later_call(fobq, ctx):
+    maps = torch.relu(torch.randn((8, 12, 12, 128), device="cuda"))
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)
+    fobq.fobq_hessian_begin(ctx.handle, 128 * 9)
+    fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, 3, 1, 1)
+    with pytest.raises(fobq.FobqError) as e:
+        fobq.fobq_hessian_accumulate_conv(ctx.handle, maps, 3, 2, 1)
+    assert e.value.code == fobq.ESTATE
+    fobq.fobq_hessian_finalize(ctx.handle, None)
+
+
 @pytest.mark.slow
 def test_hessian_int8_slices_long_pieces_fold_in_between(fobq, ctx):
     # 384 rows x 0.72 M columns: 6 tiles x 22528 k-steps over 256 workgroups = 528 k-steps per piece, more than
