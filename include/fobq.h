@@ -153,8 +153,8 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out);
  * zero-padded copy of the maps of one call ((n_img + 1) (h + 2 pad) (w + 2 pad) c floats of scratch):
  * pass fewer images per call to bound it.  N grows by n_img * ho * wo (< 2^31 per call).  One accumulation uses
  * either this call (always with the same c and k) or fobq_hessian_accumulate, not both (ESTATE).
- * In the mode FOBQ_HESSIAN_INT8_SLICES a convolution with stride 1, k = 2 or 3 and a multiple of 128
- * channels is accumulated by tap offsets: a block of H depends on its two taps through their
+ * In the mode FOBQ_HESSIAN_INT8_SLICES a convolution with stride 1, k = 2 or 3 and a multiple of 64
+ * channels (d_col >= 384) is accumulated by tap offsets: a block of H depends on its two taps through their
  * offset and the window of the padded map the first one sweeps, so the block rows of the taps
  * (0, 0) and (0, k - 1) are formed by exact digit products and every other block from one of
  * theirs by adding and removing single rows and columns of the map (fp64).  Same H to the

@@ -558,14 +558,17 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
     OffsetTables tab;
     const bool first_call = ctx->h_conv_c == 0;
     bool offsets = false;
-    if (first_call ? (i8 && stride == 1 && k >= 2 && c % 128 == 0) : ctx->h_offsets) {
+    // the tile rows (128 rows each) that hold the rows of the two base taps: two groups of the same size, apart
+    const int rect_cb = (int)((c + 127) / 128), rect_gap = (int)((k - 1) * c / 128);
+    const bool rect_fits = c % 64 == 0 && rect_gap >= rect_cb && (int)((k * c + 127) / 128) - rect_gap == rect_cb;
+    if (first_call ? (i8 && stride == 1 && k >= 2 && rect_fits) : ctx->h_offsets) {
         offsets = stride == 1 && offset_tables_build(k, pad, (int)h, (int)w, &tab);
         if (!offsets && !first_call)
             return set_err(ctx, FOBQ_ESTATE, "this accumulation takes the convolution by tap offsets (stride 1): a later call "
                                              "must have stride 1 and a map of at least k x k");
     }
     if (offsets) i8 = true;
-    const I8Rect rect = offsets ? I8Rect{(int)(c / 128), (int)((k - 1) * (c / 128))} : I8Rect();
+    const I8Rect rect = offsets ? I8Rect{rect_cb, rect_gap} : I8Rect();
     const int64_t blk = i8 ? i8_block_columns(d) : npix;
     FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
     if (i8) {
@@ -581,8 +584,9 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
         auto clear_rect = [&](int64_t n) -> int {
             const int need = xxt_i8_slabs_touched(d, n, ctx->h_splits, rect);
             if (need > ctx->h_zeroed) {
+                const int last = d - rect_gap * 128 < rect_cb * 128 ? d - rect_gap * 128 : rect_cb * 128;     // rows past d do not exist
                 FOBQ_TRY(launch_clear_slab_rows(ctx->stream, ctx->Hpart.as<double>(), d, ctx->h_zeroed, need - ctx->h_zeroed, 0,
-                                                (int)((k - 1) * c), (int)c), "clear Hessian accumulator");
+                                                rect_cb * 128, rect_gap * 128, last), "clear Hessian accumulator");
                 ctx->h_zeroed = need;
             }
             return FOBQ_OK;

@@ -226,7 +226,7 @@ struct OffsetTables {
 };
 bool offset_tables_build(int k, int pad, int h, int w, OffsetTables* tab);
 size_t offset_strips_bytes(int njobs, int c);
-hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first, int count, int row0, int row1, int nrows);
+hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first, int count, int row0, int n0, int row1, int n1);
 hipError_t launch_offset_corrections(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int d,
                                      const OffsetTables& tab, double* strips, double* corr);
 hipError_t launch_hessian_finalize_offsets(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H, int c,

@@ -199,19 +199,19 @@ __global__ __launch_bounds__(256) void hessian_finalize_offsets_kernel(const dou
     H[(int64_t)col * d + row] = s;
 }
 
-// full rows [row0, row0 + nrows) and [row1, row1 + nrows) of `count` slabs from slab `first` on
-__global__ __launch_bounds__(256) void clear_slab_rows_kernel(double* __restrict__ Hpart, int d, int first, int row0, int row1,
-                                                              int nrows)
+// full rows [row0, row0 + n0) and [row1, row1 + n1) of `count` slabs from slab `first` on
+__global__ __launch_bounds__(256) void clear_slab_rows_kernel(double* __restrict__ Hpart, int d, int first, int row0, int n0,
+                                                              int row1)
 {
-    const int r = blockIdx.x < (unsigned)nrows ? row0 + (int)blockIdx.x : row1 + (int)blockIdx.x - nrows;
+    const int r = (int)blockIdx.x < n0 ? row0 + (int)blockIdx.x : row1 + (int)blockIdx.x - n0;
     double* __restrict__ row = Hpart + ((int64_t)(first + blockIdx.y) * d + r) * d;
     for (int x = threadIdx.x; x < d; x += 256) row[x] = 0.0;
 }
 
-hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first, int count, int row0, int row1, int nrows)
+hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first, int count, int row0, int n0, int row1, int n1)
 {
-    if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(clear_slab_rows_kernel, dim3(2 * nrows, count), dim3(256), 0, s, Hpart, d, first, row0, row1, nrows);
+    if (count <= 0 || n0 + n1 <= 0) return hipSuccess;
+    hipLaunchKernelGGL(clear_slab_rows_kernel, dim3(n0 + n1, count), dim3(256), 0, s, Hpart, d, first, row0, n0, row1);
     return hipGetLastError();
 }
 

@@ -210,7 +210,7 @@ def test_hessian_int8_slices_from_feature_maps_matches_oracle(fobq, ctx, n, h, w
     _check_int8_hessian(H.cpu().numpy(), ref)
 
 
-# Stride 1 with 128 or 256 channels: the Hessian by tap offsets (two block rows from the digit-product kernel, every
+# Stride 1 with a multiple of 64 channels: the Hessian by tap offsets (two block rows from the digit-product kernel, every
 # other block by corrections over single rows and columns of the padded maps).  Same bar as the other int8 cases.
 @pytest.mark.parametrize("n,h,w,c,k,pad,per_call", [
     (16, 14, 14, 128, 3, 1, None),       # the usual 3 x 3, pad 1
@@ -219,6 +219,8 @@ def test_hessian_int8_slices_from_feature_maps_matches_oracle(fobq, ctx, n, h, w
     (6, 12, 15, 128, 3, 2, 3),           # padding wider than the kernel needs
     (12, 16, 9, 128, 2, 1, None),        # 2 x 2 kernel, padding on both sides
     (5, 5, 40, 256, 3, 1, None),         # maps barely taller than the kernel
+    (8, 20, 21, 64, 3, 1, 3),            # 64 channels: a base tap is half a 128-row tile
+    (6, 10, 12, 192, 3, 1, None),        # 192 channels: the base taps' rows end inside a tile
 ])
 def test_hessian_by_tap_offsets_matches_oracle(fobq, ctx, n, h, w, c, k, pad, per_call):
     _say(f"hessian by tap offsets n={n} h={h} w={w} c={c} k={k} pad={pad} per_call={per_call}")
