@@ -432,6 +432,33 @@ def main() -> int:
                                   "frac": round(tf / PEAK_FP64_MFMA_TFLOPS, 4)})
     workspace = ctx.workspace_bytes()
 
+    # The same layer with its Hessian accumulated from the input maps of the convolution instead of the unfolded X
+    # (what a caller that holds the maps would do): reported beside the headline, never as `value`.
+    from_maps = None
+    if spec.conv is not None and not args.from_maps and args.block != 1 and args.chunk == 0:
+        Mm = torch.from_numpy(spec.make_maps()).cuda()
+        out_m = None
+
+        def step_maps():
+            nonlocal out_m
+            ctx.hessian_conv(Mm, spec.conv[3], spec.stride, spec.conv[4])
+            out_m = ctx.quantize_layer(Wd, bits=spec.bits, group=spec.group, damp=spec.damp, block=args.block, out=out_m)
+
+        for _ in range(args.warmup):
+            step_maps()
+        torch.cuda.synchronize()
+        tm0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_maps()
+        torch.cuda.synchronize()
+        ms_maps = (time.perf_counter() - tm0) * 1e3 / args.steps
+        form_m = ctx.hessian_form()
+        from_maps = {"ms_per_step": round(ms_maps, 4), "value": round(weights / (ms_maps * 1e-3), 1), "unit": "weights/s",
+                     "hessian_arithmetic": {fobq.FORM_FP64: "fp64 MFMA", fobq.FORM_INT8_SLICES: "int8 slices",
+                                            fobq.FORM_INT8_TAP_OFFSETS: "int8 slices of two block rows, the other blocks by tap offsets"}[form_m],
+                     "codes_equal_to_the_run_from_X": bool(torch.equal(out_m.codes, out.codes))}
+        del Mm
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -488,6 +515,7 @@ def main() -> int:
         "roofline": roofline,
         "roofline_secondary": secondary,
         "workspace_bytes": workspace,
+        "same_layer_from_feature_maps": from_maps,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
