@@ -656,6 +656,12 @@ int fobq_hessian_finalize(fobq_ctx* ctx, double* H_out)
     DeviceGuard g(ctx->device);
     if (!g.ok) return set_err(ctx, FOBQ_EHIP, "cannot select device %d", ctx->device);
     const int d = (int)ctx->h_d;
+    if (ctx->h_final) {
+        // already finalized (the slabs are consumed by then): H is in the context
+        if (H_out)
+            FOBQ_TRY(hipMemcpyAsync(H_out, ctx->H.p, (size_t)d * d * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream), "copy H");
+        return FOBQ_OK;
+    }
     {
         StageScope sc(ctx, FOBQ_STAGE_FINALIZE);
         const int* poison = ctx->h_i8_used ? ctx->flags.as<int>() + FLAG_WORD_NONFINITE : nullptr;

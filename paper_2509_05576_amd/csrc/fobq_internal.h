@@ -189,7 +189,7 @@ hipError_t launch_pad_maps(hipStream_t s, const float* maps, int n_img, int h, i
 hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int k, int stride,
                            int ho, int wo, int64_t npix, double* Hpart, int splits,
                            LaunchEvents ev = LaunchEvents());
-hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
+hipError_t launch_hessian_finalize(hipStream_t s, double* Hpart, int splits, int d, double factor, double* H,
                                    int conv_c, int conv_kk, const int* poison);   // *poison != 0: H = NaN
 
 // hessian_i8.hip: X X^T by exact integer slices on the int8 matrix cores

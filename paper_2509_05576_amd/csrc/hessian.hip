@@ -585,7 +585,7 @@ hipError_t launch_xxt_conv(hipStream_t s, const float* padded, int n_img, int hp
 // H[a][b] = H[b][a] = factor * sum_s Hpart[s][a][b]   for b <= a (lower slabs hold the sums)
 // poison (may be null): a word that is non-zero when an input of the integer-slice path held an Inf or NaN;
 // H then becomes NaN throughout, as the floating-point sum would have made the rows concerned.
-__global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __restrict__ Hpart, int splits, int d,
+__global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __restrict__ Hpart, int splits, int sstride, int d,
                                                                double factor, double* __restrict__ H,
                                                                const int* __restrict__ poison)
 {
@@ -593,7 +593,7 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __r
     const int a = blockIdx.y * 16 + (threadIdx.x >> 4);
     if (a >= d || b >= d || b > a) return;
     double s = 0.0;
-    for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * d * d + (int64_t)a * d + b];
+    for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * sstride * d * d + (int64_t)a * d + b];
     s *= factor;
     if (poison && *poison) s = __builtin_nan("");
     H[(int64_t)a * d + b] = s;
@@ -601,7 +601,7 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const double* __r
 }
 
 // Convolution mode: the slabs are in tap-major row order; H is written in (c, ky, kx) order.
-__global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double* __restrict__ Hpart, int splits, int d,
+__global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double* __restrict__ Hpart, int splits, int sstride, int d,
                                                                     double factor, double* __restrict__ H, int c,
                                                                     int kk, const int* __restrict__ poison)
 {
@@ -611,7 +611,7 @@ __global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double
     const int ai = (a % kk) * c + a / kk, bi = (b % kk) * c + b / kk;
     const int hi = max(ai, bi), lo = min(ai, bi);
     double s = 0.0;
-    for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * d * d + (int64_t)hi * d + lo];
+    for (int k = 0; k < splits; ++k) s += Hpart[(int64_t)k * sstride * d * d + (int64_t)hi * d + lo];
     s *= factor;
     if (poison && *poison) s = __builtin_nan("");
     H[(int64_t)a * d + b] = s;
@@ -619,14 +619,39 @@ __global__ __launch_bounds__(256) void hessian_finalize_conv_kernel(const double
 }
 
 // conv_c > 0: the slabs were accumulated in convolution mode with conv_c channels and conv_kk taps
-hipError_t launch_hessian_finalize(hipStream_t s, const double* Hpart, int splits, int d, double factor, double* H,
+// Small d, many slabs (a tile of a 64-column layer is cut into up to 1024 pieces): the lower triangles of groups of
+// SLAB_GROUP consecutive slabs are first added into the first slab of each group, one workgroup per (16 x 16 entries,
+// group), so that the finalize kernel -- one thread per entry, the slabs one after the other -- has SLAB_GROUP times
+// fewer to walk through.  The order of the sum is fixed either way.
+constexpr int SLAB_GROUP = 32;
+__global__ __launch_bounds__(256) void hessian_group_slabs_kernel(double* __restrict__ Hpart, int splits, int d)
+{
+    const int b = blockIdx.x * 16 + (threadIdx.x & 15);
+    const int a = blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (a >= d || b >= d || b > a) return;
+    const int k0 = blockIdx.z * SLAB_GROUP, k1 = min(splits, k0 + SLAB_GROUP);
+    const int64_t at = (int64_t)a * d + b;
+    double s = 0.0;
+    for (int k = k0; k < k1; ++k) s += Hpart[(int64_t)k * d * d + at];
+    Hpart[(int64_t)k0 * d * d + at] = s;
+}
+
+hipError_t launch_hessian_finalize(hipStream_t s, double* Hpart, int splits, int d, double factor, double* H,
                                    int conv_c, int conv_kk, const int* poison)
 {
     dim3 grid((d + 15) / 16, (d + 15) / 16), block(256);
+    int sstride = 1;
+    if (splits > 2 * SLAB_GROUP) {
+        const int groups = (splits + SLAB_GROUP - 1) / SLAB_GROUP;
+        hipLaunchKernelGGL(hessian_group_slabs_kernel, dim3(grid.x, grid.y, groups), block, 0, s, Hpart, splits, d);
+        splits = groups;
+        sstride = SLAB_GROUP;
+    }
     if (conv_c > 0)
-        hipLaunchKernelGGL(hessian_finalize_conv_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, conv_c, conv_kk, poison);
+        hipLaunchKernelGGL(hessian_finalize_conv_kernel, grid, block, 0, s, Hpart, splits, sstride, d, factor, H, conv_c, conv_kk,
+                           poison);
     else
-        hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, d, factor, H, poison);
+        hipLaunchKernelGGL(hessian_finalize_kernel, grid, block, 0, s, Hpart, splits, sstride, d, factor, H, poison);
     return hipGetLastError();
 }
 
