@@ -435,7 +435,8 @@ def main() -> int:
     # The same layer with its Hessian accumulated from the input maps of the convolution instead of the unfolded X
     # (what a caller that holds the maps would do): reported beside the headline, never as `value`.
     from_maps = None
-    if spec.conv is not None and not args.from_maps and args.block != 1 and args.chunk == 0:
+    if spec.conv is not None and not args.from_maps and args.block != 1 and args.chunk == 0 and not args.copy_probe:
+        # (not in a counter-calibration run: its per-kernel averages are those of the default path alone)
         Mm = torch.from_numpy(spec.make_maps()).cuda()
         out_m = None
 
