@@ -272,9 +272,9 @@ def main() -> int:
     ap.add_argument("--obq-rows", type=int, default=0,
                     help="with the CPU baseline: also run the per-row OBQ baseline (own inverse Hessian per row) "
                          "of the oracle on this many rows and report its cost and loss next to FastOBQ's")
-    ap.add_argument("--headline-only", action="store_true",
-                    help="convolution workloads: leave out the extra run of the same layer from its feature maps "
-                         "(profiling runs: the kernel averages are then those of the headline path alone)")
+    ap.add_argument("--also-from-maps", action="store_true",
+                    help="convolution workloads: after the headline run, time the same layer once more with its Hessian "
+                         "accumulated from the feature maps and report it as `same_layer_from_feature_maps`")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain device copy of X first (known bytes; calibrates HBM byte counters)")
     args = ap.parse_args()
@@ -435,12 +435,11 @@ def main() -> int:
                                   "frac": round(tf / PEAK_FP64_MFMA_TFLOPS, 4)})
     workspace = ctx.workspace_bytes()
 
-    # The same layer with its Hessian accumulated from the input maps of the convolution instead of the unfolded X
-    # (what a caller that holds the maps would do): reported beside the headline, never as `value`.
+    # --also-from-maps: the same layer with its Hessian accumulated from the input maps of the convolution instead of
+    # the unfolded X (what a caller that holds the maps would do): reported beside the headline, never as `value`.
+    # Off by default, so that the kernels of a default run are those of the headline path alone.
     from_maps = None
-    if spec.conv is not None and not args.from_maps and args.block != 1 and args.chunk == 0 and not args.copy_probe \
-            and not args.headline_only:
-        # (not in a counter-calibration or profiling run: its per-kernel averages are those of the default path alone)
+    if spec.conv is not None and not args.from_maps and args.block != 1 and args.chunk == 0 and args.also_from_maps:
         Mm = torch.from_numpy(spec.make_maps()).cuda()
         out_m = None
 
