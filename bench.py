@@ -194,10 +194,16 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
     for c in ctxs:
         c.set_hessian_mode(hmode)
 
+    # layers are independent, so the in-flight pass may take them in any order: widest first -- a wide layer is a
+    # long chain of short launches that leaves the GPU nearly idle, and started early it runs beside the Hessians of
+    # the layers that follow instead of alone at the end (network order: 65.6 / 85.2 ms, widest first: 61.6 / 80.8)
+    flight_order = sorted(range(len(layers)), key=lambda i: -layers[i].d_col)
+
     def whole_model():
         busy = [False] * K
-        for i, (spec, W, inp, pc) in enumerate(zip(layers, Ws, Ins, per_call)):
-            k = i % K
+        for slot, i in enumerate(flight_order):
+            spec, W, inp, pc = layers[i], Ws[i], Ins[i], per_call[i]
+            k = slot % K
             if busy[k]:
                 ctxs[k].finish()
                 busy[k] = False
