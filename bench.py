@@ -262,7 +262,7 @@ def main() -> int:
     ap.add_argument("--from-maps", action="store_true",
                     help="conv workloads: accumulate the Hessian straight from the feature maps "
                          "(fobq_hessian_accumulate_conv) instead of the unfolded X")
-    ap.add_argument("--concurrency", type=int, default=8,
+    ap.add_argument("--concurrency", type=int, default=16,
                     help="whole-model sweeps: layers in flight at once (one context and stream each)")
     ap.add_argument("--hessian", choices=("i8", "f64"), default="i8",
                     help="how X X^T is formed: i8 = exact int8 slice products on the matrix cores where the mode "
