@@ -198,7 +198,12 @@ size_t i8_planes_bytes(int d, int64_t n);
 // rect.cb > 0: instead of the lower triangle, all tile columns of two groups of rect.cb tile rows (the second group
 // starts at tile row rect.gap), every entry stored
 struct I8Rect { int cb = 0, gap = 0; };
+// full > 0: the workgroups go through the tiles in step (see xxt_i8_kernel): `full` rounds of whole tiles, then the
+// `rem` tiles left over, each cut into `pieces` parts of piece_len k-steps
+struct I8Lockstep { int full = 0, rem = 0, pieces = 0; int64_t piece_len = 0; };
 int xxt_i8_slabs_touched(int d, int64_t n, int splits, I8Rect rect = I8Rect());
+// slabs of partial sums that a launch over n columns would like to have (0: no wish beyond xxt_pick_splits)
+int xxt_i8_wanted_splits(int d, int64_t n);
 int64_t i8_block_columns(int d);      // most columns one launch of the matrix kernel takes (bounds the digit scratch)
 hipError_t launch_i8_row_shifts(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, int* nonfinite);
 hipError_t launch_i8_slice(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, const int* sh, signed char* planes);

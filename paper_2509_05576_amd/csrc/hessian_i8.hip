@@ -303,7 +303,7 @@ __device__ __forceinline__ void lds_copy_block(const signed char* __restrict__ s
 // register files in that loop, 1.38 ms against 0.80 on the 2304 x 25088 layer.)
 __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restrict__ P, const int* __restrict__ sh, int d,
                                                         int dpad, int64_t ksteps, double* __restrict__ Hpart, int64_t per_wg,
-                                                        int64_t items, int classes, I8Rect rect)
+                                                        int64_t items, int classes, I8Rect rect, I8Lockstep ls)
 {
     constexpr int TN = IT, NB = TN / 32;  // row blocks of the B operand
     // [buffer][block of 32 rows][digit]: the 5 digit blocks of a row block are consecutive, as in global memory
@@ -334,39 +334,92 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
     }
 
     const int64_t g0 = vb * per_wg, g1 = min(items, g0 + per_wg);
-    if (g0 >= g1) return;
-    const int t_first = (int)(g0 / ksteps), t_last = (int)((g1 - 1) / ksteps);
-    const int npieces = t_last - t_first + 1;
     const int64_t step_bytes = (int64_t)(dpad / 32) * NS * 1024;     // one k-step of all rows
+    int npieces = 0, t_first = 0, t_last = 0;
+    if (ls.full > 0) {
+        // In step: `full` rounds of whole tiles, then the tiles left over, each cut into ls.pieces equal parts of
+        // the calibration dimension, dealt piece-major.  In every round the workgroup at position vpos takes entry
+        // round * gridDim.x + vpos, so all workgroups start a round together at the same k-step and the 32 of an XCD
+        // hold 32 consecutive tiles of the blocked order below.
+        const int64_t units = (int64_t)ls.rem * ls.pieces;
+        npieces = ls.full + (int)(vpos < units ? (units - vpos + gridDim.x - 1) / gridDim.x : 0);
+    } else {
+        if (g0 >= g1) return;
+        t_first = (int)(g0 / ksteps);
+        t_last = (int)((g1 - 1) / ksteps);
+        npieces = t_last - t_first + 1;
+    }
 
     for (int pi = 0; pi < npieces; ++pi) {
-        // All workgroups start together and advance one k-step per step, so k-step k is best visited at step
-        // k mod per_wg: workgroups on neighbouring tiles (same class, same XCD) then read the same columns at
-        // the same time.  A range inside one tile starts at its k-step whose index is a multiple of per_wg
+        // Ranges (ls.full == 0).  All workgroups start together and advance one k-step per step, so k-step k is best
+        // visited at step k mod per_wg: workgroups on neighbouring tiles (same class, same XCD) then read the same
+        // columns at the same time.  A range inside one tile starts at its k-step whose index is a multiple of per_wg
         // and wraps around; a range over two tiles takes the head of the later tile before the tail of the
         // earlier one.  The order of the sum is fixed, so results are reproducible.
-        const int tile = npieces == 2 ? t_last - pi : t_first + pi;
-        const int64_t tile_first = (int64_t)tile * ksteps;
-        const int64_t c_begin = max(g0, tile_first) - tile_first, c_end = min(g1, tile_first + ksteps) - tile_first;
-        const int64_t len = c_end - c_begin;
-        int64_t rot = 0;
-        if (npieces == 1) {
-            const int64_t aligned = (c_begin + per_wg - 1) / per_wg * per_wg;
-            if (aligned < c_end) rot = aligned - c_begin;
+        int tile, piece;
+        int64_t c_begin, c_end, rot = 0;
+        if (ls.full > 0) {
+            if (pi < ls.full) {
+                tile = pi * (int)gridDim.x + vpos;
+                piece = 0;
+                c_begin = 0;
+                c_end = ksteps;
+            } else {
+                const int64_t u = (int64_t)(pi - ls.full) * gridDim.x + vpos;
+                piece = (int)(u / ls.rem);
+                tile = ls.full * (int)gridDim.x + (int)(u - (int64_t)piece * ls.rem);
+                c_begin = min(ksteps, piece * ls.piece_len);
+                c_end = min(ksteps, c_begin + ls.piece_len);
+            }
+        } else {
+            tile = npieces == 2 ? t_last - pi : t_first + pi;
+            const int64_t tile_first = (int64_t)tile * ksteps;
+            c_begin = max(g0, tile_first) - tile_first;
+            c_end = min(g1, tile_first + ksteps) - tile_first;
+            if (npieces == 1) {
+                const int64_t aligned = (c_begin + per_wg - 1) / per_wg * per_wg;
+                if (aligned < c_end) rot = aligned - c_begin;
+            }
+            piece = (int)(vb - tile_first / per_wg);            // ranges that reached this tile before this one
         }
+        const int64_t len = c_end - c_begin;
+        if (len <= 0) continue;                                 // the same for the whole workgroup
         auto kstep_at = [&](int64_t i) {
             int64_t c = i + rot;
             if (c >= len) c -= len;
             return c_begin + c;
         };
-        const int piece = (int)(vb - tile_first / per_wg);      // ranges that reached this tile before this one
         // tile -> (I, J): I >= J, row-major over the lower triangle; or, for a list of tile rows (rect.cb > 0: two
-        // groups of rect.cb tile rows, the second starting at tile row rect.gap), all tile columns of those rows
+        // groups of rect.cb tile rows, the second starting at tile row rect.gap), all tile columns of those rows;
+        // or, in step, the lower triangle in blocks of 8 x 8 tiles (block rows top down, blocks left to right, tiles
+        // row-major inside a block): 32 consecutive tiles touch about 12 row blocks of the operands, not 33
         int I, J;
         if (rect.cb > 0) {
             const int ntj = dpad / IT, ri = tile / ntj;
             J = tile - ri * ntj;
             I = ri < rect.cb ? ri : ri - rect.cb + rect.gap;
+        } else if (ls.full > 0) {
+            const int nt = dpad / IT;
+            int Ib = 0, before = 0, rows, cnt;
+            for (;; ++Ib) {
+                rows = min(8, nt - 8 * Ib);
+                cnt = rows * 8 * Ib + rows * (rows + 1) / 2;
+                if (tile < before + cnt) break;
+                before += cnt;
+            }
+            int w = tile - before;
+            if (w < rows * 8 * Ib) {
+                const int Jb = w / (rows * 8);
+                w -= Jb * rows * 8;
+                I = 8 * Ib + w / 8;
+                J = 8 * Jb + w % 8;
+            } else {
+                w -= rows * 8 * Ib;
+                int li = 0;
+                while ((li + 1) * (li + 2) / 2 <= w) ++li;
+                I = 8 * Ib + li;
+                J = 8 * Ib + w - li * (li + 1) / 2;
+            }
         } else {
             I = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
             while ((I + 1) * (I + 2) / 2 <= tile) ++I;
@@ -466,7 +519,27 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
 }
 
 
-struct I8Plan { int nt, wgs; int64_t ksteps, items, per_wg; };
+struct I8Plan { int nt, wgs; int64_t ksteps, items, per_wg; I8Lockstep ls; };
+
+// Digits that fit the 256 MB memory-side cache are served from it however the workgroups walk them; beyond that,
+// with at least one tile per workgroup, the ranges below leave every workgroup at a k-step of its own and every
+// operand block is fetched from memory again by each tile that uses it (d = 4608, n = 49152: 37 GB for 1.1 GB of
+// digits, 5 TB/s, and the kernel waits for it).  Then the tiles are taken in step instead.
+constexpr size_t I8_INSTEP_MIN_BYTES = (size_t)256 << 20;
+constexpr int I8_MAX_PIECES = 8;
+
+static bool i8_instep_wanted(int d, int64_t n, I8Rect rect)
+{
+    const int64_t nt = i8_dpad(d) / IT;
+    return rect.cb == 0 && nt * (nt + 1) / 2 >= I8_WGS && i8_planes_bytes(d, n) > I8_INSTEP_MIN_BYTES;
+}
+
+int xxt_i8_wanted_splits(int d, int64_t n)
+{
+    if (!i8_instep_wanted(d, n, I8Rect())) return 0;
+    const int64_t fit = ((int64_t)4 << 30) / ((int64_t)d * d * (int64_t)sizeof(double));     // at most 4 GiB of slabs
+    return (int)(fit < 2 ? 2 : (fit > I8_MAX_PIECES ? I8_MAX_PIECES : fit));
+}
 
 static I8Plan i8_plan(int d, int64_t n, int splits, I8Rect rect)
 {
@@ -474,6 +547,33 @@ static I8Plan i8_plan(int d, int64_t n, int splits, I8Rect rect)
     p.nt = i8_dpad(d) / IT;
     p.ksteps = i8_ksteps(n);
     const int64_t tiles = rect.cb > 0 ? (int64_t)2 * rect.cb * p.nt : (int64_t)p.nt * (p.nt + 1) / 2;
+    if (i8_instep_wanted(d, n, rect)) {
+        // Whole rounds of one tile per workgroup, then the rem tiles left over in `pieces` parts each (part j of a
+        // tile goes to slab j): the number of parts that ends soonest, where a slab more is charged what clearing
+        // and re-reading it costs -- about d^2 / 2^20 k-steps (a k-step of a workgroup takes 1.8 us).
+        const int full = (int)(tiles / I8_WGS), rem = (int)(tiles - (int64_t)full * I8_WGS);
+        const int64_t slab_steps = (int64_t)d * d / (1 << 20) + 1;
+        int best_p = 0;
+        int64_t best_cost = 0, best_len = 0;
+        for (int q = 1; rem > 0 && q <= splits && q <= I8_MAX_PIECES; ++q) {
+            const int64_t len = (p.ksteps + q - 1) / q;
+            const int64_t rounds = ((int64_t)rem * q + I8_WGS - 1) / I8_WGS;
+            const int64_t cost = rounds * len + q * slab_steps;
+            if (best_p == 0 || cost < best_cost) { best_p = q; best_cost = cost; best_len = len; }
+        }
+        // in step unless the left-over rounds cost more than 10 % over an even split of all the work
+        const int64_t total = (int64_t)full * p.ksteps + (rem > 0 ? best_cost - best_p * slab_steps : 0);
+        if ((rem == 0 || best_p > 0) && total * I8_WGS * 10 <= tiles * p.ksteps * 11) {
+            p.ls.full = full;
+            p.ls.rem = rem;
+            p.ls.pieces = best_p;
+            p.ls.piece_len = best_len;
+            p.items = 0;
+            p.per_wg = 1;
+            p.wgs = I8_WGS;
+            return p;
+        }
+    }
     p.items = tiles * p.ksteps;
     p.per_wg = (p.items + I8_WGS - 1) / I8_WGS;
     // a tile meets at most ceil(ksteps / per_wg) + 1 ranges; that must not exceed the slabs
@@ -487,6 +587,7 @@ static I8Plan i8_plan(int d, int64_t n, int splits, I8Rect rect)
 int xxt_i8_slabs_touched(int d, int64_t n, int splits, I8Rect rect)
 {
     const I8Plan pl = i8_plan(d, n, splits, rect);
+    if (pl.ls.full > 0) return pl.ls.pieces > 1 ? pl.ls.pieces : 1;
     const int64_t p = (pl.ksteps + pl.per_wg - 1) / pl.per_wg + 1;
     return (int)(p < splits ? p : splits);
 }
@@ -547,9 +648,9 @@ hipError_t launch_xxt_i8(hipStream_t s, const signed char* planes, const int* sh
     const I8Plan pl = i8_plan(d, n, splits, rect);
     // pieces per tile, rounded: the number of classes of ranges (see the kernel)
     int classes = (int)((pl.ksteps + pl.per_wg / 2) / pl.per_wg);
-    classes = classes < 1 ? 1 : (classes > pl.wgs ? pl.wgs : classes);
+    classes = classes < 1 || pl.ls.full > 0 ? 1 : (classes > pl.wgs ? pl.wgs : classes);
     hipExtLaunchKernelGGL(xxt_i8_kernel, dim3(pl.wgs), dim3(512), 0, s, ev.start, ev.stop, 0, planes, sh, d, i8_dpad(d),
-                          pl.ksteps, Hpart, pl.per_wg, pl.items, classes, rect);
+                          pl.ksteps, Hpart, pl.per_wg, pl.items, classes, rect, pl.ls);
     return hipGetLastError();
 }
 

@@ -254,6 +254,44 @@ def test_hessian_by_tap_offsets_rejects_a_strided_later_call(fobq, ctx):
     fobq.fobq_hessian_finalize(ctx.handle, None)
 
 
+# At least one 128 x 128 tile per workgroup (256 tiles: d > 2816) and more digits than the memory-side cache holds:
+# the workgroups take the tiles in step -- whole rounds, then the tiles left over in several parts, one slab each.
+@pytest.mark.parametrize("d,n,chunk", [
+    (2900, 18700, None),       # 276 tiles: one round and 20 tiles left over, in 8 parts; ragged d and n
+    (3001, 36000, 20000),      # 300 tiles, 44 left over; the second call (16000 columns) is short enough for the
+                               # ranges of the smaller layers, into the same slabs
+])
+def test_hessian_int8_slices_tiles_in_step_matches_oracle(fobq, ctx, d, n, chunk):
+    _say(f"int8-slice hessian, tiles in step d={d} n={n} chunk={chunk}")
+    X = workloads.relu_normal_f32((d, n), 6, d)
+    ref = oracle.hessian(X)
+    H = torch.empty((d, d), dtype=torch.float64, device="cuda")
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)
+    ctx.hessian(_dev(X), chunk=chunk, H_out=H)
+    torch.cuda.synchronize()
+    _check_int8_hessian(H.cpu().numpy(), ref)
+    H2 = torch.empty_like(H)                 # a second accumulation on the context, with the slabs already grown
+    ctx.hessian(_dev(X), chunk=chunk, H_out=H2)
+    torch.cuda.synchronize()
+    assert torch.equal(H, H2)
+
+
+def test_hessian_int8_slices_tiles_in_step_from_feature_maps(fobq, ctx):
+    # stride 2 (so not by tap offsets), d = 2880 = 23 tile rows, 20000 output pixels
+    n, h, w, c, k, stride, pad = 8, 100, 100, 320, 3, 2, 1
+    _say(f"int8-slice hessian_conv, tiles in step n={n} h={h} w={w} c={c} k={k} stride={stride}")
+    rng = np.random.default_rng(811)
+    maps = np.maximum(rng.standard_normal((n, h, w, c)), 0).astype(np.float32)
+    X = workloads.im2col(maps, k, stride, pad)
+    assert X.shape == (2880, 20000)
+    ref = oracle.hessian(X)
+    H = torch.empty((2880, 2880), dtype=torch.float64, device="cuda")
+    ctx.set_hessian_mode(fobq.HESSIAN_INT8_SLICES)
+    ctx.hessian_conv(_dev(maps), k, stride, pad, H_out=H)
+    torch.cuda.synchronize()
+    _check_int8_hessian(H.cpu().numpy(), ref)
+
+
 @pytest.mark.slow
 def test_hessian_int8_slices_long_pieces_fold_in_between(fobq, ctx):
     # 384 rows x 0.72 M columns: 6 tiles x 22528 k-steps over 256 workgroups = 528 k-steps per piece, more than
