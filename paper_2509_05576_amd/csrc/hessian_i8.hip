@@ -18,9 +18,9 @@
 // at most 5 products per accumulator, |D D'| <= 2^14, 2^14 columns  ->  |sum| <= 5 * 2^28 < 2^31.
 //
 // Three kernels: row_shift_kernel (per-row exponent of a call), slice_kernel (digits, in the order the
-// matrix kernel wants them), xxt_i8_kernel (persistent workgroups, one contiguous range of
-// (tile, k-step) items each, 128 x 128 tiles on and below the diagonal, operands copied global -> LDS
-// without passing through registers).
+// matrix kernel wants them), xxt_i8_kernel (persistent workgroups, 128 x 128 tiles on and below the diagonal,
+// operands copied global -> LDS without passing through registers; a workgroup takes one contiguous range of
+// (tile, k-step) items, or, for wide layers whose digits no cache holds, whole tiles in step with the others).
 #include <hip/hip_ext.h>
 
 #include <type_traits>
@@ -283,7 +283,8 @@ __global__ __launch_bounds__(256) void slice_conv_kernel(const float* __restrict
 // The matrix kernel.  Items are (tile, k-step) pairs, tile-major over the 128 x 128 tiles on and below the
 // diagonal; persistent workgroup vb takes items [vb * per_wg, (vb + 1) * per_wg).  The part of a tile done by
 // one workgroup is a piece; piece p of a tile goes to slab p of Hpart, and one workgroup owns a given
-// (tile, piece), so the fp64 sums do not depend on the order in which workgroups finish.
+// (tile, piece), so the fp64 sums do not depend on the order in which workgroups finish.  With ls.full > 0 the
+// workgroups go through the tiles in rounds instead (see i8_plan and the comments in the kernel).
 // A workgroup is 8 wavefronts (see the kernel); the operands are copied global -> LDS directly
 // (global_load_lds_dwordx4: no staging registers), the copy of k-step q + 1 running while the MFMAs of k-step q issue.
 // 16 bytes per lane from global memory straight into LDS: lane l's bytes land at dst_block + OFF + 16 l, read
