@@ -560,7 +560,11 @@ __device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int 
 // panel is stored once instead of being recomputed by every tile (one product per tile instead of three):
 // PANEL_ONLY = workgroup i computes and stores L21_i (nothing else), PANEL_STORED = the trailing launch that
 // follows it and takes L21_i, L21_j from L (L must not be null; no inverse tiles ride along).
-enum { PANEL_FUSED = 0, PANEL_ONLY = 1, PANEL_STORED = 2 };
+// Two such panels can share one pass over the trailing matrix, which is what bounds those launches: after the
+// first panel of a pair only the next panel's tiles are updated (PANEL_NEAR: workgroup i owns tile (i, 0)), after the
+// second every trailing tile takes both panels, the older one first (PANEL_STORED2: the 128 columns o - 64 .. o + 63
+// of L) -- the same operations on every element in the same order as two PANEL_STORED launches.
+enum { PANEL_FUSED = 0, PANEL_ONLY = 1, PANEL_STORED = 2, PANEL_NEAR = 3, PANEL_STORED2 = 4 };
 template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
                                                        const double* __restrict__ Dinv, double* __restrict__ L,
@@ -610,19 +614,30 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     const int r0 = o + NB;
     int ti, tj;
     if (MODE == PANEL_ONLY) { ti = bid; tj = bid; }      // workgroup i: row tile i of the panel (ntrail = row tiles)
+    else if (MODE == PANEL_NEAR) { ti = bid; tj = 0; }   // workgroup i: tile (i, 0), the next panel (ntrail = row tiles)
     else tri_decode(bid, ti, tj);
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
+    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_NEAR || MODE == PANEL_STORED2;
 
     d4 c[2];
-    if (MODE == PANEL_STORED) {
-        // the panel blocks L21_i, L21_j as the panel launch stored them; the tile itself in flight meanwhile
-        double pa[8], pb[8];
+    if (STORED) {
+        // the panel blocks L21_i, L21_j as the panel launch(es) stored them; the tile itself in flight meanwhile
+        const int o1 = MODE == PANEL_STORED2 ? o - NB : o;      // the panel that is applied first
+        double pa[8], pb[8], qa[8], qb[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int y = wave + 8 * u, x = lane;
-            pa[u] = L[(int64_t)min(mi0 + y, d - 1) * d + o + x];
-            pb[u] = L[(int64_t)min(mj0 + y, d - 1) * d + o + x];
+            pa[u] = L[(int64_t)min(mi0 + y, d - 1) * d + o1 + x];
+            pb[u] = L[(int64_t)min(mj0 + y, d - 1) * d + o1 + x];
+        }
+        if (MODE == PANEL_STORED2) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int y = wave + 8 * u, x = lane;
+                qa[u] = L[(int64_t)min(mi0 + y, d - 1) * d + o + x];
+                qb[u] = L[(int64_t)min(mj0 + y, d - 1) * d + o + x];
+            }
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -638,6 +653,24 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
             if (!diag_tile) Pj[y * DL + x] = pb[u];
         }
         __syncthreads();
+        if (MODE == PANEL_STORED2) {
+            // the older panel's product here, then the newer panel takes its place in LDS for the product below
+            const double* Q1 = diag_tile ? Pi : Pj;
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) {
+                const double a = -Pi[(wr * 16 + fr) * DL + 4 * ks + fq];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Q1[(wn * 32 + j * 16 + fr) * DL + 4 * ks + fq], c[j]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int y = wave + 8 * u, x = lane;
+                Pi[y * DL + x] = qa[u];
+                if (!diag_tile) Pj[y * DL + x] = qb[u];
+            }
+            __syncthreads();
+        }
     } else {
     // Panel product L21 = A21 L11^-T: L11^-1 is lower triangular, so the 16 columns of column tile ct
     // (of 4) only need the k-steps 0 .. 4 ct + 3.  The wavefronts with wn = 0 take the column tiles
@@ -760,8 +793,22 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
             // throughput-bound launch: the panel once (T workgroups), then one product per trailing tile
             hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
                                Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0, c->cus);
-            hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED>), dim3(ntrail + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L,
-                               Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
+            const int T2 = T - 1, ntrail2 = T2 * (T2 + 1) / 2;
+            if (ntrail2 >= STORED_PANEL_TILES) {
+                // two panels, one pass over the trailing matrix: after this panel only the next panel's tiles (and its
+                // diagonal block, workgroup 0) are updated; the launch after the next panel applies both to the rest
+                hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_NEAR>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                                   Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0, c->cus);
+                o += NB;
+                ++it;
+                hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T2), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                                   Dinv[(it + 1) & 1], flag, T2, 0, Sacc, Hinv, mate_flag, 0, c->cus);
+                hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED2>), dim3(ntrail2 + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1],
+                                   L, Linv, Dinv[(it + 1) & 1], flag, ntrail2, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
+            } else {
+                hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED>), dim3(ntrail + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1],
+                                   L, Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
+            }
         } else if (tiles <= DENSE_LAUNCH_TILES)
             hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_FUSED>), dim3(tiles), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
                                Dinv[(it + 1) & 1], flag, ntrail, ninv, Sacc, Hinv, mate_flag, 0, c->cus);
@@ -1012,7 +1059,8 @@ __global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict_
 //   2. A22(ti, tj) -= Un12_i^T U12_j        (Eq. 12 for the 64 columns of the panel at once);
 //   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
 // MODE as for chol_iter_kernel: PANEL_ONLY = workgroup j computes and stores the pivot rows U12_j, Un12_j right of the
-// block for its tile column; PANEL_STORED = the trailing launch that follows and takes them from U and Un.
+// block for its tile column; PANEL_STORED = the trailing launch that follows and takes them from U and Un;
+// PANEL_NEAR = only the tiles (0, j) of the next panel's rows, PANEL_STORED2 = the 128 pivot rows o - 64 .. o + 63 at once.
 template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__ A, int d, int o,
                                                        const double* __restrict__ G, const double* __restrict__ rinv,
@@ -1040,19 +1088,30 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     const int r0 = o + NB;
     int ti, tj;
     if (MODE == PANEL_ONLY) { ti = bid; tj = bid; }      // workgroup j: tile column j of the pivot rows
+    else if (MODE == PANEL_NEAR) { ti = 0; tj = bid; }   // workgroup j: tile (0, j), the rows of the next panel
     else tri_decode(bid, tj, ti);     // ti <= tj
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
+    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_NEAR || MODE == PANEL_STORED2;
 
     d4 c[2];
-    if (MODE == PANEL_STORED) {
-        // Un12_i and U12_j as the panel launch stored them; the trailing tile itself in flight meanwhile
-        double pa[8], pb[8];
+    if (STORED) {
+        // Un12_i and U12_j as the panel launch(es) stored them; the trailing tile itself in flight meanwhile
+        const int o1 = MODE == PANEL_STORED2 ? o - NB : o;      // the panel that is applied first
+        double pa[8], pb[8], qa[8], qb[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int y = wave + 8 * u, x = lane;
-            pa[u] = Un[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
-            pb[u] = U[(int64_t)(o + y) * d + min(cj0 + x, d - 1)];
+            pa[u] = Un[(int64_t)(o1 + y) * d + min(ci0 + x, d - 1)];
+            pb[u] = U[(int64_t)(o1 + y) * d + min(cj0 + x, d - 1)];
+        }
+        if (MODE == PANEL_STORED2) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int y = wave + 8 * u, x = lane;
+                qa[u] = Un[(int64_t)(o + y) * d + min(ci0 + x, d - 1)];
+                qb[u] = U[(int64_t)(o + y) * d + min(cj0 + x, d - 1)];
+            }
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -1068,6 +1127,23 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
             Pj[y * DL + x] = pb[u];
         }
         __syncthreads();
+        if (MODE == PANEL_STORED2) {
+            // the older panel's product here, then the newer panel takes its place in LDS for the product below
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) {
+                const double a = -Pi[(4 * ks + fq) * DL + wr * 16 + fr];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) c[j] = mfma4(a, Pj[(4 * ks + fq) * DL + w2 * 32 + j * 16 + fr], c[j]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int y = wave + 8 * u, x = lane;
+                Pi[y * DL + x] = qa[u];
+                Pj[y * DL + x] = qb[u];
+            }
+            __syncthreads();
+        }
     } else {
     // Pivot rows U12 = G A12: G is lower triangular, so the 16 rows of row tile rt (of 4) only need
     // the k-steps 0 .. 4 rt + 3.  The wavefronts with w2 = 0 take the row tiles 0 and 3, those with
@@ -1206,9 +1282,27 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
                 // throughput-bound launch: the pivot rows once (T workgroups), then one product per trailing tile
                 hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, A, d, o, (const double*)Gb[it & 1],
                                    (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
-                hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED>), dim3(tiles + 1), dim3(NT), 0, s, nullptr, done, 0, A,
-                                      d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
-                                      rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
+                const int T2 = T - 1, tiles2 = T2 * (T2 + 1) / 2;
+                if (tiles2 >= STORED_PANEL_TILES) {
+                    // two panels, one pass over the trailing matrix (see chol_iter_kernel): the next panel's rows now,
+                    // both panels' update of everything else after the next panel
+                    hipExtLaunchKernelGGL((elim_iter_kernel<2, PANEL_NEAR>), dim3(T), dim3(NT), 0, s, nullptr, done, 0, A, d, o,
+                                          (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                          rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
+                    o += NB;
+                    ++it;
+                    hipEvent_t done2 = (rows_ready && it < (int)rows_ready->size()) ? (*rows_ready)[it] : nullptr;
+                    hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T2), dim3(NT), 0, s, A, d, o,
+                                       (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                       rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
+                    hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED2>), dim3(tiles2 + 1), dim3(NT), 0, s, nullptr, done2, 0,
+                                          A, d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                          rb[(it + 1) & 1], flag, mate_flag, ++c->mate_epoch, c->cus);
+                } else {
+                    hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED>), dim3(tiles + 1), dim3(NT), 0, s, nullptr, done, 0, A,
+                                          d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                          rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
+                }
             } else if (tiles <= DENSE_LAUNCH_TILES)
                 hipExtLaunchKernelGGL((elim_iter_kernel<2, PANEL_FUSED>), dim3(tiles + (mate ? 1 : 0)), dim3(NT), 0, s, nullptr, done, 0, A,
                                       d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
