@@ -617,6 +617,30 @@ def test_stop_after_snapshots(fobq, ctx, block):
         assert abs(float(out.loss.cpu()[0]) - ref.loss) <= 1e-9 * abs(ref.loss) + 1e-300
 
 
+def test_stop_after_snapshots_of_a_tall_layer(fobq, ctx):
+    # many more rows than columns: the deferred compensation is most of the column loop's work.  Stops after an even and
+    # an odd number of blocks, inside a block, and at the end; the running weights must be the oracle's at each.
+    r, d, n = 1100, 330, 700
+    W, X = _problem(r, d, n, 14, w_std=0.05)
+    H = oracle.hessian(X)
+    Hd_, Wd_ = _dev(H), _dev(W)
+    full = ctx.quantize_layer(Wd_, Hd_, bits=4, block=0)
+    for t in [64, 128, 150, 192, 256, 300, 330]:
+        _say(f"tall snapshot t={t}")
+        out = ctx.quantize_layer(Wd_, Hd_, bits=4, block=0, stop_after=t, debug=True)
+        ref = oracle.quantize_layer(W, H=H, bits=4, steps=t)
+        p = out.perm.cpu().numpy()
+        ref = _oracle_with_gpu_perm(W, H, p, ref, bits=4, steps=t)
+        Ww = np.empty((r, d))
+        Ww[:, p] = out.W_work.cpu().numpy()
+        assert np.allclose(Ww, ref.W_work, rtol=1e-9, atol=1e-12)
+        assert np.array_equal(out.codes.cpu().numpy().astype(np.int64), ref.codes)
+        assert abs(float(out.loss.cpu()[0]) - ref.loss) <= 1e-9 * abs(ref.loss) + 1e-300
+    # the same layer with the unblocked path (one pass per column): same codes
+    one = ctx.quantize_layer(Wd_, Hd_, bits=4, block=1)
+    assert torch.equal(full.codes, one.codes)
+
+
 def test_blocked_and_unblocked_agree_and_runs_are_deterministic(fobq, ctx):
     W, X = _problem(100, 260, 700, 11, w_std=0.05)
     Wd_ = _dev(W)
