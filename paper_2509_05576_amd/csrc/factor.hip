@@ -561,9 +561,10 @@ __device__ __forceinline__ void chol_lauum_tile(double* lds, int d, int kt, int 
 // PANEL_ONLY = workgroup i computes and stores L21_i (nothing else), PANEL_STORED = the trailing launch that
 // follows it and takes L21_i, L21_j from L (L must not be null; no inverse tiles ride along).
 // Two such panels can share one pass over the trailing matrix, which is what bounds those launches: after the
-// first panel of a pair only the next panel's tiles are updated (PANEL_NEAR: workgroup i owns tile (i, 0)), after the
-// second every trailing tile takes both panels, the older one first (PANEL_STORED2: the 128 columns o - 64 .. o + 63
-// of L) -- the same operations on every element in the same order as two PANEL_STORED launches.
+// first panel of a pair only the next panel's tiles are updated (PANEL_NEAR: one launch, workgroup i owns tile (i, 0),
+// recomputes L21_i and L21_0 like PANEL_FUSED and stores L21_i), after the second every trailing tile takes both
+// panels, the older one first (PANEL_STORED2: the 128 columns o - 64 .. o + 63 of L) -- the same operations on every
+// element in the same order as two single-panel launches.
 enum { PANEL_FUSED = 0, PANEL_ONLY = 1, PANEL_STORED = 2, PANEL_NEAR = 3, PANEL_STORED2 = 4 };
 template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__ Hd, int d, int o,
@@ -618,7 +619,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     else tri_decode(bid, ti, tj);
     const bool diag_tile = ti == tj;
     const int mi0 = r0 + NB * ti, mj0 = r0 + NB * tj;
-    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_NEAR || MODE == PANEL_STORED2;
+    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_STORED2;
 
     d4 c[2];
     if (STORED) {
@@ -704,7 +705,7 @@ __global__ __launch_bounds__(NT, WPS) void chol_iter_kernel(double* __restrict__
     }
     __syncthreads();
     // the tile itself: in flight during the panel product
-    if (MODE == PANEL_FUSED) {
+    if (MODE == PANEL_FUSED || MODE == PANEL_NEAR) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -790,9 +791,6 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
         const int nlau = Sacc ? it * (it + 1) / 2 : 0;  // tiles of Hinv that block row it - 1 of L^-1 adds to
         const int tiles = ntrail + ninv + nlau;
         if (!Sacc && L && ntrail >= STORED_PANEL_TILES) {
-            // throughput-bound launch: the panel once (T workgroups), then one product per trailing tile
-            hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
-                               Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0, c->cus);
             const int T2 = T - 1, ntrail2 = T2 * (T2 + 1) / 2;
             if (ntrail2 >= STORED_PANEL_TILES) {
                 // two panels, one pass over the trailing matrix: after this panel only the next panel's tiles (and its
@@ -806,6 +804,9 @@ hipError_t cholesky_lower(fobq_ctx* c, double* Hd, double* L, int d, double* Lin
                 hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED2>), dim3(ntrail2 + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1],
                                    L, Linv, Dinv[(it + 1) & 1], flag, ntrail2, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
             } else {
+                // throughput-bound launch: the panel once (T workgroups), then one product per trailing tile
+                hipLaunchKernelGGL((chol_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1], L, Linv,
+                                   Dinv[(it + 1) & 1], flag, T, 0, Sacc, Hinv, mate_flag, 0, c->cus);
                 hipLaunchKernelGGL((chol_iter_kernel<4, PANEL_STORED>), dim3(ntrail + 1), dim3(NT), 0, s, Hd, d, o, Dinv[it & 1],
                                    L, Linv, Dinv[(it + 1) & 1], flag, ntrail, 0, Sacc, Hinv, mate_flag, ++c->mate_epoch, c->cus);
             }
@@ -1060,7 +1061,8 @@ __global__ __launch_bounds__(NT) void elim_diag_kernel(const double* __restrict_
 //   3. workgroup 0 eliminates tile (0, 0), the next diagonal block, right away.
 // MODE as for chol_iter_kernel: PANEL_ONLY = workgroup j computes and stores the pivot rows U12_j, Un12_j right of the
 // block for its tile column; PANEL_STORED = the trailing launch that follows and takes them from U and Un;
-// PANEL_NEAR = only the tiles (0, j) of the next panel's rows, PANEL_STORED2 = the 128 pivot rows o - 64 .. o + 63 at once.
+// PANEL_NEAR = only the tiles (0, j) of the next panel's rows, each recomputing and storing its pivot rows;
+// PANEL_STORED2 = the 128 pivot rows o - 64 .. o + 63 at once.
 template <int WPS, int MODE>
 __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__ A, int d, int o,
                                                        const double* __restrict__ G, const double* __restrict__ rinv,
@@ -1092,7 +1094,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     else tri_decode(bid, tj, ti);     // ti <= tj
     const bool diag_tile = ti == tj;
     const int ci0 = r0 + NB * ti, cj0 = r0 + NB * tj;
-    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_NEAR || MODE == PANEL_STORED2;
+    constexpr bool STORED = MODE == PANEL_STORED || MODE == PANEL_STORED2;
 
     d4 c[2];
     if (STORED) {
@@ -1178,7 +1180,7 @@ __global__ __launch_bounds__(NT, WPS) void elim_iter_kernel(double* __restrict__
     if (tid < NB) rs[tid] = rsv;
     __syncthreads();
     // the trailing tile itself (rows of slice wr, the 32 columns of half w2): in flight during the product
-    if (MODE == PANEL_FUSED) {
+    if (MODE == PANEL_FUSED || MODE == PANEL_NEAR) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -1279,9 +1281,6 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
             const int epoch = mate ? ++c->mate_epoch : 0;
             int* mate_flag = c->flags.as<int>() + FLAG_WORD_MATE;
             if (tiles >= STORED_PANEL_TILES) {
-                // throughput-bound launch: the pivot rows once (T workgroups), then one product per trailing tile
-                hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, A, d, o, (const double*)Gb[it & 1],
-                                   (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1], rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
                 const int T2 = T - 1, tiles2 = T2 * (T2 + 1) / 2;
                 if (tiles2 >= STORED_PANEL_TILES) {
                     // two panels, one pass over the trailing matrix (see chol_iter_kernel): the next panel's rows now,
@@ -1299,6 +1298,10 @@ hipError_t eliminate_blocked(fobq_ctx* c, double* A, int d, int steps, int block
                                           A, d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
                                           rb[(it + 1) & 1], flag, mate_flag, ++c->mate_epoch, c->cus);
                 } else {
+                    // throughput-bound launch: the pivot rows once (T workgroups), then one product per trailing tile
+                    hipLaunchKernelGGL((elim_iter_kernel<2, PANEL_ONLY>), dim3(T), dim3(NT), 0, s, A, d, o,
+                                       (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
+                                       rb[(it + 1) & 1], flag, mate_flag, 0, c->cus);
                     hipExtLaunchKernelGGL((elim_iter_kernel<4, PANEL_STORED>), dim3(tiles + 1), dim3(NT), 0, s, nullptr, done, 0, A,
                                           d, o, (const double*)Gb[it & 1], (const double*)rb[it & 1], U, Un, Gb[(it + 1) & 1],
                                           rb[(it + 1) & 1], flag, mate_flag, epoch, c->cus);
