@@ -290,6 +290,12 @@ def test_hessian_int8_slices_tiles_in_step_from_feature_maps(fobq, ctx):
     ctx.hessian_conv(_dev(maps), k, stride, pad, H_out=H)
     torch.cuda.synchronize()
     _check_int8_hessian(H.cpu().numpy(), ref)
+    # the next accumulation on the context is a small one again (ranges, its own count of slabs)
+    Xs = np.maximum(rng.standard_normal((500, 3000)), 0).astype(np.float32)
+    Hs = torch.empty((500, 500), dtype=torch.float64, device="cuda")
+    ctx.hessian(_dev(Xs), H_out=Hs)
+    torch.cuda.synchronize()
+    _check_int8_hessian(Hs.cpu().numpy(), oracle.hessian(Xs))
 
 
 @pytest.mark.slow
