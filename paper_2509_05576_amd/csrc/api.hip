@@ -586,7 +586,8 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
                                              "must have stride 1 and a map of at least k x k");
     }
     if (offsets) i8 = true;
-    const I8Rect rect = offsets ? I8Rect{rect_cb, rect_gap} : I8Rect();
+    // 64 channels, 3 x 3: the base taps are the first halves of tile rows 0 and 1, formed as one tile row
+    const I8Rect rect = offsets ? I8Rect{rect_cb, rect_gap, (c == 64 && k == 3) ? 1 : 0} : I8Rect();
     const int64_t blk = i8 ? i8_block_columns(d) : npix;
     FOBQ_TRY(ctx->maps_pad.ensure((size_t)(n_img + 1) * hp * wp * c * sizeof(float)), "workspace padded maps");
     if (i8) {

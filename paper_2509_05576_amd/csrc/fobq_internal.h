@@ -196,8 +196,9 @@ hipError_t launch_hessian_finalize(hipStream_t s, double* Hpart, int splits, int
 int i8_dpad(int d);
 size_t i8_planes_bytes(int d, int64_t n);
 // rect.cb > 0: instead of the lower triangle, all tile columns of two groups of rect.cb tile rows (the second group
-// starts at tile row rect.gap), every entry stored
-struct I8Rect { int cb = 0, gap = 0; };
+// starts at tile row rect.gap), every entry stored.  rect.half (with cb = gap = 1): the two groups are the first 64 rows
+// of tile rows 0 and 1 only, and one tile row made of those 128 rows is formed instead of two.
+struct I8Rect { int cb = 0, gap = 0, half = 0; };
 // full > 0: the workgroups go through the tiles in step (see xxt_i8_kernel): `full` rounds of whole tiles, then the
 // `rem` tiles left over, each cut into `pieces` parts of piece_len k-steps
 struct I8Lockstep { int full = 0, rem = 0, pieces = 0; int64_t piece_len = 0; };

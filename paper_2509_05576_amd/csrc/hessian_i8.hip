@@ -395,7 +395,10 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
         // or, in step, the lower triangle in blocks of 8 x 8 tiles (block rows top down, blocks left to right, tiles
         // row-major inside a block): 32 consecutive tiles touch about 12 row blocks of the operands, not 33
         int I, J;
-        if (rect.cb > 0) {
+        if (rect.half) {
+            I = 0;
+            J = tile;
+        } else if (rect.cb > 0) {
             const int ntj = dpad / IT, ri = tile / ntj;
             J = tile - ri * ntj;
             I = ri < rect.cb ? ri : ri - rect.cb + rect.gap;
@@ -437,7 +440,9 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
             lds_copy_block<-2048>(g, l); lds_copy_block<-1024>(g, l); lds_copy_block<0>(g, l);
             lds_copy_block<1024>(g, l);  lds_copy_block<2048>(g, l);
         };
-        const signed char* __restrict__ pa = P + ((int64_t)(i0 / 32 + (wave & 3)) * NS + 2) * 1024 + lane * 16;
+        // A's four blocks of 32 rows: consecutive, or (rect.half) the rows 0 .. 63 and 128 .. 191
+        const int ablk = rect.half ? (wave & 1) + 4 * ((wave >> 1) & 1) : i0 / 32 + (wave & 3);
+        const signed char* __restrict__ pa = P + ((int64_t)ablk * NS + 2) * 1024 + lane * 16;
         const signed char* __restrict__ pb = P + ((int64_t)(j0 / 32 + (wave % NB)) * NS + 2) * 1024 + lane * 16;
         auto issue = [&](int buf, int64_t q) {      // wavefronts 0..3 take A's row blocks, 4..7 B's
             if (wave < 4) copy5(pa + q * step_bytes, &As[buf][wave][2][0]);
@@ -505,7 +510,7 @@ __global__ __launch_bounds__(512) void xxt_i8_kernel(const signed char* __restri
             for (int i = 0; i < 2; ++i) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = i0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const int row = i0 + wm * (rect.half ? 128 : 64) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                     if (row < d && col < d && (!tri || col <= row)) {
                         double sum = 0.0;
 #pragma unroll
@@ -547,7 +552,7 @@ static I8Plan i8_plan(int d, int64_t n, int splits, I8Rect rect)
     I8Plan p;
     p.nt = i8_dpad(d) / IT;
     p.ksteps = i8_ksteps(n);
-    const int64_t tiles = rect.cb > 0 ? (int64_t)2 * rect.cb * p.nt : (int64_t)p.nt * (p.nt + 1) / 2;
+    const int64_t tiles = rect.half ? p.nt : rect.cb > 0 ? (int64_t)2 * rect.cb * p.nt : (int64_t)p.nt * (p.nt + 1) / 2;
     if (i8_instep_wanted(d, n, rect)) {
         // Whole rounds of one tile per workgroup, then the rem tiles left over in `pieces` parts each (part j of a
         // tile goes to slab j): the number of parts that ends soonest, where a slab more is charged what clearing
