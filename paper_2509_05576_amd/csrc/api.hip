@@ -473,11 +473,12 @@ static int clear_slabs(fobq_ctx* ctx, int64_t n, bool conv, bool i8 = false)
 }
 
 // Before its first launch an accumulation may still take more slabs than fobq_hessian_begin reserved (the digit-product
-// kernel wants some for a wide layer with a long calibration dimension); a failure leaves no accumulation open.
-static int grow_i8_slabs(fobq_ctx* ctx, int64_t n_launch)
+// kernel wants some for a wide layer with a long calibration dimension, and for a convolution taken by tap offsets, whose
+// few tiles are cut into more pieces each); a failure leaves no accumulation open.
+static int grow_i8_slabs(fobq_ctx* ctx, int64_t n_launch, I8Rect rect = I8Rect())
 {
     if (ctx->h_n > 0 || ctx->h_zeroed > 0) return FOBQ_OK;
-    const int want = xxt_i8_wanted_splits((int)ctx->h_d, n_launch);
+    const int want = xxt_i8_wanted_splits((int)ctx->h_d, n_launch, rect);
     if (want <= ctx->h_splits) return FOBQ_OK;
     const hipError_t e = ctx->Hpart.ensure((size_t)ctx->h_d * ctx->h_d * sizeof(double) * want);
     if (e != hipSuccess) {
@@ -594,10 +595,8 @@ int fobq_hessian_accumulate_conv(fobq_ctx* ctx, const float* maps, int64_t n_img
         FOBQ_TRY(ctx->i8planes.ensure(i8_planes_bytes(d, npix < blk ? npix : blk)), "workspace digit planes");
         FOBQ_TRY(ctx->i8sh.ensure((size_t)i8_dpad(d) * sizeof(int)), "workspace row shifts");
         FOBQ_TRY(ctx->i8amax.ensure((size_t)c * sizeof(unsigned)), "workspace channel maxima");
-        if (!offsets) {
-            const int grc = grow_i8_slabs(ctx, npix < blk ? npix : blk);
-            if (grc) return grc;
-        }
+        const int grc = grow_i8_slabs(ctx, npix < blk ? npix : blk, rect);
+        if (grc) return grc;
     }
     if (offsets) {
         FOBQ_TRY(ctx->hcorr.ensure((size_t)d * d * sizeof(double)), "workspace corrections");

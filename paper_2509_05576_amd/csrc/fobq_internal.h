@@ -204,7 +204,7 @@ struct I8Rect { int cb = 0, gap = 0, half = 0; };
 struct I8Lockstep { int full = 0, rem = 0, pieces = 0; int64_t piece_len = 0; };
 int xxt_i8_slabs_touched(int d, int64_t n, int splits, I8Rect rect = I8Rect());
 // slabs of partial sums that a launch over n columns would like to have (0: no wish beyond xxt_pick_splits)
-int xxt_i8_wanted_splits(int d, int64_t n);
+int xxt_i8_wanted_splits(int d, int64_t n, I8Rect rect = I8Rect());
 int64_t i8_block_columns(int d);      // most columns one launch of the matrix kernel takes (bounds the digit scratch)
 hipError_t launch_i8_row_shifts(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, int* sh, int* nonfinite);
 hipError_t launch_i8_slice(hipStream_t s, const float* X, int64_t ld, int d, int64_t n, const int* sh, signed char* planes);

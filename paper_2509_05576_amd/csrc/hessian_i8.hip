@@ -540,10 +540,17 @@ static bool i8_instep_wanted(int d, int64_t n, I8Rect rect)
     return rect.cb == 0 && nt * (nt + 1) / 2 >= I8_WGS && i8_planes_bytes(d, n) > I8_INSTEP_MIN_BYTES;
 }
 
-int xxt_i8_wanted_splits(int d, int64_t n)
+int xxt_i8_wanted_splits(int d, int64_t n, I8Rect rect)
 {
-    if (!i8_instep_wanted(d, n, I8Rect())) return 0;
     const int64_t fit = ((int64_t)4 << 30) / ((int64_t)d * d * (int64_t)sizeof(double));     // at most 4 GiB of slabs
+    if (rect.cb > 0) {
+        // a list of tile rows has fewer tiles than the triangle that the context's count of slabs is made for: enough
+        // pieces per tile that every workgroup gets a range
+        const int64_t nt = i8_dpad(d) / IT, tiles = rect.half ? nt : 2 * rect.cb * nt;
+        const int64_t want = (I8_WGS + tiles - 1) / tiles + 1;
+        return (int)(want < fit ? want : (fit < 2 ? 2 : fit));
+    }
+    if (!i8_instep_wanted(d, n, rect)) return 0;
     return (int)(fit < 2 ? 2 : (fit > I8_MAX_PIECES ? I8_MAX_PIECES : fit));
 }
 
