@@ -238,7 +238,7 @@ def sweep(model: str, steps: int, warmup: int, concurrency: int, iid: bool, int8
             "config": {"workload": f"sweep_{model}: all layers, 4-bit per-row, damp 0.01, 128 images, "
                                    + ("every layer from an unfolded matrix of independent activations"
                                       if iid else "k x k and strided convolutions from their input maps"),
-                       "hessian_arithmetic": "int8 slices where d_col >= 384 (stride-1 k x k convolutions with a multiple of 128 channels by tap "
+                       "hessian_arithmetic": "int8 slices where d_col >= 384 (stride-1 k x k convolutions with a multiple of 64 channels by tap "
                                              "offsets), else fp64 MFMA" if int8 else "fp64 MFMA",
                        "weights": total_weights, "layers_in_flight": K, "input_bytes": input_bytes},
             "whole_model_seconds": round(med * 1e-3, 4), "runs_ms": [round(r, 2) for r in runs],
