@@ -84,25 +84,32 @@ bool offset_tables_build(int k, int pad, int h, int w, OffsetTables* tab)
 
 // ---------------------------------------------------------------------------
 // strips[half][job][c][c'] = sum over images and the job's positions q of M[q, c] * M[q + (dy, dx), c']  (fp64 MFMA on
-// exactly widened fp32 inputs), the positions cut into OFFSET_SPLITS contiguous parts whose sums are added later in a
-// fixed order.  One workgroup of 8 wavefronts (16 x 32 of the tile each: two per SIMD, as the fp64 matrix pipe
+// exactly widened fp32 inputs), the positions cut into `parts` contiguous parts whose sums are added later in a
+// fixed order (offset_parts: enough of them that a layer with few channels still fills the chip).  One workgroup of 8 wavefronts (16 x 32 of the tile each: two per SIMD, as the fp64 matrix pipe
 // wants) per (64 x 64 tile of channels, job, part); positions in chunks of 32 (a position is 64 contiguous floats per
 // operand), the loads of a chunk in flight while the chunk before is multiplied.
-constexpr int OFFSET_SPLITS = 2;
+constexpr int OFFSET_MIN_PARTS = 2, OFFSET_MAX_PARTS = 16;
+
+static int offset_parts(int njobs, int c)
+{
+    const int tiles = (c / 64) * (c / 64) * (njobs > 0 ? njobs : 1);
+    const int want = (512 + tiles - 1) / tiles;              // about two workgroups per compute unit
+    return want < OFFSET_MIN_PARTS ? OFFSET_MIN_PARTS : (want > OFFSET_MAX_PARTS ? OFFSET_MAX_PARTS : want);
+}
 
 __global__ __launch_bounds__(512) void offset_strip_kernel(const float* __restrict__ padded, int n_img, int hp, int wp, int c,
-                                                           OffsetTables tab, double* __restrict__ strips)
+                                                           OffsetTables tab, int parts, double* __restrict__ strips)
 {
     constexpr int PC = 32, LDW = 64 + 16;      // row stride 80 doubles: conflict-free 8-byte fragment reads per half-wave
     __shared__ double As[PC][LDW];
     __shared__ double Bs[PC][LDW];
-    const int jid = blockIdx.z / OFFSET_SPLITS, part = blockIdx.z % OFFSET_SPLITS;
+    const int jid = blockIdx.z / parts, part = blockIdx.z % parts;
     const OffsetJob job = tab.jobs[jid];
     const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wi = wave >> 1, wj = wave & 1;                 // rows 16 wi .., columns 32 wj ..
     const int64_t npos = (int64_t)n_img * job.len;
-    const int64_t per = ((npos + OFFSET_SPLITS - 1) / OFFSET_SPLITS + PC - 1) / PC * PC;
+    const int64_t per = ((npos + parts - 1) / parts + PC - 1) / PC * PC;
     const int64_t p_lo = part * per, p_hi = min(npos, p_lo + per);
     od4 acc[2];
     acc[0] = od4{0.0, 0.0, 0.0, 0.0};
@@ -149,8 +156,8 @@ __global__ __launch_bounds__(512) void offset_strip_kernel(const float* __restri
 }
 
 // corr[(ta c + ch), (tb c + ch')] += sum over the pair's terms of sign * strips[job][ch][ch'], tap-major d x d
-__global__ __launch_bounds__(256) void offset_apply_kernel(OffsetTables tab, const double* __restrict__ strips, int c, int d,
-                                                           double* __restrict__ corr)
+__global__ __launch_bounds__(256) void offset_apply_kernel(OffsetTables tab, const double* __restrict__ strips, int parts, int c,
+                                                           int d, double* __restrict__ corr)
 {
     const int p = blockIdx.y;
     const int e = blockIdx.x * 256 + threadIdx.x;
@@ -160,7 +167,7 @@ __global__ __launch_bounds__(256) void offset_apply_kernel(OffsetTables tab, con
     double s = 0.0;
     for (int t = t0; t < t1; ++t) {
         double v = 0.0;
-        for (int part = 0; part < OFFSET_SPLITS; ++part) v += strips[((int64_t)part * tab.njobs + tab.term_job[t]) * c * c + e];
+        for (int part = 0; part < parts; ++part) v += strips[((int64_t)part * tab.njobs + tab.term_job[t]) * c * c + e];
         s += (double)tab.term_sign[t] * v;
     }
     const int ch = e / c, ch2 = e - ch * c;
@@ -216,15 +223,16 @@ hipError_t launch_clear_slab_rows(hipStream_t s, double* Hpart, int d, int first
 }
 
 // the strips of one call (overwritten; offset_strips_bytes of scratch), then their signed sums into the correction matrix
-size_t offset_strips_bytes(int njobs, int c) { return (size_t)OFFSET_SPLITS * (njobs > 0 ? njobs : 1) * c * c * sizeof(double); }
+size_t offset_strips_bytes(int njobs, int c) { return (size_t)offset_parts(njobs, c) * (njobs > 0 ? njobs : 1) * c * c * sizeof(double); }
 
 hipError_t launch_offset_corrections(hipStream_t s, const float* padded, int n_img, int hp, int wp, int c, int d,
                                      const OffsetTables& tab, double* strips, double* corr)
 {
     if (tab.njobs == 0) return hipSuccess;
-    hipLaunchKernelGGL(offset_strip_kernel, dim3(c / 64, c / 64, tab.njobs * OFFSET_SPLITS), dim3(512), 0, s, padded, n_img, hp, wp, c,
-                       tab, strips);
-    hipLaunchKernelGGL(offset_apply_kernel, dim3((c * c + 255) / 256, tab.npairs), dim3(256), 0, s, tab, strips, c, d, corr);
+    const int parts = offset_parts(tab.njobs, c);
+    hipLaunchKernelGGL(offset_strip_kernel, dim3(c / 64, c / 64, tab.njobs * parts), dim3(512), 0, s, padded, n_img, hp, wp, c,
+                       tab, parts, strips);
+    hipLaunchKernelGGL(offset_apply_kernel, dim3((c * c + 255) / 256, tab.npairs), dim3(256), 0, s, tab, strips, parts, c, d, corr);
     return hipGetLastError();
 }
 
