@@ -292,6 +292,22 @@ int fobq_obq_rows(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, c
  * leaves the context usable. */
 int fobq_debug_fail_after(fobq_ctx* ctx, int n);
 
+/* Test hook for the host side of the tap-offset form of fobq_hessian_accumulate_conv (stride 1; needs no GPU
+ * and no context): the list of single-row / single-column correlations ("strips") and, for every pair of
+ * taps that is not taken from a base block row, the signed sum of strips that turns the base block with the
+ * same tap offset into the pair's block, for a k x k kernel on h x w maps padded by `pad`.  Written to out
+ * (host, int32) as
+ *   njobs, npairs, nterms,
+ *   njobs  x (kind, coord, start, len, dy, dx)   kind 0: row `coord` of the padded map, columns start .. start+len-1;
+ *                                                kind 1: column `coord`, rows start .. start+len-1; (dy, dx) = offset
+ *                                                of the second factor,
+ *   npairs x (tap_a, tap_b, first_term, end_term) taps as ky * k + kx,
+ *   nterms x (job, sign).
+ * *used = the number of words that takes; nothing is written when it exceeds cap (EINVAL), when an argument is
+ * out of range (EINVAL) or when the geometry does not fit the library's tables (ESTATE: such a call of
+ * fobq_hessian_accumulate_conv takes the general path). */
+int fobq_debug_offset_tables(int32_t k, int32_t pad, int64_t h, int64_t w, int32_t* out, int64_t cap, int64_t* used);
+
 /* Measurement aid for the X X^T kernel of the int8-slice mode (no part of the method): the rate, in
  * 1e12 int8 operations per second (multiply and add counted separately), at which this GPU's matrix
  * cores run that kernel's inner loop -- the 19 digit products of a k-step on 32 x 32 x 32 int8

@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.fobq_sensitivity.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), vp, vp]
     lib.fobq_sensitivity_static.argtypes = lib.fobq_sensitivity.argtypes
     lib.fobq_debug_fail_after.argtypes = [vp, i32]
+    lib.fobq_debug_offset_tables.argtypes = [i32, i32, i64, i64, ctypes.POINTER(i32), i64, ctypes.POINTER(i64)]
     lib.fobq_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
     lib.fobq_hessian_form.argtypes = [vp, ctypes.POINTER(i32)]
     lib.fobq_obq_rows.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(FobqOpts), i64, i64, vp, vp, vp, vp]
@@ -85,7 +86,7 @@ def load_library() -> ctypes.CDLL:
     for name in ("fobq_create", "fobq_destroy", "fobq_hessian_begin", "fobq_hessian_set_mode", "fobq_hessian_accumulate",
                  "fobq_hessian_accumulate_conv", "fobq_hessian_finalize", "fobq_quantize_layer",
                  "fobq_quantize_layer_enqueue", "fobq_quantize_layers_batched", "fobq_finish", "fobq_spd_inverse", "fobq_sensitivity",
-                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate", "fobq_obq_rows", "fobq_hessian_form",
+                 "fobq_sensitivity_static", "fobq_debug_fail_after", "fobq_debug_offset_tables", "fobq_workspace_bytes", "fobq_probe_int8_matrix_rate", "fobq_obq_rows", "fobq_hessian_form",
                  "fobq_profile_enable", "fobq_profile_get", "fobq_profile_reset"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -333,6 +334,29 @@ def fobq_probe_int8_matrix_rate(ctx: int, operand_kind: int) -> float:
 
 def fobq_debug_fail_after(ctx: int, n: int) -> None:
     _check(ctx, load_library().fobq_debug_fail_after(ctypes.c_void_p(ctx), n))
+
+
+def fobq_debug_offset_tables(k: int, pad: int, h: int, w: int):
+    """fobq_debug_offset_tables: (jobs, pairs, terms) as lists of tuples, or None when the geometry does not fit
+    the library's tables.  Host code only: no GPU, no context."""
+    lib = load_library()
+    cap = 3 + 6 * 128 + 4 * 81 + 2 * 384
+    buf = (ctypes.c_int32 * cap)()
+    used = ctypes.c_int64(0)
+    rc = lib.fobq_debug_offset_tables(k, pad, h, w, buf, cap, ctypes.byref(used))
+    if rc == ESTATE:
+        return None
+    if rc != OK:
+        raise FobqError(rc, "fobq_debug_offset_tables: bad argument")
+    v = list(buf[:used.value])
+    nj, npair, nt = v[0], v[1], v[2]
+    o = 3
+    jobs = [tuple(v[o + 6 * i:o + 6 * i + 6]) for i in range(nj)]
+    o += 6 * nj
+    pairs = [tuple(v[o + 4 * i:o + 4 * i + 4]) for i in range(npair)]
+    o += 4 * npair
+    terms = [tuple(v[o + 2 * i:o + 2 * i + 2]) for i in range(nt)]
+    return jobs, pairs, terms
 
 
 def FOBQ_PROFILE_STAGE(stage: int) -> int:

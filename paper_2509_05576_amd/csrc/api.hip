@@ -840,6 +840,28 @@ int fobq_obq_rows(fobq_ctx* ctx, const float* W, int64_t d_row, int64_t d_col, c
     return (rc && rc != FOBQ_EINVAL) ? drain_after_failure(ctx, rc) : rc;
 }
 
+int fobq_debug_offset_tables(int32_t k, int32_t pad, int64_t h, int64_t w, int32_t* out, int64_t cap, int64_t* used)
+{
+    if (!out || !used || k < 1 || pad < 0 || h < 1 || w < 1 || h > (1 << 20) || w > (1 << 20) || pad > (1 << 10))
+        return FOBQ_EINVAL;
+    OffsetTables tab;
+    if (!offset_tables_build(k, pad, (int)h, (int)w, &tab)) return FOBQ_ESTATE;
+    const int64_t need = 3 + 6 * (int64_t)tab.njobs + 4 * (int64_t)tab.npairs + 2 * (int64_t)tab.nterms;
+    *used = need;
+    if (need > cap) return FOBQ_EINVAL;
+    int32_t* o = out;
+    *o++ = tab.njobs; *o++ = tab.npairs; *o++ = tab.nterms;
+    for (int j = 0; j < tab.njobs; ++j) {
+        const OffsetJob& b = tab.jobs[j];
+        *o++ = b.kind; *o++ = b.coord; *o++ = b.start; *o++ = b.len; *o++ = b.dy; *o++ = b.dx;
+    }
+    for (int p = 0; p < tab.npairs; ++p) {
+        *o++ = tab.pair_ta[p]; *o++ = tab.pair_tb[p]; *o++ = tab.pair_begin[p]; *o++ = tab.pair_begin[p + 1];
+    }
+    for (int t = 0; t < tab.nterms; ++t) { *o++ = tab.term_job[t]; *o++ = tab.term_sign[t]; }
+    return FOBQ_OK;
+}
+
 int fobq_debug_fail_after(fobq_ctx* ctx, int n)
 {
     if (!ctx || n < 0) return FOBQ_EINVAL;
